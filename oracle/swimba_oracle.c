@@ -1,0 +1,226 @@
+/*
+ * CPU oracle for the Swimba token mixer.  TEST INFRASTRUCTURE ONLY.
+ *
+ * A plain, slow, sequential evaluation of the method in double precision,
+ * written from the paper's definitions.  It shares no code with the HIP
+ * library and must never be called from the product path: only the tests,
+ * the smoke check and the benchmark's cpu_baseline leg may use it.
+ *
+ * What it evaluates (paper sections "Mixture of Experts and Switching
+ * Dynamics", "Selective SSM and SSD", "MoE-parameterized SSM" and
+ * "Alternative: MoE of separated SSMs"):
+ *
+ *   router      pi_t = softmax(g_t) over all E experts (router softmax
+ *               equation); K_t = the top_k largest logits; the softmax values
+ *               are kept on K_t and NOT renormalised.
+ *   mixing      Bmix_t = sum_{e in K_t} pi_{t,e} B_t^(e),
+ *               Cmix_t = sum_{e in K_t} pi_{t,e} C_t^(e)       (Theorem 1)
+ *   recurrence  h_t = exp(dt_t A_h) h_{t-1} + dt_t Bmix_t x_t^T (mixed state
+ *               update equation, with the scalar-identity transition of SSD
+ *               and Mamba-2's dt-scaled injection)
+ *   readout     y_t = Cmix_t . h_t + D_h x_t     (mixed readout equation; the
+ *               state is read AFTER its update, as in the selective SSM
+ *               equation y_t = C_t^T h_t)
+ *   separated   h_t^(e) = exp(dt_t A_h) h_{t-1}^(e) + dt_t B_t^(e) x_t^T for
+ *               every expert e, y_t = sum_{e in K_t} pi_{t,e} C_t^(e) . h_t^(e)
+ *               + D_h x_t                       (separated-SSM equation)
+ *
+ * Readings where the paper is silent (kept in step with the design notes):
+ *   - ties between equal logits go to the lower expert index, and the active
+ *     set is reported in (logit descending, index ascending) order;
+ *   - the transition is one negative scalar A_h per head, time variation comes
+ *     only from dt; dt is a single positive stream, not routed;
+ *   - x is shared by the experts (the API has one x), so the mixed injection
+ *     is the rank-1 term dt Bmix x^T;
+ *   - B/C streams come per group, head h reads group floor(h*G/H);
+ *   - D is a per-head skip coefficient (NULL means 0);
+ *   - the state starts at h0 (NULL means zeros).
+ *
+ * Inputs are float arrays holding the exact stored values (fp32, or bf16
+ * widened to fp32); every product and sum is done in double.
+ *
+ * Pins (tests/test_oracle_pins.py): the sigmoid worked example of the
+ * expressivity theorem's proof, the geometric-series closed form, the
+ * quadratic masked form Y = M X on tiny inputs, the E=1 / one-hot / identical
+ * expert reductions to a plain selective SSM, linearity in x, the
+ * separated-vs-mixed equality regime, the BIBO bound, brute-force top-k.
+ * Nothing here is "parity unpinned".
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+typedef struct {
+    int64_t batch, seqlen, nheads, headdim, dstate, ngroups, nexperts, top_k;
+} oracle_dims;
+
+int swimba_oracle_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/* Router for one token: g[E] -> idx[k], w[k]. */
+static void route_token(const float *g, int64_t E, int64_t k, int32_t *idx, double *w)
+{
+    double m = -INFINITY, Z = 0.0;
+    for (int64_t e = 0; e < E; ++e)
+        if ((double)g[e] > m) m = (double)g[e];
+    for (int64_t e = 0; e < E; ++e)
+        Z += exp((double)g[e] - m);
+    /* k rounds of "largest logit not yet taken"; strict > keeps the lowest
+       index among equal logits (and treats +0 and -0 as equal). */
+    for (int64_t r = 0; r < k; ++r) {
+        int64_t best = -1;
+        for (int64_t e = 0; e < E; ++e) {
+            int taken = 0;
+            for (int64_t s = 0; s < r; ++s)
+                if (idx[s] == (int32_t)e) taken = 1;
+            if (taken) continue;
+            if (best < 0 || g[e] > g[best]) best = e;
+        }
+        idx[r] = (int32_t)best;
+        w[r] = exp((double)g[best] - m) / Z;
+    }
+}
+
+/* logits (T,E) -> idx (T,k), w (T,k) */
+int swimba_oracle_router(const float *logits, int64_t T, int64_t E, int64_t k,
+                         int32_t *idx, double *w)
+{
+    if (!logits || !idx || !w || E < 1 || k < 1 || k > E || T < 0) return 1;
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < T; ++t)
+        route_token(logits + t * E, E, k, idx + t * k, w + t * k);
+    return 0;
+}
+
+/*
+ * Mixed (single-trajectory) forward.
+ *   x (B,L,H,P)  dt (B,L,H)  A (H)  D (H)|NULL  Be,Ce (B,L,E,G,N)  logits (B,L,E)
+ *   h0 (B,H,P,N)|NULL
+ *   y (B,L,H,P)  h_final (B,H,P,N)|NULL  idx (B,L,k)  w (B,L,k)
+ *   snaps: if snap_every > 0, (B, ceil(L/snap_every), H, P, N): the state
+ *          BEFORE token c*snap_every is consumed (the state carried into
+ *          block c).
+ */
+int swimba_oracle_mixer_fwd(const oracle_dims *d, const float *x, const float *dt,
+                            const float *A, const float *D, const float *Be, const float *Ce,
+                            const float *logits, const double *h0, double *y, double *h_final,
+                            int32_t *idx, double *w, int64_t snap_every, double *snaps)
+{
+    const int64_t B = d->batch, L = d->seqlen, H = d->nheads, P = d->headdim, N = d->dstate,
+                  G = d->ngroups, E = d->nexperts, k = d->top_k;
+    if (B < 0 || L < 0 || H < 1 || P < 1 || N < 1 || G < 1 || E < 1 || k < 1 || k > E || H % G)
+        return 1;
+    if (swimba_oracle_router(logits, B * L, E, k, idx, w)) return 1;
+    const int64_t nsnap = snap_every > 0 ? (L + snap_every - 1) / snap_every : 0;
+
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t bh = 0; bh < B * H; ++bh) {
+        const int64_t b = bh / H, h = bh % H, q = (h * G) / H;
+        double *st = (double *)malloc(sizeof(double) * P * N);
+        double *Bm = (double *)malloc(sizeof(double) * N);
+        double *Cm = (double *)malloc(sizeof(double) * N);
+        for (int64_t i = 0; i < P * N; ++i) st[i] = h0 ? h0[(b * H + h) * P * N + i] : 0.0;
+
+        for (int64_t t = 0; t < L; ++t) {
+            const int64_t bt = b * L + t;
+            if (snap_every > 0 && t % snap_every == 0)
+                memcpy(snaps + (((b * nsnap + t / snap_every) * H + h) * P * N), st,
+                       sizeof(double) * P * N);
+            /* parameter-space mixing of the injection and readout streams */
+            for (int64_t n = 0; n < N; ++n) { Bm[n] = 0.0; Cm[n] = 0.0; }
+            for (int64_t r = 0; r < k; ++r) {
+                const int64_t e = idx[bt * k + r];
+                const double pi = w[bt * k + r];
+                const float *be = Be + ((bt * E + e) * G + q) * N;
+                const float *ce = Ce + ((bt * E + e) * G + q) * N;
+                for (int64_t n = 0; n < N; ++n) {
+                    Bm[n] += pi * (double)be[n];
+                    Cm[n] += pi * (double)ce[n];
+                }
+            }
+            /* one step of the single recurrence, then the readout */
+            const double dtt = (double)dt[bt * H + h];
+            const double a = exp(dtt * (double)A[h]);
+            for (int64_t p = 0; p < P; ++p) {
+                const double xv = (double)x[(bt * H + h) * P + p];
+                const double u = dtt * xv;
+                double *sp = st + p * N;
+                double acc = 0.0;
+                for (int64_t n = 0; n < N; ++n) {
+                    sp[n] = a * sp[n] + u * Bm[n];
+                    acc += Cm[n] * sp[n];
+                }
+                y[(bt * H + h) * P + p] = acc + (D ? (double)D[h] * xv : 0.0);
+            }
+        }
+        if (h_final) memcpy(h_final + (b * H + h) * P * N, st, sizeof(double) * P * N);
+        free(st); free(Bm); free(Cm);
+    }
+    return 0;
+}
+
+/*
+ * MoE of separated SSMs: one state per expert, every expert advances on every
+ * token with its own B stream; the readout sums the active experts only.
+ *   h_final (B,E,H,P,N)|NULL
+ */
+int swimba_oracle_separated_fwd(const oracle_dims *d, const float *x, const float *dt,
+                                const float *A, const float *D, const float *Be, const float *Ce,
+                                const float *logits, double *y, double *h_final,
+                                int32_t *idx, double *w)
+{
+    const int64_t B = d->batch, L = d->seqlen, H = d->nheads, P = d->headdim, N = d->dstate,
+                  G = d->ngroups, E = d->nexperts, k = d->top_k;
+    if (B < 0 || L < 0 || H < 1 || P < 1 || N < 1 || G < 1 || E < 1 || k < 1 || k > E || H % G)
+        return 1;
+    if (swimba_oracle_router(logits, B * L, E, k, idx, w)) return 1;
+
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t bh = 0; bh < B * H; ++bh) {
+        const int64_t b = bh / H, h = bh % H, q = (h * G) / H;
+        double *st = (double *)calloc((size_t)(E * P * N), sizeof(double));
+        for (int64_t t = 0; t < L; ++t) {
+            const int64_t bt = b * L + t;
+            const double dtt = (double)dt[bt * H + h];
+            const double a = exp(dtt * (double)A[h]);
+            for (int64_t e = 0; e < E; ++e) {
+                const float *be = Be + ((bt * E + e) * G + q) * N;
+                for (int64_t p = 0; p < P; ++p) {
+                    const double u = dtt * (double)x[(bt * H + h) * P + p];
+                    double *sp = st + (e * P + p) * N;
+                    for (int64_t n = 0; n < N; ++n) sp[n] = a * sp[n] + u * (double)be[n];
+                }
+            }
+            for (int64_t p = 0; p < P; ++p) {
+                const double xv = (double)x[(bt * H + h) * P + p];
+                double acc = 0.0;
+                for (int64_t r = 0; r < k; ++r) {
+                    const int64_t e = idx[bt * k + r];
+                    const double pi = w[bt * k + r];
+                    const float *ce = Ce + ((bt * E + e) * G + q) * N;
+                    const double *sp = st + (e * P + p) * N;
+                    double dot = 0.0;
+                    for (int64_t n = 0; n < N; ++n) dot += (double)ce[n] * sp[n];
+                    acc += pi * dot;
+                }
+                y[(bt * H + h) * P + p] = acc + (D ? (double)D[h] * xv : 0.0);
+            }
+        }
+        if (h_final)
+            for (int64_t e = 0; e < E; ++e)
+                memcpy(h_final + (((b * E + e) * H + h) * P * N), st + e * P * N,
+                       sizeof(double) * P * N);
+        free(st);
+    }
+    return 0;
+}
