@@ -1,0 +1,208 @@
+/*
+ * swimba.h - C ABI of the MI355X (gfx950) Swimba token-mixer library.
+ *
+ * The library evaluates the forward hot path of the MoE-parameterized SSM
+ * layer: a token-level router (softmax over E experts, top-k, no
+ * renormalisation), parameter-space mixing of the expert-produced injection
+ * (B) and readout (C) streams, and ONE Mamba-2 style SSD chunked recurrence
+ * over the single mixed state trajectory; plus the single-token recurrent
+ * decode step.
+ *
+ * Conventions that hold for every entry point
+ *   - Every tensor pointer is a DEVICE pointer owned by the caller (the dims
+ *     struct and the layout struct are HOST pointers).  Tensors are dense,
+ *     row-major, last index contiguous, 16-byte aligned.
+ *   - "io" tensors have the element type dims->io_dtype (fp32 or bf16);
+ *     A, D, states, weights are always fp32, indices int32.
+ *   - The library allocates no device memory.  Scratch comes from the
+ *     caller's workspace, sized by swimba_mixer_workspace_bytes().
+ *   - Calls validate their arguments on the host first (a failed call
+ *     enqueues nothing), then only enqueue kernels on `hip_stream` (a
+ *     hipStream_t passed as void*, NULL = the default stream).  They never
+ *     synchronise.  Inputs are never written; outputs are fully overwritten.
+ *   - Results do not depend on launch order or atomics: two calls on the same
+ *     inputs give bitwise-identical outputs.
+ *   - Errors are returned as swimba_status; nothing throws across the ABI.
+ *
+ * Symbols:  B batch, L seqlen, H heads, P headdim, N state size, G B/C groups
+ * (head h reads group floor(h*G/H), H % G == 0), E experts, k = top_k,
+ * Q = chunk, nc = ceil(L/Q).
+ */
+#ifndef SWIMBA_H
+#define SWIMBA_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* every entry point below is exported with default visibility */
+#pragma GCC visibility push(default)
+
+typedef enum {
+    SWIMBA_OK = 0,
+    SWIMBA_ERR_NULL = 1,        /* a required pointer is NULL */
+    SWIMBA_ERR_SHAPE = 2,       /* non-positive or inconsistent dimensions */
+    SWIMBA_ERR_DTYPE = 3,       /* io_dtype is not a swimba_dtype */
+    SWIMBA_ERR_UNSUPPORTED = 4, /* valid problem, but outside the kernels' limits */
+    SWIMBA_ERR_WORKSPACE = 5,   /* workspace NULL or smaller than the query says */
+    SWIMBA_ERR_HIP = 6          /* a HIP call failed; see swimba_last_hip_error() */
+} swimba_status;
+
+typedef enum { SWIMBA_F32 = 0, SWIMBA_BF16 = 1 } swimba_dtype;
+
+/* Limits of the kernels (anything beyond returns SWIMBA_ERR_UNSUPPORTED). */
+#define SWIMBA_MAX_EXPERTS 256
+#define SWIMBA_MAX_TOPK 16
+#define SWIMBA_MAX_DSTATE 256
+#define SWIMBA_MAX_HEADDIM 256
+#define SWIMBA_MAX_CHUNK 256
+
+typedef struct {
+    int32_t batch, seqlen, nheads, headdim, dstate, ngroups, nexperts, top_k;
+    int32_t chunk;    /* SSD chunk length Q in [1, SWIMBA_MAX_CHUNK]; ignored by swimba_step */
+    int32_t io_dtype; /* a swimba_dtype */
+} swimba_dims;
+
+/* Byte offsets of the scratch arrays inside the workspace (for tests and
+ * profiling of single stages; a plain caller only needs `total`). */
+typedef struct {
+    size_t topk_idx;  /* (B,L,k) int32 : active experts, router order              */
+    size_t topk_w;    /* (B,L,k) fp32  : their un-renormalised softmax weights      */
+    size_t cs;        /* (B,nc,H,Q) fp32 : inclusive cumsum of dt*A inside each chunk */
+    size_t states;    /* (B,nc,H,P,N) fp32 : chunk states S_c, then (after the scan)
+                         the state carried INTO chunk c                             */
+    size_t states_lp; /* (B,nc,H,P,N) bf16 copy of the carried states (bf16 MFMA path
+                         only; equals `total` when unused)                          */
+    size_t total;
+} swimba_ws_layout;
+
+/* Workspace size in bytes for swimba_mixer_fwd / the stage calls; 0 if the
+ * dims are invalid or unsupported.  `dims` is a host pointer. */
+size_t swimba_mixer_workspace_bytes(const swimba_dims *dims);
+
+/* Fills *layout (host pointer) with the offsets above. */
+swimba_status swimba_mixer_workspace_layout(const swimba_dims *dims, swimba_ws_layout *layout);
+
+/*
+ * Router (paper: router softmax equation and the top-k rule that follows it).
+ *   pi = softmax(logits) over ALL E experts; the k largest logits form the
+ *   active set; their softmax values are kept and NOT renormalised.
+ * Selection compares the raw stored logits (never the softmax values); equal
+ * logits (including +0/-0) go to the lower expert index; the active set is
+ * written in (logit descending, index ascending) order.  NaN logits are
+ * outside the contract.
+ *   logits   (tokens, E) io   [in]
+ *   topk_idx (tokens, k) int32 [out]
+ *   topk_w   (tokens, k) fp32  [out]
+ */
+swimba_status swimba_router_topk(int64_t tokens, int32_t nexperts, int32_t top_k, int32_t io_dtype,
+                                 const void *logits, int32_t *topk_idx, float *topk_w,
+                                 void *hip_stream);
+
+/*
+ * Prefill / training-forward of the token mixer (paper: mixed state update
+ * and mixed readout equations, Theorem 1; evaluated in the chunked SSD form of
+ * the background section "Mamba-2 and SSD"):
+ *
+ *   Bmix_t = sum_{e in K_t} pi_{t,e} B_t^(e),  Cmix_t likewise
+ *   h_t    = exp(dt_t A_h) h_{t-1} + dt_t Bmix_t x_t^T
+ *   y_t    = Cmix_t . h_t + D_h x_t                  (state read after its update)
+ *
+ *   x             (B,L,H,P)   io    [in]
+ *   dt            (B,L,H)     io    [in]  final positive step size (no softplus inside)
+ *   A             (H)         fp32  [in]  negative scalar transition per head
+ *   D             (H)         fp32  [in]  skip coefficient; NULL = 0
+ *   B_experts     (B,L,E,G,N) io    [in]
+ *   C_experts     (B,L,E,G,N) io    [in]
+ *   router_logits (B,L,E)     io    [in]
+ *   h0            (B,H,P,N)   fp32  [in]  initial state; NULL = zeros
+ *   y             (B,L,H,P)   io    [out]
+ *   h_final       (B,H,P,N)   fp32  [out] state after the last token; NULL = not wanted
+ *   topk_idx      (B,L,k)     int32 [out] NULL = not wanted
+ *   topk_w        (B,L,k)     fp32  [out] NULL = not wanted
+ *   workspace     >= swimba_mixer_workspace_bytes(dims) bytes, 256-byte aligned
+ *
+ * L need not be a multiple of Q (the last chunk is ragged).  B == 0 or L == 0
+ * is valid: nothing is computed (h_final = h0 or zeros when L == 0).
+ * Arithmetic: fp32 throughout for io_dtype fp32.  For bf16 io with
+ * P = 64, N = 128 and Q in {64,128,256} the contractions run on bf16 MFMA
+ * with fp32 accumulation (mixed streams, decay-weighted x, the decay-masked
+ * C.B^T block and the carried states are rounded to bf16 as operands);
+ * other bf16 shapes use the fp32 kernels.
+ */
+swimba_status swimba_mixer_fwd(const swimba_dims *dims, const void *x, const void *dt,
+                               const float *A, const float *D, const void *B_experts,
+                               const void *C_experts, const void *router_logits, const float *h0,
+                               void *y, float *h_final, int32_t *topk_idx, float *topk_w,
+                               void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * The stages of swimba_mixer_fwd, one call each, on the same workspace (for
+ * per-kernel measurement and stage-level tests).  Running router, cumsum,
+ * chunk_state, state_scan, output in this order equals swimba_mixer_fwd.
+ *   router      : logits -> ws.topk_idx, ws.topk_w
+ *   cumsum      : dt, A  -> ws.cs                (per-chunk cumsum of dt*A)
+ *   chunk_state : x, dt, B_experts, ws.{topk_*,cs} -> ws.states = S_c
+ *                 S_c = sum_j exp(cs_last - cs_j) dt_j x_j (x) Bmix_j
+ *   state_scan  : ws.states (S_c -> state carried into chunk c, in place),
+ *                 h0, ws.cs -> h_final (and ws.states_lp on the bf16 MFMA path)
+ *   output      : x, dt, D, B/C_experts, ws.* -> y
+ *                 y_i = sum_{j<=i} (Cmix_i.Bmix_j) exp(cs_i - cs_j) dt_j x_j
+ *                       + exp(cs_i) Cmix_i . H_c + D x_i
+ */
+swimba_status swimba_stage_router(const swimba_dims *dims, const void *router_logits,
+                                  void *workspace, size_t workspace_bytes, void *hip_stream);
+swimba_status swimba_stage_cumsum(const swimba_dims *dims, const void *dt, const float *A,
+                                  void *workspace, size_t workspace_bytes, void *hip_stream);
+swimba_status swimba_stage_chunk_state(const swimba_dims *dims, const void *x, const void *dt,
+                                       const void *B_experts, void *workspace,
+                                       size_t workspace_bytes, void *hip_stream);
+swimba_status swimba_stage_state_scan(const swimba_dims *dims, const float *h0, float *h_final,
+                                      void *workspace, size_t workspace_bytes, void *hip_stream);
+swimba_status swimba_stage_output(const swimba_dims *dims, const void *x, const void *dt,
+                                  const float *D, const void *B_experts, const void *C_experts,
+                                  void *y, void *workspace, size_t workspace_bytes,
+                                  void *hip_stream);
+
+/*
+ * Single-token recurrent decode step (paper: selective SSM recurrence, per
+ * channel, with the mixed injection and readout of Theorem 1): for every
+ * (b,h)
+ *   route and mix token b once;  h' = exp(dt A_h) h + dt x (x) Bmix;
+ *   y = h' . Cmix + D_h x.
+ * dims->seqlen must be 1; dims->chunk is ignored.
+ *   state_in  (B,H,P,N) fp32 [in]   state_out (B,H,P,N) fp32 [out]; they may be
+ *             the same buffer (each element is read once, then written, by one lane)
+ *   x (B,H,P) io, dt (B,H) io, A (H), D (H)|NULL, B/C_experts (B,E,G,N) io,
+ *   router_logits (B,E) io  [in]
+ *   y (B,H,P) io [out];  topk_idx (B,k) int32 [out] NULL = not wanted
+ * Arithmetic is fp32.
+ */
+swimba_status swimba_step(const swimba_dims *dims, const float *state_in, float *state_out,
+                          const void *x, const void *dt, const float *A, const float *D,
+                          const void *B_experts, const void *C_experts, const void *router_logits,
+                          void *y, int32_t *topk_idx, void *hip_stream);
+
+/*
+ * Measurement helpers (no paper operation): a plain device copy of `bytes`
+ * bytes (multiple of 16) used to calibrate bandwidth figures and profiler
+ * counters, and a register-resident bf16 MFMA loop that runs `iters`
+ * 32x32x16 MFMAs per wave on `blocks` workgroups of 256 lanes and writes one
+ * float per lane to `sink` (blocks*256 floats).
+ */
+swimba_status swimba_probe_copy(void *dst, const void *src, size_t bytes, void *hip_stream);
+swimba_status swimba_probe_mfma(float *sink, int32_t blocks, int32_t iters, void *hip_stream);
+
+const char *swimba_status_string(swimba_status s);
+/* hipError_t (as int) of the last SWIMBA_ERR_HIP returned on the calling thread, 0 if none. */
+int swimba_last_hip_error(void);
+
+#pragma GCC visibility pop
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SWIMBA_H */

@@ -1,0 +1,310 @@
+"""Thin ctypes binding of libswimba.so: argument marshalling only.
+
+Every function has the name and the argument order of the C entry point it
+calls (include/swimba.h); torch is used for device memory, dtypes and the
+current HIP stream, nothing else.  There is no CPU fallback: if the library
+has not been built, or a tensor is not on the GPU, the call raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import NamedTuple, Optional
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libswimba.so")
+
+SWIMBA_F32, SWIMBA_BF16 = 0, 1
+MAX_TOPK = 16
+
+_lib = None
+
+
+class SwimbaError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        msg = _load().swimba_status_string(status).decode()
+        if status == 6:
+            msg += " (hipError %d)" % _load().swimba_last_hip_error()
+        super().__init__("%s: %s [status %d]" % (where, msg, status))
+
+
+class swimba_dims(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_int32) for n in
+                ("batch", "seqlen", "nheads", "headdim", "dstate", "ngroups", "nexperts", "top_k",
+                 "chunk", "io_dtype")]
+
+
+class swimba_ws_layout(ctypes.Structure):
+    _fields_ = [(n, ctypes.c_size_t) for n in
+                ("topk_idx", "topk_w", "cs", "states", "states_lp", "total")]
+
+
+def _load():
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                "libswimba.so is not built (%s); run `python -c 'import __graft_entry__ as g; g.build()'`"
+                % LIB_PATH)
+        lib = ctypes.CDLL(LIB_PATH)
+        vp, i32, i64, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_int64, ctypes.c_size_t
+        dp = ctypes.POINTER(swimba_dims)
+        lib.swimba_mixer_workspace_bytes.restype = sz
+        lib.swimba_mixer_workspace_bytes.argtypes = [dp]
+        lib.swimba_mixer_workspace_layout.restype = i32
+        lib.swimba_mixer_workspace_layout.argtypes = [dp, ctypes.POINTER(swimba_ws_layout)]
+        lib.swimba_router_topk.restype = i32
+        lib.swimba_router_topk.argtypes = [i64, i32, i32, i32, vp, vp, vp, vp]
+        lib.swimba_mixer_fwd.restype = i32
+        lib.swimba_mixer_fwd.argtypes = [dp] + [vp] * 12 + [vp, sz, vp]
+        lib.swimba_stage_router.restype = i32
+        lib.swimba_stage_router.argtypes = [dp, vp, vp, sz, vp]
+        lib.swimba_stage_cumsum.restype = i32
+        lib.swimba_stage_cumsum.argtypes = [dp, vp, vp, vp, sz, vp]
+        lib.swimba_stage_chunk_state.restype = i32
+        lib.swimba_stage_chunk_state.argtypes = [dp, vp, vp, vp, vp, sz, vp]
+        lib.swimba_stage_state_scan.restype = i32
+        lib.swimba_stage_state_scan.argtypes = [dp, vp, vp, vp, sz, vp]
+        lib.swimba_stage_output.restype = i32
+        lib.swimba_stage_output.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        lib.swimba_step.restype = i32
+        lib.swimba_step.argtypes = [dp] + [vp] * 11 + [vp]
+        lib.swimba_probe_copy.restype = i32
+        lib.swimba_probe_copy.argtypes = [vp, vp, sz, vp]
+        lib.swimba_probe_mfma.restype = i32
+        lib.swimba_probe_mfma.argtypes = [vp, i32, i32, vp]
+        lib.swimba_status_string.restype = ctypes.c_char_p
+        lib.swimba_status_string.argtypes = [i32]
+        lib.swimba_last_hip_error.restype = i32
+        lib.swimba_last_hip_error.argtypes = []
+        _lib = lib
+    return _lib
+
+
+def library_loaded() -> bool:
+    return _lib is not None
+
+
+# ---- marshalling helpers -------------------------------------------------------------------
+
+def _io_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return SWIMBA_F32
+    if t.dtype == torch.bfloat16:
+        return SWIMBA_BF16
+    raise TypeError("io tensors must be float32 or bfloat16, got %s" % t.dtype)
+
+
+def _ptr(t: Optional[torch.Tensor], name: str, dtype=None, shape=None) -> Optional[int]:
+    if t is None:
+        return None
+    if not t.is_cuda:
+        raise ValueError("%s must be a GPU tensor (this library has no CPU path)" % name)
+    if not t.is_contiguous():
+        raise ValueError("%s must be contiguous" % name)
+    if dtype is not None and t.dtype != dtype:
+        raise TypeError("%s must have dtype %s, got %s" % (name, dtype, t.dtype))
+    if shape is not None and tuple(t.shape) != tuple(shape):
+        raise ValueError("%s must have shape %s, got %s" % (name, tuple(shape), tuple(t.shape)))
+    return t.data_ptr()
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _check(status: int, where: str) -> None:
+    if status != 0:
+        raise SwimbaError(status, where)
+
+
+def make_dims(batch, seqlen, nheads, headdim, dstate, ngroups, nexperts, top_k, chunk, io_dtype) -> swimba_dims:
+    if isinstance(io_dtype, torch.dtype):
+        io_dtype = {torch.float32: SWIMBA_F32, torch.bfloat16: SWIMBA_BF16}[io_dtype]
+    return swimba_dims(batch, seqlen, nheads, headdim, dstate, ngroups, nexperts, top_k, chunk, io_dtype)
+
+
+def dims_of(x: torch.Tensor, B_experts: torch.Tensor, top_k: int, chunk: int) -> swimba_dims:
+    B, L, H, P = x.shape
+    _, _, E, G, N = B_experts.shape
+    return make_dims(B, L, H, P, N, G, E, top_k, chunk, _io_code(x))
+
+
+# ---- entry points ----------------------------------------------------------------------
+
+def swimba_mixer_workspace_bytes(dims: swimba_dims) -> int:
+    return int(_load().swimba_mixer_workspace_bytes(ctypes.byref(dims)))
+
+
+def swimba_mixer_workspace_layout(dims: swimba_dims) -> swimba_ws_layout:
+    lo = swimba_ws_layout()
+    _check(_load().swimba_mixer_workspace_layout(ctypes.byref(dims), ctypes.byref(lo)),
+           "swimba_mixer_workspace_layout")
+    return lo
+
+
+def alloc_workspace(dims: swimba_dims, device) -> torch.Tensor:
+    n = swimba_mixer_workspace_bytes(dims)
+    if n == 0:
+        raise SwimbaError(_load().swimba_mixer_workspace_layout(ctypes.byref(dims),
+                                                                ctypes.byref(swimba_ws_layout())),
+                          "swimba_mixer_workspace_bytes")
+    return torch.empty(n, dtype=torch.uint8, device=device)
+
+
+def swimba_router_topk(router_logits: torch.Tensor, top_k: int, topk_idx=None, topk_w=None):
+    E = router_logits.shape[-1]
+    tokens = router_logits.numel() // E if E else 0
+    lead = tuple(router_logits.shape[:-1])
+    if topk_idx is None:
+        topk_idx = torch.empty(lead + (top_k,), dtype=torch.int32, device=router_logits.device)
+    if topk_w is None:
+        topk_w = torch.empty(lead + (top_k,), dtype=torch.float32, device=router_logits.device)
+    _check(_load().swimba_router_topk(tokens, E, top_k, _io_code(router_logits),
+                                      _ptr(router_logits, "router_logits"),
+                                      _ptr(topk_idx, "topk_idx", torch.int32, lead + (top_k,)),
+                                      _ptr(topk_w, "topk_w", torch.float32, lead + (top_k,)), _stream()),
+           "swimba_router_topk")
+    return topk_idx, topk_w
+
+
+class MixerOut(NamedTuple):
+    y: torch.Tensor
+    h_final: Optional[torch.Tensor]
+    topk_idx: Optional[torch.Tensor]
+    topk_w: Optional[torch.Tensor]
+
+
+def swimba_mixer_fwd(x, dt, A, D, B_experts, C_experts, router_logits, top_k: int, chunk: int,
+                     h0=None, *, y=None, h_final=None, topk_idx=None, topk_w=None, workspace=None,
+                     want_h_final: bool = True, want_topk: bool = False) -> MixerOut:
+    d = dims_of(x, B_experts, top_k, chunk)
+    B, L, H, P, N, G, E = d.batch, d.seqlen, d.nheads, d.headdim, d.dstate, d.ngroups, d.nexperts
+    io = x.dtype
+    dev = x.device
+    if workspace is None:
+        workspace = alloc_workspace(d, dev)
+    if y is None:
+        y = torch.empty_like(x)
+    if h_final is None and want_h_final:
+        h_final = torch.empty((B, H, P, N), dtype=torch.float32, device=dev)
+    if want_topk and topk_idx is None:
+        topk_idx = torch.empty((B, L, top_k), dtype=torch.int32, device=dev)
+    if want_topk and topk_w is None:
+        topk_w = torch.empty((B, L, top_k), dtype=torch.float32, device=dev)
+    st = _load().swimba_mixer_fwd(
+        ctypes.byref(d), _ptr(x, "x", io, (B, L, H, P)), _ptr(dt, "dt", io, (B, L, H)),
+        _ptr(A, "A", torch.float32, (H,)), _ptr(D, "D", torch.float32, (H,)),
+        _ptr(B_experts, "B_experts", io, (B, L, E, G, N)),
+        _ptr(C_experts, "C_experts", io, (B, L, E, G, N)),
+        _ptr(router_logits, "router_logits", io, (B, L, E)),
+        _ptr(h0, "h0", torch.float32, (B, H, P, N)), _ptr(y, "y", io, (B, L, H, P)),
+        _ptr(h_final, "h_final", torch.float32, (B, H, P, N)),
+        _ptr(topk_idx, "topk_idx", torch.int32, (B, L, top_k)),
+        _ptr(topk_w, "topk_w", torch.float32, (B, L, top_k)),
+        _ptr(workspace, "workspace", torch.uint8), workspace.numel(), _stream())
+    _check(st, "swimba_mixer_fwd")
+    return MixerOut(y, h_final, topk_idx, topk_w)
+
+
+def swimba_stage_router(dims, router_logits, workspace):
+    _check(_load().swimba_stage_router(ctypes.byref(dims), _ptr(router_logits, "router_logits"),
+                                       _ptr(workspace, "workspace", torch.uint8), workspace.numel(),
+                                       _stream()), "swimba_stage_router")
+
+
+def swimba_stage_cumsum(dims, dt, A, workspace):
+    _check(_load().swimba_stage_cumsum(ctypes.byref(dims), _ptr(dt, "dt"), _ptr(A, "A", torch.float32),
+                                       _ptr(workspace, "workspace", torch.uint8), workspace.numel(),
+                                       _stream()), "swimba_stage_cumsum")
+
+
+def swimba_stage_chunk_state(dims, x, dt, B_experts, workspace):
+    _check(_load().swimba_stage_chunk_state(ctypes.byref(dims), _ptr(x, "x"), _ptr(dt, "dt"),
+                                            _ptr(B_experts, "B_experts"),
+                                            _ptr(workspace, "workspace", torch.uint8),
+                                            workspace.numel(), _stream()), "swimba_stage_chunk_state")
+
+
+def swimba_stage_state_scan(dims, h0, h_final, workspace):
+    _check(_load().swimba_stage_state_scan(ctypes.byref(dims), _ptr(h0, "h0", torch.float32),
+                                           _ptr(h_final, "h_final", torch.float32),
+                                           _ptr(workspace, "workspace", torch.uint8),
+                                           workspace.numel(), _stream()), "swimba_stage_state_scan")
+
+
+def swimba_stage_output(dims, x, dt, D, B_experts, C_experts, y, workspace):
+    _check(_load().swimba_stage_output(ctypes.byref(dims), _ptr(x, "x"), _ptr(dt, "dt"),
+                                       _ptr(D, "D", torch.float32), _ptr(B_experts, "B_experts"),
+                                       _ptr(C_experts, "C_experts"), _ptr(y, "y"),
+                                       _ptr(workspace, "workspace", torch.uint8), workspace.numel(),
+                                       _stream()), "swimba_stage_output")
+
+
+def workspace_views(dims: swimba_dims, workspace: torch.Tensor):
+    """Typed views of the scratch arrays inside a workspace (for tests/profiling)."""
+    lo = swimba_mixer_workspace_layout(dims)
+    B, L, H, P, N, K, Q = (dims.batch, dims.seqlen, dims.nheads, dims.headdim, dims.dstate,
+                           dims.top_k, dims.chunk)
+    nc = (L + Q - 1) // Q
+
+    def view(off, count, dtype, shape):
+        nbytes = count * torch.empty((), dtype=dtype).element_size()
+        return workspace[off:off + nbytes].view(dtype).view(shape)
+
+    out = {
+        "topk_idx": view(lo.topk_idx, B * L * K, torch.int32, (B, L, K)),
+        "topk_w": view(lo.topk_w, B * L * K, torch.float32, (B, L, K)),
+        "cs": view(lo.cs, B * nc * H * Q, torch.float32, (B, nc, H, Q)),
+        "states": view(lo.states, B * nc * H * P * N, torch.float32, (B, nc, H, P, N)),
+    }
+    if lo.states_lp != lo.total:
+        out["states_lp"] = view(lo.states_lp, B * nc * H * P * N, torch.bfloat16, (B, nc, H, P, N))
+    return out
+
+
+class StepOut(NamedTuple):
+    y: torch.Tensor
+    state: torch.Tensor
+    topk_idx: Optional[torch.Tensor]
+
+
+def swimba_step(state, x, dt, A, D, B_experts, C_experts, router_logits, top_k: int, *,
+                state_out=None, y=None, topk_idx=None, want_topk: bool = False) -> StepOut:
+    """state (B,H,P,N) fp32, x (B,H,P), dt (B,H), B/C_experts (B,E,G,N), router_logits (B,E).
+    state_out defaults to `state` (in place)."""
+    B, H, P = x.shape
+    _, E, G, N = B_experts.shape
+    io = x.dtype
+    d = make_dims(B, 1, H, P, N, G, E, top_k, 0, _io_code(x))
+    if state_out is None:
+        state_out = state
+    if y is None:
+        y = torch.empty_like(x)
+    if want_topk and topk_idx is None:
+        topk_idx = torch.empty((B, top_k), dtype=torch.int32, device=x.device)
+    st = _load().swimba_step(
+        ctypes.byref(d), _ptr(state, "state", torch.float32, (B, H, P, N)),
+        _ptr(state_out, "state_out", torch.float32, (B, H, P, N)), _ptr(x, "x", io, (B, H, P)),
+        _ptr(dt, "dt", io, (B, H)), _ptr(A, "A", torch.float32, (H,)), _ptr(D, "D", torch.float32, (H,)),
+        _ptr(B_experts, "B_experts", io, (B, E, G, N)), _ptr(C_experts, "C_experts", io, (B, E, G, N)),
+        _ptr(router_logits, "router_logits", io, (B, E)), _ptr(y, "y", io, (B, H, P)),
+        _ptr(topk_idx, "topk_idx", torch.int32, (B, top_k)), _stream())
+    _check(st, "swimba_step")
+    return StepOut(y, state_out, topk_idx)
+
+
+def swimba_probe_copy(dst: torch.Tensor, src: torch.Tensor) -> None:
+    nbytes = src.numel() * src.element_size()
+    assert dst.numel() * dst.element_size() == nbytes
+    _check(_load().swimba_probe_copy(_ptr(dst, "dst"), _ptr(src, "src"), nbytes, _stream()),
+           "swimba_probe_copy")
+
+
+def swimba_probe_mfma(sink: torch.Tensor, blocks: int, iters: int) -> None:
+    assert sink.numel() >= blocks * 256
+    _check(_load().swimba_probe_mfma(_ptr(sink, "sink", torch.float32), blocks, iters, _stream()),
+           "swimba_probe_mfma")

@@ -1,0 +1,263 @@
+// C ABI of libswimba: host-side validation, workspace carve-up, kernel dispatch.
+#include "common.hpp"
+
+#include <string.h>
+
+namespace swimba {
+
+static thread_local int g_last_hip_error = 0;
+void set_last_hip_error(int e) { g_last_hip_error = e; }
+
+static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// Checks that hold for both entry points.
+static swimba_status check_common(const swimba_dims *d)
+{
+    if (!d) return SWIMBA_ERR_NULL;
+    if (d->io_dtype != SWIMBA_F32 && d->io_dtype != SWIMBA_BF16) return SWIMBA_ERR_DTYPE;
+    if (d->batch < 0 || d->seqlen < 0 || d->nheads < 1 || d->headdim < 1 || d->dstate < 1 ||
+        d->ngroups < 1 || d->nexperts < 1 || d->top_k < 1 || d->top_k > d->nexperts ||
+        d->nheads % d->ngroups != 0)
+        return SWIMBA_ERR_SHAPE;
+    if (d->nexperts > SWIMBA_MAX_EXPERTS || d->top_k > SWIMBA_MAX_TOPK ||
+        d->dstate > SWIMBA_MAX_DSTATE || d->headdim > SWIMBA_MAX_HEADDIM)
+        return SWIMBA_ERR_UNSUPPORTED;
+    // 32-bit block indices and 64-bit element offsets are used; keep the grid sizes sane
+    if ((int64_t)d->batch * d->nheads > (1 << 30)) return SWIMBA_ERR_UNSUPPORTED;
+    return SWIMBA_OK;
+}
+
+static swimba_status check_mixer(const swimba_dims *d)
+{
+    swimba_status st = check_common(d);
+    if (st != SWIMBA_OK) return st;
+    if (d->chunk < 1) return SWIMBA_ERR_SHAPE;
+    if (d->chunk > SWIMBA_MAX_CHUNK) return SWIMBA_ERR_UNSUPPORTED;
+    if ((int64_t)d->headdim * d->dstate > 8192) return SWIMBA_ERR_UNSUPPORTED;
+    const int64_t nc = ((int64_t)d->seqlen + d->chunk - 1) / d->chunk;
+    if ((int64_t)d->batch * nc * d->nheads * ((d->chunk + 15) / 16) > (1ll << 31) - 1)
+        return SWIMBA_ERR_UNSUPPORTED;
+    return SWIMBA_OK;
+}
+
+static void layout_of(const swimba_dims *d, swimba_ws_layout *o)
+{
+    const Shape s = make_shape(d);
+    const size_t T = (size_t)s.B * s.L;
+    size_t off = 0;
+    o->topk_idx = off; off = align_up(off + T * s.K * sizeof(int32_t), 256);
+    o->topk_w = off;   off = align_up(off + T * s.K * sizeof(float), 256);
+    o->cs = off;       off = align_up(off + (size_t)s.B * s.nc * s.H * s.Q * sizeof(float), 256);
+    const size_t nstate = (size_t)s.B * s.nc * s.H * s.P * s.N;
+    o->states = off;   off = align_up(off + nstate * sizeof(float), 256);
+    o->states_lp = off;
+    if (use_mfma_path(d)) off = align_up(off + nstate * sizeof(uint16_t), 256);
+    o->total = off > 0 ? off : 256;
+}
+
+struct Ws {
+    int32_t *idx;
+    float *w;
+    float *cs;
+    float *states;
+    void *states_lp;
+};
+
+static swimba_status carve(const swimba_dims *d, void *workspace, size_t bytes, Ws *ws)
+{
+    swimba_status st = check_mixer(d);
+    if (st != SWIMBA_OK) return st;
+    swimba_ws_layout lo;
+    layout_of(d, &lo);
+    if (!workspace || bytes < lo.total || ((uintptr_t)workspace & 255u)) return SWIMBA_ERR_WORKSPACE;
+    char *p = (char *)workspace;
+    ws->idx = (int32_t *)(p + lo.topk_idx);
+    ws->w = (float *)(p + lo.topk_w);
+    ws->cs = (float *)(p + lo.cs);
+    ws->states = (float *)(p + lo.states);
+    ws->states_lp = use_mfma_path(d) ? (void *)(p + lo.states_lp) : nullptr;
+    return SWIMBA_OK;
+}
+
+}  // namespace swimba
+
+using namespace swimba;
+
+extern "C" {
+
+size_t swimba_mixer_workspace_bytes(const swimba_dims *dims)
+{
+    if (check_mixer(dims) != SWIMBA_OK) return 0;
+    swimba_ws_layout lo;
+    layout_of(dims, &lo);
+    return lo.total;
+}
+
+swimba_status swimba_mixer_workspace_layout(const swimba_dims *dims, swimba_ws_layout *layout)
+{
+    if (!layout) return SWIMBA_ERR_NULL;
+    swimba_status st = check_mixer(dims);
+    if (st != SWIMBA_OK) return st;
+    layout_of(dims, layout);
+    return SWIMBA_OK;
+}
+
+swimba_status swimba_router_topk(int64_t tokens, int32_t nexperts, int32_t top_k, int32_t io_dtype,
+                                 const void *logits, int32_t *topk_idx, float *topk_w,
+                                 void *hip_stream)
+{
+    if (io_dtype != SWIMBA_F32 && io_dtype != SWIMBA_BF16) return SWIMBA_ERR_DTYPE;
+    if (tokens < 0 || nexperts < 1 || top_k < 1 || top_k > nexperts) return SWIMBA_ERR_SHAPE;
+    if (nexperts > SWIMBA_MAX_EXPERTS || top_k > SWIMBA_MAX_TOPK || tokens > (1ll << 38))
+        return SWIMBA_ERR_UNSUPPORTED;
+    if (tokens == 0) return SWIMBA_OK;
+    if (!logits || !topk_idx || !topk_w) return SWIMBA_ERR_NULL;
+    return launch_router(tokens, nexperts, top_k, io_dtype, logits, topk_idx, topk_w,
+                         (hipStream_t)hip_stream);
+}
+
+swimba_status swimba_stage_router(const swimba_dims *dims, const void *router_logits,
+                                  void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    Ws ws;
+    swimba_status st = carve(dims, workspace, workspace_bytes, &ws);
+    if (st != SWIMBA_OK) return st;
+    const int64_t T = (int64_t)dims->batch * dims->seqlen;
+    if (T == 0) return SWIMBA_OK;
+    if (!router_logits) return SWIMBA_ERR_NULL;
+    return launch_router(T, dims->nexperts, dims->top_k, dims->io_dtype, router_logits, ws.idx, ws.w,
+                         (hipStream_t)hip_stream);
+}
+
+swimba_status swimba_stage_cumsum(const swimba_dims *dims, const void *dt, const float *A,
+                                  void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    Ws ws;
+    swimba_status st = carve(dims, workspace, workspace_bytes, &ws);
+    if (st != SWIMBA_OK) return st;
+    if ((int64_t)dims->batch * dims->seqlen == 0) return SWIMBA_OK;
+    if (!dt || !A) return SWIMBA_ERR_NULL;
+    return launch_cumsum(make_shape(dims), dims->io_dtype, dt, A, ws.cs, (hipStream_t)hip_stream);
+}
+
+swimba_status swimba_stage_chunk_state(const swimba_dims *dims, const void *x, const void *dt,
+                                       const void *B_experts, void *workspace,
+                                       size_t workspace_bytes, void *hip_stream)
+{
+    Ws ws;
+    swimba_status st = carve(dims, workspace, workspace_bytes, &ws);
+    if (st != SWIMBA_OK) return st;
+    if ((int64_t)dims->batch * dims->seqlen == 0) return SWIMBA_OK;
+    if (!x || !dt || !B_experts) return SWIMBA_ERR_NULL;
+    const Shape s = make_shape(dims);
+    if (use_mfma_path(dims))
+        return launch_chunk_state_mfma(s, x, dt, B_experts, ws.idx, ws.w, ws.cs, ws.states,
+                                       (hipStream_t)hip_stream);
+    return launch_chunk_state_generic(s, dims->io_dtype, x, dt, B_experts, ws.idx, ws.w, ws.cs,
+                                      ws.states, (hipStream_t)hip_stream);
+}
+
+swimba_status swimba_stage_state_scan(const swimba_dims *dims, const float *h0, float *h_final,
+                                      void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    Ws ws;
+    swimba_status st = carve(dims, workspace, workspace_bytes, &ws);
+    if (st != SWIMBA_OK) return st;
+    if (dims->batch == 0) return SWIMBA_OK;
+    return launch_state_scan(make_shape(dims), h0, h_final, ws.states, ws.states_lp, ws.cs,
+                             (hipStream_t)hip_stream);
+}
+
+swimba_status swimba_stage_output(const swimba_dims *dims, const void *x, const void *dt,
+                                  const float *D, const void *B_experts, const void *C_experts,
+                                  void *y, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    Ws ws;
+    swimba_status st = carve(dims, workspace, workspace_bytes, &ws);
+    if (st != SWIMBA_OK) return st;
+    if ((int64_t)dims->batch * dims->seqlen == 0) return SWIMBA_OK;
+    if (!x || !dt || !B_experts || !C_experts || !y) return SWIMBA_ERR_NULL;
+    const Shape s = make_shape(dims);
+    if (use_mfma_path(dims))
+        return launch_output_mfma(s, x, dt, D, B_experts, C_experts, ws.idx, ws.w, ws.cs,
+                                  ws.states_lp, y, (hipStream_t)hip_stream);
+    return launch_output_generic(s, dims->io_dtype, x, dt, D, B_experts, C_experts, ws.idx, ws.w,
+                                 ws.cs, ws.states, y, (hipStream_t)hip_stream);
+}
+
+swimba_status swimba_mixer_fwd(const swimba_dims *dims, const void *x, const void *dt,
+                               const float *A, const float *D, const void *B_experts,
+                               const void *C_experts, const void *router_logits, const float *h0,
+                               void *y, float *h_final, int32_t *topk_idx, float *topk_w,
+                               void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    Ws ws;
+    swimba_status st = carve(dims, workspace, workspace_bytes, &ws);
+    if (st != SWIMBA_OK) return st;
+    const int64_t T = (int64_t)dims->batch * dims->seqlen;
+    if (T > 0 && (!x || !dt || !A || !B_experts || !C_experts || !router_logits || !y))
+        return SWIMBA_ERR_NULL;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    const Shape s = make_shape(dims);
+    if (T > 0) {
+        st = swimba_stage_router(dims, router_logits, workspace, workspace_bytes, hip_stream);
+        if (st != SWIMBA_OK) return st;
+        if (topk_idx || topk_w) {
+            const size_t n = (size_t)T * dims->top_k;
+            hipError_t e = hipSuccess;
+            if (topk_idx)
+                e = hipMemcpyAsync(topk_idx, ws.idx, n * sizeof(int32_t), hipMemcpyDeviceToDevice, stream);
+            if (e == hipSuccess && topk_w)
+                e = hipMemcpyAsync(topk_w, ws.w, n * sizeof(float), hipMemcpyDeviceToDevice, stream);
+            if (e != hipSuccess) { set_last_hip_error((int)e); return SWIMBA_ERR_HIP; }
+        }
+        st = swimba_stage_cumsum(dims, dt, A, workspace, workspace_bytes, hip_stream);
+        if (st != SWIMBA_OK) return st;
+        st = swimba_stage_chunk_state(dims, x, dt, B_experts, workspace, workspace_bytes, hip_stream);
+        if (st != SWIMBA_OK) return st;
+    }
+    // with L == 0 the scan only copies h0 (or zeros) to h_final
+    if (dims->batch > 0 && (T > 0 || h_final)) {
+        st = launch_state_scan(s, h0, h_final, ws.states, ws.states_lp, ws.cs, stream);
+        if (st != SWIMBA_OK) return st;
+    }
+    if (T > 0) {
+        st = swimba_stage_output(dims, x, dt, D, B_experts, C_experts, y, workspace, workspace_bytes,
+                                 hip_stream);
+        if (st != SWIMBA_OK) return st;
+    }
+    return SWIMBA_OK;
+}
+
+swimba_status swimba_step(const swimba_dims *dims, const float *state_in, float *state_out,
+                          const void *x, const void *dt, const float *A, const float *D,
+                          const void *B_experts, const void *C_experts, const void *router_logits,
+                          void *y, int32_t *topk_idx, void *hip_stream)
+{
+    swimba_status st = check_common(dims);
+    if (st != SWIMBA_OK) return st;
+    if (dims->seqlen != 1) return SWIMBA_ERR_SHAPE;
+    if (dims->batch == 0) return SWIMBA_OK;
+    if (!state_in || !state_out || !x || !dt || !A || !B_experts || !C_experts || !router_logits || !y)
+        return SWIMBA_ERR_NULL;
+    return launch_step(make_shape(dims), dims->io_dtype, state_in, state_out, x, dt, A, D, B_experts,
+                       C_experts, router_logits, y, topk_idx, (hipStream_t)hip_stream);
+}
+
+const char *swimba_status_string(swimba_status s)
+{
+    switch (s) {
+    case SWIMBA_OK: return "ok";
+    case SWIMBA_ERR_NULL: return "a required pointer is NULL";
+    case SWIMBA_ERR_SHAPE: return "invalid or inconsistent dimensions";
+    case SWIMBA_ERR_DTYPE: return "unknown io_dtype";
+    case SWIMBA_ERR_UNSUPPORTED: return "problem outside the kernels' limits";
+    case SWIMBA_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
+    case SWIMBA_ERR_HIP: return "HIP runtime error";
+    }
+    return "unknown status";
+}
+
+int swimba_last_hip_error(void) { return g_last_hip_error; }
+
+}  // extern "C"

@@ -1,0 +1,119 @@
+// Internal declarations shared by the HIP translation units of libswimba.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+#include "swimba.h"
+
+namespace swimba {
+
+// ---- storage types -------------------------------------------------------
+struct bf16 {
+    uint16_t bits;
+};
+
+__device__ __forceinline__ float to_float(float v) { return v; }
+__device__ __forceinline__ float to_float(bf16 v) { return __uint_as_float((uint32_t)v.bits << 16); }
+
+// fp32 -> bf16, round to nearest even (NaN stays NaN)
+__device__ __forceinline__ uint16_t bf16_bits_rne(float f)
+{
+    uint32_t u = __float_as_uint(f);
+    if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x0040u);
+    u += 0x7fffu + ((u >> 16) & 1u);
+    return (uint16_t)(u >> 16);
+}
+
+template <typename T> __device__ __forceinline__ T from_float(float v);
+template <> __device__ __forceinline__ float from_float<float>(float v) { return v; }
+template <> __device__ __forceinline__ bf16 from_float<bf16>(float v) { return bf16{bf16_bits_rne(v)}; }
+
+// ---- problem description passed to kernels ------------------------------------
+struct Shape {
+    int B, L, H, P, N, G, E, K, Q, nc;
+};
+
+inline Shape make_shape(const swimba_dims *d)
+{
+    Shape s;
+    s.B = d->batch; s.L = d->seqlen; s.H = d->nheads; s.P = d->headdim; s.N = d->dstate;
+    s.G = d->ngroups; s.E = d->nexperts; s.K = d->top_k; s.Q = d->chunk;
+    s.nc = (d->chunk > 0) ? (d->seqlen + d->chunk - 1) / d->chunk : 0;
+    return s;
+}
+
+// true when the bf16 MFMA kernels cover this problem
+inline bool use_mfma_path(const swimba_dims *d)
+{
+    return false && d->io_dtype == SWIMBA_BF16 && d->headdim == 64 && d->dstate == 128 &&
+           (d->chunk == 64 || d->chunk == 128 || d->chunk == 256);
+}
+
+void set_last_hip_error(int e);
+
+#define SWIMBA_CHECK_LAUNCH()                                  \
+    do {                                                       \
+        hipError_t e__ = hipGetLastError();                    \
+        if (e__ != hipSuccess) {                               \
+            ::swimba::set_last_hip_error((int)e__);            \
+            return SWIMBA_ERR_HIP;                             \
+        }                                                      \
+    } while (0)
+
+// ---- kernel launchers (one per translation unit) ----------------------------------
+swimba_status launch_router(int64_t tokens, int E, int K, int io_dtype, const void *logits,
+                            int32_t *idx, float *w, hipStream_t st);
+swimba_status launch_cumsum(const Shape &s, int io_dtype, const void *dt, const float *A, float *cs,
+                            hipStream_t st);
+swimba_status launch_state_scan(const Shape &s, const float *h0, float *h_final, float *states,
+                                void *states_lp, const float *cs, hipStream_t st);
+swimba_status launch_chunk_state_generic(const Shape &s, int io_dtype, const void *x, const void *dt,
+                                         const void *Be, const int32_t *idx, const float *w,
+                                         const float *cs, float *states, hipStream_t st);
+swimba_status launch_output_generic(const Shape &s, int io_dtype, const void *x, const void *dt,
+                                    const float *D, const void *Be, const void *Ce,
+                                    const int32_t *idx, const float *w, const float *cs,
+                                    const float *states, void *y, hipStream_t st);
+swimba_status launch_chunk_state_mfma(const Shape &s, const void *x, const void *dt, const void *Be,
+                                      const int32_t *idx, const float *w, const float *cs,
+                                      float *states, hipStream_t st);
+swimba_status launch_output_mfma(const Shape &s, const void *x, const void *dt, const float *D,
+                                 const void *Be, const void *Ce, const int32_t *idx, const float *w,
+                                 const float *cs, const void *states_lp, void *y, hipStream_t st);
+swimba_status launch_step(const Shape &s, int io_dtype, const float *state_in, float *state_out,
+                          const void *x, const void *dt, const float *A, const float *D,
+                          const void *Be, const void *Ce, const void *logits, void *y, int32_t *idx,
+                          hipStream_t st);
+
+// ---- device helper shared by the router kernel and the decode kernel -----------------
+// Top-k over E logits read through `load(e)`, in (logit descending, index
+// ascending) order; softmax over all E, no renormalisation.
+template <typename Load>
+__device__ __forceinline__ void route_token(Load load, int E, int K, int32_t *idx, float *w)
+{
+    float m = -INFINITY;
+    for (int e = 0; e < E; ++e) m = fmaxf(m, load(e));
+    float Z = 0.f;
+    for (int e = 0; e < E; ++e) Z += expf(load(e) - m);
+    const float invZ = 1.0f / Z;
+    float pv = 0.f;
+    int pi = -1;
+    for (int r = 0; r < K; ++r) {
+        int best = -1;
+        float bv = 0.f;
+        for (int e = 0; e < E; ++e) {
+            const float v = load(e);
+            // candidates are the experts that come after the previous pick in the order
+            const bool after = (r == 0) || (v < pv) || (v == pv && e > pi);
+            if (after && (best < 0 || v > bv)) { best = e; bv = v; }
+        }
+        idx[r] = best;
+        w[r] = expf(bv - m) * invZ;
+        pv = bv;
+        pi = best;
+    }
+}
+
+}  // namespace swimba

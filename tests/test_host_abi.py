@@ -1,0 +1,98 @@
+"""CPU-side checks of the C ABI: the library loads, exports every declared
+entry point, and rejects bad arguments on the host before touching a GPU."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2603_06938_amd import binding as sw
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "swimba.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(swimba_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    lib = sw._load()
+    names = declared_symbols()
+    assert {"swimba_mixer_fwd", "swimba_step", "swimba_router_topk"} <= set(names)
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def dims(**kw):
+    base = dict(batch=1, seqlen=256, nheads=4, headdim=16, dstate=16, ngroups=1, nexperts=4, top_k=2,
+                chunk=64, io_dtype=0)
+    base.update(kw)
+    return sw.make_dims(**base)
+
+
+def test_workspace_query_and_layout():
+    d = dims()
+    n = sw.swimba_mixer_workspace_bytes(d)
+    lo = sw.swimba_mixer_workspace_layout(d)
+    assert n == lo.total and n > 0
+    offs = [lo.topk_idx, lo.topk_w, lo.cs, lo.states, lo.states_lp]
+    assert offs == sorted(offs) and all(o % 256 == 0 for o in offs)
+    assert lo.topk_w - lo.topk_idx >= 256 * 2 * 4
+    assert lo.states - lo.cs >= 4 * 4 * 64 * 4
+    assert lo.states_lp - lo.states >= 4 * 4 * 16 * 16 * 4
+    # ragged L: one more chunk
+    assert sw.swimba_mixer_workspace_bytes(dims(seqlen=257)) > n
+    # the bf16 MFMA shape carries a low-precision copy of the states
+    m = dims(headdim=64, dstate=128, chunk=256, io_dtype=1, seqlen=512)
+    lm = sw.swimba_mixer_workspace_layout(m)
+    assert lm.total >= lm.states_lp
+
+
+@pytest.mark.parametrize("kw,status", [
+    (dict(io_dtype=7), 3),
+    (dict(nheads=0), 2), (dict(top_k=0), 2), (dict(top_k=5), 2), (dict(ngroups=3), 2),
+    (dict(chunk=0), 2), (dict(batch=-1), 2),
+    (dict(chunk=512), 4), (dict(nexperts=300, top_k=2), 4), (dict(nexperts=32, top_k=17), 4),
+    (dict(headdim=128, dstate=128), 4), (dict(dstate=512), 4),
+])
+def test_invalid_dims_are_rejected_on_the_host(kw, status):
+    d = dims(**kw)
+    assert sw.swimba_mixer_workspace_bytes(d) == 0
+    lo = sw.swimba_ws_layout()
+    assert sw._load().swimba_mixer_workspace_layout(ctypes.byref(d), ctypes.byref(lo)) == status
+    # mixer_fwd reports the same status before looking at any pointer
+    st = sw._load().swimba_mixer_fwd(ctypes.byref(d), *([None] * 12), None, 0, None)
+    assert st == status
+
+
+def test_null_and_workspace_errors_enqueue_nothing():
+    lib = sw._load()
+    d = dims()
+    assert lib.swimba_mixer_fwd(None, *([None] * 12), None, 0, None) == 1
+    # valid dims, no workspace
+    assert lib.swimba_mixer_fwd(ctypes.byref(d), *([None] * 12), None, 0, None) == 5
+    # misaligned / too small workspace (host-side pointer value only; never dereferenced)
+    assert lib.swimba_mixer_fwd(ctypes.byref(d), *([None] * 12), 4096 + 8, 1 << 30, None) == 5
+    assert lib.swimba_mixer_fwd(ctypes.byref(d), *([None] * 12), 4096, 16, None) == 5
+    # aligned and large enough workspace, but tensor pointers missing
+    assert lib.swimba_mixer_fwd(ctypes.byref(d), *([None] * 12), 4096, 1 << 30, None) == 1
+    # step: seqlen must be 1; then NULL pointers
+    assert lib.swimba_step(ctypes.byref(d), *([None] * 11), None) == 2
+    assert lib.swimba_step(ctypes.byref(dims(seqlen=1)), *([None] * 11), None) == 1
+    assert lib.swimba_router_topk(10, 4, 5, 0, None, None, None, None) == 2
+    assert lib.swimba_router_topk(10, 4, 2, 0, None, None, None, None) == 1
+    assert lib.swimba_router_topk(0, 4, 2, 0, None, None, None, None) == 0
+    assert lib.swimba_probe_copy(None, None, 16, None) == 1
+    assert lib.swimba_status_string(4).decode().startswith("problem outside")
+    assert lib.swimba_last_hip_error() == 0
+
+
+def test_binding_refuses_cpu_tensors():
+    import torch
+    x = torch.zeros(1, 4, 2, 16)
+    Be = torch.zeros(1, 4, 3, 1, 16)
+    with pytest.raises((ValueError, sw.SwimbaError)):
+        sw.swimba_mixer_fwd(x, torch.ones(1, 4, 2), -torch.ones(2), None, Be, Be, torch.zeros(1, 4, 3),
+                            2, 4, workspace=torch.zeros(1 << 16, dtype=torch.uint8))
