@@ -47,7 +47,7 @@ inline Shape make_shape(const swimba_dims *d)
 // true when the bf16 MFMA kernels cover this problem
 inline bool use_mfma_path(const swimba_dims *d)
 {
-    return false && d->io_dtype == SWIMBA_BF16 && d->headdim == 64 && d->dstate == 128 &&
+    return d->io_dtype == SWIMBA_BF16 && d->headdim == 64 && d->dstate == 128 &&
            (d->chunk == 64 || d->chunk == 128 || d->chunk == 256);
 }
 

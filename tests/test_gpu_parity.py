@@ -110,6 +110,13 @@ SMALL = [
     (2, 300, 4, 64, 128, 2, 8, 2, 128, "f32"),  # fp32 at the MFMA shape
     (2, 96, 4, 16, 16, 2, 4, 2, 32, "bf16"),
     (1, 200, 4, 32, 64, 1, 8, 2, 64, "bf16"),
+    # bf16 MFMA shape (P=64, N=128), every supported chunk length, ragged tails, groups, k=1, k=E
+    (2, 300, 4, 64, 128, 2, 8, 2, 128, "bf16"),
+    (1, 700, 6, 64, 128, 1, 8, 2, 256, "bf16"),
+    (2, 256, 3, 64, 128, 3, 4, 4, 64, "bf16"),
+    (1, 520, 8, 64, 128, 2, 16, 1, 256, "bf16"),
+    (1, 31, 2, 64, 128, 1, 4, 2, 256, "bf16"),
+    (2, 257, 2, 64, 128, 1, 8, 3, 64, "bf16"),
 ]
 
 
