@@ -1,0 +1,252 @@
+#!/usr/bin/env python3
+"""Benchmark of the Swimba token-mixer hot path on one MI355X.
+
+A step = one swimba_mixer_fwd call (router, cumsum, chunk state, state scan,
+output) over one batch of the Mamba-2-130M-shaped workload, inputs resident in
+HBM.  Prints ONE JSON line: whole-path tokens/s, the roofline of the dominant
+kernel (timed alone with HIP events on the launch stream), per-kernel figures,
+the decode step time, and the CPU oracle timed on the host cores.
+
+  python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload 1|2|3] [--no-cpu]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+# MI355X published peaks
+PEAK_HBM_GBS = 8000.0
+PEAK_BF16_TFLOPS = 2500.0
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=50)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", type=int, default=1, choices=(1, 2, 3))
+    ap.add_argument("--decode-steps", type=int, default=256)
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
+    ap.add_argument("--no-decode", action="store_true")
+    ap.add_argument("--stage", default=None,
+                    help="run only this stage in the timed loop (for profilers): "
+                         "router|cumsum|chunk_state|state_scan|output|step|copy")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+              "run with --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    from paper_2603_06938_amd import binding as sw
+    from paper_2603_06938_amd import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    w = synth.workload(args.workload)
+    io = torch.bfloat16
+    K, W = args.steps, args.warmup
+
+    # ---- inputs: several identical-shape sets, rotated, so that a step does not find its
+    # ---- inputs in the 256 MB last-level cache left by the previous step
+    p = synth.make_inputs(w)
+
+    def to_dev(a, is_io):
+        t = torch.from_numpy(np.ascontiguousarray(a))
+        return (t.to(io) if is_io else t).to(dev)
+
+    base = {k: to_dev(v, k in ("x", "dt", "B_experts", "C_experts", "router_logits")) for k, v in p.items()}
+    dims = sw.dims_of(base["x"], base["B_experts"], w.top_k, w.chunk)
+    ws_bytes = sw.swimba_mixer_workspace_bytes(dims)
+    set_bytes = sum(t.numel() * t.element_size() for t in base.values()) * 1 + ws_bytes \
+        + base["x"].numel() * 2
+    nsets = max(2, min(6, int(768e6 // set_bytes) + 1))
+    sets = []
+    for i in range(nsets):
+        d = base if i == 0 else {k: v.clone() for k, v in base.items()}
+        d["ws"] = torch.empty(ws_bytes, dtype=torch.uint8, device=dev)
+        d["y"] = torch.empty_like(d["x"])
+        d["h_final"] = torch.empty((w.batch, w.nheads, w.headdim, w.dstate), dtype=torch.float32, device=dev)
+        sets.append(d)
+
+    def step(i):
+        d = sets[i % nsets]
+        sw.swimba_mixer_fwd(d["x"], d["dt"], d["A"], d["D"], d["B_experts"], d["C_experts"],
+                            d["router_logits"], w.top_k, w.chunk, None, y=d["y"], h_final=d["h_final"],
+                            workspace=d["ws"])
+
+    stages = {
+        "router": lambda d: sw.swimba_stage_router(dims, d["router_logits"], d["ws"]),
+        "cumsum": lambda d: sw.swimba_stage_cumsum(dims, d["dt"], d["A"], d["ws"]),
+        "chunk_state": lambda d: sw.swimba_stage_chunk_state(dims, d["x"], d["dt"], d["B_experts"], d["ws"]),
+        "state_scan": lambda d: sw.swimba_stage_state_scan(dims, None, d["h_final"], d["ws"]),
+        "output": lambda d: sw.swimba_stage_output(dims, d["x"], d["dt"], d["D"], d["B_experts"],
+                                                   d["C_experts"], d["y"], d["ws"]),
+    }
+
+    def time_loop(fn, n):
+        """average ms per call of fn(i), measured with HIP events on the launch stream"""
+        e0 = torch.cuda.Event(enable_timing=True)
+        e1 = torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for i in range(n):
+            fn(i)
+        e1.record()
+        e1.synchronize()
+        return e0.elapsed_time(e1) / n
+
+    # ---- profiler mode: one stage only --------------------------------------------------
+    if args.stage:
+        for i in range(nsets):
+            step(i)   # every workspace holds valid router/cumsum/state data
+        torch.cuda.synchronize()
+        if args.stage == "copy":
+            src = torch.empty(256 << 20, dtype=torch.uint8, device=dev)
+            dst = torch.empty_like(src)
+            ms = time_loop(lambda i: sw.swimba_probe_copy(dst, src), K)
+            print(json.dumps({"stage": "copy", "bytes_per_launch": src.numel(), "ms": ms,
+                              "GBps_read_plus_write": 2 * src.numel() / ms / 1e6}))
+        elif args.stage == "step":
+            pass  # handled by the decode section below
+        else:
+            ms = time_loop(lambda i: stages[args.stage](sets[i % nsets]), K)
+            print(json.dumps({"stage": args.stage, "ms": ms}))
+            return 0
+        if args.stage == "copy":
+            return 0
+
+    # ---- whole path ------------------------------------------------------------------------
+    if not args.stage:
+        for i in range(W):
+            step(i)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for i in range(K):
+            step(W + i)
+        torch.cuda.synchronize()
+        elapsed = time.perf_counter() - t0
+        ms_per_step = elapsed * 1e3 / K
+        tokens_per_s = w.tokens * K / elapsed
+        ev_ms = time_loop(lambda i: step(i), K)
+
+    # ---- per-kernel timing, each stage alone (workspaces already hold valid data) ----------
+    T, H, P, N, G, E, k, Q = w.tokens, w.nheads, w.headdim, w.dstate, w.ngroups, w.nexperts, w.top_k, w.chunk
+    nchunks = w.batch * ((w.seqlen + Q - 1) // Q)
+    state_elems = nchunks * H * P * N
+    # algorithmic work per launch (dense counts)
+    work = {
+        "router": ("hbm", T * (E * 2 + k * 8)),
+        "cumsum": ("hbm", T * H * (2 + 4)),
+        # reads x, dt, top-k B rows; writes fp32 chunk states
+        "chunk_state": ("hbm", T * (H * P * 2 + H * 2 + k * G * N * 2) + state_elems * 4),
+        # reads fp32 chunk states, writes them back (carried states) plus the bf16 copy
+        "state_scan": ("hbm", state_elems * (4 + 4 + 2)),
+        # C.B^T once per group, masked (C B^T) X per head, C.H per head
+        "output": ("mfma", 2.0 * T * Q * N * G + 2.0 * T * Q * P * H + 2.0 * T * N * P * H),
+    }
+    kernels = {}
+    if not args.stage:
+        for name, fn in stages.items():
+            time_loop(lambda i: fn(sets[i % nsets]), 3)
+            ms = time_loop(lambda i: fn(sets[i % nsets]), K)
+            bound, amount = work[name]
+            if bound == "hbm":
+                ach, peak, unit = amount / ms / 1e6, PEAK_HBM_GBS, "GB/s"
+            else:
+                ach, peak, unit = amount / ms / 1e9, PEAK_BF16_TFLOPS, "TFLOP/s"
+            kernels[name] = {"ms": round(ms, 5), "bound": bound, "achieved": round(ach, 2), "peak": peak,
+                             "unit": unit, "frac": round(ach / peak, 4)}
+
+    # ---- decode step (workload 4) ------------------------------------------------------------
+    decode = None
+    if not args.no_decode and (not args.stage or args.stage == "step"):
+        wd = synth.workload(4)
+        S = args.decode_steps
+        pd = synth.make_decode_inputs(wd, steps=8)
+        dd = {kk: to_dev(v, kk in ("x", "dt", "B_experts", "C_experts", "router_logits")) for kk, v in pd.items()}
+        xs = dd["x"].transpose(0, 1).contiguous()
+        dts = dd["dt"].transpose(0, 1).contiguous()
+        Bs = dd["B_experts"].transpose(0, 1).contiguous()
+        Cs = dd["C_experts"].transpose(0, 1).contiguous()
+        gs = dd["router_logits"].transpose(0, 1).contiguous()
+        # four independent state buffers, round-robin: 4 x 134 MB > last-level cache
+        states = [dd["state"].clone() for _ in range(4)]
+        yd = torch.empty_like(xs[0])
+
+        def dstep(i):
+            t = i % 8
+            sw.swimba_step(states[i % 4], xs[t], dts[t], dd["A"], dd["D"], Bs[t], Cs[t], gs[t], wd.top_k, y=yd)
+
+        time_loop(dstep, 8)
+        ms = time_loop(dstep, S)
+        dbytes = 2 * wd.batch * wd.nheads * wd.headdim * wd.dstate * 4 \
+            + wd.batch * (2 * wd.nheads * wd.headdim * 2 + wd.nheads * 2 + wd.nexperts * 2
+                          + 2 * wd.top_k * wd.ngroups * wd.dstate * 2)
+        decode = {"workload": "decode_step: B64 H64 P64 N128 G1 E8 top2, fp32 state, bf16 io",
+                  "us_per_step": round(ms * 1e3, 2), "steps": S, "tokens_per_s": round(wd.batch / ms * 1e3, 1),
+                  "bound": "hbm", "achieved": round(dbytes / ms / 1e6, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                  "frac": round(dbytes / ms / 1e6 / PEAK_HBM_GBS, 4), "state_buffers_rotated": 4}
+        if args.stage == "step":
+            print(json.dumps(decode))
+            return 0
+
+    # ---- CPU oracle on the host cores (reported baseline only) -------------------------------
+    cpu = None
+    if not args.no_cpu:
+        from oracle import swimba_oracle as orc
+        runs, t_cpu = 0, 0.0
+        while runs < 5 and t_cpu < 10.0:
+            t0 = time.perf_counter()
+            orc.mixer_fwd(p["x"], p["dt"], p["A"], p["D"], p["B_experts"], p["C_experts"],
+                          p["router_logits"], w.top_k)
+            t_cpu += time.perf_counter() - t0
+            runs += 1
+        cpu = {"value": round(w.tokens * runs / t_cpu, 1), "unit": "tokens/s", "cores": orc.num_threads(),
+               "kind": "oracle",
+               "sample": "the whole %s batch (%d tokens), %d passes, fp64 sequential recurrence, "
+                         "OpenMP over (batch, head)" % (w.name, w.tokens, runs)}
+
+    dom = max(kernels, key=lambda n: kernels[n]["ms"])
+    roof = dict(kernels[dom])
+    roof.pop("ms")
+    roof["kernel"] = dom
+    roof["traffic"] = None
+    out = {
+        "metric": "Swimba mixer fwd tokens/s + % peak MFMA/HBM at 1 MI355X; decode step us",
+        "value": round(tokens_per_s, 1),
+        "unit": "tokens/s",
+        "n_gpus": 1,
+        "steps": K,
+        "warmup": W,
+        "ms_per_step": round(ms_per_step, 5),
+        "ms_per_step_hip_events": round(ev_ms, 5),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "bf16",
+        "data": "synthetic",
+        "config": {"workload": "%s: B%d L%d H%d P%d N%d G%d E%d top%d chunk%d, bf16 io / fp32 accumulate"
+                               % (w.name, w.batch, w.seqlen, H, P, N, G, E, k, Q),
+                   "input_sets_rotated": nsets},
+        "roofline": roof,
+        "kernels": kernels,
+        "decode": decode,
+        "cpu_baseline": cpu,
+    }
+    print(json.dumps(out))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())
