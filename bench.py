@@ -37,7 +37,7 @@ def main() -> int:
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--stage", default=None,
                     help="run only this stage in the timed loop (for profilers): "
-                         "router|cumsum|chunk_state|state_scan|output|step|copy")
+                         "router|cumsum|mix|chunk_state|state_scan|output|step|copy")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
@@ -89,6 +89,7 @@ def main() -> int:
     stages = {
         "router": lambda d: sw.swimba_stage_router(dims, d["router_logits"], d["ws"]),
         "cumsum": lambda d: sw.swimba_stage_cumsum(dims, d["dt"], d["A"], d["ws"]),
+        "mix": lambda d: sw.swimba_stage_mix(dims, d["B_experts"], d["C_experts"], d["ws"]),
         "chunk_state": lambda d: sw.swimba_stage_chunk_state(dims, d["x"], d["dt"], d["B_experts"], d["ws"]),
         "state_scan": lambda d: sw.swimba_stage_state_scan(dims, None, d["h_final"], d["ws"]),
         "output": lambda d: sw.swimba_stage_output(dims, d["x"], d["dt"], d["D"], d["B_experts"],
@@ -148,12 +149,14 @@ def main() -> int:
     work = {
         "router": ("hbm", T * (E * 2 + k * 8)),
         "cumsum": ("hbm", T * H * (2 + 4)),
-        # reads x, dt, top-k B rows; writes fp32 chunk states
-        "chunk_state": ("hbm", T * (H * P * 2 + H * 2 + k * G * N * 2) + state_elems * 4),
+        # reads the k active B and C rows; writes mixed C, mixed B (bf16) and the causal C.B^T tiles
+        "mix": ("hbm", T * (2 * k * G * N * 2 + 2 * G * N * 2) + nchunks * G * (Q // 32) * (Q // 32 + 1) // 2 * 2048),
+        # reads x, dt, mixed B; writes fp32 chunk states
+        "chunk_state": ("hbm", T * (H * P * 2 + H * 2 + G * N * 2) + state_elems * 4),
         # reads fp32 chunk states, writes them back (carried states) plus the bf16 copy
         "state_scan": ("hbm", state_elems * (4 + 4 + 2)),
-        # C.B^T once per group, masked (C B^T) X per head, C.H per head
-        "output": ("mfma", 2.0 * T * Q * N * G + 2.0 * T * Q * P * H + 2.0 * T * N * P * H),
+        # masked (C B^T) X per head and C.H per head, dense counts (C.B^T itself is in "mix")
+        "output": ("mfma", 2.0 * T * Q * P * H + 2.0 * T * N * P * H),
     }
     kernels = {}
     if not args.stage:

@@ -74,8 +74,12 @@ typedef struct {
     size_t cs;        /* (B,nc,H,Q) fp32 : inclusive cumsum of dt*A inside each chunk */
     size_t states;    /* (B,nc,H,P,N) fp32 : chunk states S_c, then (after the scan)
                          the state carried INTO chunk c                             */
-    size_t states_lp; /* (B,nc,H,P,N) bf16 copy of the carried states (bf16 MFMA path
-                         only; equals `total` when unused)                          */
+    /* bf16 MFMA path only (each equals the next offset when unused): */
+    size_t states_lp; /* (B,nc,H,P,N) bf16 copy of the carried states                 */
+    size_t cmix;      /* (B,nc*Q,G,N) bf16 : mixed C rows                             */
+    size_t bmix_t8;   /* (B,nc,G,Q/8,N,8) bf16 : mixed B, 8 consecutive tokens innermost */
+    size_t cb;        /* (B,nc,G,NP,2,64,8) bf16 : causal 32x32 tiles of Bmix.Cmix^T in
+                         MFMA accumulator layout, NP = (Q/32)(Q/32+1)/2               */
     size_t total;
 } swimba_ws_layout;
 
@@ -157,6 +161,9 @@ swimba_status swimba_stage_router(const swimba_dims *dims, const void *router_lo
                                   void *workspace, size_t workspace_bytes, void *hip_stream);
 swimba_status swimba_stage_cumsum(const swimba_dims *dims, const void *dt, const float *A,
                                   void *workspace, size_t workspace_bytes, void *hip_stream);
+swimba_status swimba_stage_mix(const swimba_dims *dims, const void *B_experts,
+                               const void *C_experts, void *workspace, size_t workspace_bytes,
+                               void *hip_stream);
 swimba_status swimba_stage_chunk_state(const swimba_dims *dims, const void *x, const void *dt,
                                        const void *B_experts, void *workspace,
                                        size_t workspace_bytes, void *hip_stream);

@@ -39,7 +39,7 @@ class swimba_dims(ctypes.Structure):
 
 class swimba_ws_layout(ctypes.Structure):
     _fields_ = [(n, ctypes.c_size_t) for n in
-                ("topk_idx", "topk_w", "cs", "states", "states_lp", "total")]
+                ("topk_idx", "topk_w", "cs", "states", "states_lp", "cmix", "bmix_t8", "cb", "total")]
 
 
 def _load():
@@ -64,6 +64,8 @@ def _load():
         lib.swimba_stage_router.argtypes = [dp, vp, vp, sz, vp]
         lib.swimba_stage_cumsum.restype = i32
         lib.swimba_stage_cumsum.argtypes = [dp, vp, vp, vp, sz, vp]
+        lib.swimba_stage_mix.restype = i32
+        lib.swimba_stage_mix.argtypes = [dp, vp, vp, vp, sz, vp]
         lib.swimba_stage_chunk_state.restype = i32
         lib.swimba_stage_chunk_state.argtypes = [dp, vp, vp, vp, vp, sz, vp]
         lib.swimba_stage_state_scan.restype = i32
@@ -222,6 +224,13 @@ def swimba_stage_cumsum(dims, dt, A, workspace):
                                        _stream()), "swimba_stage_cumsum")
 
 
+def swimba_stage_mix(dims, B_experts, C_experts, workspace):
+    _check(_load().swimba_stage_mix(ctypes.byref(dims), _ptr(B_experts, "B_experts"),
+                                    _ptr(C_experts, "C_experts"),
+                                    _ptr(workspace, "workspace", torch.uint8), workspace.numel(),
+                                    _stream()), "swimba_stage_mix")
+
+
 def swimba_stage_chunk_state(dims, x, dt, B_experts, workspace):
     _check(_load().swimba_stage_chunk_state(ctypes.byref(dims), _ptr(x, "x"), _ptr(dt, "dt"),
                                             _ptr(B_experts, "B_experts"),
@@ -261,7 +270,7 @@ def workspace_views(dims: swimba_dims, workspace: torch.Tensor):
         "cs": view(lo.cs, B * nc * H * Q, torch.float32, (B, nc, H, Q)),
         "states": view(lo.states, B * nc * H * P * N, torch.float32, (B, nc, H, P, N)),
     }
-    if lo.states_lp != lo.total:
+    if lo.states_lp != lo.cmix:
         out["states_lp"] = view(lo.states_lp, B * nc * H * P * N, torch.bfloat16, (B, nc, H, P, N))
     return out
 

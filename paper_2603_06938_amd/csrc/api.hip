@@ -50,8 +50,17 @@ static void layout_of(const swimba_dims *d, swimba_ws_layout *o)
     o->cs = off;       off = align_up(off + (size_t)s.B * s.nc * s.H * s.Q * sizeof(float), 256);
     const size_t nstate = (size_t)s.B * s.nc * s.H * s.P * s.N;
     o->states = off;   off = align_up(off + nstate * sizeof(float), 256);
+    const bool mf = use_mfma_path(d);
+    const size_t mixed = (size_t)s.B * s.nc * s.Q * s.G * s.N * sizeof(uint16_t);
+    const size_t nt = (size_t)s.Q / 32;
     o->states_lp = off;
-    if (use_mfma_path(d)) off = align_up(off + nstate * sizeof(uint16_t), 256);
+    if (mf) off = align_up(off + nstate * sizeof(uint16_t), 256);
+    o->cmix = off;
+    if (mf) off = align_up(off + mixed, 256);
+    o->bmix_t8 = off;
+    if (mf) off = align_up(off + mixed, 256);
+    o->cb = off;
+    if (mf) off = align_up(off + (size_t)s.B * s.nc * s.G * (nt * (nt + 1) / 2) * 2048, 256);
     o->total = off > 0 ? off : 256;
 }
 
@@ -60,7 +69,7 @@ struct Ws {
     float *w;
     float *cs;
     float *states;
-    void *states_lp;
+    void *states_lp, *cmix, *bmix_t8, *cb;
 };
 
 static swimba_status carve(const swimba_dims *d, void *workspace, size_t bytes, Ws *ws)
@@ -75,7 +84,11 @@ static swimba_status carve(const swimba_dims *d, void *workspace, size_t bytes, 
     ws->w = (float *)(p + lo.topk_w);
     ws->cs = (float *)(p + lo.cs);
     ws->states = (float *)(p + lo.states);
-    ws->states_lp = use_mfma_path(d) ? (void *)(p + lo.states_lp) : nullptr;
+    const bool mf = use_mfma_path(d);
+    ws->states_lp = mf ? (void *)(p + lo.states_lp) : nullptr;
+    ws->cmix = mf ? (void *)(p + lo.cmix) : nullptr;
+    ws->bmix_t8 = mf ? (void *)(p + lo.bmix_t8) : nullptr;
+    ws->cb = mf ? (void *)(p + lo.cb) : nullptr;
     return SWIMBA_OK;
 }
 
@@ -140,6 +153,20 @@ swimba_status swimba_stage_cumsum(const swimba_dims *dims, const void *dt, const
     return launch_cumsum(make_shape(dims), dims->io_dtype, dt, A, ws.cs, (hipStream_t)hip_stream);
 }
 
+swimba_status swimba_stage_mix(const swimba_dims *dims, const void *B_experts,
+                               const void *C_experts, void *workspace, size_t workspace_bytes,
+                               void *hip_stream)
+{
+    Ws ws;
+    swimba_status st = carve(dims, workspace, workspace_bytes, &ws);
+    if (st != SWIMBA_OK) return st;
+    if ((int64_t)dims->batch * dims->seqlen == 0) return SWIMBA_OK;
+    if (!B_experts || !C_experts) return SWIMBA_ERR_NULL;
+    if (!use_mfma_path(dims)) return SWIMBA_OK;   // the fp32 chunk kernels mix while staging
+    return launch_mix_cb_mfma(make_shape(dims), B_experts, C_experts, ws.idx, ws.w, ws.cmix,
+                              ws.bmix_t8, ws.cb, (hipStream_t)hip_stream);
+}
+
 swimba_status swimba_stage_chunk_state(const swimba_dims *dims, const void *x, const void *dt,
                                        const void *B_experts, void *workspace,
                                        size_t workspace_bytes, void *hip_stream)
@@ -151,8 +178,7 @@ swimba_status swimba_stage_chunk_state(const swimba_dims *dims, const void *x, c
     if (!x || !dt || !B_experts) return SWIMBA_ERR_NULL;
     const Shape s = make_shape(dims);
     if (use_mfma_path(dims))
-        return launch_chunk_state_mfma(s, x, dt, B_experts, ws.idx, ws.w, ws.cs, ws.states,
-                                       (hipStream_t)hip_stream);
+        return launch_chunk_state_mfma(s, x, dt, ws.bmix_t8, ws.cs, ws.states, (hipStream_t)hip_stream);
     return launch_chunk_state_generic(s, dims->io_dtype, x, dt, B_experts, ws.idx, ws.w, ws.cs,
                                       ws.states, (hipStream_t)hip_stream);
 }
@@ -179,8 +205,8 @@ swimba_status swimba_stage_output(const swimba_dims *dims, const void *x, const 
     if (!x || !dt || !B_experts || !C_experts || !y) return SWIMBA_ERR_NULL;
     const Shape s = make_shape(dims);
     if (use_mfma_path(dims))
-        return launch_output_mfma(s, x, dt, D, B_experts, C_experts, ws.idx, ws.w, ws.cs,
-                                  ws.states_lp, y, (hipStream_t)hip_stream);
+        return launch_output_mfma(s, x, dt, D, ws.cmix, ws.cb, ws.cs, ws.states_lp, y,
+                                  (hipStream_t)hip_stream);
     return launch_output_generic(s, dims->io_dtype, x, dt, D, B_experts, C_experts, ws.idx, ws.w,
                                  ws.cs, ws.states, y, (hipStream_t)hip_stream);
 }
@@ -212,6 +238,8 @@ swimba_status swimba_mixer_fwd(const swimba_dims *dims, const void *x, const voi
             if (e != hipSuccess) { set_last_hip_error((int)e); return SWIMBA_ERR_HIP; }
         }
         st = swimba_stage_cumsum(dims, dt, A, workspace, workspace_bytes, hip_stream);
+        if (st != SWIMBA_OK) return st;
+        st = swimba_stage_mix(dims, B_experts, C_experts, workspace, workspace_bytes, hip_stream);
         if (st != SWIMBA_OK) return st;
         st = swimba_stage_chunk_state(dims, x, dt, B_experts, workspace, workspace_bytes, hip_stream);
         if (st != SWIMBA_OK) return st;

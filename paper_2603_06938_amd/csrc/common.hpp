@@ -76,12 +76,14 @@ swimba_status launch_output_generic(const Shape &s, int io_dtype, const void *x,
                                     const float *D, const void *Be, const void *Ce,
                                     const int32_t *idx, const float *w, const float *cs,
                                     const float *states, void *y, hipStream_t st);
-swimba_status launch_chunk_state_mfma(const Shape &s, const void *x, const void *dt, const void *Be,
-                                      const int32_t *idx, const float *w, const float *cs,
-                                      float *states, hipStream_t st);
+swimba_status launch_mix_cb_mfma(const Shape &s, const void *Be, const void *Ce, const int32_t *idx,
+                                 const float *w, void *cmix, void *bmix_t8, void *cb, hipStream_t st);
+swimba_status launch_chunk_state_mfma(const Shape &s, const void *x, const void *dt,
+                                      const void *bmix_t8, const float *cs, float *states,
+                                      hipStream_t st);
 swimba_status launch_output_mfma(const Shape &s, const void *x, const void *dt, const float *D,
-                                 const void *Be, const void *Ce, const int32_t *idx, const float *w,
-                                 const float *cs, const void *states_lp, void *y, hipStream_t st);
+                                 const void *cmix, const void *cb, const float *cs,
+                                 const void *states_lp, void *y, hipStream_t st);
 swimba_status launch_step(const Shape &s, int io_dtype, const float *state_in, float *state_out,
                           const void *x, const void *dt, const float *A, const float *D,
                           const void *Be, const void *Ce, const void *logits, void *y, int32_t *idx,
