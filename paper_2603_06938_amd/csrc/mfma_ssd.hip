@@ -340,16 +340,24 @@ swimba_status launch_chunk_state_mfma(const Shape &s, const void *x, const void 
 // Workgroup = (batch, chunk, head).  The chunk is cut into 32-token tiles; wave w
 // owns output tiles {w, NT-1-w} (balanced under the causal mask).
 //
-// The G^T tile arrives from `cb` already in accumulator layout (rows j, cols i);
-// after the decay and bf16 rounding that layout IS the A operand of Y += M X, so
-// the Q x Q block never goes through LDS.
+// Everything is computed transposed, Y^T[p][i] (accumulator rows = channels, columns =
+// tokens), so that every per-token factor is a per-lane scalar:
+//   Y^T  = H_c . Cmix^T  scaled by exp(cs_i)                       (A = H_c rows, B = Cmix regs)
+//   Y^T += (dt x)^T . M^T,  M^T[j][i] = G^T[j][i] * decay(i,j)      (A = x^T from LDS, B = M^T)
+// The G^T tile arrives from `cb` in accumulator layout (rows j, cols i), which is also
+// a valid B-operand layout once the k index (j) is permuted; x^T is staged in LDS with
+// the same permutation (within 16 tokens: bits 2 and 3 swapped).
 // For J < I the decay factors as exp(cs_i - R_J) * exp(R_J - cs_j) with R_J = cs at the
 // last token of tile J; both factors are <= 1 (cs is non-increasing), so nothing
 // overflows and only one exp per lane and pair is needed; the second factor is
 // tabulated per token.  The diagonal tile uses exp(cs_i - cs_j) under the mask i >= j.
-// dt_j x_j is staged transposed ([p][j']) in LDS, j' = position of token j in the
-// operand order of the accumulator-as-A-operand trick (within 16 tokens: bits 2,3 swapped).
+// Accumulator row r = 8a + 4k + b holds channel 16k + 4a + b of its 32-channel half, so
+// a lane ends up with 16 consecutive channels of one token (two 16-byte stores).
+// cs is kept multiplied by log2(e): every exponential is one v_exp_f32.
 // =========================================================================================
+__device__ __forceinline__ float fast_exp2(float v) { return __builtin_amdgcn_exp2f(v); }
+constexpr float LOG2E = 1.4426950408889634f;
+
 template <int Q>
 __global__ void __launch_bounds__(MTHREADS, 2)
 output_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ dt,
@@ -363,13 +371,9 @@ output_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ 
     constexpr int SLOTS = (NT >= 8) ? 2 : 1;   // output tiles per wave
     constexpr int HSTR = MN + 8;               // row stride of the carried-state tile
     constexpr int XSTR = Q + 8;                // row stride of the transposed x tile
-    constexpr int ESTR = 36;                   // row stride (floats) of the epilogue scratch
-    constexpr int XBYTES = MP * XSTR * 2, HBYTES = MP * HSTR * 2;
-    static_assert(XBYTES + HBYTES >= 4 * 32 * ESTR * 4, "epilogue scratch must fit");
-    __shared__ __align__(16) unsigned char smem[XBYTES + HBYTES];
+    __shared__ __align__(16) uint16_t sX[MP * XSTR];
+    __shared__ __align__(16) uint16_t sH[MP * HSTR];
     __shared__ float s_cs[Q], s_dt[Q], s_f[Q];
-    uint16_t *sX = reinterpret_cast<uint16_t *>(smem);
-    uint16_t *sH = reinterpret_cast<uint16_t *>(smem + XBYTES);
 
     const int lid = xcd_logical_id(blockIdx.x, nblocks);
     if (lid >= total) return;
@@ -382,6 +386,11 @@ output_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ 
     const int64_t tok0 = (int64_t)b * s.L + (int64_t)c * Q;
     const int valid = min(Q, s.L - c * Q);
     const int64_t bcg = ((int64_t)b * s.nc + c) * s.G + g;
+    const int tokstride = s.H * MP;                          // elements between tokens of x / y
+    const uint16_t *xh = x + (tok0 * s.H + h) * MP;          // x[token 0 of the chunk][h][0]
+    uint16_t *yh = y + (tok0 * s.H + h) * MP;
+    // channel held by operand row l32 (see the header comment)
+    const int prow = 16 * ((l32 >> 2) & 1) + 4 * (l32 >> 3) + (l32 & 3);
 
     int tileI[SLOTS];
     tileI[0] = (wave < NT) ? wave : -1;
@@ -389,7 +398,7 @@ output_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ 
 
     // ---- per-token scalars ----
     if (tid < Q) {
-        s_cs[tid] = cs[(((int64_t)b * s.nc + c) * s.H + h) * Q + tid];
+        s_cs[tid] = cs[(((int64_t)b * s.nc + c) * s.H + h) * Q + tid] * LOG2E;
         s_dt[tid] = (tid < valid) ? to_float(bf16{dt[(tok0 + tid) * s.H + h]}) : 0.f;
     }
     // ---- carried state (bf16) -> LDS ----
@@ -412,7 +421,7 @@ output_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ 
         for (int ks = 0; ks < 8; ++ks) cfrag[sl][ks] = *reinterpret_cast<const uint4 *>(src + ks * 8);
     }
     __syncthreads();
-    if (tid < Q) s_f[tid] = expf(s_cs[(tid | 31)] - s_cs[tid]);
+    if (tid < Q) s_f[tid] = fast_exp2(s_cs[(tid | 31)] - s_cs[tid]);
     // ---- dt_j x_j, transposed and in operand order ----
 #pragma unroll
     for (int it = 0; it < (Q / 8) * 32 / MTHREADS; ++it) {
@@ -424,8 +433,7 @@ output_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ 
         for (int e = 0; e < 8; ++e) {
             const int j = 16 * t16 + 8 * (e >> 2) + 4 * kgx + (e & 3);
             v[e] = 0;
-            if (j < valid)
-                v[e] = *reinterpret_cast<const uint32_t *>(x + ((tok0 + j) * s.H + h) * MP + 2 * p2);
+            if (j < valid) v[e] = *reinterpret_cast<const uint32_t *>(xh + j * tokstride + 2 * p2);
         }
         float xa[8], xb[8];
 #pragma unroll
@@ -439,30 +447,29 @@ output_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ 
     }
     __syncthreads();
 
-    f32x16_t yacc[SLOTS][2];
+    const float dsk = D ? D[h] : 0.f;
+    const uint16_t *sXr0 = sX + prow * XSTR + 8 * kg;          // operand rows of the two channel halves
+    const uint16_t *sXr1 = sX + (32 + prow) * XSTR + 8 * kg;
 #pragma unroll
     for (int sl = 0; sl < SLOTS; ++sl) {
-        yacc[sl][0] = f32x16_t{0};
-        yacc[sl][1] = f32x16_t{0};
         const int I = tileI[sl];
         if (I < 0) continue;
-        // ---- exp(cs_i) Cmix_i . H_c ----
+        f32x16_t y0 = {0}, y1 = {0};
+        // ---- H_c . Cmix^T, then the per-token factor exp(cs_i) ----
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
-            const uint4 h0 = *reinterpret_cast<const uint4 *>(sH + l32 * HSTR + 64 * kg + ks * 8);
-            const uint4 h1 = *reinterpret_cast<const uint4 *>(sH + (32 + l32) * HSTR + 64 * kg + ks * 8);
-            yacc[sl][0] = mfma32(cfrag[sl][ks], h0, yacc[sl][0]);
-            yacc[sl][1] = mfma32(cfrag[sl][ks], h1, yacc[sl][1]);
+            const uint4 h0 = *reinterpret_cast<const uint4 *>(sH + prow * HSTR + 64 * kg + ks * 8);
+            const uint4 h1 = *reinterpret_cast<const uint4 *>(sH + (32 + prow) * HSTR + 64 * kg + ks * 8);
+            y0 = mfma32(h0, cfrag[sl][ks], y0);
+            y1 = mfma32(h1, cfrag[sl][ks], y1);
         }
+        const float csi = s_cs[I * 32 + l32];
+        {
+            const float sc = fast_exp2(csi);
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int il = 8 * (v >> 2) + 4 * kg + (v & 3);
-            const float sc = expf(s_cs[I * 32 + il]);
-            yacc[sl][0][v] *= sc;
-            yacc[sl][1][v] *= sc;
+            for (int v = 0; v < 16; ++v) { y0[v] *= sc; y1[v] *= sc; }
         }
         // ---- intra-chunk part ----
-        const float csi = s_cs[I * 32 + l32];
         const uint16_t *tile = cb + ((bcg * NP + I * (I + 1) / 2) * 2 * 64 + lane) * 8;
         uint4 u0 = *reinterpret_cast<const uint4 *>(tile);
         uint4 u1 = *reinterpret_cast<const uint4 *>(tile + 64 * 8);
@@ -471,70 +478,59 @@ output_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ 
             float m[16];
             unpack8(m, u0);
             unpack8(m + 8, u1);
+            const float *fj = s_f + J * 32 + 4 * kg;
+            const float *cj = s_cs + J * 32 + 4 * kg;
             if (J < I) {   // prefetch the next tile
                 tile += 2 * 64 * 8;
                 u0 = *reinterpret_cast<const uint4 *>(tile);
                 u1 = *reinterpret_cast<const uint4 *>(tile + 64 * 8);
-                const float ei = expf(csi - s_cs[J * 32 + 31]);
+                const float ei = fast_exp2(csi - s_cs[J * 32 + 31]);
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int jl = 8 * (v >> 2) + 4 * kg + (v & 3);
-                    m[v] *= ei * s_f[J * 32 + jl];
+                for (int a = 0; a < 4; ++a) {
+                    const float4 f4 = *reinterpret_cast<const float4 *>(fj + 8 * a);
+                    m[4 * a + 0] *= ei * f4.x;
+                    m[4 * a + 1] *= ei * f4.y;
+                    m[4 * a + 2] *= ei * f4.z;
+                    m[4 * a + 3] *= ei * f4.w;
                 }
             } else {
 #pragma unroll
-                for (int v = 0; v < 16; ++v) {
-                    const int jl = 8 * (v >> 2) + 4 * kg + (v & 3);
-                    const float dcy = expf(fminf(csi - s_cs[J * 32 + jl], 0.f));
-                    m[v] = (l32 >= jl) ? m[v] * dcy : 0.f;
+                for (int a = 0; a < 4; ++a) {
+                    const float4 c4 = *reinterpret_cast<const float4 *>(cj + 8 * a);
+                    const float cc[4] = {c4.x, c4.y, c4.z, c4.w};
+#pragma unroll
+                    for (int bb = 0; bb < 4; ++bb) {
+                        const int jl = 8 * a + 4 * kg + bb;
+                        const float dcy = fast_exp2(fminf(csi - cc[bb], 0.f));
+                        m[4 * a + bb] = (l32 >= jl) ? m[4 * a + bb] * dcy : 0.f;
+                    }
                 }
             }
 #pragma unroll
             for (int t = 0; t < 2; ++t) {
                 const uint4 mfrag = pack8(m + 8 * t);
-                const uint4 x0 = *reinterpret_cast<const uint4 *>(sX + l32 * XSTR + J * 32 + 16 * t + 8 * kg);
-                const uint4 x1 = *reinterpret_cast<const uint4 *>(sX + (32 + l32) * XSTR + J * 32 + 16 * t + 8 * kg);
-                yacc[sl][0] = mfma32(mfrag, x0, yacc[sl][0]);
-                yacc[sl][1] = mfma32(mfrag, x1, yacc[sl][1]);
+                const uint4 x0 = *reinterpret_cast<const uint4 *>(sXr0 + J * 32 + 16 * t);
+                const uint4 x1 = *reinterpret_cast<const uint4 *>(sXr1 + J * 32 + 16 * t);
+                y0 = mfma32(x0, mfrag, y0);
+                y1 = mfma32(x1, mfrag, y1);
             }
         }
-    }
-
-    // ---- y = acc + D x, through a per-wave LDS scratch so that global accesses are 16 bytes ----
-    __syncthreads();   // all waves are done with sX / sH
-    float *scr = reinterpret_cast<float *>(smem) + wave * 32 * ESTR;
-    const float dsk = D ? D[h] : 0.f;
+        // ---- y = acc + D x : lane (token l32, half kg) holds channels 16kg+0..15 (+32) ----
+        const int i = I * 32 + l32;
+        if (i < valid) {
+            const int off = i * tokstride + 16 * kg;
 #pragma unroll
-    for (int sl = 0; sl < SLOTS; ++sl) {
+            for (int pt = 0; pt < 2; ++pt) {
+                float a[16], xv[16];
 #pragma unroll
-        for (int pt = 0; pt < 2; ++pt) {
-            const int I = tileI[sl];
-            if (I >= 0) {
+                for (int v = 0; v < 16; ++v) a[v] = pt ? y1[v] : y0[v];
+                unpack8(xv, *reinterpret_cast<const uint4 *>(xh + off + 32 * pt));
+                unpack8(xv + 8, *reinterpret_cast<const uint4 *>(xh + off + 32 * pt + 8));
 #pragma unroll
-                for (int v = 0; v < 16; ++v)
-                    scr[(8 * (v >> 2) + 4 * kg + (v & 3)) * ESTR + l32] = yacc[sl][pt][v];
+                for (int e = 0; e < 16; ++e) a[e] += dsk * xv[e];
+                *reinterpret_cast<uint4 *>(yh + off + 32 * pt) = pack8(a);
+                *reinterpret_cast<uint4 *>(yh + off + 32 * pt + 8) = pack8(a + 8);
             }
-            __syncthreads();
-            if (I >= 0) {
-                const int row = lane >> 1, col0 = (lane & 1) * 16;
-                const int i = I * 32 + row;
-                if (i < valid) {
-                    const int64_t off = ((tok0 + i) * s.H + h) * MP + pt * 32 + col0;
-                    float a[16], xv[16];
-#pragma unroll
-                    for (int q4 = 0; q4 < 4; ++q4) {
-                        const float4 f = *reinterpret_cast<const float4 *>(scr + row * ESTR + col0 + 4 * q4);
-                        a[4 * q4] = f.x; a[4 * q4 + 1] = f.y; a[4 * q4 + 2] = f.z; a[4 * q4 + 3] = f.w;
-                    }
-                    unpack8(xv, *reinterpret_cast<const uint4 *>(x + off));
-                    unpack8(xv + 8, *reinterpret_cast<const uint4 *>(x + off + 8));
-#pragma unroll
-                    for (int e = 0; e < 16; ++e) a[e] += dsk * xv[e];
-                    *reinterpret_cast<uint4 *>(y + off) = pack8(a);
-                    *reinterpret_cast<uint4 *>(y + off + 8) = pack8(a + 8);
-                }
-            }
-            __syncthreads();
         }
     }
 }
