@@ -103,7 +103,8 @@ __device__ __forceinline__ void gather_mix_row(uint4 *frag, const uint16_t *tok,
 // =========================================================================================
 // mix_cb.  Workgroup = (batch, chunk, group, role r): output tiles I0 = r and
 // I1 = NT-1-r of the chunk (32 tokens each).  Wave w takes the j tiles J = w, w+4.
-//   cmix    (B, nc*Q, G, N)          bf16, row-major mixed C
+//   cmix    (B, nc, G, NT, 8, 64, 8) bf16, mixed C of tile I as MFMA operand registers:
+//           [ks][lane][e] = Cmix[32I + lane%32][64*(lane/32) + 8ks + e]
 //   bmix_t8 (B, nc, G, Q/8, N, 8)    bf16, mixed B with 8 consecutive tokens innermost
 //   cb      (B, nc, G, NP, 2, 64, 8) bf16, tile pair (I,J), J <= I, at index I(I+1)/2+J:
 //           the accumulator registers v = 8t..8t+7 of lane l of G^T[j][i] = Bmix_j.Cmix_i
@@ -167,9 +168,9 @@ mix_cb_kernel(const uint16_t *__restrict__ Be, const uint16_t *__restrict__ Ce,
         gather_mix_row(cfrag[sl], Ce + (bt * s.E * s.G + g) * MN, estride, idx + bt * s.K,
                        w + bt * s.K, s.K, kg, i < valid);
         if (wave == 0) {
-            uint16_t *dst = cmix + (((int64_t)b * s.nc * Q + (int64_t)c * Q + i) * s.G + g) * MN + 64 * kg;
+            uint16_t *dst = cmix + (((bcg * NT + tiles[sl]) * 8) * 64 + lane) * 8;
 #pragma unroll
-            for (int ks = 0; ks < 8; ++ks) *reinterpret_cast<uint4 *>(dst + ks * 8) = cfrag[sl][ks];
+            for (int ks = 0; ks < 8; ++ks) *reinterpret_cast<uint4 *>(dst + ks * 64 * 8) = cfrag[sl][ks];
         }
     }
 
@@ -337,8 +338,9 @@ swimba_status launch_chunk_state_mfma(const Shape &s, const void *x, const void 
 
 // =========================================================================================
 // Output:  y_i = sum_{j<=i} G[i][j] exp(cs_i-cs_j) dt_j x_j + exp(cs_i) Cmix_i.H_c + D x_i
-// Workgroup = (batch, chunk, head).  The chunk is cut into 32-token tiles; wave w
-// owns output tiles {w, NT-1-w} (balanced under the causal mask).
+// Workgroup = (batch, chunk, head), one wave per 32-token output tile (Q/32 waves).
+// Tile I has I+1 causal tile pairs; waves w and w+4, which share a SIMD, get tiles
+// whose pair counts add up to the same number on every SIMD.
 //
 // Everything is computed transposed, Y^T[p][i] (accumulator rows = channels, columns =
 // tokens), so that every per-token factor is a per-lane scalar:
@@ -352,14 +354,15 @@ swimba_status launch_chunk_state_mfma(const Shape &s, const void *x, const void 
 // overflows and only one exp per lane and pair is needed; the second factor is
 // tabulated per token.  The diagonal tile uses exp(cs_i - cs_j) under the mask i >= j.
 // Accumulator row r = 8a + 4k + b holds channel 16k + 4a + b of its 32-channel half, so
-// a lane ends up with 16 consecutive channels of one token (two 16-byte stores).
+// a lane ends up with 16 consecutive channels of one token; the tile is rounded to
+// bf16, passed through LDS and stored as full 128-byte rows (D x is added on the way).
 // cs is kept multiplied by log2(e): every exponential is one v_exp_f32.
 // =========================================================================================
 __device__ __forceinline__ float fast_exp2(float v) { return __builtin_amdgcn_exp2f(v); }
 constexpr float LOG2E = 1.4426950408889634f;
 
 template <int Q>
-__global__ void __launch_bounds__(MTHREADS, 2)
+__global__ void __launch_bounds__(64 * (Q / 32))
 output_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ dt,
                    const float *__restrict__ D, const uint16_t *__restrict__ cmix,
                    const uint16_t *__restrict__ cb, const float *__restrict__ cs,
@@ -368,7 +371,7 @@ output_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ 
 {
     constexpr int NT = Q / 32;                 // 32-token tiles in the chunk
     constexpr int NP = NT * (NT + 1) / 2;
-    constexpr int SLOTS = (NT >= 8) ? 2 : 1;   // output tiles per wave
+    constexpr int NTHR = 64 * NT;              // one wave per output tile
     constexpr int HSTR = MN + 8;               // row stride of the carried-state tile
     constexpr int XSTR = Q + 8;                // row stride of the transposed x tile
     __shared__ __align__(16) uint16_t sX[MP * XSTR];
@@ -381,7 +384,8 @@ output_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ 
     const int c = (lid / s.H) % s.nc;
     const int b = lid / (s.H * s.nc);
     const int g = (h * s.G) / s.H;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);   // wave-uniform
     const int l32 = lane & 31, kg = lane >> 5;
     const int64_t tok0 = (int64_t)b * s.L + (int64_t)c * Q;
     const int valid = min(Q, s.L - c * Q);
@@ -392,55 +396,70 @@ output_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ 
     // channel held by operand row l32 (see the header comment)
     const int prow = 16 * ((l32 >> 2) & 1) + 4 * (l32 >> 3) + (l32 & 3);
 
-    int tileI[SLOTS];
-    tileI[0] = (wave < NT) ? wave : -1;
-    if constexpr (SLOTS == 2) tileI[1] = NT - 1 - wave;
+    // Waves w and w + 4 share a SIMD: give them tiles whose causal work adds up to the
+    // same amount on every SIMD.
+    const int I = (NT == 8 && wave >= 4) ? 11 - wave : wave;
 
-    // ---- per-token scalars ----
-    if (tid < Q) {
-        s_cs[tid] = cs[(((int64_t)b * s.nc + c) * s.H + h) * Q + tid] * LOG2E;
-        s_dt[tid] = (tid < valid) ? to_float(bf16{dt[(tok0 + tid) * s.H + h]}) : 0.f;
-    }
-    // ---- carried state (bf16) -> LDS ----
+    // ---- issue every global load of the prologue before the first barrier ----
+    // (indices are clamped instead of branching, so that all loads go out back to back)
+    const int tq = min(tid, Q - 1);
+    const float cs_raw = cs[(((int64_t)b * s.nc + c) * s.H + h) * Q + tq];
+    const uint16_t dt_raw = dt[(tok0 + min(tq, valid - 1)) * s.H + h];
+    constexpr int HPASS = 64 * 16 / NTHR;      // 16-byte pieces of the state tile per lane
+    uint4 hreg[HPASS];
     {
         const uint16_t *Hc = Hlp + (((int64_t)b * s.nc + c) * s.H + h) * MP * MN;
 #pragma unroll
-        for (int pass = 0; pass < 4; ++pass) {
-            const int row = (tid >> 4) + 16 * pass, piece = tid & 15;
-            *reinterpret_cast<uint4 *>(sH + row * HSTR + piece * 8) =
-                *reinterpret_cast<const uint4 *>(Hc + row * MN + piece * 8);
+        for (int pass = 0; pass < HPASS; ++pass) {
+            const int row = (tid >> 4) + (NTHR / 16) * pass, piece = tid & 15;
+            hreg[pass] = *reinterpret_cast<const uint4 *>(Hc + row * MN + piece * 8);
         }
     }
-    // ---- mixed C rows of the owned tiles (operand registers) ----
-    uint4 cfrag[SLOTS][8];
+    // dt_j x_j staging: unit = (8 tokens in operand order) x (2 channels)
+    constexpr int XU = (Q / 8) * 32 / NTHR;
+    uint32_t xv[XU][8];
 #pragma unroll
-    for (int sl = 0; sl < SLOTS; ++sl) {
-        const int I = tileI[sl] < 0 ? 0 : tileI[sl];
-        const uint16_t *src = cmix + (((int64_t)b * s.nc * Q + (int64_t)c * Q + I * 32 + l32) * s.G + g) * MN + 64 * kg;
-#pragma unroll
-        for (int ks = 0; ks < 8; ++ks) cfrag[sl][ks] = *reinterpret_cast<const uint4 *>(src + ks * 8);
-    }
-    __syncthreads();
-    if (tid < Q) s_f[tid] = fast_exp2(s_cs[(tid | 31)] - s_cs[tid]);
-    // ---- dt_j x_j, transposed and in operand order ----
-#pragma unroll
-    for (int it = 0; it < (Q / 8) * 32 / MTHREADS; ++it) {
-        const int u = tid + it * MTHREADS;
-        const int p2 = u & 31, gi = u >> 5;          // gi: group of 8 tokens in operand order
+    for (int it = 0; it < XU; ++it) {
+        const int u = tid + it * NTHR;
+        const int p2 = u & 31, gi = u >> 5;
         const int t16 = gi >> 1, kgx = gi & 1;
-        uint32_t v[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             const int j = 16 * t16 + 8 * (e >> 2) + 4 * kgx + (e & 3);
-            v[e] = 0;
-            if (j < valid) v[e] = *reinterpret_cast<const uint32_t *>(xh + j * tokstride + 2 * p2);
+            const uint32_t ld = *reinterpret_cast<const uint32_t *>(xh + min(j, valid - 1) * tokstride + 2 * p2);
+            xv[it][e] = (j < valid) ? ld : 0u;
         }
+    }
+    // mixed C rows of the owned tiles (operand registers)
+    uint4 cfrag[8];
+    {
+        const uint16_t *src = cmix + (((bcg * NT + I) * 8) * 64 + lane) * 8;
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) cfrag[ks] = *reinterpret_cast<const uint4 *>(src + ks * 64 * 8);
+    }
+    const float cs_reg = cs_raw * LOG2E;
+    if (tid < Q) {
+        s_cs[tid] = cs_reg;
+        s_dt[tid] = (tid < valid) ? to_float(bf16{dt_raw}) : 0.f;
+    }
+#pragma unroll
+    for (int pass = 0; pass < HPASS; ++pass) {
+        const int row = (tid >> 4) + (NTHR / 16) * pass, piece = tid & 15;
+        *reinterpret_cast<uint4 *>(sH + row * HSTR + piece * 8) = hreg[pass];
+    }
+    __syncthreads();
+    if (tid < Q) s_f[tid] = fast_exp2(s_cs[(tid | 31)] - cs_reg);
+#pragma unroll
+    for (int it = 0; it < XU; ++it) {
+        const int u = tid + it * NTHR;
+        const int p2 = u & 31, gi = u >> 5;
+        const int t16 = gi >> 1, kgx = gi & 1;
         float xa[8], xb[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             const float d = s_dt[16 * t16 + 8 * (e >> 2) + 4 * kgx + (e & 3)];
-            xa[e] = bf_lo(v[e]) * d;
-            xb[e] = bf_hi(v[e]) * d;
+            xa[e] = bf_lo(xv[it][e]) * d;
+            xb[e] = bf_hi(xv[it][e]) * d;
         }
         *reinterpret_cast<uint4 *>(sX + (2 * p2) * XSTR + 16 * t16 + 8 * kgx) = pack8(xa);
         *reinterpret_cast<uint4 *>(sX + (2 * p2 + 1) * XSTR + 16 * t16 + 8 * kgx) = pack8(xb);
@@ -450,18 +469,35 @@ output_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ 
     const float dsk = D ? D[h] : 0.f;
     const uint16_t *sXr0 = sX + prow * XSTR + 8 * kg;          // operand rows of the two channel halves
     const uint16_t *sXr1 = sX + (32 + prow) * XSTR + 8 * kg;
+
+    // G^T tiles are streamed two pairs ahead of their use (tile index clamped to I, so the
+    // loads are unconditional and the wait counters stay exact).
+    const uint16_t *tile0 = cb + ((bcg * NP + I * (I + 1) / 2) * 2 * 64 + lane) * 8;
+    auto load_tile = [&](int J, uint4 &u0, uint4 &u1) {
+        const uint16_t *t = tile0 + min(J, I) * (2 * 64 * 8);
+        u0 = *reinterpret_cast<const uint4 *>(t);
+        u1 = *reinterpret_cast<const uint4 *>(t + 64 * 8);
+    };
+    uint4 uA0, uA1, uB0, uB1;
+    load_tile(0, uA0, uA1);
+    load_tile(1, uB0, uB1);
+    {
+        // x of the skip term, loaded the way y is stored: lane -> (token row, 16-byte piece)
+        const int erow = lane >> 3, epiece = lane & 7;
+        uint4 xe[4];
 #pragma unroll
-    for (int sl = 0; sl < SLOTS; ++sl) {
-        const int I = tileI[sl];
-        if (I < 0) continue;
+        for (int q4 = 0; q4 < 4; ++q4) {
+            const int i = I * 32 + erow + 8 * q4;
+            xe[q4] = *reinterpret_cast<const uint4 *>(xh + min(i, valid - 1) * tokstride + epiece * 8);
+        }
         f32x16_t y0 = {0}, y1 = {0};
         // ---- H_c . Cmix^T, then the per-token factor exp(cs_i) ----
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) {
             const uint4 h0 = *reinterpret_cast<const uint4 *>(sH + prow * HSTR + 64 * kg + ks * 8);
             const uint4 h1 = *reinterpret_cast<const uint4 *>(sH + (32 + prow) * HSTR + 64 * kg + ks * 8);
-            y0 = mfma32(h0, cfrag[sl][ks], y0);
-            y1 = mfma32(h1, cfrag[sl][ks], y1);
+            y0 = mfma32(h0, cfrag[ks], y0);
+            y1 = mfma32(h1, cfrag[ks], y1);
         }
         const float csi = s_cs[I * 32 + l32];
         {
@@ -470,20 +506,12 @@ output_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ 
             for (int v = 0; v < 16; ++v) { y0[v] *= sc; y1[v] *= sc; }
         }
         // ---- intra-chunk part ----
-        const uint16_t *tile = cb + ((bcg * NP + I * (I + 1) / 2) * 2 * 64 + lane) * 8;
-        uint4 u0 = *reinterpret_cast<const uint4 *>(tile);
-        uint4 u1 = *reinterpret_cast<const uint4 *>(tile + 64 * 8);
-#pragma unroll 1
-        for (int J = 0; J <= I; ++J) {
+        auto pair = [&](int J, uint4 u0, uint4 u1) {
             float m[16];
             unpack8(m, u0);
             unpack8(m + 8, u1);
-            const float *fj = s_f + J * 32 + 4 * kg;
-            const float *cj = s_cs + J * 32 + 4 * kg;
-            if (J < I) {   // prefetch the next tile
-                tile += 2 * 64 * 8;
-                u0 = *reinterpret_cast<const uint4 *>(tile);
-                u1 = *reinterpret_cast<const uint4 *>(tile + 64 * 8);
+            if (J < I) {
+                const float *fj = s_f + J * 32 + 4 * kg;
                 const float ei = fast_exp2(csi - s_cs[J * 32 + 31]);
 #pragma unroll
                 for (int a = 0; a < 4; ++a) {
@@ -494,6 +522,7 @@ output_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ 
                     m[4 * a + 3] *= ei * f4.w;
                 }
             } else {
+                const float *cj = s_cs + J * 32 + 4 * kg;
 #pragma unroll
                 for (int a = 0; a < 4; ++a) {
                     const float4 c4 = *reinterpret_cast<const float4 *>(cj + 8 * a);
@@ -514,22 +543,51 @@ output_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ 
                 y0 = mfma32(x0, mfrag, y0);
                 y1 = mfma32(x1, mfrag, y1);
             }
+        };
+        {   // three tile buffers rotate by name, so no register moves sit behind the loads
+            uint4 uC0, uC1;
+            int J = 0;
+            while (true) {
+                load_tile(J + 2, uC0, uC1);
+                pair(J, uA0, uA1);
+                if (++J > I) break;
+                load_tile(J + 2, uA0, uA1);
+                pair(J, uB0, uB1);
+                if (++J > I) break;
+                load_tile(J + 2, uB0, uB1);
+                pair(J, uC0, uC1);
+                if (++J > I) break;
+            }
         }
-        // ---- y = acc + D x : lane (token l32, half kg) holds channels 16kg+0..15 (+32) ----
-        const int i = I * 32 + l32;
-        if (i < valid) {
-            const int off = i * tokstride + 16 * kg;
+        // ---- y = acc + D x.  The wave's 32 x 64 tile goes through LDS (the x^T tile is
+        // dead by now) so that every global access is a full 128-byte row. ----
+        __syncthreads();
+        // scratch: 32 rows x 8 pieces of 16 bytes per wave, piece index XOR-swizzled by the row
+        static_assert(NT * 32 * MP * 2 <= MP * XSTR * 2, "epilogue scratch must fit in the x^T tile");
+        constexpr int YSTR = MP;
+        uint16_t *scr = sX + wave * 32 * YSTR;
+        {
+            float a0[16], a1[16];
 #pragma unroll
-            for (int pt = 0; pt < 2; ++pt) {
-                float a[16], xv[16];
+            for (int v = 0; v < 16; ++v) { a0[v] = y0[v]; a1[v] = y1[v]; }
+            uint16_t *dst = scr + l32 * YSTR;              // lane holds channels 16kg..16kg+15 (+32)
+            const int sw = l32 & 7;
+            *reinterpret_cast<uint4 *>(dst + (((2 * kg) ^ sw) << 3)) = pack8(a0);
+            *reinterpret_cast<uint4 *>(dst + (((2 * kg + 1) ^ sw) << 3)) = pack8(a0 + 8);
+            *reinterpret_cast<uint4 *>(dst + (((4 + 2 * kg) ^ sw) << 3)) = pack8(a1);
+            *reinterpret_cast<uint4 *>(dst + (((5 + 2 * kg) ^ sw) << 3)) = pack8(a1 + 8);
+        }
+        __syncthreads();
 #pragma unroll
-                for (int v = 0; v < 16; ++v) a[v] = pt ? y1[v] : y0[v];
-                unpack8(xv, *reinterpret_cast<const uint4 *>(xh + off + 32 * pt));
-                unpack8(xv + 8, *reinterpret_cast<const uint4 *>(xh + off + 32 * pt + 8));
+        for (int q4 = 0; q4 < 4; ++q4) {
+            const int row = erow + 8 * q4, i = I * 32 + row;
+            if (i < valid) {
+                float a[8], xf[8];
+                unpack8(a, *reinterpret_cast<const uint4 *>(scr + row * YSTR + ((epiece ^ (row & 7)) << 3)));
+                unpack8(xf, xe[q4]);
 #pragma unroll
-                for (int e = 0; e < 16; ++e) a[e] += dsk * xv[e];
-                *reinterpret_cast<uint4 *>(yh + off + 32 * pt) = pack8(a);
-                *reinterpret_cast<uint4 *>(yh + off + 32 * pt + 8) = pack8(a + 8);
+                for (int e = 0; e < 8; ++e) a[e] += dsk * xf[e];
+                *reinterpret_cast<uint4 *>(yh + i * tokstride + epiece * 8) = pack8(a);
             }
         }
     }
@@ -543,7 +601,7 @@ static swimba_status launch_out_q(const Shape &s, const void *x, const void *dt,
     const int64_t total = (int64_t)s.B * s.nc * s.H;
     if (total == 0) return SWIMBA_OK;
     const int nblocks = xcd_padded(total);
-    hipLaunchKernelGGL(output_mfma_kernel<Q>, dim3(nblocks), dim3(MTHREADS), 0, st,
+    hipLaunchKernelGGL(output_mfma_kernel<Q>, dim3(nblocks), dim3(64 * (Q / 32)), 0, st,
                        (const uint16_t *)x, (const uint16_t *)dt, D, (const uint16_t *)cmix,
                        (const uint16_t *)cb, cs, (const uint16_t *)Hlp, (uint16_t *)y, s, (int)total,
                        nblocks);
