@@ -1,8 +1,8 @@
 #!/usr/bin/env python3
 """Benchmark of the Swimba token-mixer hot path on one MI355X.
 
-A step = one swimba_mixer_fwd call (router, cumsum, chunk state, state scan,
-output) over one batch of the Mamba-2-130M-shaped workload, inputs resident in
+A step = one swimba_mixer_fwd call (router + mixing, cumsum + chunk state, state
+scan, output: four launches) over one batch of the Mamba-2-130M-shaped workload, inputs resident in
 HBM.  Prints ONE JSON line: whole-path tokens/s, the roofline of the dominant
 kernel (timed alone with HIP events on the launch stream), per-kernel figures,
 the decode step time, and the CPU oracle timed on the host cores.
@@ -37,7 +37,7 @@ def main() -> int:
     ap.add_argument("--no-decode", action="store_true")
     ap.add_argument("--stage", default=None,
                     help="run only this stage in the timed loop (for profilers): "
-                         "router|cumsum|mix|chunk_state|state_scan|output|step|copy")
+                         "mix|chunk_state|state_scan|output|step|copy")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
@@ -87,10 +87,8 @@ def main() -> int:
                             workspace=d["ws"])
 
     stages = {
-        "router": lambda d: sw.swimba_stage_router(dims, d["router_logits"], d["ws"]),
-        "cumsum": lambda d: sw.swimba_stage_cumsum(dims, d["dt"], d["A"], d["ws"]),
-        "mix": lambda d: sw.swimba_stage_mix(dims, d["B_experts"], d["C_experts"], d["ws"]),
-        "chunk_state": lambda d: sw.swimba_stage_chunk_state(dims, d["x"], d["dt"], d["B_experts"], d["ws"]),
+        "mix": lambda d: sw.swimba_stage_mix(dims, d["B_experts"], d["C_experts"], d["router_logits"], d["ws"]),
+        "chunk_state": lambda d: sw.swimba_stage_chunk_state(dims, d["x"], d["dt"], d["A"], d["B_experts"], d["ws"]),
         "state_scan": lambda d: sw.swimba_stage_state_scan(dims, None, d["h_final"], d["ws"]),
         "output": lambda d: sw.swimba_stage_output(dims, d["x"], d["dt"], d["D"], d["B_experts"],
                                                    d["C_experts"], d["y"], d["ws"]),
@@ -147,12 +145,12 @@ def main() -> int:
     state_elems = nchunks * H * P * N
     # algorithmic work per launch (dense counts)
     work = {
-        "router": ("hbm", T * (E * 2 + k * 8)),
-        "cumsum": ("hbm", T * H * (2 + 4)),
-        # reads the k active B and C rows; writes mixed C, mixed B (bf16) and the causal C.B^T tiles
-        "mix": ("hbm", T * (2 * k * G * N * 2 + 2 * G * N * 2) + nchunks * G * (Q // 32) * (Q // 32 + 1) // 2 * 2048),
-        # reads x, dt, mixed B; writes fp32 chunk states
-        "chunk_state": ("hbm", T * (H * P * 2 + H * 2 + G * N * 2) + state_elems * 4),
+        # router + mixing: reads logits and the k active B and C rows; writes top-k, mixed C,
+        # mixed B (bf16) and the causal C.B^T tiles
+        "mix": ("hbm", T * (E * 2 + k * 8 + 2 * k * G * N * 2 + 2 * G * N * 2)
+                + nchunks * G * (Q // 32) * (Q // 32 + 1) // 2 * 2048),
+        # cumsum + chunk state: reads x, dt, mixed B; writes cs and the fp32 chunk states
+        "chunk_state": ("hbm", T * (H * P * 2 + H * 2 + G * N * 2 + H * 4) + state_elems * 4),
         # reads fp32 chunk states, writes them back (carried states) plus the bf16 copy
         "state_scan": ("hbm", state_elems * (4 + 4 + 2)),
         # masked (C B^T) X per head and C.H per head, dense counts (C.B^T itself is in "mix")

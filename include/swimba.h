@@ -162,10 +162,10 @@ swimba_status swimba_stage_router(const swimba_dims *dims, const void *router_lo
 swimba_status swimba_stage_cumsum(const swimba_dims *dims, const void *dt, const float *A,
                                   void *workspace, size_t workspace_bytes, void *hip_stream);
 swimba_status swimba_stage_mix(const swimba_dims *dims, const void *B_experts,
-                               const void *C_experts, void *workspace, size_t workspace_bytes,
-                               void *hip_stream);
+                               const void *C_experts, const void *router_logits, void *workspace,
+                               size_t workspace_bytes, void *hip_stream);
 swimba_status swimba_stage_chunk_state(const swimba_dims *dims, const void *x, const void *dt,
-                                       const void *B_experts, void *workspace,
+                                       const float *A, const void *B_experts, void *workspace,
                                        size_t workspace_bytes, void *hip_stream);
 swimba_status swimba_stage_state_scan(const swimba_dims *dims, const float *h0, float *h_final,
                                       void *workspace, size_t workspace_bytes, void *hip_stream);

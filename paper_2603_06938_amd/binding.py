@@ -65,9 +65,9 @@ def _load():
         lib.swimba_stage_cumsum.restype = i32
         lib.swimba_stage_cumsum.argtypes = [dp, vp, vp, vp, sz, vp]
         lib.swimba_stage_mix.restype = i32
-        lib.swimba_stage_mix.argtypes = [dp, vp, vp, vp, sz, vp]
+        lib.swimba_stage_mix.argtypes = [dp, vp, vp, vp, vp, sz, vp]
         lib.swimba_stage_chunk_state.restype = i32
-        lib.swimba_stage_chunk_state.argtypes = [dp, vp, vp, vp, vp, sz, vp]
+        lib.swimba_stage_chunk_state.argtypes = [dp, vp, vp, vp, vp, vp, sz, vp]
         lib.swimba_stage_state_scan.restype = i32
         lib.swimba_stage_state_scan.argtypes = [dp, vp, vp, vp, sz, vp]
         lib.swimba_stage_output.restype = i32
@@ -224,16 +224,16 @@ def swimba_stage_cumsum(dims, dt, A, workspace):
                                        _stream()), "swimba_stage_cumsum")
 
 
-def swimba_stage_mix(dims, B_experts, C_experts, workspace):
+def swimba_stage_mix(dims, B_experts, C_experts, router_logits, workspace):
     _check(_load().swimba_stage_mix(ctypes.byref(dims), _ptr(B_experts, "B_experts"),
-                                    _ptr(C_experts, "C_experts"),
+                                    _ptr(C_experts, "C_experts"), _ptr(router_logits, "router_logits"),
                                     _ptr(workspace, "workspace", torch.uint8), workspace.numel(),
                                     _stream()), "swimba_stage_mix")
 
 
-def swimba_stage_chunk_state(dims, x, dt, B_experts, workspace):
+def swimba_stage_chunk_state(dims, x, dt, A, B_experts, workspace):
     _check(_load().swimba_stage_chunk_state(ctypes.byref(dims), _ptr(x, "x"), _ptr(dt, "dt"),
-                                            _ptr(B_experts, "B_experts"),
+                                            _ptr(A, "A", torch.float32), _ptr(B_experts, "B_experts"),
                                             _ptr(workspace, "workspace", torch.uint8),
                                             workspace.numel(), _stream()), "swimba_stage_chunk_state")
 

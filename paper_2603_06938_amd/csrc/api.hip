@@ -150,35 +150,37 @@ swimba_status swimba_stage_cumsum(const swimba_dims *dims, const void *dt, const
     if (st != SWIMBA_OK) return st;
     if ((int64_t)dims->batch * dims->seqlen == 0) return SWIMBA_OK;
     if (!dt || !A) return SWIMBA_ERR_NULL;
+    if (use_mfma_path(dims)) return SWIMBA_OK;   // the MFMA chunk-state kernel computes cs itself
     return launch_cumsum(make_shape(dims), dims->io_dtype, dt, A, ws.cs, (hipStream_t)hip_stream);
 }
 
 swimba_status swimba_stage_mix(const swimba_dims *dims, const void *B_experts,
-                               const void *C_experts, void *workspace, size_t workspace_bytes,
-                               void *hip_stream)
+                               const void *C_experts, const void *router_logits, void *workspace,
+                               size_t workspace_bytes, void *hip_stream)
 {
     Ws ws;
     swimba_status st = carve(dims, workspace, workspace_bytes, &ws);
     if (st != SWIMBA_OK) return st;
     if ((int64_t)dims->batch * dims->seqlen == 0) return SWIMBA_OK;
-    if (!B_experts || !C_experts) return SWIMBA_ERR_NULL;
+    if (!B_experts || !C_experts || !router_logits) return SWIMBA_ERR_NULL;
     if (!use_mfma_path(dims)) return SWIMBA_OK;   // the fp32 chunk kernels mix while staging
-    return launch_mix_cb_mfma(make_shape(dims), B_experts, C_experts, ws.idx, ws.w, ws.cmix,
-                              ws.bmix_t8, ws.cb, (hipStream_t)hip_stream);
+    return launch_mix_cb_mfma(make_shape(dims), B_experts, C_experts, router_logits, ws.idx, ws.w,
+                              ws.cmix, ws.bmix_t8, ws.cb, (hipStream_t)hip_stream);
 }
 
 swimba_status swimba_stage_chunk_state(const swimba_dims *dims, const void *x, const void *dt,
-                                       const void *B_experts, void *workspace,
+                                       const float *A, const void *B_experts, void *workspace,
                                        size_t workspace_bytes, void *hip_stream)
 {
     Ws ws;
     swimba_status st = carve(dims, workspace, workspace_bytes, &ws);
     if (st != SWIMBA_OK) return st;
     if ((int64_t)dims->batch * dims->seqlen == 0) return SWIMBA_OK;
-    if (!x || !dt || !B_experts) return SWIMBA_ERR_NULL;
+    if (!x || !dt || !A || !B_experts) return SWIMBA_ERR_NULL;
     const Shape s = make_shape(dims);
     if (use_mfma_path(dims))
-        return launch_chunk_state_mfma(s, x, dt, ws.bmix_t8, ws.cs, ws.states, (hipStream_t)hip_stream);
+        return launch_chunk_state_mfma(s, x, dt, A, ws.bmix_t8, ws.cs, ws.states,
+                                       (hipStream_t)hip_stream);
     return launch_chunk_state_generic(s, dims->io_dtype, x, dt, B_experts, ws.idx, ws.w, ws.cs,
                                       ws.states, (hipStream_t)hip_stream);
 }
@@ -225,8 +227,18 @@ swimba_status swimba_mixer_fwd(const swimba_dims *dims, const void *x, const voi
         return SWIMBA_ERR_NULL;
     hipStream_t stream = (hipStream_t)hip_stream;
     const Shape s = make_shape(dims);
+    const bool mf = use_mfma_path(dims);
     if (T > 0) {
-        st = swimba_stage_router(dims, router_logits, workspace, workspace_bytes, hip_stream);
+        // On the bf16 MFMA path the mix kernel routes the tokens itself and the chunk-state
+        // kernel computes the cumsum itself: two launches fewer.
+        if (!mf) {
+            st = swimba_stage_router(dims, router_logits, workspace, workspace_bytes, hip_stream);
+            if (st != SWIMBA_OK) return st;
+            st = swimba_stage_cumsum(dims, dt, A, workspace, workspace_bytes, hip_stream);
+            if (st != SWIMBA_OK) return st;
+        }
+        st = swimba_stage_mix(dims, B_experts, C_experts, router_logits, workspace, workspace_bytes,
+                              hip_stream);
         if (st != SWIMBA_OK) return st;
         if (topk_idx || topk_w) {
             const size_t n = (size_t)T * dims->top_k;
@@ -237,11 +249,7 @@ swimba_status swimba_mixer_fwd(const swimba_dims *dims, const void *x, const voi
                 e = hipMemcpyAsync(topk_w, ws.w, n * sizeof(float), hipMemcpyDeviceToDevice, stream);
             if (e != hipSuccess) { set_last_hip_error((int)e); return SWIMBA_ERR_HIP; }
         }
-        st = swimba_stage_cumsum(dims, dt, A, workspace, workspace_bytes, hip_stream);
-        if (st != SWIMBA_OK) return st;
-        st = swimba_stage_mix(dims, B_experts, C_experts, workspace, workspace_bytes, hip_stream);
-        if (st != SWIMBA_OK) return st;
-        st = swimba_stage_chunk_state(dims, x, dt, B_experts, workspace, workspace_bytes, hip_stream);
+        st = swimba_stage_chunk_state(dims, x, dt, A, B_experts, workspace, workspace_bytes, hip_stream);
         if (st != SWIMBA_OK) return st;
     }
     // with L == 0 the scan only copies h0 (or zeros) to h_final

@@ -76,11 +76,11 @@ swimba_status launch_output_generic(const Shape &s, int io_dtype, const void *x,
                                     const float *D, const void *Be, const void *Ce,
                                     const int32_t *idx, const float *w, const float *cs,
                                     const float *states, void *y, hipStream_t st);
-swimba_status launch_mix_cb_mfma(const Shape &s, const void *Be, const void *Ce, const int32_t *idx,
-                                 const float *w, void *cmix, void *bmix_t8, void *cb, hipStream_t st);
-swimba_status launch_chunk_state_mfma(const Shape &s, const void *x, const void *dt,
-                                      const void *bmix_t8, const float *cs, float *states,
-                                      hipStream_t st);
+swimba_status launch_mix_cb_mfma(const Shape &s, const void *Be, const void *Ce, const void *logits,
+                                 int32_t *idx, float *w, void *cmix, void *bmix_t8, void *cb,
+                                 hipStream_t st);
+swimba_status launch_chunk_state_mfma(const Shape &s, const void *x, const void *dt, const float *A,
+                                      const void *bmix_t8, float *cs, float *states, hipStream_t st);
 swimba_status launch_output_mfma(const Shape &s, const void *x, const void *dt, const float *D,
                                  const void *cmix, const void *cb, const float *cs,
                                  const void *states_lp, void *y, hipStream_t st);

@@ -75,26 +75,31 @@ __device__ __forceinline__ int xcd_logical_id(int bid, int nblocks)
 }
 static inline int xcd_padded(int64_t total) { return (int)((total + 7) / 8 * 8); }
 
+__device__ __forceinline__ float fast_exp2(float v) { return __builtin_amdgcn_exp2f(v); }
+constexpr float LOG2E = 1.4426950408889634f;
+
 // Mixed row of one token for MFMA use: lane (row, kg) gets, for ks = 0..7, the 8
 // values n = 64*kg + 8*ks + 0..7 of  sum_r w_r * S[e_r][g][n]  as packed bf16.
 // `tok` points at S[token][0][g][0]; estride = G*N elements between experts.
-__device__ __forceinline__ void gather_mix_row(uint4 *frag, const uint16_t *tok, int64_t estride,
-                                               const int32_t *idx, const float *w, int K, int kg,
-                                               bool in_range)
+// idx / w may live in LDS.  All loads are unconditional (callers clamp the token and
+// pass zero weights for tokens past the end of the sequence).
+__device__ __forceinline__ void gather_mix_row(uint4 *frag, const uint16_t *tok, int estride,
+                                               const int32_t *idx, const float *w, int K, int kg)
 {
     float acc[8][8];
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks)
 #pragma unroll
         for (int e = 0; e < 8; ++e) acc[ks][e] = 0.f;
-    if (in_range) {
-        for (int r = 0; r < K; ++r) {
-            const uint16_t *row = tok + (int64_t)idx[r] * estride + 64 * kg;
-            const float wr = w[r];
+#pragma unroll 2
+    for (int r = 0; r < K; ++r) {
+        const uint16_t *row = tok + idx[r] * estride + 64 * kg;
+        const float wr = w[r];
+        uint4 v[8];
 #pragma unroll
-            for (int ks = 0; ks < 8; ++ks)
-                fma_bf16x8(acc[ks], *reinterpret_cast<const uint4 *>(row + ks * 8), wr);
-        }
+        for (int ks = 0; ks < 8; ++ks) v[ks] = *reinterpret_cast<const uint4 *>(row + ks * 8);
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) fma_bf16x8(acc[ks], v[ks], wr);
     }
 #pragma unroll
     for (int ks = 0; ks < 8; ++ks) frag[ks] = pack8(acc[ks]);
@@ -103,6 +108,9 @@ __device__ __forceinline__ void gather_mix_row(uint4 *frag, const uint16_t *tok,
 // =========================================================================================
 // mix_cb.  Workgroup = (batch, chunk, group, role r): output tiles I0 = r and
 // I1 = NT-1-r of the chunk (32 tokens each).  Wave w takes the j tiles J = w, w+4.
+// The workgroup first routes the chunk's tokens itself (softmax over all experts,
+// top-k on the raw logits, no renormalisation) into LDS, and stores the routing of
+// its own two tiles to topk_idx / topk_w.
 //   cmix    (B, nc, G, NT, 8, 64, 8) bf16, mixed C of tile I as MFMA operand registers:
 //           [ks][lane][e] = Cmix[32I + lane%32][64*(lane/32) + 8ks + e]
 //   bmix_t8 (B, nc, G, Q/8, N, 8)    bf16, mixed B with 8 consecutive tokens innermost
@@ -112,50 +120,73 @@ __device__ __forceinline__ void gather_mix_row(uint4 *frag, const uint16_t *tok,
 template <int Q>
 __global__ void __launch_bounds__(MTHREADS)
 mix_cb_kernel(const uint16_t *__restrict__ Be, const uint16_t *__restrict__ Ce,
-              const int32_t *__restrict__ idx, const float *__restrict__ w,
-              uint16_t *__restrict__ cmix, uint16_t *__restrict__ bmix_t8,
-              uint16_t *__restrict__ cb, Shape s)
+              const uint16_t *__restrict__ logits, int32_t *__restrict__ idx_out,
+              float *__restrict__ w_out, uint16_t *__restrict__ cmix,
+              uint16_t *__restrict__ bmix_t8, uint16_t *__restrict__ cb, Shape s)
 {
     constexpr int NT = Q / 32, NR = NT / 2, NP = NT * (NT + 1) / 2;
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    int32_t *s_idx = reinterpret_cast<int32_t *>(smem_raw);        // [Q][K]
+    float *s_w = reinterpret_cast<float *>(s_idx + Q * s.K);        // [Q][K]
+
     const int r = blockIdx.x % NR;
     const int g = (blockIdx.x / NR) % s.G;
     const int c = (blockIdx.x / (NR * s.G)) % s.nc;
     const int b = blockIdx.x / (NR * s.G * s.nc);
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, kg = lane >> 5;
     const int64_t tok0 = (int64_t)b * s.L + (int64_t)c * Q;
     const int valid = min(Q, s.L - c * Q);
-    const int64_t estride = (int64_t)s.G * MN;
+    const int K = s.K;
+    const int estride = s.G * MN;
+    const int tokstride = s.E * estride;                 // elements between tokens of B/C_experts
     const int64_t bcg = ((int64_t)b * s.nc + c) * s.G + g;
     const int tiles[2] = {r, NT - 1 - r};
+    const uint16_t *Bg = Be + (tok0 * s.E * s.G + g) * MN;   // [token 0 of the chunk][expert 0][g][0]
+    const uint16_t *Cg = Ce + (tok0 * s.E * s.G + g) * MN;
 
-    // ---- (a) mixed B of the two owned tiles, 8 tokens innermost ----
-    if (tid < 128) {
-        const int sel = tid >> 6, jgl = (tid >> 4) & 3, piece = tid & 15;
-        const int jg = tiles[sel] * 4 + jgl;            // group of 8 tokens inside the chunk
-        float acc[8][8];
-#pragma unroll
-        for (int jj = 0; jj < 8; ++jj) {
-#pragma unroll
-            for (int e = 0; e < 8; ++e) acc[jj][e] = 0.f;
-            const int j = jg * 8 + jj;
-            if (j < valid) {
-                const int64_t bt = tok0 + j;
-                const uint16_t *rowbase = Be + (bt * s.E * s.G + g) * MN + piece * 8;
-                for (int rr = 0; rr < s.K; ++rr) {
-                    const int e = idx[bt * s.K + rr];
-                    const float wr = w[bt * s.K + rr];
-                    fma_bf16x8(acc[jj], *reinterpret_cast<const uint4 *>(rowbase + e * estride), wr);
+    // ---- routing of the chunk's tokens ----
+    for (int t = tid; t < Q; t += MTHREADS) {
+        if (t < valid) {
+            const uint16_t *gl = logits + (tok0 + t) * s.E;
+            route_token([&](int e) { return to_float(bf16{gl[e]}); }, s.E, K, s_idx + t * K, s_w + t * K);
+            const int tile = t >> 5;
+            if (g == 0 && (tile == tiles[0] || tile == tiles[1])) {
+                for (int rr = 0; rr < K; ++rr) {
+                    idx_out[(tok0 + t) * K + rr] = s_idx[t * K + rr];
+                    w_out[(tok0 + t) * K + rr] = s_w[t * K + rr];
                 }
             }
+        } else {
+            for (int rr = 0; rr < K; ++rr) { s_idx[t * K + rr] = 0; s_w[t * K + rr] = 0.f; }
         }
-        uint16_t *dst = bmix_t8 + ((bcg * (Q / 8) + jg) * MN + piece * 8) * 8;
+    }
+    __syncthreads();
+
+    // ---- (a) mixed B of the two owned tiles, 8 tokens innermost; a lane does 4 tokens x 8 n ----
+    {
+        const int half = tid & 1, piece = (tid >> 1) & 15, jgl = (tid >> 5) & 3, sel = tid >> 7;
+        const int jg = tiles[sel] * 4 + jgl;             // group of 8 tokens inside the chunk
+        float acc[4][8];
+#pragma unroll
+        for (int jj = 0; jj < 4; ++jj) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[jj][e] = 0.f;
+            const int j = jg * 8 + half * 4 + jj;
+            const uint16_t *rowbase = Bg + min(j, valid - 1) * tokstride + piece * 8;
+#pragma unroll 2
+            for (int rr = 0; rr < K; ++rr)
+                fma_bf16x8(acc[jj], *reinterpret_cast<const uint4 *>(rowbase + s_idx[j * K + rr] * estride),
+                           s_w[j * K + rr]);
+        }
+        uint16_t *dst = bmix_t8 + ((bcg * (Q / 8) + jg) * MN + piece * 8) * 8 + half * 4;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
-            float col[8];
-#pragma unroll
-            for (int jj = 0; jj < 8; ++jj) col[jj] = acc[jj][e];
-            *reinterpret_cast<uint4 *>(dst + e * 8) = pack8(col);
+            uint2 pk;
+            pk.x = pack_bf16x2(acc[0][e], acc[1][e]);
+            pk.y = pack_bf16x2(acc[2][e], acc[3][e]);
+            *reinterpret_cast<uint2 *>(dst + e * 8) = pk;
         }
     }
 
@@ -164,10 +195,9 @@ mix_cb_kernel(const uint16_t *__restrict__ Be, const uint16_t *__restrict__ Ce,
 #pragma unroll
     for (int sl = 0; sl < 2; ++sl) {
         const int i = tiles[sl] * 32 + l32;
-        const int64_t bt = tok0 + i;
-        gather_mix_row(cfrag[sl], Ce + (bt * s.E * s.G + g) * MN, estride, idx + bt * s.K,
-                       w + bt * s.K, s.K, kg, i < valid);
-        if (wave == 0) {
+        gather_mix_row(cfrag[sl], Cg + min(i, valid - 1) * tokstride, estride, s_idx + i * K,
+                       s_w + i * K, K, kg);
+        if (wave == sl) {
             uint16_t *dst = cmix + (((bcg * NT + tiles[sl]) * 8) * 64 + lane) * 8;
 #pragma unroll
             for (int ks = 0; ks < 8; ++ks) *reinterpret_cast<uint4 *>(dst + ks * 64 * 8) = cfrag[sl][ks];
@@ -178,9 +208,8 @@ mix_cb_kernel(const uint16_t *__restrict__ Be, const uint16_t *__restrict__ Ce,
     for (int J = wave; J <= tiles[1]; J += 4) {
         uint4 bfrag[8];
         const int j = J * 32 + l32;
-        const int64_t bt = tok0 + j;
-        gather_mix_row(bfrag, Be + (bt * s.E * s.G + g) * MN, estride, idx + bt * s.K, w + bt * s.K,
-                       s.K, kg, j < valid);
+        gather_mix_row(bfrag, Bg + min(j, valid - 1) * tokstride, estride, s_idx + j * K, s_w + j * K,
+                       K, kg);
 #pragma unroll
         for (int sl = 0; sl < 2; ++sl) {
             const int I = tiles[sl];
@@ -199,45 +228,53 @@ mix_cb_kernel(const uint16_t *__restrict__ Be, const uint16_t *__restrict__ Ce,
 }
 
 template <int Q>
-static swimba_status launch_mix_q(const Shape &s, const void *Be, const void *Ce, const int32_t *idx,
-                                  const float *w, void *cmix, void *bmix_t8, void *cb, hipStream_t st)
+static swimba_status launch_mix_q(const Shape &s, const void *Be, const void *Ce, const void *logits,
+                                  int32_t *idx, float *w, void *cmix, void *bmix_t8, void *cb,
+                                  hipStream_t st)
 {
     const int64_t total = (int64_t)s.B * s.nc * s.G * (Q / 64);
     if (total == 0) return SWIMBA_OK;
-    hipLaunchKernelGGL(mix_cb_kernel<Q>, dim3((unsigned)total), dim3(MTHREADS), 0, st,
-                       (const uint16_t *)Be, (const uint16_t *)Ce, idx, w, (uint16_t *)cmix,
-                       (uint16_t *)bmix_t8, (uint16_t *)cb, s);
+    const size_t shm = (size_t)Q * s.K * 8;
+    hipLaunchKernelGGL(mix_cb_kernel<Q>, dim3((unsigned)total), dim3(MTHREADS), shm, st,
+                       (const uint16_t *)Be, (const uint16_t *)Ce, (const uint16_t *)logits, idx, w,
+                       (uint16_t *)cmix, (uint16_t *)bmix_t8, (uint16_t *)cb, s);
     SWIMBA_CHECK_LAUNCH();
     return SWIMBA_OK;
 }
 
-swimba_status launch_mix_cb_mfma(const Shape &s, const void *Be, const void *Ce, const int32_t *idx,
-                                 const float *w, void *cmix, void *bmix_t8, void *cb, hipStream_t st)
+swimba_status launch_mix_cb_mfma(const Shape &s, const void *Be, const void *Ce, const void *logits,
+                                 int32_t *idx, float *w, void *cmix, void *bmix_t8, void *cb,
+                                 hipStream_t st)
 {
     switch (s.Q) {
-    case 64: return launch_mix_q<64>(s, Be, Ce, idx, w, cmix, bmix_t8, cb, st);
-    case 128: return launch_mix_q<128>(s, Be, Ce, idx, w, cmix, bmix_t8, cb, st);
-    case 256: return launch_mix_q<256>(s, Be, Ce, idx, w, cmix, bmix_t8, cb, st);
+    case 64: return launch_mix_q<64>(s, Be, Ce, logits, idx, w, cmix, bmix_t8, cb, st);
+    case 128: return launch_mix_q<128>(s, Be, Ce, logits, idx, w, cmix, bmix_t8, cb, st);
+    case 256: return launch_mix_q<256>(s, Be, Ce, logits, idx, w, cmix, bmix_t8, cb, st);
     }
     return SWIMBA_ERR_UNSUPPORTED;
 }
 
 // =========================================================================================
 // Chunk state:  S_c[p][n] = sum_j coef_j x[j][p] Bmix[j][n],  coef_j = dt_j exp(cs_last - cs_j)
-// Workgroup = (batch, chunk, head).  The coefficient-weighted x tile is staged
-// transposed ([p][j]) in LDS; the mixed B operand comes straight from bmix_t8.
-// Wave w owns columns n = 32w..32w+31 and both 32-row halves of p.
+// Workgroup = (batch, chunk, head).  It also computes the chunk's inclusive cumsum
+// cs of dt*A itself (block scan) and stores it for the scan and output kernels.
+// The coefficient-weighted x tile is staged transposed ([p][j]) in LDS; the mixed B
+// operand comes straight from bmix_t8.  Wave w owns columns n = 32w..32w+31 and both
+// 32-row halves of p.
 // =========================================================================================
 template <int Q>
 __global__ void __launch_bounds__(MTHREADS)
 chunk_state_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ dt,
-                        const uint16_t *__restrict__ bmix_t8, const float *__restrict__ cs,
-                        float *__restrict__ states, Shape s, int total, int nblocks)
+                        const float *__restrict__ A, const uint16_t *__restrict__ bmix_t8,
+                        float *__restrict__ cs, float *__restrict__ states, Shape s, int total,
+                        int nblocks)
 {
     constexpr int STR = Q + 8;                    // row stride of the transposed x tile (elements)
     constexpr int KS = Q / 16;
+    constexpr int XU = (Q / 8) * 32 / MTHREADS;   // x staging units per lane
     __shared__ __align__(16) uint16_t sXt[MP * STR];
     __shared__ float s_coef[Q];
+    __shared__ float s_part[4];
 
     const int lid = xcd_logical_id(blockIdx.x, nblocks);
     if (lid >= total) return;
@@ -245,47 +282,77 @@ chunk_state_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restri
     const int c = (lid / s.H) % s.nc;
     const int b = lid / (s.H * s.nc);
     const int g = (h * s.G) / s.H;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, kg = lane >> 5;
     const int64_t tok0 = (int64_t)b * s.L + (int64_t)c * Q;
     const int valid = min(Q, s.L - c * Q);
     const int64_t bcg = ((int64_t)b * s.nc + c) * s.G + g;
+    const int tokstride = s.H * MP;
+    const uint16_t *xh = x + (tok0 * s.H + h) * MP;
 
+    // ---- every global load first (clamped, unconditional) ----
+    const int tq = min(tid, Q - 1);
+    const uint16_t dt_raw = dt[(tok0 + min(tq, valid - 1)) * s.H + h];
+    const float Ah = A[h];
+    uint32_t xv[XU][8];
+#pragma unroll
+    for (int it = 0; it < XU; ++it) {
+        const int u = tid + it * MTHREADS;
+        const int p2 = u & 31, jg = u >> 5;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int j = jg * 8 + e;
+            const uint32_t ld = *reinterpret_cast<const uint32_t *>(xh + min(j, valid - 1) * tokstride + 2 * p2);
+            xv[it][e] = (j < valid) ? ld : 0u;
+        }
+    }
     // B operand: lane (n = 32*wave + l32, kg), k-step ks -> tokens 16ks + 8kg + 0..7
     uint4 bfrag[KS];
     {
         const uint16_t *src = bmix_t8 + (bcg * (Q / 8) * MN + (wave * 32 + l32)) * 8;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks)
-            bfrag[ks] = *reinterpret_cast<const uint4 *>(src + (int64_t)(2 * ks + kg) * MN * 8);
+            bfrag[ks] = *reinterpret_cast<const uint4 *>(src + (2 * ks + kg) * MN * 8);
     }
 
-    const float *csr = cs + (((int64_t)b * s.nc + c) * s.H + h) * Q;
+    // ---- cs = inclusive cumsum of dt*A over the chunk's tokens (tokens past L add 0) ----
+    const float dtv = (tid < valid) ? to_float(bf16{dt_raw}) : 0.f;
+    float incl = (tid < Q) ? dtv * Ah : 0.f;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+        const float v = __shfl_up(incl, off);
+        if (lane >= off) incl += v;
+    }
+    if (lane == 63) s_part[wave] = incl;
+    __syncthreads();
+    {
+        float base = 0.f;
+#pragma unroll
+        for (int ww = 0; ww < 3; ++ww)
+            if (ww < wave) base += s_part[ww];
+        incl += base;
+    }
+    constexpr int LASTW = (Q - 1) / 64;
+    float cs_last = 0.f;
+#pragma unroll
+    for (int ww = 0; ww <= LASTW; ++ww) cs_last += s_part[ww];
     if (tid < Q) {
-        float cf = 0.f;
-        if (tid < valid) cf = to_float(bf16{dt[(tok0 + tid) * s.H + h]}) * expf(csr[Q - 1] - csr[tid]);
-        s_coef[tid] = cf;
+        cs[(((int64_t)b * s.nc + c) * s.H + h) * Q + tid] = incl;
+        s_coef[tid] = dtv * fast_exp2((cs_last - incl) * LOG2E);
     }
     __syncthreads();
-    // coefficient-weighted x, transposed: unit = (8 tokens) x (2 channels)
+    // ---- coefficient-weighted x, transposed: unit = (8 tokens) x (2 channels) ----
 #pragma unroll
-    for (int it = 0; it < (Q / 8) * 32 / MTHREADS; ++it) {
+    for (int it = 0; it < XU; ++it) {
         const int u = tid + it * MTHREADS;
         const int p2 = u & 31, jg = u >> 5;
-        uint32_t v[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const int j = jg * 8 + e;
-            v[e] = 0;
-            if (j < valid)
-                v[e] = *reinterpret_cast<const uint32_t *>(x + ((tok0 + j) * s.H + h) * MP + 2 * p2);
-        }
         float xa[8], xb[8];
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             const float cf = s_coef[jg * 8 + e];
-            xa[e] = bf_lo(v[e]) * cf;
-            xb[e] = bf_hi(v[e]) * cf;
+            xa[e] = bf_lo(xv[it][e]) * cf;
+            xb[e] = bf_hi(xv[it][e]) * cf;
         }
         *reinterpret_cast<uint4 *>(sXt + (2 * p2) * STR + jg * 8) = pack8(xa);
         *reinterpret_cast<uint4 *>(sXt + (2 * p2 + 1) * STR + jg * 8) = pack8(xb);
@@ -305,33 +372,32 @@ chunk_state_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restri
 #pragma unroll
     for (int v = 0; v < 16; ++v) {
         const int p = 8 * (v >> 2) + 4 * kg + (v & 3);
-        out[(int64_t)p * MN] = acc0[v];
-        out[(int64_t)(32 + p) * MN] = acc1[v];
+        out[p * MN] = acc0[v];
+        out[(32 + p) * MN] = acc1[v];
     }
 }
 
 template <int Q>
-static swimba_status launch_cs_q(const Shape &s, const void *x, const void *dt, const void *bmix_t8,
-                                 const float *cs, float *states, hipStream_t st)
+static swimba_status launch_cs_q(const Shape &s, const void *x, const void *dt, const float *A,
+                                 const void *bmix_t8, float *cs, float *states, hipStream_t st)
 {
     const int64_t total = (int64_t)s.B * s.nc * s.H;
     if (total == 0) return SWIMBA_OK;
     const int nblocks = xcd_padded(total);
     hipLaunchKernelGGL(chunk_state_mfma_kernel<Q>, dim3(nblocks), dim3(MTHREADS), 0, st,
-                       (const uint16_t *)x, (const uint16_t *)dt, (const uint16_t *)bmix_t8, cs, states,
-                       s, (int)total, nblocks);
+                       (const uint16_t *)x, (const uint16_t *)dt, A, (const uint16_t *)bmix_t8, cs,
+                       states, s, (int)total, nblocks);
     SWIMBA_CHECK_LAUNCH();
     return SWIMBA_OK;
 }
 
-swimba_status launch_chunk_state_mfma(const Shape &s, const void *x, const void *dt,
-                                      const void *bmix_t8, const float *cs, float *states,
-                                      hipStream_t st)
+swimba_status launch_chunk_state_mfma(const Shape &s, const void *x, const void *dt, const float *A,
+                                      const void *bmix_t8, float *cs, float *states, hipStream_t st)
 {
     switch (s.Q) {
-    case 64: return launch_cs_q<64>(s, x, dt, bmix_t8, cs, states, st);
-    case 128: return launch_cs_q<128>(s, x, dt, bmix_t8, cs, states, st);
-    case 256: return launch_cs_q<256>(s, x, dt, bmix_t8, cs, states, st);
+    case 64: return launch_cs_q<64>(s, x, dt, A, bmix_t8, cs, states, st);
+    case 128: return launch_cs_q<128>(s, x, dt, A, bmix_t8, cs, states, st);
+    case 256: return launch_cs_q<256>(s, x, dt, A, bmix_t8, cs, states, st);
     }
     return SWIMBA_ERR_UNSUPPORTED;
 }
@@ -358,9 +424,6 @@ swimba_status launch_chunk_state_mfma(const Shape &s, const void *x, const void 
 // bf16, passed through LDS and stored as full 128-byte rows (D x is added on the way).
 // cs is kept multiplied by log2(e): every exponential is one v_exp_f32.
 // =========================================================================================
-__device__ __forceinline__ float fast_exp2(float v) { return __builtin_amdgcn_exp2f(v); }
-constexpr float LOG2E = 1.4426950408889634f;
-
 template <int Q>
 __global__ void __launch_bounds__(64 * (Q / 32))
 output_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ dt,

@@ -68,8 +68,8 @@ def test_stage_cumsum_and_carried_states(wi, L):
     ws.zero_()
     sw.swimba_stage_router(dims, d["router_logits"], ws)
     sw.swimba_stage_cumsum(dims, d["dt"], d["A"], ws)
-    sw.swimba_stage_mix(dims, d["B_experts"], d["C_experts"], ws)
-    sw.swimba_stage_chunk_state(dims, d["x"], d["dt"], d["B_experts"], ws)
+    sw.swimba_stage_mix(dims, d["B_experts"], d["C_experts"], d["router_logits"], ws)
+    sw.swimba_stage_chunk_state(dims, d["x"], d["dt"], d["A"], d["B_experts"], ws)
     hf = torch.empty((w.batch, w.nheads, w.headdim, w.dstate), device="cuda:0")
     sw.swimba_stage_state_scan(dims, None, hf, ws)
     y = torch.empty_like(d["x"])
