@@ -184,10 +184,13 @@ def main() -> int:
         # four independent state buffers, round-robin: 4 x 134 MB > last-level cache
         states = [dd["state"].clone() for _ in range(4)]
         yd = torch.empty_like(xs[0])
+        dws = torch.empty(sw.swimba_step_workspace_bytes(
+            sw.make_dims(wd.batch, 1, wd.nheads, wd.headdim, wd.dstate, wd.ngroups, wd.nexperts, wd.top_k, 0, io)),
+            dtype=torch.uint8, device=dev)
 
         def dstep(i):
             t = i % 8
-            sw.swimba_step(states[i % 4], xs[t], dts[t], dd["A"], dd["D"], Bs[t], Cs[t], gs[t], wd.top_k, y=yd)
+            sw.swimba_step(states[i % 4], xs[t], dts[t], dd["A"], dd["D"], Bs[t], Cs[t], gs[t], wd.top_k, y=yd, workspace=dws)
 
         time_loop(dstep, 8)
         ms = time_loop(dstep, S)

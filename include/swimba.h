@@ -186,12 +186,16 @@ swimba_status swimba_stage_output(const swimba_dims *dims, const void *x, const 
  *   x (B,H,P) io, dt (B,H) io, A (H), D (H)|NULL, B/C_experts (B,E,G,N) io,
  *   router_logits (B,E) io  [in]
  *   y (B,H,P) io [out];  topk_idx (B,k) int32 [out] NULL = not wanted
- * Arithmetic is fp32.
+ *   workspace: >= swimba_step_workspace_bytes(dims) bytes (the mixed streams of the
+ *             step, B*G*N*2 fp32), 256-byte aligned; 0 from the query = invalid dims
+ * Two kernels are enqueued (routing + mixing, then the state update).  Arithmetic is fp32.
  */
+size_t swimba_step_workspace_bytes(const swimba_dims *dims);
 swimba_status swimba_step(const swimba_dims *dims, const float *state_in, float *state_out,
                           const void *x, const void *dt, const float *A, const float *D,
                           const void *B_experts, const void *C_experts, const void *router_logits,
-                          void *y, int32_t *topk_idx, void *hip_stream);
+                          void *y, int32_t *topk_idx, void *workspace, size_t workspace_bytes,
+                          void *hip_stream);
 
 /*
  * Measurement helpers (no paper operation): a plain device copy of `bytes`

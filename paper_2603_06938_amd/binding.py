@@ -72,8 +72,10 @@ def _load():
         lib.swimba_stage_state_scan.argtypes = [dp, vp, vp, vp, sz, vp]
         lib.swimba_stage_output.restype = i32
         lib.swimba_stage_output.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        lib.swimba_step_workspace_bytes.restype = sz
+        lib.swimba_step_workspace_bytes.argtypes = [dp]
         lib.swimba_step.restype = i32
-        lib.swimba_step.argtypes = [dp] + [vp] * 11 + [vp]
+        lib.swimba_step.argtypes = [dp] + [vp] * 11 + [vp, sz, vp]
         lib.swimba_probe_copy.restype = i32
         lib.swimba_probe_copy.argtypes = [vp, vp, sz, vp]
         lib.swimba_probe_mfma.restype = i32
@@ -281,8 +283,12 @@ class StepOut(NamedTuple):
     topk_idx: Optional[torch.Tensor]
 
 
+def swimba_step_workspace_bytes(dims: swimba_dims) -> int:
+    return int(_load().swimba_step_workspace_bytes(ctypes.byref(dims)))
+
+
 def swimba_step(state, x, dt, A, D, B_experts, C_experts, router_logits, top_k: int, *,
-                state_out=None, y=None, topk_idx=None, want_topk: bool = False) -> StepOut:
+                state_out=None, y=None, topk_idx=None, workspace=None, want_topk: bool = False) -> StepOut:
     """state (B,H,P,N) fp32, x (B,H,P), dt (B,H), B/C_experts (B,E,G,N), router_logits (B,E).
     state_out defaults to `state` (in place)."""
     B, H, P = x.shape
@@ -295,13 +301,16 @@ def swimba_step(state, x, dt, A, D, B_experts, C_experts, router_logits, top_k: 
         y = torch.empty_like(x)
     if want_topk and topk_idx is None:
         topk_idx = torch.empty((B, top_k), dtype=torch.int32, device=x.device)
+    if workspace is None:
+        workspace = torch.empty(max(swimba_step_workspace_bytes(d), 256), dtype=torch.uint8, device=x.device)
     st = _load().swimba_step(
         ctypes.byref(d), _ptr(state, "state", torch.float32, (B, H, P, N)),
         _ptr(state_out, "state_out", torch.float32, (B, H, P, N)), _ptr(x, "x", io, (B, H, P)),
         _ptr(dt, "dt", io, (B, H)), _ptr(A, "A", torch.float32, (H,)), _ptr(D, "D", torch.float32, (H,)),
         _ptr(B_experts, "B_experts", io, (B, E, G, N)), _ptr(C_experts, "C_experts", io, (B, E, G, N)),
         _ptr(router_logits, "router_logits", io, (B, E)), _ptr(y, "y", io, (B, H, P)),
-        _ptr(topk_idx, "topk_idx", torch.int32, (B, top_k)), _stream())
+        _ptr(topk_idx, "topk_idx", torch.int32, (B, top_k)),
+        _ptr(workspace, "workspace", torch.uint8), workspace.numel(), _stream())
     _check(st, "swimba_step")
     return StepOut(y, state_out, topk_idx)
 

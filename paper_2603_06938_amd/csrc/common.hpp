@@ -87,7 +87,7 @@ swimba_status launch_output_mfma(const Shape &s, const void *x, const void *dt, 
 swimba_status launch_step(const Shape &s, int io_dtype, const float *state_in, float *state_out,
                           const void *x, const void *dt, const float *A, const float *D,
                           const void *Be, const void *Ce, const void *logits, void *y, int32_t *idx,
-                          hipStream_t st);
+                          float *bc, hipStream_t st);
 
 // ---- device helper shared by the router kernel and the decode kernel -----------------
 // Top-k over E logits read through `load(e)`, in (logit descending, index

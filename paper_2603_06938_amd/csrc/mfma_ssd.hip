@@ -256,32 +256,41 @@ swimba_status launch_mix_cb_mfma(const Shape &s, const void *Be, const void *Ce,
 
 // =========================================================================================
 // Chunk state:  S_c[p][n] = sum_j coef_j x[j][p] Bmix[j][n],  coef_j = dt_j exp(cs_last - cs_j)
-// Workgroup = (batch, chunk, head).  It also computes the chunk's inclusive cumsum
-// cs of dt*A itself (block scan) and stores it for the scan and output kernels.
-// The coefficient-weighted x tile is staged transposed ([p][j]) in LDS; the mixed B
-// operand comes straight from bmix_t8.  Wave w owns columns n = 32w..32w+31 and both
-// 32-row halves of p.
+// Workgroup = (batch, chunk, group, run of heads of that group).  The mixed B operand
+// (shared by the group's heads) is read once from bmix_t8 into registers.  The heads
+// are walked in a software pipeline: while the MFMAs and the state stores of head k
+// run, the x rows of head k+1 are already in flight, and they are staged into the other
+// half of a double-buffered LDS tile.
+// Per head the kernel also computes the chunk's inclusive cumsum cs of dt*A (block
+// scan) and stores it for the scan and output kernels.
+// The coefficient-weighted x tile is staged transposed ([p][j]); wave w owns columns
+// n = 32w..32w+31 and both 32-row halves of p.
 // =========================================================================================
 template <int Q>
 __global__ void __launch_bounds__(MTHREADS)
 chunk_state_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ dt,
                         const float *__restrict__ A, const uint16_t *__restrict__ bmix_t8,
-                        float *__restrict__ cs, float *__restrict__ states, Shape s, int total,
-                        int nblocks)
+                        float *__restrict__ cs, float *__restrict__ states, Shape s, int ipw,
+                        int nruns, int total, int nblocks)
 {
     constexpr int STR = Q + 8;                    // row stride of the transposed x tile (elements)
     constexpr int KS = Q / 16;
     constexpr int XU = (Q / 8) * 32 / MTHREADS;   // x staging units per lane
-    __shared__ __align__(16) uint16_t sXt[MP * STR];
-    __shared__ float s_coef[Q];
-    __shared__ float s_part[4];
+    constexpr int LASTW = (Q - 1) / 64;
+    extern __shared__ __align__(16) unsigned char smem_raw[];
+    uint16_t *sXt = reinterpret_cast<uint16_t *>(smem_raw);                  // [2][MP][STR]
+    float *s_coef = reinterpret_cast<float *>(sXt + 2 * MP * STR);            // [2][Q]
+    float *s_part = s_coef + 2 * Q;                                           // [2][4]
 
     const int lid = xcd_logical_id(blockIdx.x, nblocks);
     if (lid >= total) return;
-    const int h = lid % s.H;
-    const int c = (lid / s.H) % s.nc;
-    const int b = lid / (s.H * s.nc);
-    const int g = (h * s.G) / s.H;
+    const int run = lid % nruns;
+    const int g = (lid / nruns) % s.G;
+    const int c = (lid / (nruns * s.G)) % s.nc;
+    const int b = lid / (nruns * s.G * s.nc);
+    const int hpg = s.H / s.G;
+    const int h0 = g * hpg + run * ipw;
+    const int count = min(ipw, hpg - run * ipw);
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, kg = lane >> 5;
@@ -289,24 +298,8 @@ chunk_state_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restri
     const int valid = min(Q, s.L - c * Q);
     const int64_t bcg = ((int64_t)b * s.nc + c) * s.G + g;
     const int tokstride = s.H * MP;
-    const uint16_t *xh = x + (tok0 * s.H + h) * MP;
-
-    // ---- every global load first (clamped, unconditional) ----
     const int tq = min(tid, Q - 1);
-    const uint16_t dt_raw = dt[(tok0 + min(tq, valid - 1)) * s.H + h];
-    const float Ah = A[h];
-    uint32_t xv[XU][8];
-#pragma unroll
-    for (int it = 0; it < XU; ++it) {
-        const int u = tid + it * MTHREADS;
-        const int p2 = u & 31, jg = u >> 5;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const int j = jg * 8 + e;
-            const uint32_t ld = *reinterpret_cast<const uint32_t *>(xh + min(j, valid - 1) * tokstride + 2 * p2);
-            xv[it][e] = (j < valid) ? ld : 0u;
-        }
-    }
+
     // B operand: lane (n = 32*wave + l32, kg), k-step ks -> tokens 16ks + 8kg + 0..7
     uint4 bfrag[KS];
     {
@@ -316,64 +309,93 @@ chunk_state_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restri
             bfrag[ks] = *reinterpret_cast<const uint4 *>(src + (2 * ks + kg) * MN * 8);
     }
 
-    // ---- cs = inclusive cumsum of dt*A over the chunk's tokens (tokens past L add 0) ----
-    const float dtv = (tid < valid) ? to_float(bf16{dt_raw}) : 0.f;
-    float incl = (tid < Q) ? dtv * Ah : 0.f;
+    uint16_t dt_raw;
+    uint32_t xv[XU][8];
+    // all global loads of one head, clamped and unconditional
+    auto issue_loads = [&](int h) {
+        const uint16_t *xh = x + (tok0 * s.H + h) * MP;
+        dt_raw = dt[(tok0 + min(tq, valid - 1)) * s.H + h];
 #pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-        const float v = __shfl_up(incl, off);
-        if (lane >= off) incl += v;
-    }
-    if (lane == 63) s_part[wave] = incl;
-    __syncthreads();
-    {
-        float base = 0.f;
+        for (int it = 0; it < XU; ++it) {
+            const int u = tid + it * MTHREADS;
+            const int p2 = u & 31, jg = u >> 5;
 #pragma unroll
-        for (int ww = 0; ww < 3; ++ww)
-            if (ww < wave) base += s_part[ww];
-        incl += base;
-    }
-    constexpr int LASTW = (Q - 1) / 64;
-    float cs_last = 0.f;
-#pragma unroll
-    for (int ww = 0; ww <= LASTW; ++ww) cs_last += s_part[ww];
-    if (tid < Q) {
-        cs[(((int64_t)b * s.nc + c) * s.H + h) * Q + tid] = incl;
-        s_coef[tid] = dtv * fast_exp2((cs_last - incl) * LOG2E);
-    }
-    __syncthreads();
-    // ---- coefficient-weighted x, transposed: unit = (8 tokens) x (2 channels) ----
-#pragma unroll
-    for (int it = 0; it < XU; ++it) {
-        const int u = tid + it * MTHREADS;
-        const int p2 = u & 31, jg = u >> 5;
-        float xa[8], xb[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const float cf = s_coef[jg * 8 + e];
-            xa[e] = bf_lo(xv[it][e]) * cf;
-            xb[e] = bf_hi(xv[it][e]) * cf;
+            for (int e = 0; e < 8; ++e) {
+                const int j = jg * 8 + e;
+                const uint32_t ld = *reinterpret_cast<const uint32_t *>(xh + min(j, valid - 1) * tokstride + 2 * p2);
+                xv[it][e] = (j < valid) ? ld : 0u;
+            }
         }
-        *reinterpret_cast<uint4 *>(sXt + (2 * p2) * STR + jg * 8) = pack8(xa);
-        *reinterpret_cast<uint4 *>(sXt + (2 * p2 + 1) * STR + jg * 8) = pack8(xb);
-    }
-    __syncthreads();
+    };
+    // cumsum, coefficients and the transposed x tile of head h into buffer `buf`
+    auto stage = [&](int buf, int h) {
+        const float dtv = (tid < valid) ? to_float(bf16{dt_raw}) : 0.f;
+        float incl = (tid < Q) ? dtv * A[h] : 0.f;
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const float v = __shfl_up(incl, off);
+            if (lane >= off) incl += v;
+        }
+        if (lane == 63) s_part[buf * 4 + wave] = incl;
+        __syncthreads();
+        {
+            float base = 0.f;
+#pragma unroll
+            for (int ww = 0; ww < 3; ++ww)
+                if (ww < wave) base += s_part[buf * 4 + ww];
+            incl += base;
+        }
+        float cs_last = 0.f;
+#pragma unroll
+        for (int ww = 0; ww <= LASTW; ++ww) cs_last += s_part[buf * 4 + ww];
+        if (tid < Q) {
+            cs[(((int64_t)b * s.nc + c) * s.H + h) * Q + tid] = incl;
+            s_coef[buf * Q + tid] = dtv * fast_exp2((cs_last - incl) * LOG2E);
+        }
+        __syncthreads();
+        uint16_t *dstX = sXt + buf * MP * STR;
+#pragma unroll
+        for (int it = 0; it < XU; ++it) {
+            const int u = tid + it * MTHREADS;
+            const int p2 = u & 31, jg = u >> 5;
+            float xa[8], xb[8];
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const float cf = s_coef[buf * Q + jg * 8 + e];
+                xa[e] = bf_lo(xv[it][e]) * cf;
+                xb[e] = bf_hi(xv[it][e]) * cf;
+            }
+            *reinterpret_cast<uint4 *>(dstX + (2 * p2) * STR + jg * 8) = pack8(xa);
+            *reinterpret_cast<uint4 *>(dstX + (2 * p2 + 1) * STR + jg * 8) = pack8(xb);
+        }
+    };
 
-    f32x16_t acc0 = {0}, acc1 = {0};
+    issue_loads(h0);
+    stage(0, h0);
+    __syncthreads();
+    for (int k = 0; k < count; ++k) {
+        const int h = h0 + k;
+        const bool more = (k + 1 < count);
+        if (more) issue_loads(h + 1);
+        const uint16_t *srcX = sXt + (k & 1) * MP * STR;
+        f32x16_t acc0 = {0}, acc1 = {0};
 #pragma unroll
-    for (int ks = 0; ks < KS; ++ks) {
-        const int kb = ks * 16 + kg * 8;
-        const uint4 a0 = *reinterpret_cast<const uint4 *>(sXt + l32 * STR + kb);
-        const uint4 a1 = *reinterpret_cast<const uint4 *>(sXt + (32 + l32) * STR + kb);
-        acc0 = mfma32(a0, bfrag[ks], acc0);
-        acc1 = mfma32(a1, bfrag[ks], acc1);
-    }
-    float *out = states + (((int64_t)b * s.nc + c) * s.H + h) * MP * MN + wave * 32 + l32;
+        for (int ks = 0; ks < KS; ++ks) {
+            const int kb = ks * 16 + kg * 8;
+            const uint4 a0 = *reinterpret_cast<const uint4 *>(srcX + l32 * STR + kb);
+            const uint4 a1 = *reinterpret_cast<const uint4 *>(srcX + (32 + l32) * STR + kb);
+            acc0 = mfma32(a0, bfrag[ks], acc0);
+            acc1 = mfma32(a1, bfrag[ks], acc1);
+        }
+        float *out = states + (((int64_t)b * s.nc + c) * s.H + h) * MP * MN + wave * 32 + l32;
 #pragma unroll
-    for (int v = 0; v < 16; ++v) {
-        const int p = 8 * (v >> 2) + 4 * kg + (v & 3);
-        out[p * MN] = acc0[v];
-        out[(32 + p) * MN] = acc1[v];
+        for (int v = 0; v < 16; ++v) {
+            const int p = 8 * (v >> 2) + 4 * kg + (v & 3);
+            out[p * MN] = acc0[v];
+            out[(32 + p) * MN] = acc1[v];
+        }
+        if (more) stage((k + 1) & 1, h + 1);
+        __syncthreads();
     }
 }
 
@@ -381,12 +403,25 @@ template <int Q>
 static swimba_status launch_cs_q(const Shape &s, const void *x, const void *dt, const float *A,
                                  const void *bmix_t8, float *cs, float *states, hipStream_t st)
 {
-    const int64_t total = (int64_t)s.B * s.nc * s.H;
+    const int hpg = s.H / s.G;
+    // heads per workgroup: as many as possible while at least ~2 workgroups per CU remain
+    int ipw = hpg;
+    while (ipw > 1 && (int64_t)s.B * s.nc * s.G * ((hpg + ipw - 1) / ipw) < 512) ipw = (ipw + 1) / 2;
+    const int nruns = (hpg + ipw - 1) / ipw;
+    const int64_t total = (int64_t)s.B * s.nc * s.G * nruns;
     if (total == 0) return SWIMBA_OK;
     const int nblocks = xcd_padded(total);
-    hipLaunchKernelGGL(chunk_state_mfma_kernel<Q>, dim3(nblocks), dim3(MTHREADS), 0, st,
+    const size_t shm = (size_t)2 * MP * (Q + 8) * 2 + 2 * Q * sizeof(float) + 8 * sizeof(float);
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void *)chunk_state_mfma_kernel<Q>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)shm);
+        if (e != hipSuccess) { set_last_hip_error((int)e); return SWIMBA_ERR_HIP; }
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(chunk_state_mfma_kernel<Q>, dim3(nblocks), dim3(MTHREADS), shm, st,
                        (const uint16_t *)x, (const uint16_t *)dt, A, (const uint16_t *)bmix_t8, cs,
-                       states, s, (int)total, nblocks);
+                       states, s, ipw, nruns, (int)total, nblocks);
     SWIMBA_CHECK_LAUNCH();
     return SWIMBA_OK;
 }

@@ -1,112 +1,118 @@
 // Single-token recurrent decode step (paper: selective SSM recurrence per
 // channel, with the router-mixed injection and readout of Theorem 1).
-// HBM-bound: the fp32 state is read once and written once.
+// Two launches: a tiny kernel routes every token and mixes its B and C streams
+// (fp32, into the caller's workspace); the update kernel then only streams the
+// fp32 state through once (read, h' = decay*h + dt*x (x) Bmix, y = h'.Cmix, write).
+// The update kernel is HBM-bound; its shape (one or two 16-byte accesses per lane,
+// small workgroups, non-temporal loads and stores, no dependent load chain) is the
+// one that measured fastest for an in-place stream on this chip.
 #include "common.hpp"
 
 namespace swimba {
 
 constexpr int STEP_THREADS = 256;
+typedef float __attribute__((ext_vector_type(4))) f32x4_t;
 
-// Routing + mixing of one token, done redundantly by every block of that
-// batch row (E logits and k*N elements: negligible next to the 2*P*N*4 state
-// bytes).  Leaves Bmix, Cmix in LDS.
+// ---- routing + mixing: block = (b, g), mixed (B; C) rows of N fp32 each ------------------
 template <typename T>
-__device__ __forceinline__ void route_and_mix(const T *__restrict__ logits_b,
-                                              const T *__restrict__ Be_b, const T *__restrict__ Ce_b,
-                                              int E, int K, int G, int N, int g, float *sB, float *sC,
-                                              int32_t *s_idx, float *s_w, int tid)
+__global__ void __launch_bounds__(128)
+step_mix_kernel(const T *__restrict__ Be, const T *__restrict__ Ce, const T *__restrict__ logits,
+                float *__restrict__ bc, int32_t *__restrict__ idx_out, Shape s)
 {
-    if (tid == 0) route_token([&](int e) { return to_float(logits_b[e]); }, E, K, s_idx, s_w);
-    __syncthreads();
-    for (int n = tid; n < N; n += STEP_THREADS) {
-        float bm = 0.f, cm = 0.f;
-        for (int r = 0; r < K; ++r) {
-            const int64_t o = ((int64_t)s_idx[r] * G + g) * N + n;
-            bm += s_w[r] * to_float(Be_b[o]);
-            cm += s_w[r] * to_float(Ce_b[o]);
-        }
-        sB[n] = bm;
-        sC[n] = cm;
+    __shared__ float s_w[SWIMBA_MAX_TOPK];
+    __shared__ int32_t s_idx[SWIMBA_MAX_TOPK];
+    const int b = blockIdx.x / s.G, g = blockIdx.x % s.G;
+    const int tid = threadIdx.x;
+    if (tid == 0) {
+        const T *gl = logits + (int64_t)b * s.E;
+        route_token([&](int e) { return to_float(gl[e]); }, s.E, s.K, s_idx, s_w);
     }
     __syncthreads();
+    if (idx_out && g == 0 && tid < s.K) idx_out[(int64_t)b * s.K + tid] = s_idx[tid];
+    const T *Bb = Be + ((int64_t)b * s.E * s.G + g) * s.N;
+    const T *Cb = Ce + ((int64_t)b * s.E * s.G + g) * s.N;
+    float *out = bc + (int64_t)blockIdx.x * 2 * s.N;
+    for (int n = tid; n < s.N; n += 128) {
+        float bm = 0.f, cm = 0.f;
+        for (int r = 0; r < s.K; ++r) {
+            const int64_t o = (int64_t)s_idx[r] * s.G * s.N + n;
+            bm += s_w[r] * to_float(Bb[o]);
+            cm += s_w[r] * to_float(Cb[o]);
+        }
+        out[n] = bm;
+        out[s.N + n] = cm;
+    }
 }
 
-// ---- N = 128: a wave covers two state rows per access, float4 per lane ----------------
-// Block (b,h): lane -> columns n4..n4+3, row group rg = tid/32; rows p = rg + 8*i.
-template <typename T, int ROWS_PER_LANE>
+// ---- state update, N = 128 ---------------------------------------------------------------
+// Block = (b, h, slice of 16 rows p); lane -> columns n4..n4+3, rows p0 = 16*slice + tid/32
+// and p0 + 8.
+template <typename T>
 __global__ void __launch_bounds__(STEP_THREADS)
-step_kernel_n128(const float *state_in, float *state_out, const T *__restrict__ x,
-                 const T *__restrict__ dt, const float *__restrict__ A, const float *__restrict__ D,
-                 const T *__restrict__ Be, const T *__restrict__ Ce, const T *__restrict__ logits,
-                 T *__restrict__ y, int32_t *__restrict__ idx_out, Shape s)
+step_update_n128_kernel(const float *state_in, float *state_out, const T *__restrict__ x,
+                        const T *__restrict__ dt, const float *__restrict__ A,
+                        const float *__restrict__ D, const float *__restrict__ bc,
+                        T *__restrict__ y, Shape s, int slices)
 {
     constexpr int N = 128;
-    __shared__ float sB[N], sC[N], s_w[SWIMBA_MAX_TOPK];
-    __shared__ int32_t s_idx[SWIMBA_MAX_TOPK];
-    const int b = blockIdx.x / s.H, h = blockIdx.x % s.H, g = (h * s.G) / s.H;
+    const int sl = blockIdx.x % slices;
+    const int h = (blockIdx.x / slices) % s.H;
+    const int b = blockIdx.x / (slices * s.H);
+    const int g = (h * s.G) / s.H;
     const int tid = threadIdx.x;
-    const int n4 = (tid & 31) * 4, rg = tid >> 5;
-    const int64_t base = ((int64_t)b * s.H + h) * s.P * N;
+    const int n4 = (tid & 31) * 4;
     const int P = s.P;
+    const int p0 = sl * 16 + (tid >> 5), p1 = p0 + 8;
+    const bool ok0 = p0 < P, ok1 = p1 < P;
+    const int q0 = min(p0, P - 1), q1 = min(p1, P - 1);
+    const int64_t base = ((int64_t)b * s.H + h) * P * N;
 
-    // issue the state loads first: they are the long-latency part
-    float4 st[ROWS_PER_LANE];
-#pragma unroll
-    for (int i = 0; i < ROWS_PER_LANE; ++i) {
-        const int p = rg + 8 * i;
-        st[i] = (p < P) ? *reinterpret_cast<const float4 *>(state_in + base + (int64_t)p * N + n4)
-                        : make_float4(0.f, 0.f, 0.f, 0.f);
-    }
-
-    route_and_mix(logits + (int64_t)b * s.E, Be + (int64_t)b * s.E * s.G * N,
-                  Ce + (int64_t)b * s.E * s.G * N, s.E, s.K, s.G, N, g, sB, sC, s_idx, s_w, tid);
-    if (idx_out && h == 0 && tid < s.K) idx_out[(int64_t)b * s.K + tid] = s_idx[tid];
-
+    f32x4_t v0 = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t *>(state_in + base + (int64_t)q0 * N + n4));
+    f32x4_t v1 = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t *>(state_in + base + (int64_t)q1 * N + n4));
+    const float *mix = bc + ((int64_t)b * s.G + g) * 2 * N + n4;
+    const f32x4_t bm = *reinterpret_cast<const f32x4_t *>(mix);
+    const f32x4_t cm = *reinterpret_cast<const f32x4_t *>(mix + N);
     const float dtv = to_float(dt[(int64_t)b * s.H + h]);
+    const T *xr = x + ((int64_t)b * s.H + h) * P;
+    const float x0 = to_float(xr[q0]), x1 = to_float(xr[q1]);
     const float decay = expf(dtv * A[h]);
     const float dsk = D ? D[h] : 0.f;
-    const float4 bm = *reinterpret_cast<const float4 *>(sB + n4);
-    const float4 cm = *reinterpret_cast<const float4 *>(sC + n4);
-
+    const float u0 = dtv * x0, u1 = dtv * x1;
 #pragma unroll
-    for (int i = 0; i < ROWS_PER_LANE; ++i) {
-        const int p = rg + 8 * i;
-        if (p < P) {   // uniform over each 32-lane half
-            const float xv = to_float(x[((int64_t)b * s.H + h) * P + p]);
-            const float u = dtv * xv;
-            float4 v = st[i];
-            v.x = decay * v.x + u * bm.x;
-            v.y = decay * v.y + u * bm.y;
-            v.z = decay * v.z + u * bm.z;
-            v.w = decay * v.w + u * bm.w;
-            *reinterpret_cast<float4 *>(state_out + base + (int64_t)p * N + n4) = v;
-            float part = (v.x * cm.x + v.y * cm.y) + (v.z * cm.z + v.w * cm.w);
+    for (int q = 0; q < 4; ++q) {
+        v0[q] = decay * v0[q] + u0 * bm[q];
+        v1[q] = decay * v1[q] + u1 * bm[q];
+    }
+    float part0 = (v0[0] * cm[0] + v0[1] * cm[1]) + (v0[2] * cm[2] + v0[3] * cm[3]);
+    float part1 = (v1[0] * cm[0] + v1[1] * cm[1]) + (v1[2] * cm[2] + v1[3] * cm[3]);
+    if (ok0) __builtin_nontemporal_store(v0, reinterpret_cast<f32x4_t *>(state_out + base + (int64_t)p0 * N + n4));
+    if (ok1) __builtin_nontemporal_store(v1, reinterpret_cast<f32x4_t *>(state_out + base + (int64_t)p1 * N + n4));
 #pragma unroll
-            for (int off = 16; off >= 1; off >>= 1) part += __shfl_xor(part, off);
-            if ((tid & 31) == 0) y[((int64_t)b * s.H + h) * P + p] = from_float<T>(part + dsk * xv);
-        }
+    for (int off = 16; off >= 1; off >>= 1) {
+        part0 += __shfl_xor(part0, off);
+        part1 += __shfl_xor(part1, off);
+    }
+    if ((tid & 31) == 0) {
+        T *yr = y + ((int64_t)b * s.H + h) * P;
+        if (ok0) yr[p0] = from_float<T>(part0 + dsk * x0);
+        if (ok1) yr[p1] = from_float<T>(part1 + dsk * x1);
     }
 }
 
-// ---- any N: a wave walks one state row at a time ----------------------------------------
+// ---- state update, any N: block = (b, h), a wave walks one state row at a time ------------
 template <typename T>
 __global__ void __launch_bounds__(STEP_THREADS)
-step_kernel_generic(const float *state_in, float *state_out, const T *__restrict__ x,
-                    const T *__restrict__ dt, const float *__restrict__ A, const float *__restrict__ D,
-                    const T *__restrict__ Be, const T *__restrict__ Ce, const T *__restrict__ logits,
-                    T *__restrict__ y, int32_t *__restrict__ idx_out, Shape s)
+step_update_generic_kernel(const float *state_in, float *state_out, const T *__restrict__ x,
+                           const T *__restrict__ dt, const float *__restrict__ A,
+                           const float *__restrict__ D, const float *__restrict__ bc,
+                           T *__restrict__ y, Shape s)
 {
-    __shared__ float sB[SWIMBA_MAX_DSTATE], sC[SWIMBA_MAX_DSTATE], s_w[SWIMBA_MAX_TOPK];
-    __shared__ int32_t s_idx[SWIMBA_MAX_TOPK];
     const int b = blockIdx.x / s.H, h = blockIdx.x % s.H, g = (h * s.G) / s.H;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int N = s.N, P = s.P;
     const int64_t base = ((int64_t)b * s.H + h) * P * N;
-
-    route_and_mix(logits + (int64_t)b * s.E, Be + (int64_t)b * s.E * s.G * N,
-                  Ce + (int64_t)b * s.E * s.G * N, s.E, s.K, s.G, N, g, sB, sC, s_idx, s_w, tid);
-    if (idx_out && h == 0 && tid < s.K) idx_out[(int64_t)b * s.K + tid] = s_idx[tid];
-
+    const float *bm = bc + ((int64_t)b * s.G + g) * 2 * N;
+    const float *cm = bm + N;
     const float dtv = to_float(dt[(int64_t)b * s.H + h]);
     const float decay = expf(dtv * A[h]);
     const float dsk = D ? D[h] : 0.f;
@@ -115,9 +121,9 @@ step_kernel_generic(const float *state_in, float *state_out, const T *__restrict
         const float u = dtv * xv;
         float part = 0.f;
         for (int n = lane; n < N; n += 64) {
-            const float v = decay * state_in[base + (int64_t)p * N + n] + u * sB[n];
+            const float v = decay * state_in[base + (int64_t)p * N + n] + u * bm[n];
             state_out[base + (int64_t)p * N + n] = v;
-            part += v * sC[n];
+            part += v * cm[n];
         }
 #pragma unroll
         for (int off = 32; off >= 1; off >>= 1) part += __shfl_xor(part, off);
@@ -129,19 +135,21 @@ template <typename T>
 static swimba_status launch_step_t(const Shape &s, const float *state_in, float *state_out,
                                    const void *x, const void *dt, const float *A, const float *D,
                                    const void *Be, const void *Ce, const void *logits, void *y,
-                                   int32_t *idx, hipStream_t st)
+                                   int32_t *idx, float *bc, hipStream_t st)
 {
     const int64_t blocks = (int64_t)s.B * s.H;
     if (blocks == 0) return SWIMBA_OK;
-    dim3 grid((unsigned)blocks), block(STEP_THREADS);
-    if (s.N == 128 && s.P <= 64)
-        hipLaunchKernelGGL((step_kernel_n128<T, 8>), grid, block, 0, st, state_in, state_out,
-                           (const T *)x, (const T *)dt, A, D, (const T *)Be, (const T *)Ce,
-                           (const T *)logits, (T *)y, idx, s);
+    hipLaunchKernelGGL(step_mix_kernel<T>, dim3((unsigned)(s.B * s.G)), dim3(128), 0, st,
+                       (const T *)Be, (const T *)Ce, (const T *)logits, bc, idx, s);
+    SWIMBA_CHECK_LAUNCH();
+    const int slices = (s.P + 15) / 16;
+    if (s.N == 128 && blocks * slices < (1ll << 31))
+        hipLaunchKernelGGL(step_update_n128_kernel<T>, dim3((unsigned)(blocks * slices)),
+                           dim3(STEP_THREADS), 0, st, state_in, state_out, (const T *)x, (const T *)dt,
+                           A, D, bc, (T *)y, s, slices);
     else
-        hipLaunchKernelGGL(step_kernel_generic<T>, grid, block, 0, st, state_in, state_out,
-                           (const T *)x, (const T *)dt, A, D, (const T *)Be, (const T *)Ce,
-                           (const T *)logits, (T *)y, idx, s);
+        hipLaunchKernelGGL(step_update_generic_kernel<T>, dim3((unsigned)blocks), dim3(STEP_THREADS), 0,
+                           st, state_in, state_out, (const T *)x, (const T *)dt, A, D, bc, (T *)y, s);
     SWIMBA_CHECK_LAUNCH();
     return SWIMBA_OK;
 }
@@ -149,11 +157,11 @@ static swimba_status launch_step_t(const Shape &s, const float *state_in, float 
 swimba_status launch_step(const Shape &s, int io_dtype, const float *state_in, float *state_out,
                           const void *x, const void *dt, const float *A, const float *D,
                           const void *Be, const void *Ce, const void *logits, void *y, int32_t *idx,
-                          hipStream_t st)
+                          float *bc, hipStream_t st)
 {
     if (io_dtype == SWIMBA_BF16)
-        return launch_step_t<bf16>(s, state_in, state_out, x, dt, A, D, Be, Ce, logits, y, idx, st);
-    return launch_step_t<float>(s, state_in, state_out, x, dt, A, D, Be, Ce, logits, y, idx, st);
+        return launch_step_t<bf16>(s, state_in, state_out, x, dt, A, D, Be, Ce, logits, y, idx, bc, st);
+    return launch_step_t<float>(s, state_in, state_out, x, dt, A, D, Be, Ce, logits, y, idx, bc, st);
 }
 
 }  // namespace swimba

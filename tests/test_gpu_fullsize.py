@@ -49,9 +49,12 @@ def test_decode_1024_steps(G):
     state = d["state"].clone()
     ys = torch.empty_like(xs)
     idx = torch.empty((steps, w.batch, w.top_k), dtype=torch.int32, device="cuda:0")
+    ws = torch.empty(sw.swimba_step_workspace_bytes(
+        sw.make_dims(w.batch, 1, w.nheads, w.headdim, w.dstate, w.ngroups, w.nexperts, w.top_k, 0, torch.bfloat16)),
+        dtype=torch.uint8, device="cuda:0")
     for t in range(steps):
         sw.swimba_step(state, xs[t], dts[t], d["A"], d["D"], Bs[t], Cs[t], gs[t], w.top_k,
-                       y=ys[t], topk_idx=idx[t])
+                       y=ys[t], topk_idx=idx[t], workspace=ws)
     torch.cuda.synchronize()
     # 1024 steps of the recurrence == the sequential forward from the same initial state
     ref = orc.mixer_fwd(p["x"], p["dt"], p["A"], p["D"], p["B_experts"], p["C_experts"],

@@ -81,8 +81,11 @@ def test_null_and_workspace_errors_enqueue_nothing():
     # aligned and large enough workspace, but tensor pointers missing
     assert lib.swimba_mixer_fwd(ctypes.byref(d), *([None] * 12), 4096, 1 << 30, None) == 1
     # step: seqlen must be 1; then NULL pointers
-    assert lib.swimba_step(ctypes.byref(d), *([None] * 11), None) == 2
-    assert lib.swimba_step(ctypes.byref(dims(seqlen=1)), *([None] * 11), None) == 1
+    assert lib.swimba_step(ctypes.byref(d), *([None] * 11), None, 0, None) == 2
+    d1 = dims(seqlen=1)
+    assert lib.swimba_step(ctypes.byref(d1), *([None] * 11), None, 0, None) == 5
+    assert sw.swimba_step_workspace_bytes(d1) >= 1 * 1 * 16 * 2 * 4 and sw.swimba_step_workspace_bytes(d) == 0
+    assert lib.swimba_step(ctypes.byref(d1), *([None] * 11), 4096, 1 << 20, None) == 1
     assert lib.swimba_router_topk(10, 4, 5, 0, None, None, None, None) == 2
     assert lib.swimba_router_topk(10, 4, 2, 0, None, None, None, None) == 1
     assert lib.swimba_router_topk(0, 4, 2, 0, None, None, None, None) == 0
