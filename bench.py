@@ -149,10 +149,10 @@ def main() -> int:
         # mixed B (bf16) and the causal C.B^T tiles
         "mix": ("hbm", T * (E * 2 + k * 8 + 2 * k * G * N * 2 + 2 * G * N * 2)
                 + nchunks * G * (Q // 32) * (Q // 32 + 1) // 2 * 2048),
-        # cumsum + chunk state: reads x, dt, mixed B; writes cs and the fp32 chunk states
-        "chunk_state": ("hbm", T * (H * P * 2 + H * 2 + G * N * 2 + H * 4) + state_elems * 4),
-        # reads fp32 chunk states, writes them back (carried states) plus the bf16 copy
-        "state_scan": ("hbm", state_elems * (4 + 4 + 2)),
+        # cumsum + chunk state: reads x, dt, mixed B; writes cs and the bf16 chunk states
+        "chunk_state": ("hbm", T * (H * P * 2 + H * 2 + G * N * 2 + H * 4) + state_elems * 2),
+        # reads the bf16 chunk states, writes the bf16 carried states in place, and h_final
+        "state_scan": ("hbm", state_elems * (2 + 2) + w.batch * H * P * N * 4),
         # masked (C B^T) X per head and C.H per head, dense counts (C.B^T itself is in "mix")
         "output": ("mfma", 2.0 * T * Q * P * H + 2.0 * T * N * P * H),
     }

@@ -73,9 +73,10 @@ typedef struct {
     size_t topk_w;    /* (B,L,k) fp32  : their un-renormalised softmax weights      */
     size_t cs;        /* (B,nc,H,Q) fp32 : inclusive cumsum of dt*A inside each chunk */
     size_t states;    /* (B,nc,H,P,N) fp32 : chunk states S_c, then (after the scan)
-                         the state carried INTO chunk c                             */
+                         the state carried INTO chunk c; fp32 path only (empty on the
+                         bf16 MFMA path)                                            */
     /* bf16 MFMA path only (each equals the next offset when unused): */
-    size_t states_lp; /* (B,nc,H,P,N) bf16 copy of the carried states                 */
+    size_t states_lp; /* (B,nc,H,P,N) bf16 : chunk states S_c, then the carried states  */
     size_t cmix;      /* (B,nc,G,Q/32,8,64,8) bf16 : mixed C rows, MFMA operand layout   */
     size_t bmix_t8;   /* (B,nc,G,Q/8,N,8) bf16 : mixed B, 8 consecutive tokens innermost */
     size_t cb;        /* (B,nc,G,NP,2,64,8) bf16 : causal 32x32 tiles of Bmix.Cmix^T in
@@ -133,8 +134,9 @@ swimba_status swimba_router_topk(int64_t tokens, int32_t nexperts, int32_t top_k
  * is valid: nothing is computed (h_final = h0 or zeros when L == 0).
  * Arithmetic: fp32 throughout for io_dtype fp32.  For bf16 io with
  * P = 64, N = 128 and Q in {64,128,256} the contractions run on bf16 MFMA
- * with fp32 accumulation (mixed streams, decay-weighted x, the decay-masked
- * C.B^T block and the carried states are rounded to bf16 as operands);
+ * with fp32 accumulation (mixed streams, decay-weighted x, the C.B^T block before and
+ * after the decay mask, the chunk states and the carried states are rounded to bf16
+ * as operands; the inter-chunk recurrence itself runs in fp32);
  * other bf16 shapes use the fp32 kernels.
  */
 swimba_status swimba_mixer_fwd(const swimba_dims *dims, const void *x, const void *dt,
@@ -151,8 +153,9 @@ swimba_status swimba_mixer_fwd(const swimba_dims *dims, const void *x, const voi
  *   cumsum      : dt, A  -> ws.cs                (per-chunk cumsum of dt*A)
  *   chunk_state : x, dt, B_experts, ws.{topk_*,cs} -> ws.states = S_c
  *                 S_c = sum_j exp(cs_last - cs_j) dt_j x_j (x) Bmix_j
- *   state_scan  : ws.states (S_c -> state carried into chunk c, in place),
- *                 h0, ws.cs -> h_final (and ws.states_lp on the bf16 MFMA path)
+ *   state_scan  : ws.states (ws.states_lp on the bf16 MFMA path): S_c -> state carried
+ *                 into chunk c, in place; h0, ws.cs -> h_final.  The running state is
+ *                 fp32 in registers on both paths.
  *   output      : x, dt, D, B/C_experts, ws.* -> y
  *                 y_i = sum_{j<=i} (Cmix_i.Bmix_j) exp(cs_i - cs_j) dt_j x_j
  *                       + exp(cs_i) Cmix_i . H_c + D x_i

@@ -270,10 +270,12 @@ def workspace_views(dims: swimba_dims, workspace: torch.Tensor):
         "topk_idx": view(lo.topk_idx, B * L * K, torch.int32, (B, L, K)),
         "topk_w": view(lo.topk_w, B * L * K, torch.float32, (B, L, K)),
         "cs": view(lo.cs, B * nc * H * Q, torch.float32, (B, nc, H, Q)),
-        "states": view(lo.states, B * nc * H * P * N, torch.float32, (B, nc, H, P, N)),
     }
+    # chunk / carried states: fp32 on the fp32 path, bf16 on the bf16 MFMA path
     if lo.states_lp != lo.cmix:
-        out["states_lp"] = view(lo.states_lp, B * nc * H * P * N, torch.bfloat16, (B, nc, H, P, N))
+        out["states"] = view(lo.states_lp, B * nc * H * P * N, torch.bfloat16, (B, nc, H, P, N))
+    else:
+        out["states"] = view(lo.states, B * nc * H * P * N, torch.float32, (B, nc, H, P, N))
     return out
 
 

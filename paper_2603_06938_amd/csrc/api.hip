@@ -49,8 +49,9 @@ static void layout_of(const swimba_dims *d, swimba_ws_layout *o)
     o->topk_w = off;   off = align_up(off + T * s.K * sizeof(float), 256);
     o->cs = off;       off = align_up(off + (size_t)s.B * s.nc * s.H * s.Q * sizeof(float), 256);
     const size_t nstate = (size_t)s.B * s.nc * s.H * s.P * s.N;
-    o->states = off;   off = align_up(off + nstate * sizeof(float), 256);
     const bool mf = use_mfma_path(d);
+    o->states = off;
+    if (!mf) off = align_up(off + nstate * sizeof(float), 256);
     const size_t mixed = (size_t)s.B * s.nc * s.Q * s.G * s.N * sizeof(uint16_t);
     const size_t nt = (size_t)s.Q / 32;
     o->states_lp = off;
@@ -179,7 +180,7 @@ swimba_status swimba_stage_chunk_state(const swimba_dims *dims, const void *x, c
     if (!x || !dt || !A || !B_experts) return SWIMBA_ERR_NULL;
     const Shape s = make_shape(dims);
     if (use_mfma_path(dims))
-        return launch_chunk_state_mfma(s, x, dt, A, ws.bmix_t8, ws.cs, ws.states,
+        return launch_chunk_state_mfma(s, x, dt, A, ws.bmix_t8, ws.cs, ws.states_lp,
                                        (hipStream_t)hip_stream);
     return launch_chunk_state_generic(s, dims->io_dtype, x, dt, B_experts, ws.idx, ws.w, ws.cs,
                                       ws.states, (hipStream_t)hip_stream);
@@ -192,7 +193,10 @@ swimba_status swimba_stage_state_scan(const swimba_dims *dims, const float *h0, 
     swimba_status st = carve(dims, workspace, workspace_bytes, &ws);
     if (st != SWIMBA_OK) return st;
     if (dims->batch == 0) return SWIMBA_OK;
-    return launch_state_scan(make_shape(dims), h0, h_final, ws.states, ws.states_lp, ws.cs,
+    if (use_mfma_path(dims))
+        return launch_state_scan_lp(make_shape(dims), h0, h_final, ws.states_lp, ws.cs,
+                                    (hipStream_t)hip_stream);
+    return launch_state_scan(make_shape(dims), h0, h_final, ws.states, nullptr, ws.cs,
                              (hipStream_t)hip_stream);
 }
 
@@ -254,7 +258,8 @@ swimba_status swimba_mixer_fwd(const swimba_dims *dims, const void *x, const voi
     }
     // with L == 0 the scan only copies h0 (or zeros) to h_final
     if (dims->batch > 0 && (T > 0 || h_final)) {
-        st = launch_state_scan(s, h0, h_final, ws.states, ws.states_lp, ws.cs, stream);
+        st = mf ? launch_state_scan_lp(s, h0, h_final, ws.states_lp, ws.cs, stream)
+                : launch_state_scan(s, h0, h_final, ws.states, nullptr, ws.cs, stream);
         if (st != SWIMBA_OK) return st;
     }
     if (T > 0) {

@@ -80,7 +80,9 @@ swimba_status launch_mix_cb_mfma(const Shape &s, const void *Be, const void *Ce,
                                  int32_t *idx, float *w, void *cmix, void *bmix_t8, void *cb,
                                  hipStream_t st);
 swimba_status launch_chunk_state_mfma(const Shape &s, const void *x, const void *dt, const float *A,
-                                      const void *bmix_t8, float *cs, float *states, hipStream_t st);
+                                      const void *bmix_t8, float *cs, void *states_lp, hipStream_t st);
+swimba_status launch_state_scan_lp(const Shape &s, const float *h0, float *h_final, void *states_lp,
+                                   const float *cs, hipStream_t st);
 swimba_status launch_output_mfma(const Shape &s, const void *x, const void *dt, const float *D,
                                  const void *cmix, const void *cb, const float *cs,
                                  const void *states_lp, void *y, hipStream_t st);

@@ -264,13 +264,13 @@ swimba_status launch_mix_cb_mfma(const Shape &s, const void *Be, const void *Ce,
 // Per head the kernel also computes the chunk's inclusive cumsum cs of dt*A (block
 // scan) and stores it for the scan and output kernels.
 // The coefficient-weighted x tile is staged transposed ([p][j]); wave w owns columns
-// n = 32w..32w+31 and both 32-row halves of p.
+// n = 32w..32w+31 and both 32-channel halves of p.  The chunk state is stored in bf16.
 // =========================================================================================
 template <int Q>
 __global__ void __launch_bounds__(MTHREADS)
 chunk_state_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ dt,
                         const float *__restrict__ A, const uint16_t *__restrict__ bmix_t8,
-                        float *__restrict__ cs, float *__restrict__ states, Shape s, int ipw,
+                        float *__restrict__ cs, uint16_t *__restrict__ states_lp, Shape s, int ipw,
                         int nruns, int total, int nblocks)
 {
     constexpr int STR = Q + 8;                    // row stride of the transposed x tile (elements)
@@ -300,10 +300,14 @@ chunk_state_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restri
     const int tokstride = s.H * MP;
     const int tq = min(tid, Q - 1);
 
-    // B operand: lane (n = 32*wave + l32, kg), k-step ks -> tokens 16ks + 8kg + 0..7
+    // The tile is computed transposed, S^T[n][p] = Bmix^T . (coef x): the mixed B is the A
+    // operand.  Operand row l32 holds column n = 32*wave + prow, so that accumulator row
+    // 8a + 4k + b is n = 32*wave + 16k + 4a + b: a lane ends up with 16 consecutive n of one
+    // channel p (two 16-byte bf16 stores).  k-step ks covers tokens 16ks + 8kg + 0..7.
+    const int prow = 16 * ((l32 >> 2) & 1) + 4 * (l32 >> 3) + (l32 & 3);
     uint4 bfrag[KS];
     {
-        const uint16_t *src = bmix_t8 + (bcg * (Q / 8) * MN + (wave * 32 + l32)) * 8;
+        const uint16_t *src = bmix_t8 + (bcg * (Q / 8) * MN + (wave * 32 + prow)) * 8;
 #pragma unroll
         for (int ks = 0; ks < KS; ++ks)
             bfrag[ks] = *reinterpret_cast<const uint4 *>(src + (2 * ks + kg) * MN * 8);
@@ -384,15 +388,19 @@ chunk_state_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restri
             const int kb = ks * 16 + kg * 8;
             const uint4 a0 = *reinterpret_cast<const uint4 *>(srcX + l32 * STR + kb);
             const uint4 a1 = *reinterpret_cast<const uint4 *>(srcX + (32 + l32) * STR + kb);
-            acc0 = mfma32(a0, bfrag[ks], acc0);
-            acc1 = mfma32(a1, bfrag[ks], acc1);
+            acc0 = mfma32(bfrag[ks], a0, acc0);
+            acc1 = mfma32(bfrag[ks], a1, acc1);
         }
-        float *out = states + (((int64_t)b * s.nc + c) * s.H + h) * MP * MN + wave * 32 + l32;
+        // chunk state as bf16 (it is only ever an MFMA operand or a summand of the fp32 scan)
+        uint16_t *out = states_lp + ((((int64_t)b * s.nc + c) * s.H + h) * MP + l32) * MN + wave * 32 + 16 * kg;
+        {
+            float t0[16], t1[16];
 #pragma unroll
-        for (int v = 0; v < 16; ++v) {
-            const int p = 8 * (v >> 2) + 4 * kg + (v & 3);
-            out[p * MN] = acc0[v];
-            out[(32 + p) * MN] = acc1[v];
+            for (int v = 0; v < 16; ++v) { t0[v] = acc0[v]; t1[v] = acc1[v]; }
+            *reinterpret_cast<uint4 *>(out) = pack8(t0);
+            *reinterpret_cast<uint4 *>(out + 8) = pack8(t0 + 8);
+            *reinterpret_cast<uint4 *>(out + 32 * MN) = pack8(t1);
+            *reinterpret_cast<uint4 *>(out + 32 * MN + 8) = pack8(t1 + 8);
         }
         if (more) stage((k + 1) & 1, h + 1);
         __syncthreads();
@@ -401,7 +409,7 @@ chunk_state_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restri
 
 template <int Q>
 static swimba_status launch_cs_q(const Shape &s, const void *x, const void *dt, const float *A,
-                                 const void *bmix_t8, float *cs, float *states, hipStream_t st)
+                                 const void *bmix_t8, float *cs, void *states_lp, hipStream_t st)
 {
     const int hpg = s.H / s.G;
     // heads per workgroup: as many as possible while at least ~2 workgroups per CU remain
@@ -421,18 +429,18 @@ static swimba_status launch_cs_q(const Shape &s, const void *x, const void *dt, 
     }
     hipLaunchKernelGGL(chunk_state_mfma_kernel<Q>, dim3(nblocks), dim3(MTHREADS), shm, st,
                        (const uint16_t *)x, (const uint16_t *)dt, A, (const uint16_t *)bmix_t8, cs,
-                       states, s, ipw, nruns, (int)total, nblocks);
+                       (uint16_t *)states_lp, s, ipw, nruns, (int)total, nblocks);
     SWIMBA_CHECK_LAUNCH();
     return SWIMBA_OK;
 }
 
 swimba_status launch_chunk_state_mfma(const Shape &s, const void *x, const void *dt, const float *A,
-                                      const void *bmix_t8, float *cs, float *states, hipStream_t st)
+                                      const void *bmix_t8, float *cs, void *states_lp, hipStream_t st)
 {
     switch (s.Q) {
-    case 64: return launch_cs_q<64>(s, x, dt, A, bmix_t8, cs, states, st);
-    case 128: return launch_cs_q<128>(s, x, dt, A, bmix_t8, cs, states, st);
-    case 256: return launch_cs_q<256>(s, x, dt, A, bmix_t8, cs, states, st);
+    case 64: return launch_cs_q<64>(s, x, dt, A, bmix_t8, cs, states_lp, st);
+    case 128: return launch_cs_q<128>(s, x, dt, A, bmix_t8, cs, states_lp, st);
+    case 256: return launch_cs_q<256>(s, x, dt, A, bmix_t8, cs, states_lp, st);
     }
     return SWIMBA_ERR_UNSUPPORTED;
 }

@@ -47,6 +47,7 @@ def test_workspace_query_and_layout():
     # the bf16 MFMA shape carries a low-precision copy of the states
     m = dims(headdim=64, dstate=128, chunk=256, io_dtype=1, seqlen=512)
     lm = sw.swimba_mixer_workspace_layout(m)
+    assert lm.states_lp == lm.states          # no fp32 states on the MFMA path
     assert lm.cmix - lm.states_lp >= 2 * 4 * 64 * 128 * 2
     assert lm.bmix_t8 - lm.cmix >= 512 * 128 * 2 and lm.cb - lm.bmix_t8 >= 512 * 128 * 2
     assert lm.total - lm.cb >= 2 * 36 * 2048
