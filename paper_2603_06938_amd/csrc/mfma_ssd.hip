@@ -76,6 +76,16 @@ __device__ __forceinline__ int xcd_logical_id(int bid, int nblocks)
 static inline int xcd_padded(int64_t total) { return (int)((total + 7) / 8 * 8); }
 
 __device__ __forceinline__ float fast_exp2(float v) { return __builtin_amdgcn_exp2f(v); }
+
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every
+// outstanding global load and store of the wave, which would drain the prefetches and
+// the result stores these kernels deliberately keep in flight across barriers.
+__device__ __forceinline__ void lds_barrier()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
 constexpr float LOG2E = 1.4426950408889634f;
 
 // Mixed row of one token for MFMA use: lane (row, kg) gets, for ks = 0..7, the 8
@@ -162,7 +172,7 @@ mix_cb_kernel(const uint16_t *__restrict__ Be, const uint16_t *__restrict__ Ce,
             for (int rr = 0; rr < K; ++rr) { s_idx[t * K + rr] = 0; s_w[t * K + rr] = 0.f; }
         }
     }
-    __syncthreads();
+    lds_barrier();
 
     // ---- (a) mixed B of the two owned tiles, 8 tokens innermost; a lane does 4 tokens x 8 n ----
     {
@@ -341,7 +351,7 @@ chunk_state_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restri
             if (lane >= off) incl += v;
         }
         if (lane == 63) s_part[buf * 4 + wave] = incl;
-        __syncthreads();
+        lds_barrier();
         {
             float base = 0.f;
 #pragma unroll
@@ -356,7 +366,7 @@ chunk_state_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restri
             cs[(((int64_t)b * s.nc + c) * s.H + h) * Q + tid] = incl;
             s_coef[buf * Q + tid] = dtv * fast_exp2((cs_last - incl) * LOG2E);
         }
-        __syncthreads();
+        lds_barrier();
         uint16_t *dstX = sXt + buf * MP * STR;
 #pragma unroll
         for (int it = 0; it < XU; ++it) {
@@ -376,7 +386,7 @@ chunk_state_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restri
 
     issue_loads(h0);
     stage(0, h0);
-    __syncthreads();
+    lds_barrier();
     for (int k = 0; k < count; ++k) {
         const int h = h0 + k;
         const bool more = (k + 1 < count);
@@ -403,7 +413,7 @@ chunk_state_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restri
             *reinterpret_cast<uint4 *>(out + 32 * MN + 8) = pack8(t1 + 8);
         }
         if (more) stage((k + 1) & 1, h + 1);
-        __syncthreads();
+        lds_barrier();
     }
 }
 
@@ -553,7 +563,7 @@ output_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ 
         const int row = (tid >> 4) + (NTHR / 16) * pass, piece = tid & 15;
         *reinterpret_cast<uint4 *>(sH + row * HSTR + piece * 8) = hreg[pass];
     }
-    __syncthreads();
+    lds_barrier();
     if (tid < Q) s_f[tid] = fast_exp2(s_cs[(tid | 31)] - cs_reg);
 #pragma unroll
     for (int it = 0; it < XU; ++it) {
@@ -570,7 +580,7 @@ output_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ 
         *reinterpret_cast<uint4 *>(sX + (2 * p2) * XSTR + 16 * t16 + 8 * kgx) = pack8(xa);
         *reinterpret_cast<uint4 *>(sX + (2 * p2 + 1) * XSTR + 16 * t16 + 8 * kgx) = pack8(xb);
     }
-    __syncthreads();
+    lds_barrier();
 
     const float dsk = D ? D[h] : 0.f;
     const uint16_t *sXr0 = sX + prow * XSTR + 8 * kg;          // operand rows of the two channel halves
@@ -667,7 +677,7 @@ output_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ 
         }
         // ---- y = acc + D x.  The wave's 32 x 64 tile goes through LDS (the x^T tile is
         // dead by now) so that every global access is a full 128-byte row. ----
-        __syncthreads();
+        lds_barrier();
         // scratch: 32 rows x 8 pieces of 16 bytes per wave, piece index XOR-swizzled by the row
         static_assert(NT * 32 * MP * 2 <= MP * XSTR * 2, "epilogue scratch must fit in the x^T tile");
         constexpr int YSTR = MP;
@@ -683,7 +693,7 @@ output_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ 
             *reinterpret_cast<uint4 *>(dst + (((4 + 2 * kg) ^ sw) << 3)) = pack8(a1);
             *reinterpret_cast<uint4 *>(dst + (((5 + 2 * kg) ^ sw) << 3)) = pack8(a1 + 8);
         }
-        __syncthreads();
+        lds_barrier();
 #pragma unroll
         for (int q4 = 0; q4 < 4; ++q4) {
             const int row = erow + 8 * q4, i = I * 32 + row;
