@@ -464,7 +464,7 @@ swimba_status launch_chunk_state_mfma(const Shape &s, const void *x, const void 
 // Everything is computed transposed, Y^T[p][i] (accumulator rows = channels, columns =
 // tokens), so that every per-token factor is a per-lane scalar:
 //   Y^T  = H_c . Cmix^T  scaled by exp(cs_i)                       (A = H_c rows, B = Cmix regs)
-//   Y^T += (dt x)^T . M^T,  M^T[j][i] = G^T[j][i] * decay(i,j)      (A = x^T from LDS, B = M^T)
+//   Y^T += x^T . M^T,  M^T[j][i] = G^T[j][i] * decay(i,j) * dt_j    (A = x^T from LDS, B = M^T)
 // The G^T tile arrives from `cb` in accumulator layout (rows j, cols i), which is also
 // a valid B-operand layout once the k index (j) is permuted; x^T is staged in LDS with
 // the same permutation (within 16 tokens: bits 2 and 3 swapped).
@@ -519,7 +519,9 @@ output_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ 
     // ---- issue every global load of the prologue before the first barrier ----
     // (indices are clamped instead of branching, so that all loads go out back to back)
     const int tq = min(tid, Q - 1);
-    const float cs_raw = cs[(((int64_t)b * s.nc + c) * s.H + h) * Q + tq];
+    const float *csr = cs + (((int64_t)b * s.nc + c) * s.H + h) * Q;
+    const float cs_raw = csr[tq];
+    const float cs_end = csr[tq | 31];           // cs at the last token of this token's tile
     const uint16_t dt_raw = dt[(tok0 + min(tq, valid - 1)) * s.H + h];
     constexpr int HPASS = 64 * 16 / NTHR;      // 16-byte pieces of the state tile per lane
     uint4 hreg[HPASS];
@@ -531,7 +533,7 @@ output_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ 
             hreg[pass] = *reinterpret_cast<const uint4 *>(Hc + row * MN + piece * 8);
         }
     }
-    // dt_j x_j staging: unit = (8 tokens in operand order) x (2 channels)
+    // x staging: unit = (8 tokens in operand order) x (2 channels)
     constexpr int XU = (Q / 8) * 32 / NTHR;
     uint32_t xv[XU][8];
 #pragma unroll
@@ -553,32 +555,36 @@ output_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ 
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) cfrag[ks] = *reinterpret_cast<const uint4 *>(src + ks * 64 * 8);
     }
-    const float cs_reg = cs_raw * LOG2E;
+    // per-token tables: cs (times log2 e), dt, and dt * exp(R_J - cs_j) for the tiles J < I.
+    // dt is applied through these tables (i.e. on the M^T operand), so x itself is staged
+    // unscaled: a pure bf16 transpose.
     if (tid < Q) {
-        s_cs[tid] = cs_reg;
-        s_dt[tid] = (tid < valid) ? to_float(bf16{dt_raw}) : 0.f;
+        const float dtv = (tid < valid) ? to_float(bf16{dt_raw}) : 0.f;
+        s_cs[tid] = cs_raw * LOG2E;
+        s_dt[tid] = dtv;
+        s_f[tid] = dtv * fast_exp2((cs_end - cs_raw) * LOG2E);
     }
 #pragma unroll
     for (int pass = 0; pass < HPASS; ++pass) {
         const int row = (tid >> 4) + (NTHR / 16) * pass, piece = tid & 15;
         *reinterpret_cast<uint4 *>(sH + row * HSTR + piece * 8) = hreg[pass];
     }
-    lds_barrier();
-    if (tid < Q) s_f[tid] = fast_exp2(s_cs[(tid | 31)] - cs_reg);
 #pragma unroll
     for (int it = 0; it < XU; ++it) {
         const int u = tid + it * NTHR;
         const int p2 = u & 31, gi = u >> 5;
         const int t16 = gi >> 1, kgx = gi & 1;
-        float xa[8], xb[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const float d = s_dt[16 * t16 + 8 * (e >> 2) + 4 * kgx + (e & 3)];
-            xa[e] = bf_lo(xv[it][e]) * d;
-            xb[e] = bf_hi(xv[it][e]) * d;
-        }
-        *reinterpret_cast<uint4 *>(sX + (2 * p2) * XSTR + 16 * t16 + 8 * kgx) = pack8(xa);
-        *reinterpret_cast<uint4 *>(sX + (2 * p2 + 1) * XSTR + 16 * t16 + 8 * kgx) = pack8(xb);
+        uint4 lo, hi;   // channel 2*p2 and 2*p2+1 of the unit's 8 tokens
+        lo.x = __builtin_amdgcn_perm(xv[it][1], xv[it][0], 0x05040100u);
+        lo.y = __builtin_amdgcn_perm(xv[it][3], xv[it][2], 0x05040100u);
+        lo.z = __builtin_amdgcn_perm(xv[it][5], xv[it][4], 0x05040100u);
+        lo.w = __builtin_amdgcn_perm(xv[it][7], xv[it][6], 0x05040100u);
+        hi.x = __builtin_amdgcn_perm(xv[it][1], xv[it][0], 0x07060302u);
+        hi.y = __builtin_amdgcn_perm(xv[it][3], xv[it][2], 0x07060302u);
+        hi.z = __builtin_amdgcn_perm(xv[it][5], xv[it][4], 0x07060302u);
+        hi.w = __builtin_amdgcn_perm(xv[it][7], xv[it][6], 0x07060302u);
+        *reinterpret_cast<uint4 *>(sX + (2 * p2) * XSTR + 16 * t16 + 8 * kgx) = lo;
+        *reinterpret_cast<uint4 *>(sX + (2 * p2 + 1) * XSTR + 16 * t16 + 8 * kgx) = hi;
     }
     lds_barrier();
 
@@ -627,6 +633,7 @@ output_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ 
             unpack8(m, u0);
             unpack8(m + 8, u1);
             if (J < I) {
+                // dt_j exp(R_J - cs_j) from the table, exp(cs_i - R_J) once per lane
                 const float *fj = s_f + J * 32 + 4 * kg;
                 const float ei = fast_exp2(csi - s_cs[J * 32 + 31]);
 #pragma unroll
@@ -639,15 +646,19 @@ output_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ 
                 }
             } else {
                 const float *cj = s_cs + J * 32 + 4 * kg;
+                const float *dj = s_dt + J * 32 + 4 * kg;
 #pragma unroll
                 for (int a = 0; a < 4; ++a) {
                     const float4 c4 = *reinterpret_cast<const float4 *>(cj + 8 * a);
+                    const float4 d4 = *reinterpret_cast<const float4 *>(dj + 8 * a);
                     const float cc[4] = {c4.x, c4.y, c4.z, c4.w};
+                    const float dd[4] = {d4.x, d4.y, d4.z, d4.w};
 #pragma unroll
                     for (int bb = 0; bb < 4; ++bb) {
                         const int jl = 8 * a + 4 * kg + bb;
-                        const float dcy = fast_exp2(fminf(csi - cc[bb], 0.f));
-                        m[4 * a + bb] = (l32 >= jl) ? m[4 * a + bb] * dcy : 0.f;
+                        // masked entries (j > i) get a hugely negative exponent: exp2 -> 0
+                        const float arg = (l32 >= jl) ? fminf(csi - cc[bb], 0.f) : -1.0e30f;
+                        m[4 * a + bb] *= fast_exp2(arg) * dd[bb];
                     }
                 }
             }
