@@ -174,19 +174,78 @@ mix_cb_kernel(const uint16_t *__restrict__ Be, const uint16_t *__restrict__ Ce,
     }
     lds_barrier();
 
-    // ---- (a) mixed B of the two owned tiles, 8 tokens innermost; a lane does 4 tokens x 8 n ----
+    // All gathers of the workgroup are independent once the routing is known: the loads of
+    // (a), (b) and of the first j tile of (c) are issued back to back before any of them is
+    // consumed (one memory latency instead of four).  Experts are taken two at a time.
+    auto row_loads = [&](uint4 (&v)[2][8], const uint16_t *tok, const int32_t *ix, int r0) {
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            const uint16_t *row = tok + ix[min(r0 + q, K - 1)] * estride + 64 * kg;
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) v[q][ks] = *reinterpret_cast<const uint4 *>(row + ks * 8);
+        }
+    };
+    auto row_accumulate = [&](float (&acc)[8][8], const uint4 (&v)[2][8], const float *wt, int r0) {
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            const float wr = (r0 + q < K) ? wt[r0 + q] : 0.f;
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) fma_bf16x8(acc[ks], v[q][ks], wr);
+        }
+    };
+    // mixed row (operand layout) of token j of stream S, given the loads of its first two experts
+    auto finish_row = [&](uint4 *frag, uint4 (&v)[2][8], const uint16_t *tok, int j) {
+        float acc[8][8];
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks)
+#pragma unroll
+            for (int e = 0; e < 8; ++e) acc[ks][e] = 0.f;
+        row_accumulate(acc, v, s_w + j * K, 0);
+        for (int r0 = 2; r0 < K; r0 += 2) {       // top_k > 2: the remaining experts, pair by pair
+            row_loads(v, tok, s_idx + j * K, r0);
+            row_accumulate(acc, v, s_w + j * K, r0);
+        }
+#pragma unroll
+        for (int ks = 0; ks < 8; ++ks) frag[ks] = pack8(acc[ks]);
+    };
+
+    // (a) mixed B of the two owned tiles, 8 tokens innermost; a lane does 4 tokens x 8 n
+    const int half = tid & 1, piece = (tid >> 1) & 15, jgl = (tid >> 5) & 3, sel = tid >> 7;
+    const int jg = tiles[sel] * 4 + jgl;                 // group of 8 tokens inside the chunk
+    uint4 va[4][2];
+#pragma unroll
+    for (int jj = 0; jj < 4; ++jj) {
+        const int j = jg * 8 + half * 4 + jj;
+        const uint16_t *rowbase = Bg + min(j, valid - 1) * tokstride + piece * 8;
+#pragma unroll
+        for (int q = 0; q < 2; ++q)
+            va[jj][q] = *reinterpret_cast<const uint4 *>(rowbase + s_idx[j * K + min(q, K - 1)] * estride);
+    }
+    // (b) mixed C rows of the owned tiles; (c) mixed B rows of the first j tile of this wave
+    // (a wave beyond the chunk's last j tile has no (c) work: its early load is clamped to a
+    // valid token so that the expert index it reads is a real one)
+    const int i0 = tiles[0] * 32 + l32, i1 = tiles[1] * 32 + l32;
+    const int jfirst = min(wave, tiles[1]) * 32 + l32;
+    const uint16_t *tokc0 = Cg + min(i0, valid - 1) * tokstride;
+    const uint16_t *tokc1 = Cg + min(i1, valid - 1) * tokstride;
+    const uint16_t *tokb = Bg + min(jfirst, valid - 1) * tokstride;
+    uint4 vc0[2][8], vc1[2][8], vb[2][8];
+    row_loads(vc0, tokc0, s_idx + i0 * K, 0);
+    row_loads(vc1, tokc1, s_idx + i1 * K, 0);
+    row_loads(vb, tokb, s_idx + jfirst * K, 0);
+
+    // ---- consume (a) ----
     {
-        const int half = tid & 1, piece = (tid >> 1) & 15, jgl = (tid >> 5) & 3, sel = tid >> 7;
-        const int jg = tiles[sel] * 4 + jgl;             // group of 8 tokens inside the chunk
         float acc[4][8];
 #pragma unroll
         for (int jj = 0; jj < 4; ++jj) {
 #pragma unroll
             for (int e = 0; e < 8; ++e) acc[jj][e] = 0.f;
             const int j = jg * 8 + half * 4 + jj;
+            fma_bf16x8(acc[jj], va[jj][0], s_w[j * K]);
+            fma_bf16x8(acc[jj], va[jj][1], K > 1 ? s_w[j * K + 1] : 0.f);
             const uint16_t *rowbase = Bg + min(j, valid - 1) * tokstride + piece * 8;
-#pragma unroll 2
-            for (int rr = 0; rr < K; ++rr)
+            for (int rr = 2; rr < K; ++rr)
                 fma_bf16x8(acc[jj], *reinterpret_cast<const uint4 *>(rowbase + s_idx[j * K + rr] * estride),
                            s_w[j * K + rr]);
         }
@@ -199,14 +258,12 @@ mix_cb_kernel(const uint16_t *__restrict__ Be, const uint16_t *__restrict__ Ce,
             *reinterpret_cast<uint2 *>(dst + e * 8) = pk;
         }
     }
-
-    // ---- (b) mixed C rows of the owned tiles as operand registers; wave 0 also stores them ----
+    // ---- consume (b): operand registers; waves 0 and 1 also store one tile each ----
     uint4 cfrag[2][8];
+    finish_row(cfrag[0], vc0, tokc0, i0);
+    finish_row(cfrag[1], vc1, tokc1, i1);
 #pragma unroll
     for (int sl = 0; sl < 2; ++sl) {
-        const int i = tiles[sl] * 32 + l32;
-        gather_mix_row(cfrag[sl], Cg + min(i, valid - 1) * tokstride, estride, s_idx + i * K,
-                       s_w + i * K, K, kg);
         if (wave == sl) {
             uint16_t *dst = cmix + (((bcg * NT + tiles[sl]) * 8) * 64 + lane) * 8;
 #pragma unroll
@@ -216,10 +273,11 @@ mix_cb_kernel(const uint16_t *__restrict__ Be, const uint16_t *__restrict__ Ce,
 
     // ---- (c) G^T tiles ----
     for (int J = wave; J <= tiles[1]; J += 4) {
-        uint4 bfrag[8];
         const int j = J * 32 + l32;
-        gather_mix_row(bfrag, Bg + min(j, valid - 1) * tokstride, estride, s_idx + j * K, s_w + j * K,
-                       K, kg);
+        const uint16_t *tok = Bg + min(j, valid - 1) * tokstride;
+        if (J != wave) row_loads(vb, tok, s_idx + j * K, 0);
+        uint4 bfrag[8];
+        finish_row(bfrag, vb, tok, j);
 #pragma unroll
         for (int sl = 0; sl < 2; ++sl) {
             const int I = tiles[sl];
