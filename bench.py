@@ -143,31 +143,36 @@ def main() -> int:
     T, H, P, N, G, E, k, Q = w.tokens, w.nheads, w.headdim, w.dstate, w.ngroups, w.nexperts, w.top_k, w.chunk
     nchunks = w.batch * ((w.seqlen + Q - 1) // Q)
     state_elems = nchunks * H * P * N
-    # algorithmic work per launch (dense counts)
+    # algorithmic work per launch: (HBM bytes, MFMA flops); see DESIGN.md "Measurement"
+    NT = Q // 32
+    cb_bytes = nchunks * G * (NT * (NT + 1) // 2) * 2048
     work = {
         # router + mixing: reads logits and the k active B and C rows; writes top-k, mixed C,
-        # mixed B (bf16) and the causal C.B^T tiles
-        "mix": ("hbm", T * (E * 2 + k * 8 + 2 * k * G * N * 2 + 2 * G * N * 2)
-                + nchunks * G * (Q // 32) * (Q // 32 + 1) // 2 * 2048),
+        # mixed B (bf16) and the causal C.B^T tiles; C.B^T on MFMA (dense count 2 T Q N G)
+        "mix": (T * (E * 2 + k * 8 + 2 * k * G * N * 2 + 2 * G * N * 2) + cb_bytes, 2.0 * T * Q * N * G),
         # cumsum + chunk state: reads x, dt, mixed B; writes cs and the bf16 chunk states
-        "chunk_state": ("hbm", T * (H * P * 2 + H * 2 + G * N * 2 + H * 4) + state_elems * 2),
+        "chunk_state": (T * (H * P * 2 + H * 2 + G * N * 2 + H * 4) + state_elems * 2, 2.0 * T * N * P * H),
         # reads the bf16 chunk states, writes the bf16 carried states in place, and h_final
-        "state_scan": ("hbm", state_elems * (2 + 2) + w.batch * H * P * N * 4),
-        # masked (C B^T) X per head and C.H per head, dense counts (C.B^T itself is in "mix")
-        "output": ("mfma", 2.0 * T * Q * P * H + 2.0 * T * N * P * H),
+        "state_scan": (state_elems * (2 + 2) + w.batch * H * P * N * 4, 0.0),
+        # reads x, dt, cs, carried states, mixed C, C.B^T tiles; writes y; masked (C B^T) X and
+        # C.H per head on MFMA (dense counts; causally skipped tiles are counted)
+        "output": (T * (2 * H * P * 2 + H * 2 + H * 4 + G * N * 2) + state_elems * 2 + cb_bytes,
+                   2.0 * T * Q * P * H + 2.0 * T * N * P * H),
     }
     kernels = {}
     if not args.stage:
         for name, fn in stages.items():
             time_loop(lambda i: fn(sets[i % nsets]), 3)
             ms = time_loop(lambda i: fn(sets[i % nsets]), K)
-            bound, amount = work[name]
-            if bound == "hbm":
-                ach, peak, unit = amount / ms / 1e6, PEAK_HBM_GBS, "GB/s"
-            else:
-                ach, peak, unit = amount / ms / 1e9, PEAK_BF16_TFLOPS, "TFLOP/s"
+            nbytes, flops = work[name]
+            gbs, tfs = nbytes / ms / 1e6, flops / ms / 1e9
+            # the roofline that bounds the kernel is the one with the larger time floor
+            bound = "hbm" if nbytes / PEAK_HBM_GBS / 1e6 >= flops / PEAK_BF16_TFLOPS / 1e9 else "mfma"
+            ach, peak, unit = (gbs, PEAK_HBM_GBS, "GB/s") if bound == "hbm" else (tfs, PEAK_BF16_TFLOPS, "TFLOP/s")
             kernels[name] = {"ms": round(ms, 5), "bound": bound, "achieved": round(ach, 2), "peak": peak,
-                             "unit": unit, "frac": round(ach / peak, 4)}
+                             "unit": unit, "frac": round(ach / peak, 4),
+                             "hbm_GBps": round(gbs, 1), "mfma_TFLOPs": round(tfs, 1),
+                             "mfma_frac": round(tfs / PEAK_BF16_TFLOPS, 4)}
 
     # ---- decode step (workload 4) ------------------------------------------------------------
     decode = None
@@ -222,10 +227,17 @@ def main() -> int:
                          "OpenMP over (batch, head)" % (w.name, w.tokens, runs)}
 
     dom = max(kernels, key=lambda n: kernels[n]["ms"])
-    roof = dict(kernels[dom])
-    roof.pop("ms")
+    roof = {kk: kernels[dom][kk] for kk in ("bound", "achieved", "peak", "unit", "frac")}
     roof["kernel"] = dom
+    roof["mfma_frac"] = kernels[dom]["mfma_frac"]
+    # HBM bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE (scaled by a
+    # copy kernel of known size); recorded in profiles/ by hand after a counter run
     roof["traffic"] = None
+    tf = os.path.join(ROOT, "profiles", "hbm_traffic_%s_%s.txt" % (dom, w.name))
+    if os.path.exists(tf):
+        for line in open(tf):
+            if line.startswith("traffic_bytes_per_launch:"):
+                roof["traffic"] = float(line.split(":")[1])
     out = {
         "metric": "Swimba mixer fwd tokens/s + % peak MFMA/HBM at 1 MI355X; decode step us",
         "value": round(tokens_per_s, 1),
