@@ -178,6 +178,24 @@ swimba_status swimba_stage_output(const swimba_dims *dims, const void *x, const 
                                   void *hip_stream);
 
 /*
+ * Contrast path: MoE of separated SSMs (paper: section "Alternative: MoE of separated
+ * SSMs"): every expert keeps its own state trajectory, all E of them advance on every
+ * token with their own un-weighted B stream, and the readout sums the active experts,
+ *   h_t^(e) = exp(dt_t A_h) h_{t-1}^(e) + dt_t B_t^(e) x_t^T,
+ *   y_t = sum_{e in K_t} pi_{t,e} C_t^(e) . h_t^(e) + D_h x_t          (zero initial states).
+ * Same tensors as swimba_mixer_fwd (no h0 / h_final).  It is E plain SSM passes through
+ * the mixer's own kernels (one per expert) plus an fp32 accumulation of the per-expert
+ * outputs: a measure of what replicating the recurrence costs, not a tuned path.
+ *   workspace >= swimba_separated_workspace_bytes(dims), 256-byte aligned.
+ */
+size_t swimba_separated_workspace_bytes(const swimba_dims *dims);
+swimba_status swimba_separated_fwd(const swimba_dims *dims, const void *x, const void *dt,
+                                   const float *A, const float *D, const void *B_experts,
+                                   const void *C_experts, const void *router_logits, void *y,
+                                   int32_t *topk_idx, float *topk_w, void *workspace,
+                                   size_t workspace_bytes, void *hip_stream);
+
+/*
  * Single-token recurrent decode step (paper: selective SSM recurrence, per
  * channel, with the mixed injection and readout of Theorem 1): for every
  * (b,h)

@@ -72,6 +72,10 @@ def _load():
         lib.swimba_stage_state_scan.argtypes = [dp, vp, vp, vp, sz, vp]
         lib.swimba_stage_output.restype = i32
         lib.swimba_stage_output.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        lib.swimba_separated_workspace_bytes.restype = sz
+        lib.swimba_separated_workspace_bytes.argtypes = [dp]
+        lib.swimba_separated_fwd.restype = i32
+        lib.swimba_separated_fwd.argtypes = [dp] + [vp] * 10 + [vp, sz, vp]
         lib.swimba_step_workspace_bytes.restype = sz
         lib.swimba_step_workspace_bytes.argtypes = [dp]
         lib.swimba_step.restype = i32
@@ -212,6 +216,39 @@ def swimba_mixer_fwd(x, dt, A, D, B_experts, C_experts, router_logits, top_k: in
         _ptr(workspace, "workspace", torch.uint8), workspace.numel(), _stream())
     _check(st, "swimba_mixer_fwd")
     return MixerOut(y, h_final, topk_idx, topk_w)
+
+
+def swimba_separated_workspace_bytes(dims: swimba_dims) -> int:
+    return int(_load().swimba_separated_workspace_bytes(ctypes.byref(dims)))
+
+
+def swimba_separated_fwd(x, dt, A, D, B_experts, C_experts, router_logits, top_k: int, chunk: int, *,
+                         y=None, topk_idx=None, topk_w=None, workspace=None, want_topk: bool = False) -> MixerOut:
+    """MoE of separated SSMs (contrast path); same tensors as swimba_mixer_fwd, zero initial states."""
+    d = dims_of(x, B_experts, top_k, chunk)
+    B, L, H, P, N, G, E = d.batch, d.seqlen, d.nheads, d.headdim, d.dstate, d.ngroups, d.nexperts
+    io, dev = x.dtype, x.device
+    if workspace is None:
+        n = swimba_separated_workspace_bytes(d)
+        if n == 0:
+            alloc_workspace(d, dev)   # raises with the status of the dims
+        workspace = torch.empty(n, dtype=torch.uint8, device=dev)
+    if y is None:
+        y = torch.empty_like(x)
+    if want_topk and topk_idx is None:
+        topk_idx = torch.empty((B, L, top_k), dtype=torch.int32, device=dev)
+    if want_topk and topk_w is None:
+        topk_w = torch.empty((B, L, top_k), dtype=torch.float32, device=dev)
+    st = _load().swimba_separated_fwd(
+        ctypes.byref(d), _ptr(x, "x", io, (B, L, H, P)), _ptr(dt, "dt", io, (B, L, H)),
+        _ptr(A, "A", torch.float32, (H,)), _ptr(D, "D", torch.float32, (H,)),
+        _ptr(B_experts, "B_experts", io, (B, L, E, G, N)), _ptr(C_experts, "C_experts", io, (B, L, E, G, N)),
+        _ptr(router_logits, "router_logits", io, (B, L, E)), _ptr(y, "y", io, (B, L, H, P)),
+        _ptr(topk_idx, "topk_idx", torch.int32, (B, L, top_k)),
+        _ptr(topk_w, "topk_w", torch.float32, (B, L, top_k)),
+        _ptr(workspace, "workspace", torch.uint8), workspace.numel(), _stream())
+    _check(st, "swimba_separated_fwd")
+    return MixerOut(y, None, topk_idx, topk_w)
 
 
 def swimba_stage_router(dims, router_logits, workspace):

@@ -166,7 +166,7 @@ swimba_status swimba_stage_mix(const swimba_dims *dims, const void *B_experts,
     if (!B_experts || !C_experts || !router_logits) return SWIMBA_ERR_NULL;
     if (!use_mfma_path(dims)) return SWIMBA_OK;   // the fp32 chunk kernels mix while staging
     return launch_mix_cb_mfma(make_shape(dims), B_experts, C_experts, router_logits, ws.idx, ws.w,
-                              ws.cmix, ws.bmix_t8, ws.cb, (hipStream_t)hip_stream);
+                              ws.cmix, ws.bmix_t8, ws.cb, -1, (hipStream_t)hip_stream);
 }
 
 swimba_status swimba_stage_chunk_state(const swimba_dims *dims, const void *x, const void *dt,
@@ -214,7 +214,7 @@ swimba_status swimba_stage_output(const swimba_dims *dims, const void *x, const 
         return launch_output_mfma(s, x, dt, D, ws.cmix, ws.cb, ws.cs, ws.states_lp, y,
                                   (hipStream_t)hip_stream);
     return launch_output_generic(s, dims->io_dtype, x, dt, D, B_experts, C_experts, ws.idx, ws.w,
-                                 ws.cs, ws.states, y, (hipStream_t)hip_stream);
+                                 ws.w, ws.cs, ws.states, y, (hipStream_t)hip_stream);
 }
 
 swimba_status swimba_mixer_fwd(const swimba_dims *dims, const void *x, const void *dt,
@@ -266,6 +266,110 @@ swimba_status swimba_mixer_fwd(const swimba_dims *dims, const void *x, const voi
         st = swimba_stage_output(dims, x, dt, D, B_experts, C_experts, y, workspace, workspace_bytes,
                                  hip_stream);
         if (st != SWIMBA_OK) return st;
+    }
+    return SWIMBA_OK;
+}
+
+// ---- separated-SSM contrast ---------------------------------------------------------------
+struct SepLayout {
+    size_t mixer, y_e, acc, idx1, wb1, wc1, total;
+};
+static void sep_layout_of(const swimba_dims *d, SepLayout *o)
+{
+    swimba_ws_layout lo;
+    layout_of(d, &lo);
+    const size_t T = (size_t)d->batch * d->seqlen;
+    const size_t n = T * d->nheads * d->headdim;
+    const size_t io = d->io_dtype == SWIMBA_BF16 ? 2 : 4;
+    size_t off = 0;
+    o->mixer = off; off = align_up(off + lo.total, 256);
+    o->y_e = off;   off = align_up(off + n * io, 256);
+    o->acc = off;   off = align_up(off + n * sizeof(float), 256);
+    o->idx1 = off;  off = align_up(off + T * sizeof(int32_t), 256);
+    o->wb1 = off;   off = align_up(off + T * sizeof(float), 256);
+    o->wc1 = off;   off = align_up(off + T * sizeof(float), 256);
+    o->total = off;
+}
+
+size_t swimba_separated_workspace_bytes(const swimba_dims *dims)
+{
+    if (check_mixer(dims) != SWIMBA_OK) return 0;
+    SepLayout sl;
+    sep_layout_of(dims, &sl);
+    return sl.total;
+}
+
+swimba_status swimba_separated_fwd(const swimba_dims *dims, const void *x, const void *dt,
+                                   const float *A, const float *D, const void *B_experts,
+                                   const void *C_experts, const void *router_logits, void *y,
+                                   int32_t *topk_idx, float *topk_w, void *workspace,
+                                   size_t workspace_bytes, void *hip_stream)
+{
+    swimba_status st = check_mixer(dims);
+    if (st != SWIMBA_OK) return st;
+    SepLayout sl;
+    sep_layout_of(dims, &sl);
+    if (!workspace || workspace_bytes < sl.total || ((uintptr_t)workspace & 255u)) return SWIMBA_ERR_WORKSPACE;
+    const int64_t T = (int64_t)dims->batch * dims->seqlen;
+    if (T == 0) return SWIMBA_OK;
+    if (!x || !dt || !A || !B_experts || !C_experts || !router_logits || !y) return SWIMBA_ERR_NULL;
+    char *base = (char *)workspace;
+    Ws ws;
+    swimba_ws_layout lo;
+    layout_of(dims, &lo);
+    st = carve(dims, base + sl.mixer, lo.total, &ws);
+    if (st != SWIMBA_OK) return st;
+    void *y_e = base + sl.y_e;
+    float *acc = (float *)(base + sl.acc);
+    int32_t *idx1 = (int32_t *)(base + sl.idx1);
+    float *wb1 = (float *)(base + sl.wb1), *wc1 = (float *)(base + sl.wc1);
+    hipStream_t stream = (hipStream_t)hip_stream;
+    const Shape s = make_shape(dims);
+    const bool mf = use_mfma_path(dims);
+    const int64_t n = T * dims->nheads * dims->headdim;
+    Shape s1 = s;
+    s1.K = 1;   // one expert at a time on the fp32 kernels
+    if (!mf) {
+        st = launch_router(T, s.E, s.K, dims->io_dtype, router_logits, ws.idx, ws.w, stream);
+        if (st != SWIMBA_OK) return st;
+        st = launch_cumsum(s, dims->io_dtype, dt, A, ws.cs, stream);
+        if (st != SWIMBA_OK) return st;
+    }
+    for (int e = 0; e < s.E; ++e) {
+        if (mf) {
+            st = launch_mix_cb_mfma(s, B_experts, C_experts, router_logits, ws.idx, ws.w, ws.cmix,
+                                    ws.bmix_t8, ws.cb, e, stream);
+            if (st != SWIMBA_OK) return st;
+            st = launch_chunk_state_mfma(s, x, dt, A, ws.bmix_t8, ws.cs, ws.states_lp, stream);
+            if (st != SWIMBA_OK) return st;
+            st = launch_state_scan_lp(s, nullptr, nullptr, ws.states_lp, ws.cs, stream);
+            if (st != SWIMBA_OK) return st;
+            st = launch_output_mfma(s, x, dt, nullptr, ws.cmix, ws.cb, ws.cs, ws.states_lp, y_e, stream);
+            if (st != SWIMBA_OK) return st;
+        } else {
+            st = launch_sep_prepare(s, e, ws.idx, ws.w, idx1, wb1, wc1, stream);
+            if (st != SWIMBA_OK) return st;
+            st = launch_chunk_state_generic(s1, dims->io_dtype, x, dt, B_experts, idx1, wb1, ws.cs,
+                                            ws.states, stream);
+            if (st != SWIMBA_OK) return st;
+            st = launch_state_scan(s1, nullptr, nullptr, ws.states, nullptr, ws.cs, stream);
+            if (st != SWIMBA_OK) return st;
+            st = launch_output_generic(s1, dims->io_dtype, x, dt, nullptr, B_experts, C_experts, idx1,
+                                       wb1, wc1, ws.cs, ws.states, y_e, stream);
+            if (st != SWIMBA_OK) return st;
+        }
+        st = launch_sep_accumulate(dims->io_dtype, n, y_e, acc, e == 0, stream);
+        if (st != SWIMBA_OK) return st;
+    }
+    st = launch_sep_finish(s, dims->io_dtype, acc, x, D, y, stream);
+    if (st != SWIMBA_OK) return st;
+    if (topk_idx || topk_w) {
+        const size_t cnt = (size_t)T * dims->top_k;
+        hipError_t e = hipSuccess;
+        if (topk_idx) e = hipMemcpyAsync(topk_idx, ws.idx, cnt * sizeof(int32_t), hipMemcpyDeviceToDevice, stream);
+        if (e == hipSuccess && topk_w)
+            e = hipMemcpyAsync(topk_w, ws.w, cnt * sizeof(float), hipMemcpyDeviceToDevice, stream);
+        if (e != hipSuccess) { set_last_hip_error((int)e); return SWIMBA_ERR_HIP; }
     }
     return SWIMBA_OK;
 }

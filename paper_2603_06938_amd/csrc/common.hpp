@@ -74,11 +74,17 @@ swimba_status launch_chunk_state_generic(const Shape &s, int io_dtype, const voi
                                          const float *cs, float *states, hipStream_t st);
 swimba_status launch_output_generic(const Shape &s, int io_dtype, const void *x, const void *dt,
                                     const float *D, const void *Be, const void *Ce,
-                                    const int32_t *idx, const float *w, const float *cs,
-                                    const float *states, void *y, hipStream_t st);
+                                    const int32_t *idx, const float *w, const float *wc,
+                                    const float *cs, const float *states, void *y, hipStream_t st);
 swimba_status launch_mix_cb_mfma(const Shape &s, const void *Be, const void *Ce, const void *logits,
                                  int32_t *idx, float *w, void *cmix, void *bmix_t8, void *cb,
-                                 hipStream_t st);
+                                 int sep_e, hipStream_t st);
+swimba_status launch_sep_prepare(const Shape &s, int e, const int32_t *idx, const float *w,
+                                 int32_t *idx1, float *wb1, float *wc1, hipStream_t st);
+swimba_status launch_sep_accumulate(int io_dtype, int64_t n, const void *y_e, float *acc, int first,
+                                    hipStream_t st);
+swimba_status launch_sep_finish(const Shape &s, int io_dtype, const float *acc, const void *x,
+                                const float *D, void *y, hipStream_t st);
 swimba_status launch_chunk_state_mfma(const Shape &s, const void *x, const void *dt, const float *A,
                                       const void *bmix_t8, float *cs, void *states_lp, hipStream_t st);
 swimba_status launch_state_scan_lp(const Shape &s, const float *h0, float *h_final, void *states_lp,

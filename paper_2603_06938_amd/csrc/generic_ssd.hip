@@ -112,7 +112,8 @@ swimba_status launch_chunk_state_generic(const Shape &s, int io_dtype, const voi
 }
 
 // ---- y_i = sum_{j<=i} (Cmix_i.Bmix_j) exp(cs_i-cs_j) dt_j x_j + exp(cs_i) Cmix_i.H_c + D x_i --
-// One block owns GEN_TI consecutive tokens of one (b, chunk, head).
+// One block owns GEN_TI consecutive tokens of one (b, chunk, head).  `w` weighs the B rows,
+// `wc` the C rows (the same array for the mixed model; they differ for the separated contrast).
 constexpr int GEN_MAX_YPT = (GEN_TI * SWIMBA_MAX_HEADDIM) / GEN_THREADS;  // (i,p) pairs per lane
 
 template <typename T>
@@ -120,8 +121,8 @@ __global__ void __launch_bounds__(GEN_THREADS)
 output_generic_kernel(const T *__restrict__ x, const T *__restrict__ dt, const float *__restrict__ D,
                       const T *__restrict__ Be, const T *__restrict__ Ce,
                       const int32_t *__restrict__ idx, const float *__restrict__ w,
-                      const float *__restrict__ cs, const float *__restrict__ states,
-                      T *__restrict__ y, Shape s)
+                      const float *__restrict__ wc, const float *__restrict__ cs,
+                      const float *__restrict__ states, T *__restrict__ y, Shape s)
 {
     extern __shared__ float smem[];
     float *sc = smem;                         // [GEN_TI][N] mixed C of the block's tokens
@@ -147,7 +148,7 @@ output_generic_kernel(const T *__restrict__ x, const T *__restrict__ dt, const f
         float v = 0.f;
         if (q < s.Q && t < s.L) {
             const int64_t bt = (int64_t)b * s.L + t;
-            v = mix_elem(Ce + bt * s.E * s.G * s.N, idx + bt * s.K, w + bt * s.K, s.K, s.G, s.N, g, n);
+            v = mix_elem(Ce + bt * s.E * s.G * s.N, idx + bt * s.K, wc + bt * s.K, s.K, s.G, s.N, g, n);
         }
         sc[i] = v;
     }
@@ -237,8 +238,8 @@ output_generic_kernel(const T *__restrict__ x, const T *__restrict__ dt, const f
 
 swimba_status launch_output_generic(const Shape &s, int io_dtype, const void *x, const void *dt,
                                     const float *D, const void *Be, const void *Ce,
-                                    const int32_t *idx, const float *w, const float *cs,
-                                    const float *states, void *y, hipStream_t st)
+                                    const int32_t *idx, const float *w, const float *wc,
+                                    const float *cs, const float *states, void *y, hipStream_t st)
 {
     static_assert(GEN_THREADS == GEN_TI * GEN_TI, "one lane per (i,j) pair of a tile");
     const int nib = (s.Q + GEN_TI - 1) / GEN_TI;
@@ -248,11 +249,11 @@ swimba_status launch_output_generic(const Shape &s, int io_dtype, const void *x,
     if (io_dtype == SWIMBA_BF16)
         hipLaunchKernelGGL(output_generic_kernel<bf16>, dim3((unsigned)blocks), dim3(GEN_THREADS), shm,
                            st, (const bf16 *)x, (const bf16 *)dt, D, (const bf16 *)Be,
-                           (const bf16 *)Ce, idx, w, cs, states, (bf16 *)y, s);
+                           (const bf16 *)Ce, idx, w, wc, cs, states, (bf16 *)y, s);
     else
         hipLaunchKernelGGL(output_generic_kernel<float>, dim3((unsigned)blocks), dim3(GEN_THREADS), shm,
                            st, (const float *)x, (const float *)dt, D, (const float *)Be,
-                           (const float *)Ce, idx, w, cs, states, (float *)y, s);
+                           (const float *)Ce, idx, w, wc, cs, states, (float *)y, s);
     SWIMBA_CHECK_LAUNCH();
     return SWIMBA_OK;
 }

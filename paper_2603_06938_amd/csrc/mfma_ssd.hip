@@ -120,7 +120,9 @@ __device__ __forceinline__ void gather_mix_row(uint4 *frag, const uint16_t *tok,
 // I1 = NT-1-r of the chunk (32 tokens each).  Wave w takes the j tiles J = w, w+4.
 // The workgroup first routes the chunk's tokens itself (softmax over all experts,
 // top-k on the raw logits, no renormalisation) into LDS, and stores the routing of
-// its own two tiles to topk_idx / topk_w.
+// its own two tiles to topk_idx / topk_w.  With sep_e >= 0 it prepares the streams of
+// ONE expert for the separated-SSM contrast instead: Bmix = B^(e), Cmix = gate * C^(e),
+// gate = pi_{t,e} if e is in the token's active set, else 0.
 //   cmix    (B, nc, G, NT, 8, 64, 8) bf16, mixed C of tile I as MFMA operand registers:
 //           [ks][lane][e] = Cmix[32I + lane%32][64*(lane/32) + 8ks + e]
 //   bmix_t8 (B, nc, G, Q/8, N, 8)    bf16, mixed B with 8 consecutive tokens innermost
@@ -132,12 +134,16 @@ __global__ void __launch_bounds__(MTHREADS)
 mix_cb_kernel(const uint16_t *__restrict__ Be, const uint16_t *__restrict__ Ce,
               const uint16_t *__restrict__ logits, int32_t *__restrict__ idx_out,
               float *__restrict__ w_out, uint16_t *__restrict__ cmix,
-              uint16_t *__restrict__ bmix_t8, uint16_t *__restrict__ cb, Shape s)
+              uint16_t *__restrict__ bmix_t8, uint16_t *__restrict__ cb, Shape s, int sep_e)
 {
     constexpr int NT = Q / 32, NR = NT / 2, NP = NT * (NT + 1) / 2;
     extern __shared__ __align__(16) unsigned char smem_raw[];
     int32_t *s_idx = reinterpret_cast<int32_t *>(smem_raw);        // [Q][K]
     float *s_w = reinterpret_cast<float *>(s_idx + Q * s.K);        // [Q][K]
+    // separated-SSM contrast (sep_e >= 0): expert sep_e alone, B unweighted, C gated
+    int32_t *s_idx1 = reinterpret_cast<int32_t *>(s_w + Q * s.K);   // [Q]
+    float *s_wb1 = reinterpret_cast<float *>(s_idx1 + Q);           // [Q]
+    float *s_wc1 = s_wb1 + Q;                                       // [Q]
 
     const int r = blockIdx.x % NR;
     const int g = (blockIdx.x / NR) % s.G;
@@ -148,7 +154,7 @@ mix_cb_kernel(const uint16_t *__restrict__ Be, const uint16_t *__restrict__ Ce,
     const int l32 = lane & 31, kg = lane >> 5;
     const int64_t tok0 = (int64_t)b * s.L + (int64_t)c * Q;
     const int valid = min(Q, s.L - c * Q);
-    const int K = s.K;
+    const int Kr = s.K;                                  // experts kept by the router
     const int estride = s.G * MN;
     const int tokstride = s.E * estride;                 // elements between tokens of B/C_experts
     const int64_t bcg = ((int64_t)b * s.nc + c) * s.G + g;
@@ -160,19 +166,34 @@ mix_cb_kernel(const uint16_t *__restrict__ Be, const uint16_t *__restrict__ Ce,
     for (int t = tid; t < Q; t += MTHREADS) {
         if (t < valid) {
             const uint16_t *gl = logits + (tok0 + t) * s.E;
-            route_token([&](int e) { return to_float(bf16{gl[e]}); }, s.E, K, s_idx + t * K, s_w + t * K);
+            route_token([&](int e) { return to_float(bf16{gl[e]}); }, s.E, Kr, s_idx + t * Kr, s_w + t * Kr);
             const int tile = t >> 5;
-            if (g == 0 && (tile == tiles[0] || tile == tiles[1])) {
-                for (int rr = 0; rr < K; ++rr) {
-                    idx_out[(tok0 + t) * K + rr] = s_idx[t * K + rr];
-                    w_out[(tok0 + t) * K + rr] = s_w[t * K + rr];
+            if (g == 0 && sep_e <= 0 && (tile == tiles[0] || tile == tiles[1])) {
+                for (int rr = 0; rr < Kr; ++rr) {
+                    idx_out[(tok0 + t) * Kr + rr] = s_idx[t * Kr + rr];
+                    w_out[(tok0 + t) * Kr + rr] = s_w[t * Kr + rr];
                 }
             }
         } else {
-            for (int rr = 0; rr < K; ++rr) { s_idx[t * K + rr] = 0; s_w[t * K + rr] = 0.f; }
+            for (int rr = 0; rr < Kr; ++rr) { s_idx[t * Kr + rr] = 0; s_w[t * Kr + rr] = 0.f; }
+        }
+        if (sep_e >= 0) {
+            // MoE of separated SSMs (paper: separated-SSM equation): expert sep_e keeps its own
+            // state, B_t^(e) enters unweighted, the readout weight is pi_{t,e} on the active set
+            float gate = 0.f;
+            for (int rr = 0; rr < Kr; ++rr)
+                if (s_idx[t * Kr + rr] == sep_e) gate += s_w[t * Kr + rr];
+            s_idx1[t] = sep_e;
+            s_wb1[t] = (t < valid) ? 1.f : 0.f;
+            s_wc1[t] = (t < valid) ? gate : 0.f;
         }
     }
     lds_barrier();
+    // tables the gathers read: K experts per token, separate weights for the B and C streams
+    const int K = (sep_e >= 0) ? 1 : Kr;
+    const int32_t *ixt = (sep_e >= 0) ? s_idx1 : s_idx;
+    const float *wtB = (sep_e >= 0) ? s_wb1 : s_w;
+    const float *wtC = (sep_e >= 0) ? s_wc1 : s_w;
 
     // All gathers of the workgroup are independent once the routing is known: the loads of
     // (a), (b) and of the first j tile of (c) are issued back to back before any of them is
@@ -194,16 +215,16 @@ mix_cb_kernel(const uint16_t *__restrict__ Be, const uint16_t *__restrict__ Ce,
         }
     };
     // mixed row (operand layout) of token j of stream S, given the loads of its first two experts
-    auto finish_row = [&](uint4 *frag, uint4 (&v)[2][8], const uint16_t *tok, int j) {
+    auto finish_row = [&](uint4 *frag, uint4 (&v)[2][8], const uint16_t *tok, int j, const float *wt) {
         float acc[8][8];
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks)
 #pragma unroll
             for (int e = 0; e < 8; ++e) acc[ks][e] = 0.f;
-        row_accumulate(acc, v, s_w + j * K, 0);
+        row_accumulate(acc, v, wt + j * K, 0);
         for (int r0 = 2; r0 < K; r0 += 2) {       // top_k > 2: the remaining experts, pair by pair
-            row_loads(v, tok, s_idx + j * K, r0);
-            row_accumulate(acc, v, s_w + j * K, r0);
+            row_loads(v, tok, ixt + j * K, r0);
+            row_accumulate(acc, v, wt + j * K, r0);
         }
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) frag[ks] = pack8(acc[ks]);
@@ -219,7 +240,7 @@ mix_cb_kernel(const uint16_t *__restrict__ Be, const uint16_t *__restrict__ Ce,
         const uint16_t *rowbase = Bg + min(j, valid - 1) * tokstride + piece * 8;
 #pragma unroll
         for (int q = 0; q < 2; ++q)
-            va[jj][q] = *reinterpret_cast<const uint4 *>(rowbase + s_idx[j * K + min(q, K - 1)] * estride);
+            va[jj][q] = *reinterpret_cast<const uint4 *>(rowbase + ixt[j * K + min(q, K - 1)] * estride);
     }
     // (b) mixed C rows of the owned tiles; (c) mixed B rows of the first j tile of this wave
     // (a wave beyond the chunk's last j tile has no (c) work: its early load is clamped to a
@@ -230,9 +251,9 @@ mix_cb_kernel(const uint16_t *__restrict__ Be, const uint16_t *__restrict__ Ce,
     const uint16_t *tokc1 = Cg + min(i1, valid - 1) * tokstride;
     const uint16_t *tokb = Bg + min(jfirst, valid - 1) * tokstride;
     uint4 vc0[2][8], vc1[2][8], vb[2][8];
-    row_loads(vc0, tokc0, s_idx + i0 * K, 0);
-    row_loads(vc1, tokc1, s_idx + i1 * K, 0);
-    row_loads(vb, tokb, s_idx + jfirst * K, 0);
+    row_loads(vc0, tokc0, ixt + i0 * K, 0);
+    row_loads(vc1, tokc1, ixt + i1 * K, 0);
+    row_loads(vb, tokb, ixt + jfirst * K, 0);
 
     // ---- consume (a) ----
     {
@@ -242,12 +263,12 @@ mix_cb_kernel(const uint16_t *__restrict__ Be, const uint16_t *__restrict__ Ce,
 #pragma unroll
             for (int e = 0; e < 8; ++e) acc[jj][e] = 0.f;
             const int j = jg * 8 + half * 4 + jj;
-            fma_bf16x8(acc[jj], va[jj][0], s_w[j * K]);
-            fma_bf16x8(acc[jj], va[jj][1], K > 1 ? s_w[j * K + 1] : 0.f);
+            fma_bf16x8(acc[jj], va[jj][0], wtB[j * K]);
+            fma_bf16x8(acc[jj], va[jj][1], K > 1 ? wtB[j * K + 1] : 0.f);
             const uint16_t *rowbase = Bg + min(j, valid - 1) * tokstride + piece * 8;
             for (int rr = 2; rr < K; ++rr)
-                fma_bf16x8(acc[jj], *reinterpret_cast<const uint4 *>(rowbase + s_idx[j * K + rr] * estride),
-                           s_w[j * K + rr]);
+                fma_bf16x8(acc[jj], *reinterpret_cast<const uint4 *>(rowbase + ixt[j * K + rr] * estride),
+                           wtB[j * K + rr]);
         }
         uint16_t *dst = bmix_t8 + ((bcg * (Q / 8) + jg) * MN + piece * 8) * 8 + half * 4;
 #pragma unroll
@@ -260,8 +281,8 @@ mix_cb_kernel(const uint16_t *__restrict__ Be, const uint16_t *__restrict__ Ce,
     }
     // ---- consume (b): operand registers; waves 0 and 1 also store one tile each ----
     uint4 cfrag[2][8];
-    finish_row(cfrag[0], vc0, tokc0, i0);
-    finish_row(cfrag[1], vc1, tokc1, i1);
+    finish_row(cfrag[0], vc0, tokc0, i0, wtC);
+    finish_row(cfrag[1], vc1, tokc1, i1, wtC);
 #pragma unroll
     for (int sl = 0; sl < 2; ++sl) {
         if (wave == sl) {
@@ -275,9 +296,9 @@ mix_cb_kernel(const uint16_t *__restrict__ Be, const uint16_t *__restrict__ Ce,
     for (int J = wave; J <= tiles[1]; J += 4) {
         const int j = J * 32 + l32;
         const uint16_t *tok = Bg + min(j, valid - 1) * tokstride;
-        if (J != wave) row_loads(vb, tok, s_idx + j * K, 0);
+        if (J != wave) row_loads(vb, tok, ixt + j * K, 0);
         uint4 bfrag[8];
-        finish_row(bfrag, vb, tok, j);
+        finish_row(bfrag, vb, tok, j, wtB);
 #pragma unroll
         for (int sl = 0; sl < 2; ++sl) {
             const int I = tiles[sl];
@@ -298,26 +319,26 @@ mix_cb_kernel(const uint16_t *__restrict__ Be, const uint16_t *__restrict__ Ce,
 template <int Q>
 static swimba_status launch_mix_q(const Shape &s, const void *Be, const void *Ce, const void *logits,
                                   int32_t *idx, float *w, void *cmix, void *bmix_t8, void *cb,
-                                  hipStream_t st)
+                                  int sep_e, hipStream_t st)
 {
     const int64_t total = (int64_t)s.B * s.nc * s.G * (Q / 64);
     if (total == 0) return SWIMBA_OK;
-    const size_t shm = (size_t)Q * s.K * 8;
+    const size_t shm = (size_t)Q * s.K * 8 + (size_t)Q * 12;
     hipLaunchKernelGGL(mix_cb_kernel<Q>, dim3((unsigned)total), dim3(MTHREADS), shm, st,
                        (const uint16_t *)Be, (const uint16_t *)Ce, (const uint16_t *)logits, idx, w,
-                       (uint16_t *)cmix, (uint16_t *)bmix_t8, (uint16_t *)cb, s);
+                       (uint16_t *)cmix, (uint16_t *)bmix_t8, (uint16_t *)cb, s, sep_e);
     SWIMBA_CHECK_LAUNCH();
     return SWIMBA_OK;
 }
 
 swimba_status launch_mix_cb_mfma(const Shape &s, const void *Be, const void *Ce, const void *logits,
                                  int32_t *idx, float *w, void *cmix, void *bmix_t8, void *cb,
-                                 hipStream_t st)
+                                 int sep_e, hipStream_t st)
 {
     switch (s.Q) {
-    case 64: return launch_mix_q<64>(s, Be, Ce, logits, idx, w, cmix, bmix_t8, cb, st);
-    case 128: return launch_mix_q<128>(s, Be, Ce, logits, idx, w, cmix, bmix_t8, cb, st);
-    case 256: return launch_mix_q<256>(s, Be, Ce, logits, idx, w, cmix, bmix_t8, cb, st);
+    case 64: return launch_mix_q<64>(s, Be, Ce, logits, idx, w, cmix, bmix_t8, cb, sep_e, st);
+    case 128: return launch_mix_q<128>(s, Be, Ce, logits, idx, w, cmix, bmix_t8, cb, sep_e, st);
+    case 256: return launch_mix_q<256>(s, Be, Ce, logits, idx, w, cmix, bmix_t8, cb, sep_e, st);
     }
     return SWIMBA_ERR_UNSUPPORTED;
 }
