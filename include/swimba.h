@@ -79,6 +79,7 @@ typedef struct {
     size_t states_lp; /* (B,nc,H,P,N) bf16 : chunk states S_c, then the carried states  */
     size_t cmix;      /* (B,nc,G,Q/32,8,64,8) bf16 : mixed C rows, MFMA operand layout   */
     size_t bmix_t8;   /* (B,nc,G,Q/8,N,8) bf16 : mixed B, 8 consecutive tokens innermost */
+    size_t bmix_frag; /* (B,nc,G,Q/32,8,64,8) bf16 : mixed B rows, MFMA operand layout   */
     size_t cb;        /* (B,nc,G,NP,2,64,8) bf16 : causal 32x32 tiles of Bmix.Cmix^T in
                          MFMA accumulator layout, NP = (Q/32)(Q/32+1)/2               */
     size_t total;

@@ -39,7 +39,7 @@ class swimba_dims(ctypes.Structure):
 
 class swimba_ws_layout(ctypes.Structure):
     _fields_ = [(n, ctypes.c_size_t) for n in
-                ("topk_idx", "topk_w", "cs", "states", "states_lp", "cmix", "bmix_t8", "cb", "total")]
+                ("topk_idx", "topk_w", "cs", "states", "states_lp", "cmix", "bmix_t8", "bmix_frag", "cb", "total")]
 
 
 def _load():

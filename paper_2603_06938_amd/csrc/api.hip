@@ -60,6 +60,8 @@ static void layout_of(const swimba_dims *d, swimba_ws_layout *o)
     if (mf) off = align_up(off + mixed, 256);
     o->bmix_t8 = off;
     if (mf) off = align_up(off + mixed, 256);
+    o->bmix_frag = off;
+    if (mf) off = align_up(off + mixed, 256);
     o->cb = off;
     if (mf) off = align_up(off + (size_t)s.B * s.nc * s.G * (nt * (nt + 1) / 2) * 2048, 256);
     o->total = off > 0 ? off : 256;
@@ -70,7 +72,7 @@ struct Ws {
     float *w;
     float *cs;
     float *states;
-    void *states_lp, *cmix, *bmix_t8, *cb;
+    void *states_lp, *cmix, *bmix_t8, *bmix_frag, *cb;
 };
 
 static swimba_status carve(const swimba_dims *d, void *workspace, size_t bytes, Ws *ws)
@@ -89,6 +91,7 @@ static swimba_status carve(const swimba_dims *d, void *workspace, size_t bytes, 
     ws->states_lp = mf ? (void *)(p + lo.states_lp) : nullptr;
     ws->cmix = mf ? (void *)(p + lo.cmix) : nullptr;
     ws->bmix_t8 = mf ? (void *)(p + lo.bmix_t8) : nullptr;
+    ws->bmix_frag = mf ? (void *)(p + lo.bmix_frag) : nullptr;
     ws->cb = mf ? (void *)(p + lo.cb) : nullptr;
     return SWIMBA_OK;
 }
@@ -165,8 +168,8 @@ swimba_status swimba_stage_mix(const swimba_dims *dims, const void *B_experts,
     if ((int64_t)dims->batch * dims->seqlen == 0) return SWIMBA_OK;
     if (!B_experts || !C_experts || !router_logits) return SWIMBA_ERR_NULL;
     if (!use_mfma_path(dims)) return SWIMBA_OK;   // the fp32 chunk kernels mix while staging
-    return launch_mix_cb_mfma(make_shape(dims), B_experts, C_experts, router_logits, ws.idx, ws.w,
-                              ws.cmix, ws.bmix_t8, ws.cb, -1, (hipStream_t)hip_stream);
+    return launch_mix_rows_mfma(make_shape(dims), B_experts, C_experts, router_logits, ws.idx, ws.w,
+                                ws.cmix, ws.bmix_frag, ws.bmix_t8, -1, (hipStream_t)hip_stream);
 }
 
 swimba_status swimba_stage_chunk_state(const swimba_dims *dims, const void *x, const void *dt,
@@ -194,8 +197,8 @@ swimba_status swimba_stage_state_scan(const swimba_dims *dims, const float *h0, 
     if (st != SWIMBA_OK) return st;
     if (dims->batch == 0) return SWIMBA_OK;
     if (use_mfma_path(dims))
-        return launch_state_scan_lp(make_shape(dims), h0, h_final, ws.states_lp, ws.cs,
-                                    (hipStream_t)hip_stream);
+        return launch_scan_cb_mfma(make_shape(dims), h0, h_final, ws.states_lp, ws.cs, ws.cmix,
+                                   ws.bmix_frag, ws.cb, (hipStream_t)hip_stream);
     return launch_state_scan(make_shape(dims), h0, h_final, ws.states, nullptr, ws.cs,
                              (hipStream_t)hip_stream);
 }
@@ -258,7 +261,7 @@ swimba_status swimba_mixer_fwd(const swimba_dims *dims, const void *x, const voi
     }
     // with L == 0 the scan only copies h0 (or zeros) to h_final
     if (dims->batch > 0 && (T > 0 || h_final)) {
-        st = mf ? launch_state_scan_lp(s, h0, h_final, ws.states_lp, ws.cs, stream)
+        st = mf ? launch_scan_cb_mfma(s, h0, h_final, ws.states_lp, ws.cs, ws.cmix, ws.bmix_frag, ws.cb, stream)
                 : launch_state_scan(s, h0, h_final, ws.states, nullptr, ws.cs, stream);
         if (st != SWIMBA_OK) return st;
     }
@@ -337,12 +340,12 @@ swimba_status swimba_separated_fwd(const swimba_dims *dims, const void *x, const
     }
     for (int e = 0; e < s.E; ++e) {
         if (mf) {
-            st = launch_mix_cb_mfma(s, B_experts, C_experts, router_logits, ws.idx, ws.w, ws.cmix,
-                                    ws.bmix_t8, ws.cb, e, stream);
+            st = launch_mix_rows_mfma(s, B_experts, C_experts, router_logits, ws.idx, ws.w, ws.cmix,
+                                      ws.bmix_frag, ws.bmix_t8, e, stream);
             if (st != SWIMBA_OK) return st;
             st = launch_chunk_state_mfma(s, x, dt, A, ws.bmix_t8, ws.cs, ws.states_lp, stream);
             if (st != SWIMBA_OK) return st;
-            st = launch_state_scan_lp(s, nullptr, nullptr, ws.states_lp, ws.cs, stream);
+            st = launch_scan_cb_mfma(s, nullptr, nullptr, ws.states_lp, ws.cs, ws.cmix, ws.bmix_frag, ws.cb, stream);
             if (st != SWIMBA_OK) return st;
             st = launch_output_mfma(s, x, dt, nullptr, ws.cmix, ws.cb, ws.cs, ws.states_lp, y_e, stream);
             if (st != SWIMBA_OK) return st;

@@ -76,9 +76,9 @@ swimba_status launch_output_generic(const Shape &s, int io_dtype, const void *x,
                                     const float *D, const void *Be, const void *Ce,
                                     const int32_t *idx, const float *w, const float *wc,
                                     const float *cs, const float *states, void *y, hipStream_t st);
-swimba_status launch_mix_cb_mfma(const Shape &s, const void *Be, const void *Ce, const void *logits,
-                                 int32_t *idx, float *w, void *cmix, void *bmix_t8, void *cb,
-                                 int sep_e, hipStream_t st);
+swimba_status launch_mix_rows_mfma(const Shape &s, const void *Be, const void *Ce, const void *logits,
+                                   int32_t *idx, float *w, void *cmix, void *bfrag, void *bmix_t8,
+                                   int sep_e, hipStream_t st);
 swimba_status launch_sep_prepare(const Shape &s, int e, const int32_t *idx, const float *w,
                                  int32_t *idx1, float *wb1, float *wc1, hipStream_t st);
 swimba_status launch_sep_accumulate(int io_dtype, int64_t n, const void *y_e, float *acc, int first,
@@ -87,8 +87,9 @@ swimba_status launch_sep_finish(const Shape &s, int io_dtype, const float *acc, 
                                 const float *D, void *y, hipStream_t st);
 swimba_status launch_chunk_state_mfma(const Shape &s, const void *x, const void *dt, const float *A,
                                       const void *bmix_t8, float *cs, void *states_lp, hipStream_t st);
-swimba_status launch_state_scan_lp(const Shape &s, const float *h0, float *h_final, void *states_lp,
-                                   const float *cs, hipStream_t st);
+swimba_status launch_scan_cb_mfma(const Shape &s, const float *h0, float *h_final, void *states_lp,
+                                  const float *cs, const void *cmix, const void *bfrag, void *cb,
+                                  hipStream_t st);
 swimba_status launch_output_mfma(const Shape &s, const void *x, const void *dt, const float *D,
                                  const void *cmix, const void *cb, const float *cs,
                                  const void *states_lp, void *y, hipStream_t st);
@@ -100,13 +101,17 @@ swimba_status launch_step(const Shape &s, int io_dtype, const float *state_in, f
 // ---- device helper shared by the router kernel and the decode kernel -----------------
 // Top-k over E logits read through `load(e)`, in (logit descending, index
 // ascending) order; softmax over all E, no renormalisation.
+// exp(v) for v <= 0 through the hardware exp2 (about 1 ulp; the product v * log2(e) adds a
+// relative error of |v| * 2^-24, far inside the 1e-5 the routing weights are held to)
+__device__ __forceinline__ float route_exp(float v) { return __builtin_amdgcn_exp2f(v * 1.4426950408889634f); }
+
 template <typename Load>
 __device__ __forceinline__ void route_token(Load load, int E, int K, int32_t *idx, float *w)
 {
     float m = -INFINITY;
     for (int e = 0; e < E; ++e) m = fmaxf(m, load(e));
     float Z = 0.f;
-    for (int e = 0; e < E; ++e) Z += expf(load(e) - m);
+    for (int e = 0; e < E; ++e) Z += route_exp(load(e) - m);
     const float invZ = 1.0f / Z;
     float pv = 0.f;
     int pi = -1;
@@ -120,7 +125,7 @@ __device__ __forceinline__ void route_token(Load load, int E, int K, int32_t *id
             if (after && (best < 0 || v > bv)) { best = e; bv = v; }
         }
         idx[r] = best;
-        w[r] = expf(bv - m) * invZ;
+        w[r] = route_exp(bv - m) * invZ;
         pv = bv;
         pi = best;
     }

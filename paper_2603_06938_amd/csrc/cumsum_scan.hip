@@ -132,77 +132,6 @@ state_scan_kernel(float *__restrict__ states, uint16_t *__restrict__ lp,
     }
 }
 
-// ---- the same scan over bf16 chunk states (bf16 MFMA path): the running state is fp32 in
-// ---- registers, chunk states are read as bf16 and replaced by the bf16 carried states.
-__device__ __forceinline__ void unpack_bf16x8(float *a, uint4 u)
-{
-    a[0] = __uint_as_float(u.x << 16); a[1] = __uint_as_float(u.x & 0xffff0000u);
-    a[2] = __uint_as_float(u.y << 16); a[3] = __uint_as_float(u.y & 0xffff0000u);
-    a[4] = __uint_as_float(u.z << 16); a[5] = __uint_as_float(u.z & 0xffff0000u);
-    a[6] = __uint_as_float(u.w << 16); a[7] = __uint_as_float(u.w & 0xffff0000u);
-}
-
-__global__ void __launch_bounds__(256)
-state_scan_lp_kernel(uint16_t *__restrict__ lp, const float *__restrict__ h0,
-                     float *__restrict__ h_final, const float *__restrict__ cs, Shape s)
-{
-    const int64_t per_bh = (int64_t)s.P * s.N / 8;
-    const int64_t gid = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (gid >= per_bh * s.B * s.H) return;
-    const int64_t bh = gid / per_bh;
-    const int64_t pn = (gid % per_bh) * 8;
-    const int b = (int)(bh / s.H), h = (int)(bh % s.H);
-    const int64_t PN = (int64_t)s.P * s.N;
-
-    float run[8];
-#pragma unroll
-    for (int v = 0; v < 8; ++v) run[v] = h0 ? h0[bh * PN + pn + v] : 0.f;
-
-    constexpr int UN = 4;  // chunks whose loads are issued together
-    for (int c0 = 0; c0 < s.nc; c0 += UN) {
-        uint4 S[UN];
-        float decay[UN];
-#pragma unroll
-        for (int u = 0; u < UN; ++u) {
-            const int c = min(c0 + u, s.nc - 1);
-            S[u] = *reinterpret_cast<const uint4 *>(lp + (((int64_t)b * s.nc + c) * s.H + h) * PN + pn);
-            decay[u] = expf(cs[(((int64_t)b * s.nc + c) * s.H + h) * s.Q + s.Q - 1]);
-        }
-#pragma unroll
-        for (int u = 0; u < UN; ++u) {
-            const int c = c0 + u;
-            if (c < s.nc) {
-                uint4 pk;
-                pk.x = (uint32_t)bf16_bits_rne(run[0]) | ((uint32_t)bf16_bits_rne(run[1]) << 16);
-                pk.y = (uint32_t)bf16_bits_rne(run[2]) | ((uint32_t)bf16_bits_rne(run[3]) << 16);
-                pk.z = (uint32_t)bf16_bits_rne(run[4]) | ((uint32_t)bf16_bits_rne(run[5]) << 16);
-                pk.w = (uint32_t)bf16_bits_rne(run[6]) | ((uint32_t)bf16_bits_rne(run[7]) << 16);
-                *reinterpret_cast<uint4 *>(lp + (((int64_t)b * s.nc + c) * s.H + h) * PN + pn) = pk;
-                float sv[8];
-                unpack_bf16x8(sv, S[u]);
-#pragma unroll
-                for (int v = 0; v < 8; ++v) run[v] = decay[u] * run[v] + sv[v];
-            }
-        }
-    }
-    if (h_final) {
-#pragma unroll
-        for (int v = 0; v < 8; ++v) h_final[bh * PN + pn + v] = run[v];
-    }
-}
-
-swimba_status launch_state_scan_lp(const Shape &s, const float *h0, float *h_final, void *states_lp,
-                                   const float *cs, hipStream_t st)
-{
-    const int64_t elems = (int64_t)s.B * s.H * s.P * s.N;   // N is a multiple of 8 on this path
-    if (elems == 0) return SWIMBA_OK;
-    const unsigned grid = (unsigned)((elems / 8 + 255) / 256);
-    hipLaunchKernelGGL(state_scan_lp_kernel, dim3(grid), dim3(256), 0, st, (uint16_t *)states_lp, h0,
-                       h_final, cs, s);
-    SWIMBA_CHECK_LAUNCH();
-    return SWIMBA_OK;
-}
-
 swimba_status launch_state_scan(const Shape &s, const float *h0, float *h_final, float *states,
                                 void *states_lp, const float *cs, hipStream_t st)
 {

@@ -2,13 +2,15 @@
 // (paper, background section on SSD: matrix multiplications inside chunks;
 // Theorem 1: the mixed streams feed one plain SSM).
 //
-// Three kernels:
-//   mix_cb       per (batch, chunk, group): gathers the k active expert rows of every
-//                token, mixes them with the router weights in fp32, and writes, in
-//                bf16 and in the register layout of the MFMA operands that consume
-//                them: the mixed C rows, the mixed B rows transposed in groups of 8
-//                tokens, and the causal 32x32 tiles of G^T = Bmix . Cmix^T.  These are
-//                shared by all heads of the group.
+// Four kernels:
+//   mix_rows     per (batch, chunk, group, 32-token tile): routes the tile's tokens,
+//                gathers their k active expert rows, mixes them with the router weights
+//                in fp32 and writes, in bf16 and in the register layout of the MFMA
+//                operands that consume them, the mixed C rows, the mixed B rows, and
+//                the mixed B rows transposed in groups of 8 tokens.  Shared by all
+//                heads of the group.
+//   scan_cb      the inter-chunk scan of the states; the same launch also computes the
+//                causal 32x32 tiles of G^T = Bmix . Cmix^T from the mixed rows.
 //   chunk_state  per (batch, chunk, head): S = (coef * x)^T . Bmix
 //   output       per (batch, chunk, head): y = (decay-masked G) (dt x) + exp(cs) Cmix . H + D x
 //
@@ -116,59 +118,65 @@ __device__ __forceinline__ void gather_mix_row(uint4 *frag, const uint16_t *tok,
 }
 
 // =========================================================================================
-// mix_cb.  Workgroup = (batch, chunk, group, role r): output tiles I0 = r and
-// I1 = NT-1-r of the chunk (32 tokens each).  Wave w takes the j tiles J = w, w+4.
-// The workgroup first routes the chunk's tokens itself (softmax over all experts,
-// top-k on the raw logits, no renormalisation) into LDS, and stores the routing of
-// its own two tiles to topk_idx / topk_w.  With sep_e >= 0 it prepares the streams of
-// ONE expert for the separated-SSM contrast instead: Bmix = B^(e), Cmix = gate * C^(e),
-// gate = pi_{t,e} if e is in the token's active set, else 0.
-//   cmix    (B, nc, G, NT, 8, 64, 8) bf16, mixed C of tile I as MFMA operand registers:
-//           [ks][lane][e] = Cmix[32I + lane%32][64*(lane/32) + 8ks + e]
+// mix_rows.  Workgroup = (batch, chunk, group, 32-token tile).  Lanes 0..31 route the
+// tile's tokens (softmax over all experts, top-k on the raw logits, no renormalisation)
+// into LDS and store the routing to topk_idx / topk_w; then wave 0 mixes the C rows,
+// wave 1 the B rows (both as MFMA operand registers) and waves 2, 3 the B rows again in
+// the token-innermost layout the chunk-state kernel contracts over.  With sep_e >= 0 it
+// prepares the streams of ONE expert for the separated-SSM contrast instead:
+// Bmix = B^(e), Cmix = gate * C^(e), gate = pi_{t,e} if e is in the active set, else 0.
+//   cmix, bfrag (B, nc, G, NT, 8, 64, 8) bf16, mixed rows of tile I as operand registers:
+//           [ks][lane][e] = mix[32I + lane%32][64*(lane/32) + 8ks + e]
 //   bmix_t8 (B, nc, G, Q/8, N, 8)    bf16, mixed B with 8 consecutive tokens innermost
-//   cb      (B, nc, G, NP, 2, 64, 8) bf16, tile pair (I,J), J <= I, at index I(I+1)/2+J:
-//           the accumulator registers v = 8t..8t+7 of lane l of G^T[j][i] = Bmix_j.Cmix_i
 // =========================================================================================
-template <int Q>
 __global__ void __launch_bounds__(MTHREADS)
-mix_cb_kernel(const uint16_t *__restrict__ Be, const uint16_t *__restrict__ Ce,
-              const uint16_t *__restrict__ logits, int32_t *__restrict__ idx_out,
-              float *__restrict__ w_out, uint16_t *__restrict__ cmix,
-              uint16_t *__restrict__ bmix_t8, uint16_t *__restrict__ cb, Shape s, int sep_e)
+mix_rows_kernel(const uint16_t *__restrict__ Be, const uint16_t *__restrict__ Ce,
+                const uint16_t *__restrict__ logits, int32_t *__restrict__ idx_out,
+                float *__restrict__ w_out, uint16_t *__restrict__ cmix, uint16_t *__restrict__ bfrag,
+                uint16_t *__restrict__ bmix_t8, Shape s, int sep_e)
 {
-    constexpr int NT = Q / 32, NR = NT / 2, NP = NT * (NT + 1) / 2;
     extern __shared__ __align__(16) unsigned char smem_raw[];
-    int32_t *s_idx = reinterpret_cast<int32_t *>(smem_raw);        // [Q][K]
-    float *s_w = reinterpret_cast<float *>(s_idx + Q * s.K);        // [Q][K]
+    const int Kr = s.K;                                             // experts kept by the router
+    int32_t *s_idx = reinterpret_cast<int32_t *>(smem_raw);        // [32][K]
+    float *s_w = reinterpret_cast<float *>(s_idx + 32 * Kr);        // [32][K]
     // separated-SSM contrast (sep_e >= 0): expert sep_e alone, B unweighted, C gated
-    int32_t *s_idx1 = reinterpret_cast<int32_t *>(s_w + Q * s.K);   // [Q]
-    float *s_wb1 = reinterpret_cast<float *>(s_idx1 + Q);           // [Q]
-    float *s_wc1 = s_wb1 + Q;                                       // [Q]
+    int32_t *s_idx1 = reinterpret_cast<int32_t *>(s_w + 32 * Kr);   // [32]
+    float *s_wb1 = reinterpret_cast<float *>(s_idx1 + 32);          // [32]
+    float *s_wc1 = s_wb1 + 32;                                      // [32]
+    constexpr int MIXROW = MN + 8;                                  // bf16 elements per padded row
+    uint16_t *s_mix = reinterpret_cast<uint16_t *>(s_wc1 + 32);     // [2][32][MIXROW], 16-byte aligned
+    float *s_log = reinterpret_cast<float *>(s_mix + 2 * 32 * MIXROW);   // [32][E + 1]
 
-    const int r = blockIdx.x % NR;
-    const int g = (blockIdx.x / NR) % s.G;
-    const int c = (blockIdx.x / (NR * s.G)) % s.nc;
-    const int b = blockIdx.x / (NR * s.G * s.nc);
+    const int NT = s.Q / 32;
+    const int tile = blockIdx.x % NT;
+    const int g = (blockIdx.x / NT) % s.G;
+    const int c = (blockIdx.x / (NT * s.G)) % s.nc;
+    const int b = blockIdx.x / (NT * s.G * s.nc);
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, kg = lane >> 5;
-    const int64_t tok0 = (int64_t)b * s.L + (int64_t)c * Q;
-    const int valid = min(Q, s.L - c * Q);
-    const int Kr = s.K;                                  // experts kept by the router
+    const int valid = min(s.Q, s.L - c * s.Q) - tile * 32;     // tokens of this tile inside the sequence
+    const int64_t tok0 = (int64_t)b * s.L + (int64_t)c * s.Q + tile * 32;
+    const int64_t last = (int64_t)b * s.L + min(s.L, (c + 1) * s.Q) - 1 - tok0;   // clamp for padded rows
     const int estride = s.G * MN;
     const int tokstride = s.E * estride;                 // elements between tokens of B/C_experts
     const int64_t bcg = ((int64_t)b * s.nc + c) * s.G + g;
-    const int tiles[2] = {r, NT - 1 - r};
-    const uint16_t *Bg = Be + (tok0 * s.E * s.G + g) * MN;   // [token 0 of the chunk][expert 0][g][0]
+    const uint16_t *Bg = Be + (tok0 * s.E * s.G + g) * MN;   // [token 0 of the tile][expert 0][g][0]
     const uint16_t *Cg = Ce + (tok0 * s.E * s.G + g) * MN;
 
-    // ---- routing of the chunk's tokens ----
-    for (int t = tid; t < Q; t += MTHREADS) {
+    // ---- routing of the tile's tokens: logits staged through LDS (one coalesced read) ----
+    {
+        const int nlog = max(0, min(valid, 32)) * s.E;
+        const uint16_t *gl = logits + tok0 * s.E;
+        for (int i = tid; i < nlog; i += MTHREADS) s_log[(i / s.E) * (s.E + 1) + i % s.E] = to_float(bf16{gl[i]});
+    }
+    lds_barrier();
+    if (tid < 32) {
+        const int t = tid;
         if (t < valid) {
-            const uint16_t *gl = logits + (tok0 + t) * s.E;
-            route_token([&](int e) { return to_float(bf16{gl[e]}); }, s.E, Kr, s_idx + t * Kr, s_w + t * Kr);
-            const int tile = t >> 5;
-            if (g == 0 && sep_e <= 0 && (tile == tiles[0] || tile == tiles[1])) {
+            const float *gl = s_log + t * (s.E + 1);
+            route_token([&](int e) { return gl[e]; }, s.E, Kr, s_idx + t * Kr, s_w + t * Kr);
+            if (g == 0 && sep_e <= 0) {
                 for (int rr = 0; rr < Kr; ++rr) {
                     idx_out[(tok0 + t) * Kr + rr] = s_idx[t * Kr + rr];
                     w_out[(tok0 + t) * Kr + rr] = s_w[t * Kr + rr];
@@ -195,152 +203,195 @@ mix_cb_kernel(const uint16_t *__restrict__ Be, const uint16_t *__restrict__ Ce,
     const float *wtB = (sep_e >= 0) ? s_wb1 : s_w;
     const float *wtC = (sep_e >= 0) ? s_wc1 : s_w;
 
-    // All gathers of the workgroup are independent once the routing is known: the loads of
-    // (a), (b) and of the first j tile of (c) are issued back to back before any of them is
-    // consumed (one memory latency instead of four).  Experts are taken two at a time.
-    auto row_loads = [&](uint4 (&v)[2][8], const uint16_t *tok, const int32_t *ix, int r0) {
+    // ---- gather and mix: a lane owns one 16-byte piece (8 n) of tokens tg and tg+16, both
+    // streams; 16 consecutive lanes read one whole 256-byte expert row.  Experts two at a time.
+    const int piece = tid & 15, tg = tid >> 4;
+    float accB[2][8], accC[2][8];
 #pragma unroll
-        for (int q = 0; q < 2; ++q) {
-            const uint16_t *row = tok + ix[min(r0 + q, K - 1)] * estride + 64 * kg;
+    for (int jj = 0; jj < 2; ++jj)
 #pragma unroll
-            for (int ks = 0; ks < 8; ++ks) v[q][ks] = *reinterpret_cast<const uint4 *>(row + ks * 8);
+        for (int e = 0; e < 8; ++e) accB[jj][e] = accC[jj][e] = 0.f;
+    for (int r0 = 0; r0 < K; r0 += 2) {
+        uint4 vb[2][2], vc[2][2];
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj) {
+            const int j = tg + 16 * jj;
+            const int64_t rowoff = min((int64_t)j, last) * tokstride + piece * 8;
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {
+                const int eo = ixt[j * K + min(r0 + q, K - 1)] * estride;
+                vb[jj][q] = *reinterpret_cast<const uint4 *>(Bg + rowoff + eo);
+                vc[jj][q] = *reinterpret_cast<const uint4 *>(Cg + rowoff + eo);
+            }
         }
-    };
-    auto row_accumulate = [&](float (&acc)[8][8], const uint4 (&v)[2][8], const float *wt, int r0) {
 #pragma unroll
-        for (int q = 0; q < 2; ++q) {
-            const float wr = (r0 + q < K) ? wt[r0 + q] : 0.f;
+        for (int jj = 0; jj < 2; ++jj) {
+            const int j = tg + 16 * jj;
 #pragma unroll
-            for (int ks = 0; ks < 8; ++ks) fma_bf16x8(acc[ks], v[q][ks], wr);
+            for (int q = 0; q < 2; ++q) {
+                const bool on = r0 + q < K;
+                fma_bf16x8(accB[jj], vb[jj][q], on ? wtB[j * K + r0 + q] : 0.f);
+                fma_bf16x8(accC[jj], vc[jj][q], on ? wtC[j * K + r0 + q] : 0.f);
+            }
         }
-    };
-    // mixed row (operand layout) of token j of stream S, given the loads of its first two experts
-    auto finish_row = [&](uint4 *frag, uint4 (&v)[2][8], const uint16_t *tok, int j, const float *wt) {
-        float acc[8][8];
+    }
+    // mixed tiles, row-major bf16 with padded rows: [stream][32][MIXROW]
+#pragma unroll
+    for (int jj = 0; jj < 2; ++jj) {
+        const int j = tg + 16 * jj;
+        *reinterpret_cast<uint4 *>(s_mix + j * MIXROW + piece * 8) = pack8(accB[jj]);
+        *reinterpret_cast<uint4 *>(s_mix + (32 + j) * MIXROW + piece * 8) = pack8(accC[jj]);
+    }
+    lds_barrier();
+
+    if (wave < 2) {
+        // operand registers: lane (l32, kg) holds n = 64 kg + 8 ks .. + 7 of token l32
+        const uint16_t *src = s_mix + ((wave == 0 ? 32 : 0) + l32) * MIXROW + 64 * kg;
+        uint16_t *dst = (wave == 0 ? cmix : bfrag) + (((bcg * NT + tile) * 8) * 64 + lane) * 8;
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks)
+            *reinterpret_cast<uint4 *>(dst + ks * 64 * 8) = *reinterpret_cast<const uint4 *>(src + ks * 8);
+    } else {
+        // mixed B, 8 tokens innermost: lane = state index n, one 16-byte store per token octet
+        const int n = tid - 128;
 #pragma unroll
-            for (int e = 0; e < 8; ++e) acc[ks][e] = 0.f;
-        row_accumulate(acc, v, wt + j * K, 0);
-        for (int r0 = 2; r0 < K; r0 += 2) {       // top_k > 2: the remaining experts, pair by pair
-            row_loads(v, tok, ixt + j * K, r0);
-            row_accumulate(acc, v, wt + j * K, r0);
-        }
+        for (int jgl = 0; jgl < 4; ++jgl) {
+            uint32_t pk[4];
 #pragma unroll
-        for (int ks = 0; ks < 8; ++ks) frag[ks] = pack8(acc[ks]);
-    };
-
-    // (a) mixed B of the two owned tiles, 8 tokens innermost; a lane does 4 tokens x 8 n
-    const int half = tid & 1, piece = (tid >> 1) & 15, jgl = (tid >> 5) & 3, sel = tid >> 7;
-    const int jg = tiles[sel] * 4 + jgl;                 // group of 8 tokens inside the chunk
-    uint4 va[4][2];
-#pragma unroll
-    for (int jj = 0; jj < 4; ++jj) {
-        const int j = jg * 8 + half * 4 + jj;
-        const uint16_t *rowbase = Bg + min(j, valid - 1) * tokstride + piece * 8;
-#pragma unroll
-        for (int q = 0; q < 2; ++q)
-            va[jj][q] = *reinterpret_cast<const uint4 *>(rowbase + ixt[j * K + min(q, K - 1)] * estride);
-    }
-    // (b) mixed C rows of the owned tiles; (c) mixed B rows of the first j tile of this wave
-    // (a wave beyond the chunk's last j tile has no (c) work: its early load is clamped to a
-    // valid token so that the expert index it reads is a real one)
-    const int i0 = tiles[0] * 32 + l32, i1 = tiles[1] * 32 + l32;
-    const int jfirst = min(wave, tiles[1]) * 32 + l32;
-    const uint16_t *tokc0 = Cg + min(i0, valid - 1) * tokstride;
-    const uint16_t *tokc1 = Cg + min(i1, valid - 1) * tokstride;
-    const uint16_t *tokb = Bg + min(jfirst, valid - 1) * tokstride;
-    uint4 vc0[2][8], vc1[2][8], vb[2][8];
-    row_loads(vc0, tokc0, ixt + i0 * K, 0);
-    row_loads(vc1, tokc1, ixt + i1 * K, 0);
-    row_loads(vb, tokb, ixt + jfirst * K, 0);
-
-    // ---- consume (a) ----
-    {
-        float acc[4][8];
-#pragma unroll
-        for (int jj = 0; jj < 4; ++jj) {
-#pragma unroll
-            for (int e = 0; e < 8; ++e) acc[jj][e] = 0.f;
-            const int j = jg * 8 + half * 4 + jj;
-            fma_bf16x8(acc[jj], va[jj][0], wtB[j * K]);
-            fma_bf16x8(acc[jj], va[jj][1], K > 1 ? wtB[j * K + 1] : 0.f);
-            const uint16_t *rowbase = Bg + min(j, valid - 1) * tokstride + piece * 8;
-            for (int rr = 2; rr < K; ++rr)
-                fma_bf16x8(acc[jj], *reinterpret_cast<const uint4 *>(rowbase + ixt[j * K + rr] * estride),
-                           wtB[j * K + rr]);
-        }
-        uint16_t *dst = bmix_t8 + ((bcg * (Q / 8) + jg) * MN + piece * 8) * 8 + half * 4;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            uint2 pk;
-            pk.x = pack_bf16x2(acc[0][e], acc[1][e]);
-            pk.y = pack_bf16x2(acc[2][e], acc[3][e]);
-            *reinterpret_cast<uint2 *>(dst + e * 8) = pk;
-        }
-    }
-    // ---- consume (b): operand registers; waves 0 and 1 also store one tile each ----
-    uint4 cfrag[2][8];
-    finish_row(cfrag[0], vc0, tokc0, i0, wtC);
-    finish_row(cfrag[1], vc1, tokc1, i1, wtC);
-#pragma unroll
-    for (int sl = 0; sl < 2; ++sl) {
-        if (wave == sl) {
-            uint16_t *dst = cmix + (((bcg * NT + tiles[sl]) * 8) * 64 + lane) * 8;
-#pragma unroll
-            for (int ks = 0; ks < 8; ++ks) *reinterpret_cast<uint4 *>(dst + ks * 64 * 8) = cfrag[sl][ks];
-        }
-    }
-
-    // ---- (c) G^T tiles ----
-    for (int J = wave; J <= tiles[1]; J += 4) {
-        const int j = J * 32 + l32;
-        const uint16_t *tok = Bg + min(j, valid - 1) * tokstride;
-        if (J != wave) row_loads(vb, tok, ixt + j * K, 0);
-        uint4 bfrag[8];
-        finish_row(bfrag, vb, tok, j, wtB);
-#pragma unroll
-        for (int sl = 0; sl < 2; ++sl) {
-            const int I = tiles[sl];
-            if (J > I) continue;
-            f32x16_t acc = {0};
-#pragma unroll
-            for (int ks = 0; ks < 8; ++ks) acc = mfma32(bfrag[ks], cfrag[sl][ks], acc);
-            float m[16];
-#pragma unroll
-            for (int v = 0; v < 16; ++v) m[v] = acc[v];
-            uint16_t *dst = cb + ((bcg * NP + I * (I + 1) / 2 + J) * 2 * 64 + lane) * 8;
-            *reinterpret_cast<uint4 *>(dst) = pack8(m);
-            *reinterpret_cast<uint4 *>(dst + 64 * 8) = pack8(m + 8);
+            for (int q = 0; q < 4; ++q) {
+                const uint32_t lo = s_mix[(jgl * 8 + 2 * q) * MIXROW + n];
+                const uint32_t hi = s_mix[(jgl * 8 + 2 * q + 1) * MIXROW + n];
+                pk[q] = lo | (hi << 16);
+            }
+            *reinterpret_cast<uint4 *>(bmix_t8 + ((bcg * (s.Q / 8) + tile * 4 + jgl) * MN + n) * 8) =
+                make_uint4(pk[0], pk[1], pk[2], pk[3]);
         }
     }
 }
 
-template <int Q>
-static swimba_status launch_mix_q(const Shape &s, const void *Be, const void *Ce, const void *logits,
-                                  int32_t *idx, float *w, void *cmix, void *bmix_t8, void *cb,
-                                  int sep_e, hipStream_t st)
+// =========================================================================================
+// cb tile of one wave: pair p = I(I+1)/2 + J, J <= I, of one (batch, chunk, group):
+//   cb (B, nc, G, NP, 2, 64, 8) bf16: the accumulator registers v = 8t..8t+7 of lane l
+//   of G^T[j][i] = Bmix_j . Cmix_i  (32 x 32 tile)
+// Both operands are read as the register images mix_rows stored.
+// =========================================================================================
+__device__ __forceinline__ void cb_pair(const uint16_t *__restrict__ cmix, const uint16_t *__restrict__ bfrag,
+                                        uint16_t *__restrict__ cb, int NT, int64_t bcg, int p, int lane)
 {
-    const int64_t total = (int64_t)s.B * s.nc * s.G * (Q / 64);
-    if (total == 0) return SWIMBA_OK;
-    const size_t shm = (size_t)Q * s.K * 8 + (size_t)Q * 12;
-    hipLaunchKernelGGL(mix_cb_kernel<Q>, dim3((unsigned)total), dim3(MTHREADS), shm, st,
+    const int NP = NT * (NT + 1) / 2;
+    int I = 0;
+    while ((I + 1) * (I + 2) / 2 <= p) ++I;
+    const int J = p - I * (I + 1) / 2;
+    const uint16_t *cs = cmix + (((bcg * NT + I) * 8) * 64 + lane) * 8;
+    const uint16_t *bs = bfrag + (((bcg * NT + J) * 8) * 64 + lane) * 8;
+    uint4 cf[8], bf[8];
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) {
+        cf[ks] = *reinterpret_cast<const uint4 *>(cs + ks * 64 * 8);
+        bf[ks] = *reinterpret_cast<const uint4 *>(bs + ks * 64 * 8);
+    }
+    f32x16_t acc = {0};
+#pragma unroll
+    for (int ks = 0; ks < 8; ++ks) acc = mfma32(bf[ks], cf[ks], acc);
+    float m[16];
+#pragma unroll
+    for (int v = 0; v < 16; ++v) m[v] = acc[v];
+    uint16_t *dst = cb + ((bcg * NP + p) * 2 * 64 + lane) * 8;
+    *reinterpret_cast<uint4 *>(dst) = pack8(m);
+    *reinterpret_cast<uint4 *>(dst + 64 * 8) = pack8(m + 8);
+}
+
+// =========================================================================================
+// Inter-chunk scan over bf16 chunk states, H_0 = h0, H_{c+1} = exp(cs_c[Q-1]) H_c + S_c,
+// states[c] <- H_c in place: the running state is fp32 in registers, 8 state elements per
+// lane, the loads of 4 chunks in flight.  The first ncb workgroups of the launch do
+// not scan: each of their waves computes one cb tile (see cb_pair), work that only
+// depends on the mixed rows and is needed by the output kernel alone, so it rides in
+// this launch instead of paying for one of its own.
+// =========================================================================================
+__global__ void __launch_bounds__(MTHREADS)
+scan_cb_kernel(uint16_t *__restrict__ lp, const float *__restrict__ h0, float *__restrict__ h_final,
+               const float *__restrict__ cs, const uint16_t *__restrict__ cmix,
+               const uint16_t *__restrict__ bfrag, uint16_t *__restrict__ cb, Shape s, int ncb, int64_t nbcg)
+{
+    if ((int)blockIdx.x < ncb) {
+        const int NT = s.Q / 32, PB = (NT * (NT + 1) / 2 + 3) / 4;
+        // consecutive logical ids (the pairs of one (batch, chunk, group)) share an XCD and its L2
+        const int64_t id = xcd_logical_id(blockIdx.x, ncb);
+        const int64_t bcg = id / PB;
+        const int p = (int)(id % PB) * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+        if (bcg < nbcg && p < NT * (NT + 1) / 2) cb_pair(cmix, bfrag, cb, NT, bcg, p, threadIdx.x & 63);
+        return;
+    }
+    const int64_t per_bh = (int64_t)s.P * s.N / 8;
+    const int64_t gid = (int64_t)(blockIdx.x - ncb) * blockDim.x + threadIdx.x;
+    if (gid >= per_bh * s.B * s.H) return;
+    const int64_t bh = gid / per_bh;
+    const int64_t pn = (gid % per_bh) * 8;
+    const int b = (int)(bh / s.H), h = (int)(bh % s.H);
+    const int64_t PN = (int64_t)s.P * s.N;
+
+    float run[8];
+#pragma unroll
+    for (int v = 0; v < 8; ++v) run[v] = h0 ? h0[bh * PN + pn + v] : 0.f;
+
+    constexpr int UN = 4;  // chunks whose loads are issued together
+    for (int c0 = 0; c0 < s.nc; c0 += UN) {
+        uint4 S[UN];
+        float decay[UN];
+#pragma unroll
+        for (int u = 0; u < UN; ++u) {
+            const int c = min(c0 + u, s.nc - 1);
+            S[u] = *reinterpret_cast<const uint4 *>(lp + (((int64_t)b * s.nc + c) * s.H + h) * PN + pn);
+            decay[u] = fast_exp2(cs[(((int64_t)b * s.nc + c) * s.H + h) * s.Q + s.Q - 1] * LOG2E);
+        }
+#pragma unroll
+        for (int u = 0; u < UN; ++u) {
+            const int c = c0 + u;
+            if (c < s.nc) {
+                *reinterpret_cast<uint4 *>(lp + (((int64_t)b * s.nc + c) * s.H + h) * PN + pn) = pack8(run);
+                float sv[8];
+                unpack8(sv, S[u]);
+#pragma unroll
+                for (int v = 0; v < 8; ++v) run[v] = decay[u] * run[v] + sv[v];
+            }
+        }
+    }
+    if (h_final) {
+#pragma unroll
+        for (int v = 0; v < 8; ++v) h_final[bh * PN + pn + v] = run[v];
+    }
+}
+
+swimba_status launch_mix_rows_mfma(const Shape &s, const void *Be, const void *Ce, const void *logits,
+                                   int32_t *idx, float *w, void *cmix, void *bfrag, void *bmix_t8,
+                                   int sep_e, hipStream_t st)
+{
+    const int NT = s.Q / 32;
+    const int64_t nbcg = (int64_t)s.B * s.nc * s.G;
+    if (nbcg == 0) return SWIMBA_OK;
+    const size_t shm = (size_t)32 * s.K * 8 + 32 * 12 + (size_t)2 * 32 * (MN + 8) * 2 + (size_t)32 * (s.E + 1) * 4;
+    hipLaunchKernelGGL(mix_rows_kernel, dim3((unsigned)(nbcg * NT)), dim3(MTHREADS), shm, st,
                        (const uint16_t *)Be, (const uint16_t *)Ce, (const uint16_t *)logits, idx, w,
-                       (uint16_t *)cmix, (uint16_t *)bmix_t8, (uint16_t *)cb, s, sep_e);
+                       (uint16_t *)cmix, (uint16_t *)bfrag, (uint16_t *)bmix_t8, s, sep_e);
     SWIMBA_CHECK_LAUNCH();
     return SWIMBA_OK;
 }
 
-swimba_status launch_mix_cb_mfma(const Shape &s, const void *Be, const void *Ce, const void *logits,
-                                 int32_t *idx, float *w, void *cmix, void *bmix_t8, void *cb,
-                                 int sep_e, hipStream_t st)
+swimba_status launch_scan_cb_mfma(const Shape &s, const float *h0, float *h_final, void *states_lp,
+                                  const float *cs, const void *cmix, const void *bfrag, void *cb,
+                                  hipStream_t st)
 {
-    switch (s.Q) {
-    case 64: return launch_mix_q<64>(s, Be, Ce, logits, idx, w, cmix, bmix_t8, cb, sep_e, st);
-    case 128: return launch_mix_q<128>(s, Be, Ce, logits, idx, w, cmix, bmix_t8, cb, sep_e, st);
-    case 256: return launch_mix_q<256>(s, Be, Ce, logits, idx, w, cmix, bmix_t8, cb, sep_e, st);
-    }
-    return SWIMBA_ERR_UNSUPPORTED;
+    const int64_t elems = (int64_t)s.B * s.H * MP * MN;
+    const int64_t nbcg = (int64_t)s.B * s.nc * s.G;
+    if (elems == 0) return SWIMBA_OK;
+    const int NT = s.Q / 32;
+    const int ncb = xcd_padded(nbcg * ((NT * (NT + 1) / 2 + 3) / 4));   // 0 for an empty sequence
+    const unsigned grid = (unsigned)(ncb + (elems / 8 + MTHREADS - 1) / MTHREADS);
+    hipLaunchKernelGGL(scan_cb_kernel, dim3(grid), dim3(MTHREADS), 0, st, (uint16_t *)states_lp, h0, h_final, cs,
+                       (const uint16_t *)cmix, (const uint16_t *)bfrag, (uint16_t *)cb, s, ncb, nbcg);
+    SWIMBA_CHECK_LAUNCH();
+    return SWIMBA_OK;
 }
 
 // =========================================================================================

@@ -37,7 +37,7 @@ def test_workspace_query_and_layout():
     n = sw.swimba_mixer_workspace_bytes(d)
     lo = sw.swimba_mixer_workspace_layout(d)
     assert n == lo.total and n > 0
-    offs = [lo.topk_idx, lo.topk_w, lo.cs, lo.states, lo.states_lp, lo.cmix, lo.bmix_t8, lo.cb]
+    offs = [lo.topk_idx, lo.topk_w, lo.cs, lo.states, lo.states_lp, lo.cmix, lo.bmix_t8, lo.bmix_frag, lo.cb]
     assert offs == sorted(offs) and all(o % 256 == 0 for o in offs)
     assert lo.topk_w - lo.topk_idx >= 256 * 2 * 4
     assert lo.states - lo.cs >= 4 * 4 * 64 * 4
@@ -49,7 +49,8 @@ def test_workspace_query_and_layout():
     lm = sw.swimba_mixer_workspace_layout(m)
     assert lm.states_lp == lm.states          # no fp32 states on the MFMA path
     assert lm.cmix - lm.states_lp >= 2 * 4 * 64 * 128 * 2
-    assert lm.bmix_t8 - lm.cmix >= 512 * 128 * 2 and lm.cb - lm.bmix_t8 >= 512 * 128 * 2
+    assert lm.bmix_t8 - lm.cmix >= 512 * 128 * 2 and lm.bmix_frag - lm.bmix_t8 >= 512 * 128 * 2
+    assert lm.cb - lm.bmix_frag >= 512 * 128 * 2
     assert lm.total - lm.cb >= 2 * 36 * 2048
 
 
