@@ -147,13 +147,15 @@ def main() -> int:
     NT = Q // 32
     cb_bytes = nchunks * G * (NT * (NT + 1) // 2) * 2048
     work = {
-        # router + mixing: reads logits and the k active B and C rows; writes top-k, mixed C,
-        # mixed B (bf16) and the causal C.B^T tiles; C.B^T on MFMA (dense count 2 T Q N G)
-        "mix": (T * (E * 2 + k * 8 + 2 * k * G * N * 2 + 2 * G * N * 2) + cb_bytes, 2.0 * T * Q * N * G),
+        # router + mixing: reads logits and the k active B and C rows; writes top-k, the mixed C
+        # rows and the mixed B rows in two layouts (bf16)
+        "mix": (T * (E * 2 + k * 8 + 2 * k * G * N * 2 + 3 * G * N * 2), 0.0),
         # cumsum + chunk state: reads x, dt, mixed B; writes cs and the bf16 chunk states
         "chunk_state": (T * (H * P * 2 + H * 2 + G * N * 2 + H * 4) + state_elems * 2, 2.0 * T * N * P * H),
-        # reads the bf16 chunk states, writes the bf16 carried states in place, and h_final
-        "state_scan": (state_elems * (2 + 2) + w.batch * H * P * N * 4, 0.0),
+        # reads the bf16 chunk states, writes the bf16 carried states in place, and h_final; the
+        # same launch reads the mixed rows and writes the causal C.B^T tiles (dense count 2 T Q N G)
+        "state_scan": (state_elems * (2 + 2) + w.batch * H * P * N * 4 + T * 2 * G * N * 2 + cb_bytes,
+                       2.0 * T * Q * N * G),
         # reads x, dt, cs, carried states, mixed C, C.B^T tiles; writes y; masked (C B^T) X and
         # C.H per head on MFMA (dense counts; causally skipped tiles are counted)
         "output": (T * (2 * H * P * 2 + H * 2 + H * 4 + G * N * 2) + state_elems * 2 + cb_bytes,

@@ -77,6 +77,19 @@ __device__ __forceinline__ int xcd_logical_id(int bid, int nblocks)
 }
 static inline int xcd_padded(int64_t total) { return (int)((total + 7) / 8 * 8); }
 
+// 16-byte accesses that are not worth caching (read once / written once by this kernel)
+typedef unsigned int __attribute__((ext_vector_type(4))) u32x4_t;
+__device__ __forceinline__ uint4 load_nt(const uint16_t *p)
+{
+    const u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(p));
+    return make_uint4(v.x, v.y, v.z, v.w);
+}
+__device__ __forceinline__ void store_nt(uint16_t *p, uint4 v)
+{
+    const u32x4_t pv = {v.x, v.y, v.z, v.w};
+    __builtin_nontemporal_store(pv, reinterpret_cast<u32x4_t *>(p));
+}
+
 __device__ __forceinline__ float fast_exp2(float v) { return __builtin_amdgcn_exp2f(v); }
 
 // Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every
@@ -660,7 +673,7 @@ output_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ 
 #pragma unroll
         for (int pass = 0; pass < HPASS; ++pass) {
             const int row = (tid >> 4) + (NTHR / 16) * pass, piece = tid & 15;
-            hreg[pass] = *reinterpret_cast<const uint4 *>(Hc + row * MN + piece * 8);
+            hreg[pass] = load_nt(Hc + row * MN + piece * 8);   // the carried state is read once
         }
     }
     // x staging: unit = (8 tokens in operand order) x (2 channels)
@@ -844,7 +857,7 @@ output_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ 
                 unpack8(xf, xe[q4]);
 #pragma unroll
                 for (int e = 0; e < 8; ++e) a[e] += dsk * xf[e];
-                *reinterpret_cast<uint4 *>(yh + i * tokstride + epiece * 8) = pack8(a);
+                store_nt(yh + i * tokstride + epiece * 8, pack8(a));
             }
         }
     }

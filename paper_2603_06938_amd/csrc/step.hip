@@ -23,10 +23,11 @@ step_mix_kernel(const T *__restrict__ Be, const T *__restrict__ Ce, const T *__r
     __shared__ int32_t s_idx[SWIMBA_MAX_TOPK];
     const int b = blockIdx.x / s.G, g = blockIdx.x % s.G;
     const int tid = threadIdx.x;
-    if (tid == 0) {
-        const T *gl = logits + (int64_t)b * s.E;
-        route_token([&](int e) { return to_float(gl[e]); }, s.E, s.K, s_idx, s_w);
-    }
+    // the logits go through LDS first: one memory latency instead of one per pass of the router
+    __shared__ float s_log[SWIMBA_MAX_EXPERTS];
+    for (int e = tid; e < s.E; e += 128) s_log[e] = to_float(logits[(int64_t)b * s.E + e]);
+    __syncthreads();
+    if (tid == 0) route_token([&](int e) { return s_log[e]; }, s.E, s.K, s_idx, s_w);
     __syncthreads();
     if (idx_out && g == 0 && tid < s.K) idx_out[(int64_t)b * s.K + tid] = s_idx[tid];
     const T *Bb = Be + ((int64_t)b * s.E * s.G + g) * s.N;
