@@ -148,15 +148,19 @@ swimba_status swimba_mixer_fwd(const swimba_dims *dims, const void *x, const voi
 
 /*
  * The stages of swimba_mixer_fwd, one call each, on the same workspace (for
- * per-kernel measurement and stage-level tests).  Running router, cumsum,
+ * per-kernel measurement and stage-level tests).  Running router, cumsum, mix,
  * chunk_state, state_scan, output in this order equals swimba_mixer_fwd.
- *   router      : logits -> ws.topk_idx, ws.topk_w
- *   cumsum      : dt, A  -> ws.cs                (per-chunk cumsum of dt*A)
+ *   router      : logits -> ws.topk_idx, ws.topk_w     (no-op on the bf16 MFMA path: mix routes)
+ *   cumsum      : dt, A  -> ws.cs   (per-chunk cumsum of dt*A; no-op on the bf16 MFMA path:
+ *                 chunk_state computes it)
+ *   mix         : bf16 MFMA path only (no-op otherwise): logits, B/C_experts -> ws.topk_*,
+ *                 ws.cmix, ws.bmix_frag, ws.bmix_t8 (router + parameter-space mixing)
  *   chunk_state : x, dt, B_experts, ws.{topk_*,cs} -> ws.states = S_c
  *                 S_c = sum_j exp(cs_last - cs_j) dt_j x_j (x) Bmix_j
  *   state_scan  : ws.states (ws.states_lp on the bf16 MFMA path): S_c -> state carried
  *                 into chunk c, in place; h0, ws.cs -> h_final.  The running state is
- *                 fp32 in registers on both paths.
+ *                 fp32 in registers on both paths.  On the bf16 MFMA path the same launch
+ *                 also turns ws.cmix, ws.bmix_frag into ws.cb (tiles of Bmix.Cmix^T).
  *   output      : x, dt, D, B/C_experts, ws.* -> y
  *                 y_i = sum_{j<=i} (Cmix_i.Bmix_j) exp(cs_i - cs_j) dt_j x_j
  *                       + exp(cs_i) Cmix_i . H_c + D x_i
