@@ -35,6 +35,8 @@ def main() -> int:
     ap.add_argument("--decode-steps", type=int, default=256)
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--no-decode", action="store_true")
+    ap.add_argument("--contrast", action="store_true",
+                    help="also time the separated-SSM contrast (E state trajectories) on the same inputs")
     ap.add_argument("--stage", default=None,
                     help="run only this stage in the timed loop (for profilers): "
                          "mix|chunk_state|state_scan|output|step|copy")
@@ -212,6 +214,23 @@ def main() -> int:
             print(json.dumps(decode))
             return 0
 
+    # ---- separated-SSM contrast: E plain SSM passes through the same kernels --------------------
+    contrast = None
+    if args.contrast and not args.stage:
+        d0 = sets[0]
+        sws = torch.empty(sw.swimba_separated_workspace_bytes(dims), dtype=torch.uint8, device=dev)
+
+        def sep(i):
+            d = sets[i % nsets]
+            sw.swimba_separated_fwd(d["x"], d["dt"], d["A"], d["D"], d["B_experts"], d["C_experts"],
+                                    d["router_logits"], w.top_k, w.chunk, y=d["y"], workspace=sws)
+
+        time_loop(sep, 2)
+        ms = time_loop(sep, max(3, K // 5))
+        contrast = {"what": "MoE of separated SSMs, %d state trajectories" % w.nexperts, "ms_per_step": round(ms, 4),
+                    "tokens_per_s": round(w.tokens / ms * 1e3, 1), "slowdown_vs_mixed": round(ms / ev_ms, 2)}
+        del sws, d0
+
     # ---- CPU oracle on the host cores (reported baseline only) -------------------------------
     cpu = None
     if not args.no_cpu:
@@ -262,6 +281,8 @@ def main() -> int:
         "decode": decode,
         "cpu_baseline": cpu,
     }
+    if contrast:
+        out["separated_contrast"] = contrast
     print(json.dumps(out))
     return 0
 

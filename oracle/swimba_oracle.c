@@ -24,6 +24,10 @@
  *   separated   h_t^(e) = exp(dt_t A_h) h_{t-1}^(e) + dt_t B_t^(e) x_t^T for
  *               every expert e, y_t = sum_{e in K_t} pi_{t,e} C_t^(e) . h_t^(e)
  *               + D_h x_t                       (separated-SSM equation)
+ *   expert x    the mixed state update in its full form, with one input stream
+ *               per expert: h_t = exp(dt_t A_h) h_{t-1}
+ *               + dt_t sum_{e in K_t} pi_{t,e} x_t^(e) (x) B_t^(e); same readout
+ *               (swimba_oracle_mixer_fwd_xe)
  *
  * Readings where the paper is silent (kept in step with the design notes):
  *   - ties between equal logits go to the lower expert index, and the active
@@ -31,7 +35,9 @@
  *   - the transition is one negative scalar A_h per head, time variation comes
  *     only from dt; dt is a single positive stream, not routed;
  *   - x is shared by the experts (the API has one x), so the mixed injection
- *     is the rank-1 term dt Bmix x^T;
+ *     is the rank-1 term dt Bmix x^T; the expert-x function takes the paper's
+ *     per-expert input streams instead, and its skip term D_h multiplies the
+ *     mixed input sum_{e in K_t} pi_{t,e} x_t^(e) (the paper has no skip term);
  *   - B/C streams come per group, head h reads group floor(h*G/H);
  *   - D is a per-head skip coefficient (NULL means 0);
  *   - the state starts at h0 (NULL means zeros).
@@ -165,6 +171,68 @@ int swimba_oracle_mixer_fwd(const oracle_dims *d, const float *x, const float *d
         }
         if (h_final) memcpy(h_final + (b * H + h) * P * N, st, sizeof(double) * P * N);
         free(st); free(Bm); free(Cm);
+    }
+    return 0;
+}
+
+/*
+ * Mixed forward with expert-specific input streams (paper: mixed state update
+ * equation in its full form, every expert brings its own X stream):
+ *   h_t = exp(dt_t A_h) h_{t-1} + dt_t sum_{e in K_t} pi_{t,e} x_t^(e) (x) B_t^(e)
+ *   y_t = (sum_{e in K_t} pi_{t,e} C_t^(e)) . h_t + D_h xbar_t,
+ *   xbar_t = sum_{e in K_t} pi_{t,e} x_t^(e)    (the skip term sees the mixed input)
+ * The injection is a sum of k outer products per token (rank k), the state is one.
+ *   xe (B,L,E,H,P); everything else as in swimba_oracle_mixer_fwd.
+ */
+int swimba_oracle_mixer_fwd_xe(const oracle_dims *d, const float *xe, const float *dt,
+                               const float *A, const float *D, const float *Be, const float *Ce,
+                               const float *logits, const double *h0, double *y, double *h_final,
+                               int32_t *idx, double *w)
+{
+    const int64_t B = d->batch, L = d->seqlen, H = d->nheads, P = d->headdim, N = d->dstate,
+                  G = d->ngroups, E = d->nexperts, k = d->top_k;
+    if (B < 0 || L < 0 || H < 1 || P < 1 || N < 1 || G < 1 || E < 1 || k < 1 || k > E || H % G)
+        return 1;
+    if (swimba_oracle_router(logits, B * L, E, k, idx, w)) return 1;
+
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int64_t bh = 0; bh < B * H; ++bh) {
+        const int64_t b = bh / H, h = bh % H, q = (h * G) / H;
+        double *st = (double *)malloc(sizeof(double) * P * N);
+        double *Cm = (double *)malloc(sizeof(double) * N);
+        for (int64_t i = 0; i < P * N; ++i) st[i] = h0 ? h0[(b * H + h) * P * N + i] : 0.0;
+
+        for (int64_t t = 0; t < L; ++t) {
+            const int64_t bt = b * L + t;
+            const double dtt = (double)dt[bt * H + h];
+            const double a = exp(dtt * (double)A[h]);
+            /* decay, then the k weighted outer products of the active experts */
+            for (int64_t i = 0; i < P * N; ++i) st[i] *= a;
+            for (int64_t n = 0; n < N; ++n) Cm[n] = 0.0;
+            for (int64_t r = 0; r < k; ++r) {
+                const int64_t e = idx[bt * k + r];
+                const double pi = w[bt * k + r];
+                const float *be = Be + ((bt * E + e) * G + q) * N;
+                const float *ce = Ce + ((bt * E + e) * G + q) * N;
+                const float *xr = xe + ((bt * E + e) * H + h) * P;
+                for (int64_t n = 0; n < N; ++n) Cm[n] += pi * (double)ce[n];
+                for (int64_t p = 0; p < P; ++p) {
+                    const double u = dtt * pi * (double)xr[p];
+                    double *sp = st + p * N;
+                    for (int64_t n = 0; n < N; ++n) sp[n] += u * (double)be[n];
+                }
+            }
+            for (int64_t p = 0; p < P; ++p) {
+                const double *sp = st + p * N;
+                double acc = 0.0, xbar = 0.0;
+                for (int64_t n = 0; n < N; ++n) acc += Cm[n] * sp[n];
+                for (int64_t r = 0; r < k; ++r)
+                    xbar += w[bt * k + r] * (double)xe[((bt * E + idx[bt * k + r]) * H + h) * P + p];
+                y[(bt * H + h) * P + p] = acc + (D ? (double)D[h] * xbar : 0.0);
+            }
+        }
+        if (h_final) memcpy(h_final + (b * H + h) * P * N, st, sizeof(double) * P * N);
+        free(st); free(Cm);
     }
     return 0;
 }

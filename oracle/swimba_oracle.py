@@ -119,6 +119,29 @@ def mixer_fwd(x, dt, A, D, B_experts, C_experts, router_logits, top_k: int,
     return out
 
 
+def mixer_fwd_xe(x_experts, dt, A, D, B_experts, C_experts, router_logits, top_k: int,
+                 h0=None) -> Dict[str, np.ndarray]:
+    """Mixed forward with one input stream per expert, x_experts (B,L,E,H,P): the injection
+    is sum_e pi_e x^(e) (x) B^(e); the skip term sees sum_e pi_e x^(e).
+    Returns y (B,L,H,P), h_final (B,H,P,N), topk_idx, topk_w."""
+    xe = _f32(x_experts); dt = _f32(dt); A = _f32(A)
+    D = None if D is None else _f32(D)
+    Be = _f32(B_experts); Ce = _f32(C_experts); g = _f32(router_logits)
+    B, L, E, H, P = xe.shape
+    dims, (B, L, H, P, N, G, E) = _dims_of(np.empty((B, L, H, P), dtype=np.float32), Be, top_k)
+    assert xe.shape == (B, L, E, H, P)
+    h0 = None if h0 is None else np.ascontiguousarray(h0, dtype=np.float64)
+    y = np.zeros((B, L, H, P), dtype=np.float64)
+    hf = np.zeros((B, H, P, N), dtype=np.float64)
+    idx = np.zeros((B, L, top_k), dtype=np.int32)
+    w = np.zeros((B, L, top_k), dtype=np.float64)
+    rc = _load().swimba_oracle_mixer_fwd_xe(ctypes.byref(dims), _p(xe), _p(dt), _p(A), _p(D), _p(Be), _p(Ce),
+                                            _p(g), _p(h0), _p(y), _p(hf), _p(idx), _p(w))
+    if rc:
+        raise ValueError("oracle mixer_fwd_xe: bad arguments")
+    return {"y": y, "h_final": hf, "topk_idx": idx, "topk_w": w}
+
+
 def separated_fwd(x, dt, A, D, B_experts, C_experts, router_logits, top_k: int) -> Dict[str, np.ndarray]:
     """MoE of separated SSMs (one trajectory per expert, zero initial states).
     Returns y (B,L,H,P), h_final (B,E,H,P,N), topk_idx, topk_w."""

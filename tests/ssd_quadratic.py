@@ -58,3 +58,31 @@ def ssd_quadratic(x, dt, A, D, Bm, Cm):
 def swimba_quadratic(x, dt, A, D, Be, Ce, logits, top_k):
     wts, order = dense_router_weights(logits, top_k)
     return ssd_quadratic(x, dt, A, D, mix_streams(Be, wts), mix_streams(Ce, wts)), order
+
+
+def swimba_quadratic_xe(x_experts, dt, A, D, Be, Ce, logits, top_k):
+    """Expert-specific input streams, x_experts (B,L,E,H,P), quadratic form:
+    y_t = sum_{s<=t} Lambda[t,s] dt_s sum_e w_{s,e} (Cmix_t . B_s^(e)) x_s^(e)  +  D xbar_t,
+    xbar = sum_e w_e x^(e): the k outer products of a token enter as k separate columns
+    of the masked matrix product (one term per expert, dense over all E with zero weights)."""
+    xe = np.asarray(x_experts, dtype=np.float64)
+    dt = np.asarray(dt, dtype=np.float64)
+    A = np.asarray(A, dtype=np.float64)
+    Be = np.asarray(Be, dtype=np.float64)
+    wts, order = dense_router_weights(logits, top_k)
+    Cm = mix_streams(Ce, wts)
+    B_, L, E, H, P = xe.shape
+    G = Be.shape[3]
+    y = np.zeros((B_, L, H, P))
+    for b in range(B_):
+        for h in range(H):
+            q = (h * G) // H
+            a = dt[b, :, h] * A[h]
+            cum = np.concatenate([[0.0], np.cumsum(a)])
+            lam = np.tril(np.exp(np.subtract.outer(cum[1:], cum[1:])))   # exp(sum_{s+1..t} a)
+            for e in range(E):
+                M = lam * (Cm[b, :, q, :] @ Be[b, :, e, q, :].T)
+                y[b, :, h, :] += M @ ((dt[b, :, h] * wts[b, :, e])[:, None] * xe[b, :, e, h, :])
+            if D is not None:
+                y[b, :, h, :] += D[h] * np.einsum("le,lep->lp", wts[b], xe[b, :, :, h, :])
+    return y, order

@@ -13,7 +13,8 @@ import pytest
 
 from oracle import swimba_oracle as orc
 from paper_2603_06938_amd import synth
-from ssd_quadratic import dense_router_weights, mix_streams, ssd_quadratic, swimba_quadratic
+from ssd_quadratic import (dense_router_weights, mix_streams, ssd_quadratic, swimba_quadratic,
+                           swimba_quadratic_xe)
 
 GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
 
@@ -230,6 +231,94 @@ def test_split_resume_and_steps():
         np.testing.assert_allclose(y, full["y"][:, t], rtol=1e-13, atol=1e-14)
         np.testing.assert_array_equal(idx, full["topk_idx"][:, t])
     np.testing.assert_allclose(st, full["h_final"], rtol=1e-13, atol=1e-14)
+
+
+# --- expert-specific input streams (the paper's full mixed state update) -------------------
+
+def xe_problem(seed, **kw):
+    p = small_problem(seed, **kw)
+    B, L, H, P = p["x"].shape
+    E = p["B_experts"].shape[2]
+    rng = np.random.default_rng(1000 + seed)
+    p["x_experts"] = rng.standard_normal((B, L, E, H, P)).astype(np.float32)
+    return p
+
+
+def call_xe(p, top_k, **kw):
+    return orc.mixer_fwd_xe(p["x_experts"], p["dt"], p["A"], p["D"], p["B_experts"], p["C_experts"],
+                            p["router_logits"], top_k, **kw)
+
+
+@pytest.mark.parametrize("seed,G,E,k", [(0, 1, 4, 2), (1, 2, 5, 3), (2, 4, 3, 1), (3, 2, 4, 4)])
+def test_xe_recurrence_equals_quadratic_form(seed, G, E, k):
+    p = xe_problem(seed, B=2, L=18, H=4, P=3, N=5, G=G, E=E)
+    r = call_xe(p, k)
+    yq, order = swimba_quadratic_xe(p["x_experts"], p["dt"], p["A"], p["D"], p["B_experts"], p["C_experts"],
+                                    p["router_logits"], k)
+    np.testing.assert_allclose(r["y"], yq, rtol=1e-11, atol=1e-12)
+    np.testing.assert_array_equal(r["topk_idx"], order)
+
+
+def test_xe_with_shared_input_is_the_shared_x_path():
+    # all experts bring the same x: the injection is Bmix x^T again; the skip term sees
+    # s_t x_t (s_t = kept softmax mass), so compare without D, and with D at k = E (s = 1)
+    p = xe_problem(21, E=4)
+    p["x_experts"] = np.repeat(p["x"][:, :, None], 4, axis=2).copy()
+    for k, with_d in ((2, False), (4, True), (1, False)):
+        q = dict(p, D=p["D"] if with_d else None)
+        np.testing.assert_allclose(call_xe(q, k)["y"], call(q, k)["y"], rtol=1e-12, atol=1e-13)
+        np.testing.assert_allclose(call_xe(q, k)["h_final"], call(q, k)["h_final"], rtol=1e-12, atol=1e-13)
+
+
+def test_xe_top1_is_a_plain_ssm_on_gathered_streams():
+    # k = 1: one expert per token; the model is a plain SSM whose B, C and x are that
+    # expert's rows, B and C each scaled by the expert's softmax weight
+    p = xe_problem(22, E=5, G=2)
+    r = call_xe(dict(p, D=None), 1)
+    wts, order = dense_router_weights(p["router_logits"], 1)
+    e = order[..., 0]
+    bi, li = np.meshgrid(np.arange(e.shape[0]), np.arange(e.shape[1]), indexing="ij")
+    pi = wts[bi, li, e]
+    xg = p["x_experts"][bi, li, e]                               # (B,L,H,P)
+    Bg = p["B_experts"][bi, li, e] * pi[..., None, None]         # (B,L,G,N)
+    Cg = p["C_experts"][bi, li, e] * pi[..., None, None]
+    np.testing.assert_allclose(r["y"], ssd_quadratic(xg, p["dt"], p["A"], None, Bg, Cg), rtol=1e-11, atol=1e-12)
+
+
+def test_xe_is_linear_in_the_input_streams_and_resumes():
+    p = xe_problem(23)
+    rng = np.random.default_rng(5)
+    # coarse values and power-of-two coefficients keep the combination float32-exact
+    x1 = (np.round(p["x_experts"] * 64) / 64).astype(np.float32)
+    x2 = (np.round(rng.standard_normal(x1.shape) * 64) / 64).astype(np.float32)
+    mixed = dict(p, x_experts=(2.0 * x1 + 0.5 * x2).astype(np.float32))
+    lhs = call_xe(mixed, 2)["y"]
+    rhs = 2.0 * call_xe(dict(p, x_experts=x1), 2)["y"] + 0.5 * call_xe(dict(p, x_experts=x2), 2)["y"]
+    np.testing.assert_allclose(lhs, rhs, rtol=1e-10, atol=1e-12)
+    # split in two halves, resume from h_final
+    half = {k: (v[:, :12] if v.ndim > 1 else v) for k, v in p.items()}
+    rest = {k: (v[:, 12:] if v.ndim > 1 else v) for k, v in p.items()}
+    r1 = call_xe(half, 2)
+    r2 = call_xe(rest, 2, h0=r1["h_final"])
+    full = call_xe(p, 2)
+    np.testing.assert_allclose(np.concatenate([r1["y"], r2["y"]], 1), full["y"], rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(r2["h_final"], full["h_final"], rtol=1e-12, atol=1e-13)
+
+
+def test_xe_one_token_closed_form():
+    # one token, zero state: h = dt sum_e pi_e x_e (x) B_e;  y = Cmix . h + D xbar, by hand
+    p = xe_problem(24, B=1, L=1, H=2, P=2, N=3, G=1, E=3)
+    r = call_xe(p, 2)
+    wts, _ = dense_router_weights(p["router_logits"], 2)
+    w = wts[0, 0]
+    for h in range(2):
+        dtv = float(p["dt"][0, 0, h])
+        hs = sum(w[e] * np.outer(p["x_experts"][0, 0, e, h].astype(np.float64),
+                                 p["B_experts"][0, 0, e, 0].astype(np.float64)) for e in range(3)) * dtv
+        cm = sum(w[e] * p["C_experts"][0, 0, e, 0].astype(np.float64) for e in range(3))
+        xbar = sum(w[e] * p["x_experts"][0, 0, e, h].astype(np.float64) for e in range(3))
+        np.testing.assert_allclose(r["y"][0, 0, h], hs @ cm + float(p["D"][h]) * xbar, rtol=1e-12)
+        np.testing.assert_allclose(r["h_final"][0, h], hs, rtol=1e-12)
 
 
 # --- P7: separated vs mixed (Theorem 4) -------------------------------------------------------
