@@ -201,6 +201,24 @@ swimba_status swimba_separated_fwd(const swimba_dims *dims, const void *x, const
                                    size_t workspace_bytes, void *hip_stream);
 
 /*
+ * Mixed forward with one input stream per expert (paper: mixed state update equation as
+ * printed, the injection mixes the products B^(e) X^(e)):
+ *   h_t = exp(dt_t A_h) h_{t-1} + dt_t sum_{e in K_t} pi_{t,e} x_t^(e) (x) B_t^(e)
+ *   y_t = Cmix_t . h_t + D_h xbar_t,   xbar_t = sum_{e in K_t} pi_{t,e} x_t^(e)
+ * x_experts (B,L,E,H,P) io; every other argument as in swimba_mixer_fwd.  One state
+ * trajectory; the rank-k injection is evaluated as k rank-1 passes through the mixer's
+ * kernels (the state is linear in the injection) whose outputs and final states are summed
+ * in fp32: about k times the time of swimba_mixer_fwd.
+ *   workspace >= swimba_mixer_xe_workspace_bytes(dims), 256-byte aligned.
+ */
+size_t swimba_mixer_xe_workspace_bytes(const swimba_dims *dims);
+swimba_status swimba_mixer_fwd_xe(const swimba_dims *dims, const void *x_experts, const void *dt,
+                                  const float *A, const float *D, const void *B_experts,
+                                  const void *C_experts, const void *router_logits, const float *h0,
+                                  void *y, float *h_final, int32_t *topk_idx, float *topk_w,
+                                  void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
  * Single-token recurrent decode step (paper: selective SSM recurrence, per
  * channel, with the mixed injection and readout of Theorem 1): for every
  * (b,h)

@@ -76,6 +76,10 @@ def _load():
         lib.swimba_separated_workspace_bytes.argtypes = [dp]
         lib.swimba_separated_fwd.restype = i32
         lib.swimba_separated_fwd.argtypes = [dp] + [vp] * 10 + [vp, sz, vp]
+        lib.swimba_mixer_xe_workspace_bytes.restype = sz
+        lib.swimba_mixer_xe_workspace_bytes.argtypes = [dp]
+        lib.swimba_mixer_fwd_xe.restype = i32
+        lib.swimba_mixer_fwd_xe.argtypes = [dp] + [vp] * 12 + [vp, sz, vp]
         lib.swimba_step_workspace_bytes.restype = sz
         lib.swimba_step_workspace_bytes.argtypes = [dp]
         lib.swimba_step.restype = i32
@@ -215,6 +219,46 @@ def swimba_mixer_fwd(x, dt, A, D, B_experts, C_experts, router_logits, top_k: in
         _ptr(topk_w, "topk_w", torch.float32, (B, L, top_k)),
         _ptr(workspace, "workspace", torch.uint8), workspace.numel(), _stream())
     _check(st, "swimba_mixer_fwd")
+    return MixerOut(y, h_final, topk_idx, topk_w)
+
+
+def swimba_mixer_xe_workspace_bytes(dims: swimba_dims) -> int:
+    return int(_load().swimba_mixer_xe_workspace_bytes(ctypes.byref(dims)))
+
+
+def swimba_mixer_fwd_xe(x_experts, dt, A, D, B_experts, C_experts, router_logits, top_k: int, chunk: int,
+                        h0=None, *, y=None, h_final=None, topk_idx=None, topk_w=None, workspace=None,
+                        want_h_final: bool = True, want_topk: bool = False) -> MixerOut:
+    """Mixed forward with one input stream per expert, x_experts (B,L,E,H,P)."""
+    B, L, E, H, P = x_experts.shape
+    io, dev = x_experts.dtype, x_experts.device
+    _, _, _, G, N = B_experts.shape
+    d = make_dims(B, L, H, P, N, G, E, top_k, chunk, _io_code(x_experts))
+    if workspace is None:
+        n = swimba_mixer_xe_workspace_bytes(d)
+        if n == 0:
+            alloc_workspace(d, dev)   # raises with the status of the dims
+        workspace = torch.empty(n, dtype=torch.uint8, device=dev)
+    if y is None:
+        y = torch.empty((B, L, H, P), dtype=io, device=dev)
+    if h_final is None and want_h_final:
+        h_final = torch.empty((B, H, P, N), dtype=torch.float32, device=dev)
+    if want_topk and topk_idx is None:
+        topk_idx = torch.empty((B, L, top_k), dtype=torch.int32, device=dev)
+    if want_topk and topk_w is None:
+        topk_w = torch.empty((B, L, top_k), dtype=torch.float32, device=dev)
+    st = _load().swimba_mixer_fwd_xe(
+        ctypes.byref(d), _ptr(x_experts, "x_experts", io, (B, L, E, H, P)), _ptr(dt, "dt", io, (B, L, H)),
+        _ptr(A, "A", torch.float32, (H,)), _ptr(D, "D", torch.float32, (H,)),
+        _ptr(B_experts, "B_experts", io, (B, L, E, G, N)),
+        _ptr(C_experts, "C_experts", io, (B, L, E, G, N)),
+        _ptr(router_logits, "router_logits", io, (B, L, E)),
+        _ptr(h0, "h0", torch.float32, (B, H, P, N)), _ptr(y, "y", io, (B, L, H, P)),
+        _ptr(h_final, "h_final", torch.float32, (B, H, P, N)),
+        _ptr(topk_idx, "topk_idx", torch.int32, (B, L, top_k)),
+        _ptr(topk_w, "topk_w", torch.float32, (B, L, top_k)),
+        _ptr(workspace, "workspace", torch.uint8), workspace.numel(), _stream())
+    _check(st, "swimba_mixer_fwd_xe")
     return MixerOut(y, h_final, topk_idx, topk_w)
 
 

@@ -169,7 +169,7 @@ swimba_status swimba_stage_mix(const swimba_dims *dims, const void *B_experts,
     if (!B_experts || !C_experts || !router_logits) return SWIMBA_ERR_NULL;
     if (!use_mfma_path(dims)) return SWIMBA_OK;   // the fp32 chunk kernels mix while staging
     return launch_mix_rows_mfma(make_shape(dims), B_experts, C_experts, router_logits, ws.idx, ws.w,
-                                ws.cmix, ws.bmix_frag, ws.bmix_t8, -1, (hipStream_t)hip_stream);
+                                ws.cmix, ws.bmix_frag, ws.bmix_t8, -1, -1, (hipStream_t)hip_stream);
 }
 
 swimba_status swimba_stage_chunk_state(const swimba_dims *dims, const void *x, const void *dt,
@@ -341,7 +341,7 @@ swimba_status swimba_separated_fwd(const swimba_dims *dims, const void *x, const
     for (int e = 0; e < s.E; ++e) {
         if (mf) {
             st = launch_mix_rows_mfma(s, B_experts, C_experts, router_logits, ws.idx, ws.w, ws.cmix,
-                                      ws.bmix_frag, ws.bmix_t8, e, stream);
+                                      ws.bmix_frag, ws.bmix_t8, e, -1, stream);
             if (st != SWIMBA_OK) return st;
             st = launch_chunk_state_mfma(s, x, dt, A, ws.bmix_t8, ws.cs, ws.states_lp, stream);
             if (st != SWIMBA_OK) return st;
@@ -365,6 +365,126 @@ swimba_status swimba_separated_fwd(const swimba_dims *dims, const void *x, const
         if (st != SWIMBA_OK) return st;
     }
     st = launch_sep_finish(s, dims->io_dtype, acc, x, D, y, stream);
+    if (st != SWIMBA_OK) return st;
+    if (topk_idx || topk_w) {
+        const size_t cnt = (size_t)T * dims->top_k;
+        hipError_t e = hipSuccess;
+        if (topk_idx) e = hipMemcpyAsync(topk_idx, ws.idx, cnt * sizeof(int32_t), hipMemcpyDeviceToDevice, stream);
+        if (e == hipSuccess && topk_w)
+            e = hipMemcpyAsync(topk_w, ws.w, cnt * sizeof(float), hipMemcpyDeviceToDevice, stream);
+        if (e != hipSuccess) { set_last_hip_error((int)e); return SWIMBA_ERR_HIP; }
+    }
+    return SWIMBA_OK;
+}
+
+// ---- mixed forward with one input stream per expert -----------------------------------------
+struct XeLayout {
+    size_t mixer, xg, y_r, acc, xbar, wslot, hf, total;
+};
+static void xe_layout_of(const swimba_dims *d, XeLayout *o)
+{
+    swimba_ws_layout lo;
+    layout_of(d, &lo);
+    const size_t T = (size_t)d->batch * d->seqlen;
+    const size_t n = T * d->nheads * d->headdim;
+    const size_t io = d->io_dtype == SWIMBA_BF16 ? 2 : 4;
+    size_t off = 0;
+    o->mixer = off; off = align_up(off + lo.total, 256);
+    o->xg = off;    off = align_up(off + n * io, 256);
+    o->y_r = off;   off = align_up(off + n * io, 256);
+    o->acc = off;   off = align_up(off + n * sizeof(float), 256);
+    o->xbar = off;  off = align_up(off + n * sizeof(float), 256);
+    o->wslot = off; off = align_up(off + T * d->top_k * sizeof(float), 256);
+    o->hf = off;    off = align_up(off + (size_t)d->batch * d->nheads * d->headdim * d->dstate * sizeof(float), 256);
+    o->total = off;
+}
+
+size_t swimba_mixer_xe_workspace_bytes(const swimba_dims *dims)
+{
+    if (check_mixer(dims) != SWIMBA_OK) return 0;
+    XeLayout xl;
+    xe_layout_of(dims, &xl);
+    return xl.total;
+}
+
+swimba_status swimba_mixer_fwd_xe(const swimba_dims *dims, const void *x_experts, const void *dt,
+                                  const float *A, const float *D, const void *B_experts,
+                                  const void *C_experts, const void *router_logits, const float *h0,
+                                  void *y, float *h_final, int32_t *topk_idx, float *topk_w,
+                                  void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    swimba_status st = check_mixer(dims);
+    if (st != SWIMBA_OK) return st;
+    XeLayout xl;
+    xe_layout_of(dims, &xl);
+    if (!workspace || workspace_bytes < xl.total || ((uintptr_t)workspace & 255u)) return SWIMBA_ERR_WORKSPACE;
+    const int64_t T = (int64_t)dims->batch * dims->seqlen;
+    if (T > 0 && (!x_experts || !dt || !A || !B_experts || !C_experts || !router_logits || !y))
+        return SWIMBA_ERR_NULL;
+    char *base = (char *)workspace;
+    Ws ws;
+    swimba_ws_layout lo;
+    layout_of(dims, &lo);
+    st = carve(dims, base + xl.mixer, lo.total, &ws);
+    if (st != SWIMBA_OK) return st;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    const Shape s = make_shape(dims);
+    const bool mf = use_mfma_path(dims);
+    if (T == 0) {
+        // nothing to inject: the final state is the initial one
+        if (dims->batch > 0 && h_final)
+            return mf ? launch_scan_cb_mfma(s, h0, h_final, ws.states_lp, ws.cs, ws.cmix, ws.bmix_frag, ws.cb, stream)
+                      : launch_state_scan(s, h0, h_final, ws.states, nullptr, ws.cs, stream);
+        return SWIMBA_OK;
+    }
+    void *xg = base + xl.xg, *y_r = base + xl.y_r;
+    float *acc = (float *)(base + xl.acc), *xbar = D ? (float *)(base + xl.xbar) : nullptr;
+    float *wslot = (float *)(base + xl.wslot), *hf_tmp = (float *)(base + xl.hf);
+    const int64_t n = T * dims->nheads * dims->headdim;
+    const int64_t nstate = (int64_t)dims->batch * dims->nheads * dims->headdim * dims->dstate;
+    if (!mf) {
+        st = launch_router(T, s.E, s.K, dims->io_dtype, router_logits, ws.idx, ws.w, stream);
+        if (st != SWIMBA_OK) return st;
+        st = launch_cumsum(s, dims->io_dtype, dt, A, ws.cs, stream);
+        if (st != SWIMBA_OK) return st;
+    }
+    for (int r = 0; r < s.K; ++r) {
+        const float *h0_r = (r == 0) ? h0 : nullptr;       // the initial state enters the sum once
+        float *hf_r = !h_final ? nullptr : (r == 0 ? h_final : hf_tmp);
+        if (mf) {
+            st = launch_mix_rows_mfma(s, B_experts, C_experts, router_logits, ws.idx, ws.w, ws.cmix,
+                                      ws.bmix_frag, ws.bmix_t8, -1, r, stream);
+            if (st != SWIMBA_OK) return st;
+            st = launch_xe_gather(s, dims->io_dtype, r, r == 0, x_experts, ws.idx, ws.w, xg, xbar, stream);
+            if (st != SWIMBA_OK) return st;
+            st = launch_chunk_state_mfma(s, xg, dt, A, ws.bmix_t8, ws.cs, ws.states_lp, stream);
+            if (st != SWIMBA_OK) return st;
+            st = launch_scan_cb_mfma(s, h0_r, hf_r, ws.states_lp, ws.cs, ws.cmix, ws.bmix_frag, ws.cb, stream);
+            if (st != SWIMBA_OK) return st;
+            st = launch_output_mfma(s, xg, dt, nullptr, ws.cmix, ws.cb, ws.cs, ws.states_lp, y_r, stream);
+            if (st != SWIMBA_OK) return st;
+        } else {
+            st = launch_xe_slot_weights(s, r, ws.w, wslot, stream);
+            if (st != SWIMBA_OK) return st;
+            st = launch_xe_gather(s, dims->io_dtype, r, r == 0, x_experts, ws.idx, ws.w, xg, xbar, stream);
+            if (st != SWIMBA_OK) return st;
+            st = launch_chunk_state_generic(s, dims->io_dtype, xg, dt, B_experts, ws.idx, wslot, ws.cs,
+                                            ws.states, stream);
+            if (st != SWIMBA_OK) return st;
+            st = launch_state_scan(s, h0_r, hf_r, ws.states, nullptr, ws.cs, stream);
+            if (st != SWIMBA_OK) return st;
+            st = launch_output_generic(s, dims->io_dtype, xg, dt, nullptr, B_experts, C_experts, ws.idx,
+                                       wslot, ws.w, ws.cs, ws.states, y_r, stream);
+            if (st != SWIMBA_OK) return st;
+        }
+        st = launch_sep_accumulate(dims->io_dtype, n, y_r, acc, r == 0, stream);
+        if (st != SWIMBA_OK) return st;
+        if (h_final && r > 0) {
+            st = launch_sep_accumulate(SWIMBA_F32, nstate, hf_tmp, h_final, 0, stream);
+            if (st != SWIMBA_OK) return st;
+        }
+    }
+    st = launch_xe_finish(s, dims->io_dtype, acc, xbar, D, y, stream);
     if (st != SWIMBA_OK) return st;
     if (topk_idx || topk_w) {
         const size_t cnt = (size_t)T * dims->top_k;

@@ -78,7 +78,13 @@ swimba_status launch_output_generic(const Shape &s, int io_dtype, const void *x,
                                     const float *cs, const float *states, void *y, hipStream_t st);
 swimba_status launch_mix_rows_mfma(const Shape &s, const void *Be, const void *Ce, const void *logits,
                                    int32_t *idx, float *w, void *cmix, void *bfrag, void *bmix_t8,
-                                   int sep_e, hipStream_t st);
+                                   int sep_e, int slot, hipStream_t st);
+// expert-specific input streams (xe.hip)
+swimba_status launch_xe_gather(const Shape &s, int io_dtype, int slot, int first, const void *x_experts,
+                               const int32_t *idx, const float *w, void *xg, float *xbar, hipStream_t st);
+swimba_status launch_xe_slot_weights(const Shape &s, int slot, const float *w, float *wslot, hipStream_t st);
+swimba_status launch_xe_finish(const Shape &s, int io_dtype, const float *acc, const float *xbar,
+                               const float *D, void *y, hipStream_t st);
 swimba_status launch_sep_prepare(const Shape &s, int e, const int32_t *idx, const float *w,
                                  int32_t *idx1, float *wb1, float *wc1, hipStream_t st);
 swimba_status launch_sep_accumulate(int io_dtype, int64_t n, const void *y_e, float *acc, int first,

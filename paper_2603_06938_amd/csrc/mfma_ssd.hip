@@ -138,6 +138,8 @@ __device__ __forceinline__ void gather_mix_row(uint4 *frag, const uint16_t *tok,
 // the token-innermost layout the chunk-state kernel contracts over.  With sep_e >= 0 it
 // prepares the streams of ONE expert for the separated-SSM contrast instead:
 // Bmix = B^(e), Cmix = gate * C^(e), gate = pi_{t,e} if e is in the active set, else 0.
+// With slot >= 0 (one input stream per expert) Bmix keeps only the term of the token's
+// slot-th active expert, Bmix = pi_{t,e_slot} B^(e_slot); Cmix is the full mix.
 //   cmix, bfrag (B, nc, G, NT, 8, 64, 8) bf16, mixed rows of tile I as operand registers:
 //           [ks][lane][e] = mix[32I + lane%32][64*(lane/32) + 8ks + e]
 //   bmix_t8 (B, nc, G, Q/8, N, 8)    bf16, mixed B with 8 consecutive tokens innermost
@@ -146,7 +148,7 @@ __global__ void __launch_bounds__(MTHREADS)
 mix_rows_kernel(const uint16_t *__restrict__ Be, const uint16_t *__restrict__ Ce,
                 const uint16_t *__restrict__ logits, int32_t *__restrict__ idx_out,
                 float *__restrict__ w_out, uint16_t *__restrict__ cmix, uint16_t *__restrict__ bfrag,
-                uint16_t *__restrict__ bmix_t8, Shape s, int sep_e)
+                uint16_t *__restrict__ bmix_t8, Shape s, int sep_e, int slot)
 {
     extern __shared__ __align__(16) unsigned char smem_raw[];
     const int Kr = s.K;                                             // experts kept by the router
@@ -159,6 +161,8 @@ mix_rows_kernel(const uint16_t *__restrict__ Be, const uint16_t *__restrict__ Ce
     constexpr int MIXROW = MN + 8;                                  // bf16 elements per padded row
     uint16_t *s_mix = reinterpret_cast<uint16_t *>(s_wc1 + 32);     // [2][32][MIXROW], 16-byte aligned
     float *s_log = reinterpret_cast<float *>(s_mix + 2 * 32 * MIXROW);   // [32][E + 1]
+    // expert-specific input streams (slot >= 0): B keeps the weight of active expert `slot` only
+    float *s_wslot = s_log + 32 * (s.E + 1);                             // [32][K]
 
     const int NT = s.Q / 32;
     const int tile = blockIdx.x % NT;
@@ -189,7 +193,7 @@ mix_rows_kernel(const uint16_t *__restrict__ Be, const uint16_t *__restrict__ Ce
         if (t < valid) {
             const float *gl = s_log + t * (s.E + 1);
             route_token([&](int e) { return gl[e]; }, s.E, Kr, s_idx + t * Kr, s_w + t * Kr);
-            if (g == 0 && sep_e <= 0) {
+            if (g == 0 && sep_e <= 0 && slot <= 0) {
                 for (int rr = 0; rr < Kr; ++rr) {
                     idx_out[(tok0 + t) * Kr + rr] = s_idx[t * Kr + rr];
                     w_out[(tok0 + t) * Kr + rr] = s_w[t * Kr + rr];
@@ -198,6 +202,8 @@ mix_rows_kernel(const uint16_t *__restrict__ Be, const uint16_t *__restrict__ Ce
         } else {
             for (int rr = 0; rr < Kr; ++rr) { s_idx[t * Kr + rr] = 0; s_w[t * Kr + rr] = 0.f; }
         }
+        if (slot >= 0)
+            for (int rr = 0; rr < Kr; ++rr) s_wslot[t * Kr + rr] = (rr == slot) ? s_w[t * Kr + rr] : 0.f;
         if (sep_e >= 0) {
             // MoE of separated SSMs (paper: separated-SSM equation): expert sep_e keeps its own
             // state, B_t^(e) enters unweighted, the readout weight is pi_{t,e} on the active set
@@ -213,7 +219,7 @@ mix_rows_kernel(const uint16_t *__restrict__ Be, const uint16_t *__restrict__ Ce
     // tables the gathers read: K experts per token, separate weights for the B and C streams
     const int K = (sep_e >= 0) ? 1 : Kr;
     const int32_t *ixt = (sep_e >= 0) ? s_idx1 : s_idx;
-    const float *wtB = (sep_e >= 0) ? s_wb1 : s_w;
+    const float *wtB = (sep_e >= 0) ? s_wb1 : (slot >= 0) ? s_wslot : s_w;
     const float *wtC = (sep_e >= 0) ? s_wc1 : s_w;
 
     // ---- gather and mix: a lane owns one 16-byte piece (8 n) of tokens tg and tg+16, both
@@ -378,15 +384,16 @@ scan_cb_kernel(uint16_t *__restrict__ lp, const float *__restrict__ h0, float *_
 
 swimba_status launch_mix_rows_mfma(const Shape &s, const void *Be, const void *Ce, const void *logits,
                                    int32_t *idx, float *w, void *cmix, void *bfrag, void *bmix_t8,
-                                   int sep_e, hipStream_t st)
+                                   int sep_e, int slot, hipStream_t st)
 {
     const int NT = s.Q / 32;
     const int64_t nbcg = (int64_t)s.B * s.nc * s.G;
     if (nbcg == 0) return SWIMBA_OK;
-    const size_t shm = (size_t)32 * s.K * 8 + 32 * 12 + (size_t)2 * 32 * (MN + 8) * 2 + (size_t)32 * (s.E + 1) * 4;
+    const size_t shm = (size_t)32 * s.K * 8 + 32 * 12 + (size_t)2 * 32 * (MN + 8) * 2 + (size_t)32 * (s.E + 1) * 4
+                       + (size_t)32 * s.K * 4;
     hipLaunchKernelGGL(mix_rows_kernel, dim3((unsigned)(nbcg * NT)), dim3(MTHREADS), shm, st,
                        (const uint16_t *)Be, (const uint16_t *)Ce, (const uint16_t *)logits, idx, w,
-                       (uint16_t *)cmix, (uint16_t *)bfrag, (uint16_t *)bmix_t8, s, sep_e);
+                       (uint16_t *)cmix, (uint16_t *)bfrag, (uint16_t *)bmix_t8, s, sep_e, slot);
     SWIMBA_CHECK_LAUNCH();
     return SWIMBA_OK;
 }
