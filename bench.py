@@ -35,6 +35,8 @@ def main() -> int:
     ap.add_argument("--decode-steps", type=int, default=256)
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--no-decode", action="store_true")
+    ap.add_argument("--xe", action="store_true",
+                    help="also time the forward with one input stream per expert (rank-k injection)")
     ap.add_argument("--contrast", action="store_true",
                     help="also time the separated-SSM contrast (E state trajectories) on the same inputs")
     ap.add_argument("--stage", default=None,
@@ -231,6 +233,28 @@ def main() -> int:
                     "tokens_per_s": round(w.tokens / ms * 1e3, 1), "slowdown_vs_mixed": round(ms / ev_ms, 2)}
         del sws, d0
 
+    # ---- one input stream per expert: k rank-1 passes through the same kernels ------------------
+    xe_res = None
+    if args.xe and not args.stage:
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(69380 + 100 + args.workload)
+        xes = [torch.randn((w.batch, w.seqlen, E, H, P), generator=gen, device=dev, dtype=torch.float32).to(io)
+               for _ in range(2)]
+        xws = torch.empty(sw.swimba_mixer_xe_workspace_bytes(dims), dtype=torch.uint8, device=dev)
+
+        def xe_step(i):
+            d = sets[i % nsets]
+            sw.swimba_mixer_fwd_xe(xes[i % 2], d["dt"], d["A"], d["D"], d["B_experts"], d["C_experts"],
+                                   d["router_logits"], w.top_k, w.chunk, None, y=d["y"], h_final=d["h_final"],
+                                   workspace=xws)
+
+        time_loop(xe_step, 3)
+        ms = time_loop(xe_step, max(5, K // 2))
+        xe_res = {"what": "mixed forward with one x stream per expert (rank-%d injection), %d passes" % (k, k),
+                  "ms_per_step": round(ms, 4), "tokens_per_s": round(w.tokens / ms * 1e3, 1),
+                  "slowdown_vs_shared_x": round(ms / ev_ms, 2)}
+        del xes, xws
+
     # ---- CPU oracle on the host cores (reported baseline only) -------------------------------
     cpu = None
     if not args.no_cpu:
@@ -283,6 +307,8 @@ def main() -> int:
     }
     if contrast:
         out["separated_contrast"] = contrast
+    if xe_res:
+        out["expert_x"] = xe_res
     print(json.dumps(out))
     return 0
 

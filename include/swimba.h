@@ -207,8 +207,8 @@ swimba_status swimba_separated_fwd(const swimba_dims *dims, const void *x, const
  *   y_t = Cmix_t . h_t + D_h xbar_t,   xbar_t = sum_{e in K_t} pi_{t,e} x_t^(e)
  * x_experts (B,L,E,H,P) io; every other argument as in swimba_mixer_fwd.  One state
  * trajectory; the rank-k injection is evaluated as k rank-1 passes through the mixer's
- * kernels (the state is linear in the injection) whose outputs and final states are summed
- * in fp32: about k times the time of swimba_mixer_fwd.
+ * kernels (the state is linear in the injection): pass r adds its output to y (in the io
+ * dtype) and its final state to h_final (fp32); about k times the time of swimba_mixer_fwd.
  *   workspace >= swimba_mixer_xe_workspace_bytes(dims), 256-byte aligned.
  */
 size_t swimba_mixer_xe_workspace_bytes(const swimba_dims *dims);

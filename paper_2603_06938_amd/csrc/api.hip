@@ -214,10 +214,10 @@ swimba_status swimba_stage_output(const swimba_dims *dims, const void *x, const 
     if (!x || !dt || !B_experts || !C_experts || !y) return SWIMBA_ERR_NULL;
     const Shape s = make_shape(dims);
     if (use_mfma_path(dims))
-        return launch_output_mfma(s, x, dt, D, ws.cmix, ws.cb, ws.cs, ws.states_lp, y,
+        return launch_output_mfma(s, x, dt, D, ws.cmix, ws.cb, ws.cs, ws.states_lp, y, nullptr, 0, 0,
                                   (hipStream_t)hip_stream);
     return launch_output_generic(s, dims->io_dtype, x, dt, D, B_experts, C_experts, ws.idx, ws.w,
-                                 ws.w, ws.cs, ws.states, y, (hipStream_t)hip_stream);
+                                 ws.w, ws.cs, ws.states, y, nullptr, 0, 0, (hipStream_t)hip_stream);
 }
 
 swimba_status swimba_mixer_fwd(const swimba_dims *dims, const void *x, const void *dt,
@@ -347,7 +347,8 @@ swimba_status swimba_separated_fwd(const swimba_dims *dims, const void *x, const
             if (st != SWIMBA_OK) return st;
             st = launch_scan_cb_mfma(s, nullptr, nullptr, ws.states_lp, ws.cs, ws.cmix, ws.bmix_frag, ws.cb, stream);
             if (st != SWIMBA_OK) return st;
-            st = launch_output_mfma(s, x, dt, nullptr, ws.cmix, ws.cb, ws.cs, ws.states_lp, y_e, stream);
+            st = launch_output_mfma(s, x, dt, nullptr, ws.cmix, ws.cb, ws.cs, ws.states_lp, y_e, nullptr, 0, 0,
+                                    stream);
             if (st != SWIMBA_OK) return st;
         } else {
             st = launch_sep_prepare(s, e, ws.idx, ws.w, idx1, wb1, wc1, stream);
@@ -358,7 +359,7 @@ swimba_status swimba_separated_fwd(const swimba_dims *dims, const void *x, const
             st = launch_state_scan(s1, nullptr, nullptr, ws.states, nullptr, ws.cs, stream);
             if (st != SWIMBA_OK) return st;
             st = launch_output_generic(s1, dims->io_dtype, x, dt, nullptr, B_experts, C_experts, idx1,
-                                       wb1, wc1, ws.cs, ws.states, y_e, stream);
+                                       wb1, wc1, ws.cs, ws.states, y_e, nullptr, 0, 0, stream);
             if (st != SWIMBA_OK) return st;
         }
         st = launch_sep_accumulate(dims->io_dtype, n, y_e, acc, e == 0, stream);
@@ -379,7 +380,7 @@ swimba_status swimba_separated_fwd(const swimba_dims *dims, const void *x, const
 
 // ---- mixed forward with one input stream per expert -----------------------------------------
 struct XeLayout {
-    size_t mixer, xg, y_r, acc, xbar, wslot, hf, total;
+    size_t mixer, xg, wslot, hf, total;
 };
 static void xe_layout_of(const swimba_dims *d, XeLayout *o)
 {
@@ -391,9 +392,6 @@ static void xe_layout_of(const swimba_dims *d, XeLayout *o)
     size_t off = 0;
     o->mixer = off; off = align_up(off + lo.total, 256);
     o->xg = off;    off = align_up(off + n * io, 256);
-    o->y_r = off;   off = align_up(off + n * io, 256);
-    o->acc = off;   off = align_up(off + n * sizeof(float), 256);
-    o->xbar = off;  off = align_up(off + n * sizeof(float), 256);
     o->wslot = off; off = align_up(off + T * d->top_k * sizeof(float), 256);
     o->hf = off;    off = align_up(off + (size_t)d->batch * d->nheads * d->headdim * d->dstate * sizeof(float), 256);
     o->total = off;
@@ -437,10 +435,8 @@ swimba_status swimba_mixer_fwd_xe(const swimba_dims *dims, const void *x_experts
                       : launch_state_scan(s, h0, h_final, ws.states, nullptr, ws.cs, stream);
         return SWIMBA_OK;
     }
-    void *xg = base + xl.xg, *y_r = base + xl.y_r;
-    float *acc = (float *)(base + xl.acc), *xbar = D ? (float *)(base + xl.xbar) : nullptr;
+    void *xg = base + xl.xg;
     float *wslot = (float *)(base + xl.wslot), *hf_tmp = (float *)(base + xl.hf);
-    const int64_t n = T * dims->nheads * dims->headdim;
     const int64_t nstate = (int64_t)dims->batch * dims->nheads * dims->headdim * dims->dstate;
     if (!mf) {
         st = launch_router(T, s.E, s.K, dims->io_dtype, router_logits, ws.idx, ws.w, stream);
@@ -451,41 +447,40 @@ swimba_status swimba_mixer_fwd_xe(const swimba_dims *dims, const void *x_experts
     for (int r = 0; r < s.K; ++r) {
         const float *h0_r = (r == 0) ? h0 : nullptr;       // the initial state enters the sum once
         float *hf_r = !h_final ? nullptr : (r == 0 ? h_final : hf_tmp);
+        // pass r adds its output to y; its skip term is D pi_{t,e_r} x_t^(e_r)
+        const float *skip_w = ws.w + r;
         if (mf) {
             st = launch_mix_rows_mfma(s, B_experts, C_experts, router_logits, ws.idx, ws.w, ws.cmix,
                                       ws.bmix_frag, ws.bmix_t8, -1, r, stream);
             if (st != SWIMBA_OK) return st;
-            st = launch_xe_gather(s, dims->io_dtype, r, r == 0, x_experts, ws.idx, ws.w, xg, xbar, stream);
+            st = launch_xe_gather(s, dims->io_dtype, r, x_experts, ws.idx, xg, stream);
             if (st != SWIMBA_OK) return st;
             st = launch_chunk_state_mfma(s, xg, dt, A, ws.bmix_t8, ws.cs, ws.states_lp, stream);
             if (st != SWIMBA_OK) return st;
             st = launch_scan_cb_mfma(s, h0_r, hf_r, ws.states_lp, ws.cs, ws.cmix, ws.bmix_frag, ws.cb, stream);
             if (st != SWIMBA_OK) return st;
-            st = launch_output_mfma(s, xg, dt, nullptr, ws.cmix, ws.cb, ws.cs, ws.states_lp, y_r, stream);
+            st = launch_output_mfma(s, xg, dt, D, ws.cmix, ws.cb, ws.cs, ws.states_lp, y, skip_w, s.K, r > 0,
+                                    stream);
             if (st != SWIMBA_OK) return st;
         } else {
             st = launch_xe_slot_weights(s, r, ws.w, wslot, stream);
             if (st != SWIMBA_OK) return st;
-            st = launch_xe_gather(s, dims->io_dtype, r, r == 0, x_experts, ws.idx, ws.w, xg, xbar, stream);
+            st = launch_xe_gather(s, dims->io_dtype, r, x_experts, ws.idx, xg, stream);
             if (st != SWIMBA_OK) return st;
             st = launch_chunk_state_generic(s, dims->io_dtype, xg, dt, B_experts, ws.idx, wslot, ws.cs,
                                             ws.states, stream);
             if (st != SWIMBA_OK) return st;
             st = launch_state_scan(s, h0_r, hf_r, ws.states, nullptr, ws.cs, stream);
             if (st != SWIMBA_OK) return st;
-            st = launch_output_generic(s, dims->io_dtype, xg, dt, nullptr, B_experts, C_experts, ws.idx,
-                                       wslot, ws.w, ws.cs, ws.states, y_r, stream);
+            st = launch_output_generic(s, dims->io_dtype, xg, dt, D, B_experts, C_experts, ws.idx, wslot,
+                                       ws.w, ws.cs, ws.states, y, skip_w, s.K, r > 0, stream);
             if (st != SWIMBA_OK) return st;
         }
-        st = launch_sep_accumulate(dims->io_dtype, n, y_r, acc, r == 0, stream);
-        if (st != SWIMBA_OK) return st;
         if (h_final && r > 0) {
             st = launch_sep_accumulate(SWIMBA_F32, nstate, hf_tmp, h_final, 0, stream);
             if (st != SWIMBA_OK) return st;
         }
     }
-    st = launch_xe_finish(s, dims->io_dtype, acc, xbar, D, y, stream);
-    if (st != SWIMBA_OK) return st;
     if (topk_idx || topk_w) {
         const size_t cnt = (size_t)T * dims->top_k;
         hipError_t e = hipSuccess;

@@ -75,16 +75,15 @@ swimba_status launch_chunk_state_generic(const Shape &s, int io_dtype, const voi
 swimba_status launch_output_generic(const Shape &s, int io_dtype, const void *x, const void *dt,
                                     const float *D, const void *Be, const void *Ce,
                                     const int32_t *idx, const float *w, const float *wc,
-                                    const float *cs, const float *states, void *y, hipStream_t st);
+                                    const float *cs, const float *states, void *y, const float *skip_w,
+                                    int skip_stride, int accumulate, hipStream_t st);
 swimba_status launch_mix_rows_mfma(const Shape &s, const void *Be, const void *Ce, const void *logits,
                                    int32_t *idx, float *w, void *cmix, void *bfrag, void *bmix_t8,
                                    int sep_e, int slot, hipStream_t st);
 // expert-specific input streams (xe.hip)
-swimba_status launch_xe_gather(const Shape &s, int io_dtype, int slot, int first, const void *x_experts,
-                               const int32_t *idx, const float *w, void *xg, float *xbar, hipStream_t st);
+swimba_status launch_xe_gather(const Shape &s, int io_dtype, int slot, const void *x_experts,
+                               const int32_t *idx, void *xg, hipStream_t st);
 swimba_status launch_xe_slot_weights(const Shape &s, int slot, const float *w, float *wslot, hipStream_t st);
-swimba_status launch_xe_finish(const Shape &s, int io_dtype, const float *acc, const float *xbar,
-                               const float *D, void *y, hipStream_t st);
 swimba_status launch_sep_prepare(const Shape &s, int e, const int32_t *idx, const float *w,
                                  int32_t *idx1, float *wb1, float *wc1, hipStream_t st);
 swimba_status launch_sep_accumulate(int io_dtype, int64_t n, const void *y_e, float *acc, int first,
@@ -98,7 +97,8 @@ swimba_status launch_scan_cb_mfma(const Shape &s, const float *h0, float *h_fina
                                   hipStream_t st);
 swimba_status launch_output_mfma(const Shape &s, const void *x, const void *dt, const float *D,
                                  const void *cmix, const void *cb, const float *cs,
-                                 const void *states_lp, void *y, hipStream_t st);
+                                 const void *states_lp, void *y, const float *skip_w, int skip_stride,
+                                 int accumulate, hipStream_t st);
 swimba_status launch_step(const Shape &s, int io_dtype, const float *state_in, float *state_out,
                           const void *x, const void *dt, const float *A, const float *D,
                           const void *Be, const void *Ce, const void *logits, void *y, int32_t *idx,

@@ -114,6 +114,8 @@ swimba_status launch_chunk_state_generic(const Shape &s, int io_dtype, const voi
 // ---- y_i = sum_{j<=i} (Cmix_i.Bmix_j) exp(cs_i-cs_j) dt_j x_j + exp(cs_i) Cmix_i.H_c + D x_i --
 // One block owns GEN_TI consecutive tokens of one (b, chunk, head).  `w` weighs the B rows,
 // `wc` the C rows (the same array for the mixed model; they differ for the separated contrast).
+// skip_w (optional): per-token factor of the skip term, skip_w[token * skip_stride];
+// accumulate: add to what y already holds (passes of the forward with per-expert inputs).
 constexpr int GEN_MAX_YPT = (GEN_TI * SWIMBA_MAX_HEADDIM) / GEN_THREADS;  // (i,p) pairs per lane
 
 template <typename T>
@@ -122,7 +124,8 @@ output_generic_kernel(const T *__restrict__ x, const T *__restrict__ dt, const f
                       const T *__restrict__ Be, const T *__restrict__ Ce,
                       const int32_t *__restrict__ idx, const float *__restrict__ w,
                       const float *__restrict__ wc, const float *__restrict__ cs,
-                      const float *__restrict__ states, T *__restrict__ y, Shape s)
+                      const float *__restrict__ states, T *__restrict__ y, Shape s,
+                      const float *__restrict__ skip_w, int skip_stride, int accumulate)
 {
     extern __shared__ float smem[];
     float *sc = smem;                         // [GEN_TI][N] mixed C of the block's tokens
@@ -228,8 +231,10 @@ output_generic_kernel(const T *__restrict__ x, const T *__restrict__ dt, const f
                 const int ii = o / s.P, p = o % s.P, q = i0 + ii, t = c * s.Q + q;
                 if (q < s.Q && t < s.L) {
                     const int64_t off = (((int64_t)b * s.L + t) * s.H + h) * s.P + p;
-                    const float skip = D ? D[h] * to_float(x[off]) : 0.f;
-                    y[off] = from_float<T>(acc[r] + skip);
+                    float skip = D ? D[h] * to_float(x[off]) : 0.f;
+                    if (skip_w) skip *= skip_w[((int64_t)b * s.L + t) * skip_stride];
+                    const float prev = accumulate ? to_float(y[off]) : 0.f;
+                    y[off] = from_float<T>(acc[r] + skip + prev);
                 }
             }
         }
@@ -239,7 +244,8 @@ output_generic_kernel(const T *__restrict__ x, const T *__restrict__ dt, const f
 swimba_status launch_output_generic(const Shape &s, int io_dtype, const void *x, const void *dt,
                                     const float *D, const void *Be, const void *Ce,
                                     const int32_t *idx, const float *w, const float *wc,
-                                    const float *cs, const float *states, void *y, hipStream_t st)
+                                    const float *cs, const float *states, void *y, const float *skip_w,
+                                    int skip_stride, int accumulate, hipStream_t st)
 {
     static_assert(GEN_THREADS == GEN_TI * GEN_TI, "one lane per (i,j) pair of a tile");
     const int nib = (s.Q + GEN_TI - 1) / GEN_TI;
@@ -249,11 +255,11 @@ swimba_status launch_output_generic(const Shape &s, int io_dtype, const void *x,
     if (io_dtype == SWIMBA_BF16)
         hipLaunchKernelGGL(output_generic_kernel<bf16>, dim3((unsigned)blocks), dim3(GEN_THREADS), shm,
                            st, (const bf16 *)x, (const bf16 *)dt, D, (const bf16 *)Be,
-                           (const bf16 *)Ce, idx, w, wc, cs, states, (bf16 *)y, s);
+                           (const bf16 *)Ce, idx, w, wc, cs, states, (bf16 *)y, s, skip_w, skip_stride, accumulate);
     else
         hipLaunchKernelGGL(output_generic_kernel<float>, dim3((unsigned)blocks), dim3(GEN_THREADS), shm,
                            st, (const float *)x, (const float *)dt, D, (const float *)Be,
-                           (const float *)Ce, idx, w, wc, cs, states, (float *)y, s);
+                           (const float *)Ce, idx, w, wc, cs, states, (float *)y, s, skip_w, skip_stride, accumulate);
     SWIMBA_CHECK_LAUNCH();
     return SWIMBA_OK;
 }

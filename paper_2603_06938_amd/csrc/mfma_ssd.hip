@@ -627,13 +627,16 @@ swimba_status launch_chunk_state_mfma(const Shape &s, const void *x, const void 
 // bf16, passed through LDS and stored as full 128-byte rows (D x is added on the way).
 // cs is kept multiplied by log2(e): every exponential is one v_exp_f32.
 // =========================================================================================
-template <int Q>
+// XE (passes of the forward with one input stream per expert): the skip term carries the
+// per-token factor skip_w[token * skip_stride], and with `accumulate` the result is added to
+// what y already holds.
+template <int Q, bool XE>
 __global__ void __launch_bounds__(64 * (Q / 32))
 output_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ dt,
                    const float *__restrict__ D, const uint16_t *__restrict__ cmix,
                    const uint16_t *__restrict__ cb, const float *__restrict__ cs,
                    const uint16_t *__restrict__ Hlp, uint16_t *__restrict__ y, Shape s, int total,
-                   int nblocks)
+                   int nblocks, const float *__restrict__ skip_w, int skip_stride, int accumulate)
 {
     constexpr int NT = Q / 32;                 // 32-token tiles in the chunk
     constexpr int NP = NT * (NT + 1) / 2;
@@ -862,8 +865,18 @@ output_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ 
                 float a[8], xf[8];
                 unpack8(a, *reinterpret_cast<const uint4 *>(scr + row * YSTR + ((epiece ^ (row & 7)) << 3)));
                 unpack8(xf, xe[q4]);
+                float dski = dsk;
+                if (XE) {
+                    if (skip_w) dski *= skip_w[(tok0 + i) * skip_stride];
+                    if (accumulate) {
+                        float prev[8];
+                        unpack8(prev, *reinterpret_cast<const uint4 *>(yh + i * tokstride + epiece * 8));
 #pragma unroll
-                for (int e = 0; e < 8; ++e) a[e] += dsk * xf[e];
+                        for (int e = 0; e < 8; ++e) a[e] += prev[e];
+                    }
+                }
+#pragma unroll
+                for (int e = 0; e < 8; ++e) a[e] += dski * xf[e];
                 store_nt(yh + i * tokstride + epiece * 8, pack8(a));
             }
         }
@@ -873,27 +886,35 @@ output_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ 
 template <int Q>
 static swimba_status launch_out_q(const Shape &s, const void *x, const void *dt, const float *D,
                                   const void *cmix, const void *cb, const float *cs, const void *Hlp,
-                                  void *y, hipStream_t st)
+                                  void *y, const float *skip_w, int skip_stride, int accumulate,
+                                  hipStream_t st)
 {
     const int64_t total = (int64_t)s.B * s.nc * s.H;
     if (total == 0) return SWIMBA_OK;
     const int nblocks = xcd_padded(total);
-    hipLaunchKernelGGL(output_mfma_kernel<Q>, dim3(nblocks), dim3(64 * (Q / 32)), 0, st,
-                       (const uint16_t *)x, (const uint16_t *)dt, D, (const uint16_t *)cmix,
-                       (const uint16_t *)cb, cs, (const uint16_t *)Hlp, (uint16_t *)y, s, (int)total,
-                       nblocks);
+    if (skip_w || accumulate)
+        hipLaunchKernelGGL((output_mfma_kernel<Q, true>), dim3(nblocks), dim3(64 * (Q / 32)), 0, st,
+                           (const uint16_t *)x, (const uint16_t *)dt, D, (const uint16_t *)cmix,
+                           (const uint16_t *)cb, cs, (const uint16_t *)Hlp, (uint16_t *)y, s, (int)total,
+                           nblocks, skip_w, skip_stride, accumulate);
+    else
+        hipLaunchKernelGGL((output_mfma_kernel<Q, false>), dim3(nblocks), dim3(64 * (Q / 32)), 0, st,
+                           (const uint16_t *)x, (const uint16_t *)dt, D, (const uint16_t *)cmix,
+                           (const uint16_t *)cb, cs, (const uint16_t *)Hlp, (uint16_t *)y, s, (int)total,
+                           nblocks, nullptr, 0, 0);
     SWIMBA_CHECK_LAUNCH();
     return SWIMBA_OK;
 }
 
 swimba_status launch_output_mfma(const Shape &s, const void *x, const void *dt, const float *D,
                                  const void *cmix, const void *cb, const float *cs,
-                                 const void *states_lp, void *y, hipStream_t st)
+                                 const void *states_lp, void *y, const float *skip_w, int skip_stride,
+                                 int accumulate, hipStream_t st)
 {
     switch (s.Q) {
-    case 64: return launch_out_q<64>(s, x, dt, D, cmix, cb, cs, states_lp, y, st);
-    case 128: return launch_out_q<128>(s, x, dt, D, cmix, cb, cs, states_lp, y, st);
-    case 256: return launch_out_q<256>(s, x, dt, D, cmix, cb, cs, states_lp, y, st);
+    case 64: return launch_out_q<64>(s, x, dt, D, cmix, cb, cs, states_lp, y, skip_w, skip_stride, accumulate, st);
+    case 128: return launch_out_q<128>(s, x, dt, D, cmix, cb, cs, states_lp, y, skip_w, skip_stride, accumulate, st);
+    case 256: return launch_out_q<256>(s, x, dt, D, cmix, cb, cs, states_lp, y, skip_w, skip_stride, accumulate, st);
     }
     return SWIMBA_ERR_UNSUPPORTED;
 }
