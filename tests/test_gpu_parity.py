@@ -223,3 +223,29 @@ def test_step_out_of_place_leaves_input_untouched():
     o2 = sw.swimba_step(d["state"], *args)
     torch.cuda.synchronize()
     assert torch.equal(d["state"], dst) and torch.equal(o1.y, o2.y)
+
+
+def test_prefill_hands_its_state_to_decode():
+    """Prefill of the first L tokens, then one swimba_step per further token from h_final,
+    equals the oracle's forward over all tokens (state handed over in fp32)."""
+    w = synth.Workload("handoff", 2, 140, 4, 64, 128, 2, 8, 2, 64, "bf16", 7)
+    p = synth.make_inputs(w, seed=4242)
+    L0 = 128
+    ref = oracle_fwd(p, w.top_k)
+    d = to_device(p, "bf16")
+    pre = sw.swimba_mixer_fwd(d["x"][:, :L0].contiguous(), d["dt"][:, :L0].contiguous(), d["A"], d["D"],
+                              d["B_experts"][:, :L0].contiguous(), d["C_experts"][:, :L0].contiguous(),
+                              d["router_logits"][:, :L0].contiguous(), w.top_k, w.chunk)
+    state = pre.h_final
+    ys = []
+    for t in range(L0, w.seqlen):
+        out = sw.swimba_step(state, d["x"][:, t].contiguous(), d["dt"][:, t].contiguous(), d["A"], d["D"],
+                             d["B_experts"][:, t].contiguous(), d["C_experts"][:, t].contiguous(),
+                             d["router_logits"][:, t].contiguous(), w.top_k)
+        ys.append(out.y)
+    torch.cuda.synchronize()
+    y = torch.cat([pre.y, torch.stack(ys, dim=1)], dim=1)
+    l2, linf = rel_errors(host(y), ref["y"], (0, 2))
+    assert l2 <= TOL["bf16"] and linf <= TOL["bf16"], (l2, linf)
+    l2, linf = rel_errors(host(state), ref["h_final"], (0, 1))
+    assert l2 <= TOL["bf16"] and linf <= TOL["bf16"], (l2, linf)

@@ -103,3 +103,13 @@ def test_binding_refuses_cpu_tensors():
     with pytest.raises((ValueError, sw.SwimbaError)):
         sw.swimba_mixer_fwd(x, torch.ones(1, 4, 2), -torch.ones(2), None, Be, Be, torch.zeros(1, 4, 3),
                             2, 4, workspace=torch.zeros(1 << 16, dtype=torch.uint8))
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True,
+                       text=True, timeout=120)
+    assert r.returncode != 0
+    assert "ONE GPU" in r.stderr and r.stdout.strip() == ""
