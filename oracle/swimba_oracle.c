@@ -24,6 +24,8 @@
  *   separated   h_t^(e) = exp(dt_t A_h) h_{t-1}^(e) + dt_t B_t^(e) x_t^T for
  *               every expert e, y_t = sum_{e in K_t} pi_{t,e} C_t^(e) . h_t^(e)
  *               + D_h x_t                       (separated-SSM equation)
+ *   projection  B_t^(e), C_t^(e) for the active experts only, as expert-specific
+ *               linear maps of the token features (swimba_oracle_expert_proj)
  *   expert x    the mixed state update in its full form, with one input stream
  *               per expert: h_t = exp(dt_t A_h) h_{t-1}
  *               + dt_t sum_{e in K_t} pi_{t,e} x_t^(e) (x) B_t^(e); same readout
@@ -233,6 +235,41 @@ int swimba_oracle_mixer_fwd_xe(const oracle_dims *d, const float *xe, const floa
         }
         if (h_final) memcpy(h_final + (b * H + h) * P * N, st, sizeof(double) * P * N);
         free(st); free(Cm);
+    }
+    return 0;
+}
+
+/*
+ * Routed expert in-projection (paper, MoE-parameterized SSM: the expert streams are
+ * expert-specific linear projections of the same token features; only the experts of the
+ * active set K_t enter the mix, so only their rows are needed):
+ *   for every token t and every e in K_t:
+ *     B_t^(e)[c] = sum_d WB[e][c][d] u_t[d],   C_t^(e)[c] = sum_d WC[e][c][d] u_t[d]
+ *   u (T,Dm)  WB, WC (E, GN, Dm)  logits (T,E)  ->  Be, Ce (T,E,GN): rows of the active
+ *   experts are written (double), all other rows are left as they are.
+ */
+int swimba_oracle_expert_proj(int64_t T, int64_t Dm, int64_t E, int64_t k, int64_t GN,
+                              const float *u, const float *WB, const float *WC,
+                              const float *logits, double *Be, double *Ce, int32_t *idx, double *w)
+{
+    if (T < 0 || Dm < 1 || GN < 1 || E < 1 || k < 1 || k > E) return 1;
+    if (swimba_oracle_router(logits, T, E, k, idx, w)) return 1;
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < T; ++t) {
+        for (int64_t r = 0; r < k; ++r) {
+            const int64_t e = idx[t * k + r];
+            for (int64_t c = 0; c < GN; ++c) {
+                const float *wb = WB + (e * GN + c) * Dm;
+                const float *wc = WC + (e * GN + c) * Dm;
+                double sb = 0.0, sc = 0.0;
+                for (int64_t d = 0; d < Dm; ++d) {
+                    sb += (double)wb[d] * (double)u[t * Dm + d];
+                    sc += (double)wc[d] * (double)u[t * Dm + d];
+                }
+                Be[(t * E + e) * GN + c] = sb;
+                Ce[(t * E + e) * GN + c] = sc;
+            }
+        }
     }
     return 0;
 }

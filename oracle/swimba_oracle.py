@@ -142,6 +142,26 @@ def mixer_fwd_xe(x_experts, dt, A, D, B_experts, C_experts, router_logits, top_k
     return {"y": y, "h_final": hf, "topk_idx": idx, "topk_w": w}
 
 
+def expert_proj(u, W_B, W_C, router_logits, top_k: int, fill=np.nan):
+    """Routed expert in-projection.  u (B,L,Dm), W_B/W_C (E,G,N,Dm), router_logits (B,L,E)
+    -> B_experts, C_experts (B,L,E,G,N) float64 with the rows of the active experts computed and
+    every other row equal to `fill`; topk_idx, topk_w."""
+    u = _f32(u); WB = _f32(W_B); WC = _f32(W_C); g = _f32(router_logits)
+    B, L, Dm = u.shape
+    E, G, N, Dm2 = WB.shape
+    assert Dm2 == Dm and WC.shape == WB.shape and g.shape == (B, L, E)
+    Be = np.full((B, L, E, G, N), fill, dtype=np.float64)
+    Ce = np.full((B, L, E, G, N), fill, dtype=np.float64)
+    idx = np.zeros((B, L, top_k), dtype=np.int32)
+    w = np.zeros((B, L, top_k), dtype=np.float64)
+    i64 = ctypes.c_int64
+    rc = _load().swimba_oracle_expert_proj(i64(B * L), i64(Dm), i64(E), i64(top_k), i64(G * N), _p(u), _p(WB),
+                                           _p(WC), _p(g), _p(Be), _p(Ce), _p(idx), _p(w))
+    if rc:
+        raise ValueError("oracle expert_proj: bad arguments")
+    return {"B_experts": Be, "C_experts": Ce, "topk_idx": idx, "topk_w": w}
+
+
 def separated_fwd(x, dt, A, D, B_experts, C_experts, router_logits, top_k: int) -> Dict[str, np.ndarray]:
     """MoE of separated SSMs (one trajectory per expert, zero initial states).
     Returns y (B,L,H,P), h_final (B,E,H,P,N), topk_idx, topk_w."""

@@ -321,6 +321,49 @@ def test_xe_one_token_closed_form():
         np.testing.assert_allclose(r["h_final"][0, h], hs, rtol=1e-12)
 
 
+# --- routed expert in-projection -----------------------------------------------------------
+
+def test_expert_proj_matches_dense_projection_on_the_active_set():
+    rng = np.random.default_rng(31)
+    B, L, Dm, E, G, N, k = 2, 9, 12, 5, 2, 3, 2
+    u = rng.standard_normal((B, L, Dm)).astype(np.float32)
+    WB = rng.standard_normal((E, G, N, Dm)).astype(np.float32)
+    WC = rng.standard_normal((E, G, N, Dm)).astype(np.float32)
+    g = rng.standard_normal((B, L, E)).astype(np.float32)
+    r = orc.expert_proj(u, WB, WC, g, k)
+    # dense projection of every expert with a library contraction, then look at the kept rows
+    dB = np.einsum("bld,egnd->blegn", u.astype(np.float64), WB.astype(np.float64))
+    dC = np.einsum("bld,egnd->blegn", u.astype(np.float64), WC.astype(np.float64))
+    wts, order = dense_router_weights(g, k)
+    keep = wts > 0
+    np.testing.assert_array_equal(r["topk_idx"], order)
+    np.testing.assert_allclose(r["B_experts"][keep], dB[keep], rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(r["C_experts"][keep], dC[keep], rtol=1e-12, atol=1e-13)
+    # exactly k rows per token are written, the others keep the fill value
+    assert np.isnan(r["B_experts"][~keep]).all() and np.isnan(r["C_experts"][~keep]).all()
+    assert keep.sum() == B * L * k
+    # B and C use their own weights (swapping them swaps the outputs)
+    r2 = orc.expert_proj(u, WC, WB, g, k)
+    np.testing.assert_allclose(r2["B_experts"][keep], r["C_experts"][keep], rtol=0, atol=0)
+
+
+def test_expert_proj_feeds_the_mixer_like_a_dense_projection():
+    # the mixer only reads the active rows: routed projection + mixer == dense projection + mixer
+    rng = np.random.default_rng(32)
+    p = small_problem(32, B=1, L=12, H=2, P=2, N=3, G=1, E=4)
+    Dm = 6
+    u = rng.standard_normal((1, 12, Dm)).astype(np.float32)
+    WB = (rng.standard_normal((4, 1, 3, Dm)) / 4).astype(np.float32)
+    WC = (rng.standard_normal((4, 1, 3, Dm)) / 4).astype(np.float32)
+    routed = orc.expert_proj(u, WB, WC, p["router_logits"], 2, fill=0.0)
+    dense_B = np.einsum("bld,egnd->blegn", u.astype(np.float64), WB.astype(np.float64))
+    dense_C = np.einsum("bld,egnd->blegn", u.astype(np.float64), WC.astype(np.float64))
+    # float32 copies so both go through the same oracle entry point
+    a = call(dict(p, B_experts=routed["B_experts"].astype(np.float32), C_experts=routed["C_experts"].astype(np.float32)), 2)
+    b = call(dict(p, B_experts=dense_B.astype(np.float32), C_experts=dense_C.astype(np.float32)), 2)
+    np.testing.assert_allclose(a["y"], b["y"], rtol=1e-12, atol=1e-14)
+
+
 # --- P7: separated vs mixed (Theorem 4) -------------------------------------------------------
 
 def test_separated_equals_mixed_in_equality_regime():
