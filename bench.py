@@ -35,6 +35,8 @@ def main() -> int:
     ap.add_argument("--decode-steps", type=int, default=256)
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU oracle leg")
     ap.add_argument("--no-decode", action="store_true")
+    ap.add_argument("--proj", type=int, default=0, metavar="D_MODEL",
+                    help="also time the routed expert in-projection from token features of this width")
     ap.add_argument("--xe", action="store_true",
                     help="also time the forward with one input stream per expert (rank-k injection)")
     ap.add_argument("--contrast", action="store_true",
@@ -233,6 +235,33 @@ def main() -> int:
                     "tokens_per_s": round(w.tokens / ms * 1e3, 1), "slowdown_vs_mixed": round(ms / ev_ms, 2)}
         del sws, d0
 
+    # ---- routed expert in-projection (upstream of the mixer): grouped GEMM on MFMA --------------
+    proj_res = None
+    if args.proj and not args.stage:
+        Dm = args.proj
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(69380 + 200 + args.workload)
+        us = [torch.randn((w.batch, w.seqlen, Dm), generator=gen, device=dev).to(io) for _ in range(3)]
+        WBs = (torch.randn((E, G, N, Dm), generator=gen, device=dev) / Dm ** 0.5).to(io)
+        WCs = (torch.randn((E, G, N, Dm), generator=gen, device=dev) / Dm ** 0.5).to(io)
+        pws = torch.empty(sw.swimba_expert_proj_workspace_bytes(dims, Dm), dtype=torch.uint8, device=dev)
+
+        def proj_step(i):
+            d = sets[i % nsets]
+            sw.swimba_expert_proj(us[i % 3], WBs, WCs, d["router_logits"], w.top_k, B_experts=d["B_experts"],
+                                  C_experts=d["C_experts"], workspace=pws)
+
+        time_loop(proj_step, 3)
+        ms = time_loop(proj_step, K)
+        pflops = 2.0 * T * k * Dm * 2 * G * N
+        pbytes = T * (Dm * 2 + E * 2 + k * 2 * G * N * 2) + 2 * E * G * N * Dm * 2
+        proj_res = {"what": "routed expert in-projection, d_model %d -> B, C rows of the top-%d experts" % (Dm, k),
+                    "ms": round(ms, 5), "mfma_TFLOPs": round(pflops / ms / 1e9, 1),
+                    "mfma_frac": round(pflops / ms / 1e9 / PEAK_BF16_TFLOPS, 4),
+                    "hbm_GBps": round(pbytes / ms / 1e6, 1), "hbm_frac": round(pbytes / ms / 1e6 / PEAK_HBM_GBS, 4)}
+        # the projection overwrote the synthetic expert rows of every set with its own values
+        del us, WBs, WCs, pws
+
     # ---- one input stream per expert: k rank-1 passes through the same kernels ------------------
     xe_res = None
     if args.xe and not args.stage:
@@ -309,6 +338,8 @@ def main() -> int:
         out["separated_contrast"] = contrast
     if xe_res:
         out["expert_x"] = xe_res
+    if proj_res:
+        out["expert_proj"] = proj_res
     print(json.dumps(out))
     return 0
 

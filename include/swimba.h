@@ -219,6 +219,30 @@ swimba_status swimba_mixer_fwd_xe(const swimba_dims *dims, const void *x_experts
                                   void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * Routed expert in-projection, the step upstream of the mixer (paper, MoE-parameterized
+ * SSM: the expert streams are expert-specific linear projections of the token features;
+ * only the active set K_t enters the mix).  For every token t and every e in K_t:
+ *   B_t^(e)[g][n] = sum_d W_B[e][g][n][d] u_t[d],   C_t^(e) likewise with W_C.
+ *   u             (B,L,d_model) io  token features
+ *   W_B, W_C      (E,G,N,d_model) io  projection weights, input index d contiguous
+ *   router_logits (B,L,E) io
+ *   B_experts, C_experts (B,L,E,G,N) io [out]: the rows of each token's top_k experts are
+ *                 written; rows of inactive experts are NOT touched (swimba_mixer_fwd with the
+ *                 same logits and top_k never reads them).
+ *   topk_idx, topk_w (B,L,k) [out, nullable]
+ * Uses dims->batch, seqlen, dstate, ngroups, nexperts, top_k, io_dtype.  bf16 io with
+ * d_model % 16 == 0 and (G*N) % 64 == 0 runs as a grouped GEMM on bf16 MFMA (fp32
+ * accumulation); anything else on plain fp32 arithmetic.  The router's linear layer is not
+ * part of this call: the logits are an input, so that the routing decision is the caller's.
+ *   workspace >= swimba_expert_proj_workspace_bytes(dims, d_model), 256-byte aligned.
+ */
+size_t swimba_expert_proj_workspace_bytes(const swimba_dims *dims, int32_t d_model);
+swimba_status swimba_expert_proj(const swimba_dims *dims, int32_t d_model, const void *u, const void *W_B,
+                                 const void *W_C, const void *router_logits, void *B_experts,
+                                 void *C_experts, int32_t *topk_idx, float *topk_w, void *workspace,
+                                 size_t workspace_bytes, void *hip_stream);
+
+/*
  * Single-token recurrent decode step (paper: selective SSM recurrence, per
  * channel, with the mixed injection and readout of Theorem 1): for every
  * (b,h)

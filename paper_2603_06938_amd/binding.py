@@ -76,6 +76,10 @@ def _load():
         lib.swimba_separated_workspace_bytes.argtypes = [dp]
         lib.swimba_separated_fwd.restype = i32
         lib.swimba_separated_fwd.argtypes = [dp] + [vp] * 10 + [vp, sz, vp]
+        lib.swimba_expert_proj_workspace_bytes.restype = sz
+        lib.swimba_expert_proj_workspace_bytes.argtypes = [dp, i32]
+        lib.swimba_expert_proj.restype = i32
+        lib.swimba_expert_proj.argtypes = [dp, i32] + [vp] * 8 + [vp, sz, vp]
         lib.swimba_mixer_xe_workspace_bytes.restype = sz
         lib.swimba_mixer_xe_workspace_bytes.argtypes = [dp]
         lib.swimba_mixer_fwd_xe.restype = i32
@@ -220,6 +224,46 @@ def swimba_mixer_fwd(x, dt, A, D, B_experts, C_experts, router_logits, top_k: in
         _ptr(workspace, "workspace", torch.uint8), workspace.numel(), _stream())
     _check(st, "swimba_mixer_fwd")
     return MixerOut(y, h_final, topk_idx, topk_w)
+
+
+def swimba_expert_proj_workspace_bytes(dims: swimba_dims, d_model: int) -> int:
+    return int(_load().swimba_expert_proj_workspace_bytes(ctypes.byref(dims), d_model))
+
+
+class ProjOut(NamedTuple):
+    B_experts: torch.Tensor
+    C_experts: torch.Tensor
+    topk_idx: Optional[torch.Tensor]
+    topk_w: Optional[torch.Tensor]
+
+
+def swimba_expert_proj(u, W_B, W_C, router_logits, top_k: int, *, B_experts=None, C_experts=None,
+                       workspace=None, want_topk: bool = False) -> ProjOut:
+    """u (B,L,Dm), W_B/W_C (E,G,N,Dm), router_logits (B,L,E) -> B_experts, C_experts (B,L,E,G,N) with
+    the rows of the active experts written (new outputs start as zeros)."""
+    B, L, Dm = u.shape
+    E, G, N, _ = W_B.shape
+    io, dev = u.dtype, u.device
+    d = make_dims(B, L, G, 1, N, G, E, top_k, 1, _io_code(u))
+    if workspace is None:
+        n = swimba_expert_proj_workspace_bytes(d, Dm)
+        if n == 0:
+            raise SwimbaError(2, "swimba_expert_proj_workspace_bytes")
+        workspace = torch.empty(n, dtype=torch.uint8, device=dev)
+    if B_experts is None:
+        B_experts = torch.zeros((B, L, E, G, N), dtype=io, device=dev)
+    if C_experts is None:
+        C_experts = torch.zeros((B, L, E, G, N), dtype=io, device=dev)
+    topk_idx = torch.empty((B, L, top_k), dtype=torch.int32, device=dev) if want_topk else None
+    topk_w = torch.empty((B, L, top_k), dtype=torch.float32, device=dev) if want_topk else None
+    st = _load().swimba_expert_proj(
+        ctypes.byref(d), Dm, _ptr(u, "u", io, (B, L, Dm)), _ptr(W_B, "W_B", io, (E, G, N, Dm)),
+        _ptr(W_C, "W_C", io, (E, G, N, Dm)), _ptr(router_logits, "router_logits", io, (B, L, E)),
+        _ptr(B_experts, "B_experts", io, (B, L, E, G, N)), _ptr(C_experts, "C_experts", io, (B, L, E, G, N)),
+        _ptr(topk_idx, "topk_idx", torch.int32, (B, L, top_k)), _ptr(topk_w, "topk_w", torch.float32, (B, L, top_k)),
+        _ptr(workspace, "workspace", torch.uint8), workspace.numel(), _stream())
+    _check(st, "swimba_expert_proj")
+    return ProjOut(B_experts, C_experts, topk_idx, topk_w)
 
 
 def swimba_mixer_xe_workspace_bytes(dims: swimba_dims) -> int:

@@ -492,6 +492,64 @@ swimba_status swimba_mixer_fwd_xe(const swimba_dims *dims, const void *x_experts
     return SWIMBA_OK;
 }
 
+// ---- routed expert in-projection --------------------------------------------------------------
+struct ProjLayout {
+    size_t idx, w, counts, lists, total;
+};
+static swimba_status proj_layout_of(const swimba_dims *d, int32_t d_model, ProjLayout *o)
+{
+    swimba_status st = check_common(d);
+    if (st != SWIMBA_OK) return st;
+    if (d_model < 1) return SWIMBA_ERR_SHAPE;
+    const int64_t T = (int64_t)d->batch * d->seqlen;
+    if (d_model > 65536 || T * d->top_k > (1ll << 31) - 1 || T * d->nexperts > (1ll << 31) - 1)
+        return SWIMBA_ERR_UNSUPPORTED;
+    size_t off = 0;
+    o->idx = off;    off = align_up(off + (size_t)T * d->top_k * sizeof(int32_t), 256);
+    o->w = off;      off = align_up(off + (size_t)T * d->top_k * sizeof(float), 256);
+    o->counts = off; off = align_up(off + SWIMBA_MAX_EXPERTS * sizeof(int32_t), 256);
+    o->lists = off;  off = align_up(off + (size_t)T * d->nexperts * sizeof(int32_t), 256);
+    o->total = off;
+    return SWIMBA_OK;
+}
+
+size_t swimba_expert_proj_workspace_bytes(const swimba_dims *dims, int32_t d_model)
+{
+    ProjLayout pl;
+    return proj_layout_of(dims, d_model, &pl) == SWIMBA_OK ? pl.total : 0;
+}
+
+swimba_status swimba_expert_proj(const swimba_dims *dims, int32_t d_model, const void *u, const void *W_B,
+                                 const void *W_C, const void *router_logits, void *B_experts,
+                                 void *C_experts, int32_t *topk_idx, float *topk_w, void *workspace,
+                                 size_t workspace_bytes, void *hip_stream)
+{
+    ProjLayout pl;
+    swimba_status st = proj_layout_of(dims, d_model, &pl);
+    if (st != SWIMBA_OK) return st;
+    if (!workspace || workspace_bytes < pl.total || ((uintptr_t)workspace & 255u)) return SWIMBA_ERR_WORKSPACE;
+    const int64_t T = (int64_t)dims->batch * dims->seqlen;
+    if (T == 0) return SWIMBA_OK;
+    if (!u || !W_B || !W_C || !router_logits || !B_experts || !C_experts) return SWIMBA_ERR_NULL;
+    char *base = (char *)workspace;
+    int32_t *idx = (int32_t *)(base + pl.idx);
+    float *w = (float *)(base + pl.w);
+    hipStream_t stream = (hipStream_t)hip_stream;
+    st = launch_expert_proj(T, dims->nexperts, dims->top_k, dims->ngroups * dims->dstate, d_model, dims->io_dtype,
+                            u, W_B, W_C, router_logits, B_experts, C_experts, idx, w,
+                            (int32_t *)(base + pl.counts), (int32_t *)(base + pl.lists), stream);
+    if (st != SWIMBA_OK) return st;
+    if (topk_idx || topk_w) {
+        const size_t cnt = (size_t)T * dims->top_k;
+        hipError_t e = hipSuccess;
+        if (topk_idx) e = hipMemcpyAsync(topk_idx, idx, cnt * sizeof(int32_t), hipMemcpyDeviceToDevice, stream);
+        if (e == hipSuccess && topk_w)
+            e = hipMemcpyAsync(topk_w, w, cnt * sizeof(float), hipMemcpyDeviceToDevice, stream);
+        if (e != hipSuccess) { set_last_hip_error((int)e); return SWIMBA_ERR_HIP; }
+    }
+    return SWIMBA_OK;
+}
+
 size_t swimba_step_workspace_bytes(const swimba_dims *dims)
 {
     if (check_common(dims) != SWIMBA_OK || dims->seqlen != 1) return 0;

@@ -80,6 +80,10 @@ swimba_status launch_output_generic(const Shape &s, int io_dtype, const void *x,
 swimba_status launch_mix_rows_mfma(const Shape &s, const void *Be, const void *Ce, const void *logits,
                                    int32_t *idx, float *w, void *cmix, void *bfrag, void *bmix_t8,
                                    int sep_e, int slot, hipStream_t st);
+// routed expert in-projection (expert_proj.hip)
+swimba_status launch_expert_proj(int64_t tokens, int E, int K, int GN, int Dm, int io_dtype, const void *u,
+                                 const void *WB, const void *WC, const void *logits, void *Be, void *Ce,
+                                 int32_t *idx, float *w, int32_t *counts, int32_t *lists, hipStream_t st);
 // expert-specific input streams (xe.hip)
 swimba_status launch_xe_gather(const Shape &s, int io_dtype, int slot, const void *x_experts,
                                const int32_t *idx, void *xg, hipStream_t st);
@@ -103,6 +107,16 @@ swimba_status launch_step(const Shape &s, int io_dtype, const float *state_in, f
                           const void *x, const void *dt, const float *A, const float *D,
                           const void *Be, const void *Ce, const void *logits, void *y, int32_t *idx,
                           float *bc, hipStream_t st);
+
+// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every
+// outstanding global load and store of the wave, which would drain the prefetches and
+// the result stores these kernels deliberately keep in flight across barriers.
+__device__ __forceinline__ void lds_barrier()
+{
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
+    __builtin_amdgcn_s_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
+}
 
 // ---- device helper shared by the router kernel and the decode kernel -----------------
 // Top-k over E logits read through `load(e)`, in (logit descending, index

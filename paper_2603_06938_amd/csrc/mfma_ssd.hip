@@ -92,15 +92,6 @@ __device__ __forceinline__ void store_nt(uint16_t *p, uint4 v)
 
 __device__ __forceinline__ float fast_exp2(float v) { return __builtin_amdgcn_exp2f(v); }
 
-// Workgroup barrier that orders LDS traffic only.  __syncthreads() also waits for every
-// outstanding global load and store of the wave, which would drain the prefetches and
-// the result stores these kernels deliberately keep in flight across barriers.
-__device__ __forceinline__ void lds_barrier()
-{
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup", "local");
-    __builtin_amdgcn_s_barrier();
-    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "workgroup", "local");
-}
 constexpr float LOG2E = 1.4426950408889634f;
 
 // Mixed row of one token for MFMA use: lane (row, kg) gets, for ks = 0..7, the 8

@@ -67,3 +67,25 @@ def test_decode_1024_steps(G):
     l2, linf = rel_errors(host(ys).transpose(1, 0, 2, 3), ref["y"], (0, 2))
     print("y rel l2 %.3e linf %.3e" % (l2, linf), flush=True)
     assert l2 <= TOL["bf16"] and linf <= TOL["bf16"]
+
+
+def test_expert_proj_workload1_size():
+    """Routed in-projection at the token count of workload 1 from 768 features (the width of
+    the 130M model): every written row against the oracle."""
+    w = synth.workload(1)
+    B, L, E, G, N, k, Dm = w.batch, w.seqlen, w.nexperts, w.ngroups, w.dstate, w.top_k, 768
+    rng = np.random.default_rng(69380 + 201)
+    u = synth.round_to_bf16(rng.standard_normal((B, L, Dm)).astype(np.float32))
+    WB = synth.round_to_bf16((rng.standard_normal((E, G, N, Dm)) / np.sqrt(Dm)).astype(np.float32))
+    WC = synth.round_to_bf16((rng.standard_normal((E, G, N, Dm)) / np.sqrt(Dm)).astype(np.float32))
+    g = synth.make_inputs(w)["router_logits"]
+    bf = lambda a: torch.from_numpy(a).to(torch.bfloat16).to("cuda:0")
+    out = sw.swimba_expert_proj(bf(u), bf(WB), bf(WC), bf(g), k, want_topk=True)
+    torch.cuda.synchronize()
+    ref = orc.expert_proj(u, WB, WC, g, k, fill=0.0)
+    np.testing.assert_array_equal(out.topk_idx.cpu().numpy(), ref["topk_idx"])
+    for name, got, want in (("B", host(out.B_experts), ref["B_experts"]), ("C", host(out.C_experts), ref["C_experts"])):
+        l2 = np.linalg.norm(got - want) / np.linalg.norm(want)
+        linf = np.abs(got - want).max() / np.abs(want).max()
+        print(name, "rel l2 %.3e linf %.3e" % (l2, linf), flush=True)
+        assert l2 <= TOL["bf16"] and linf <= TOL["bf16"]
