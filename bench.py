@@ -214,6 +214,27 @@ def main() -> int:
                   "us_per_step": round(ms * 1e3, 2), "steps": S, "tokens_per_s": round(wd.batch / ms * 1e3, 1),
                   "bound": "hbm", "achieved": round(dbytes / ms / 1e6, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
                   "frac": round(dbytes / ms / 1e6 / PEAK_HBM_GBS, 4), "state_buffers_rotated": 4}
+        # several tokens per call (speculative / short-chunk decoding): same state bytes per call
+        multi = {}
+        for Lm in (4, 8):
+            xm = dd["x"][:, :Lm].contiguous()
+            dtm = dd["dt"][:, :Lm].contiguous()
+            Bm = dd["B_experts"][:, :Lm].contiguous()
+            Cm = dd["C_experts"][:, :Lm].contiguous()
+            gm = dd["router_logits"][:, :Lm].contiguous()
+            ym = torch.empty_like(xm)
+            mws = torch.empty(sw.swimba_step_multi_workspace_bytes(
+                sw.make_dims(wd.batch, Lm, wd.nheads, wd.headdim, wd.dstate, wd.ngroups, wd.nexperts, wd.top_k, 0, io)),
+                dtype=torch.uint8, device=dev)
+
+            def mstep(i):
+                sw.swimba_step_multi(states[i % 4], xm, dtm, dd["A"], dd["D"], Bm, Cm, gm, wd.top_k, y=ym, workspace=mws)
+
+            time_loop(mstep, 8)
+            mms = time_loop(mstep, max(32, S // 4))
+            multi["L%d" % Lm] = {"us_per_call": round(mms * 1e3, 2), "tokens_per_s": round(wd.batch * Lm / mms * 1e3, 1),
+                                  "frac": round(dbytes / mms / 1e6 / PEAK_HBM_GBS, 4)}
+        decode["multi_token"] = multi
         if args.stage == "step":
             print(json.dumps(decode))
             return 0

@@ -59,6 +59,7 @@ typedef enum { SWIMBA_F32 = 0, SWIMBA_BF16 = 1 } swimba_dtype;
 #define SWIMBA_MAX_DSTATE 256
 #define SWIMBA_MAX_HEADDIM 256
 #define SWIMBA_MAX_CHUNK 256
+#define SWIMBA_MAX_STEP_TOKENS 64   /* tokens per sequence in one swimba_step_multi call */
 
 typedef struct {
     int32_t batch, seqlen, nheads, headdim, dstate, ngroups, nexperts, top_k;
@@ -264,6 +265,23 @@ swimba_status swimba_step(const swimba_dims *dims, const float *state_in, float 
                           const void *B_experts, const void *C_experts, const void *router_logits,
                           void *y, int32_t *topk_idx, void *workspace, size_t workspace_bytes,
                           void *hip_stream);
+
+/*
+ * Several decode tokens per call (the same recurrence as swimba_step, paper: selective SSM
+ * recurrence with the router-mixed injection and readout, applied to L = dims->seqlen tokens
+ * of every sequence in order): for speculative or short-chunk decoding.  The fp32 state is
+ * read once, kept in registers over the L tokens, and written once, so a call moves the same
+ * state bytes as a single swimba_step.
+ *   state_in/out (B,H,P,N) fp32 (may alias); x (B,L,H,P), dt (B,L,H), B/C_experts (B,L,E,G,N),
+ *   router_logits (B,L,E), y (B,L,H,P) [out], topk_idx (B,L,k) [out, nullable]
+ *   1 <= L <= SWIMBA_MAX_STEP_TOKENS; workspace >= swimba_step_multi_workspace_bytes(dims).
+ */
+size_t swimba_step_multi_workspace_bytes(const swimba_dims *dims);
+swimba_status swimba_step_multi(const swimba_dims *dims, const float *state_in, float *state_out,
+                                const void *x, const void *dt, const float *A, const float *D,
+                                const void *B_experts, const void *C_experts, const void *router_logits,
+                                void *y, int32_t *topk_idx, void *workspace, size_t workspace_bytes,
+                                void *hip_stream);
 
 /*
  * Measurement helpers (no paper operation): a plain device copy of `bytes`

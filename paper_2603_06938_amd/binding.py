@@ -76,6 +76,10 @@ def _load():
         lib.swimba_separated_workspace_bytes.argtypes = [dp]
         lib.swimba_separated_fwd.restype = i32
         lib.swimba_separated_fwd.argtypes = [dp] + [vp] * 10 + [vp, sz, vp]
+        lib.swimba_step_multi_workspace_bytes.restype = sz
+        lib.swimba_step_multi_workspace_bytes.argtypes = [dp]
+        lib.swimba_step_multi.restype = i32
+        lib.swimba_step_multi.argtypes = [dp] + [vp] * 11 + [vp, sz, vp]
         lib.swimba_expert_proj_workspace_bytes.restype = sz
         lib.swimba_expert_proj_workspace_bytes.argtypes = [dp, i32]
         lib.swimba_expert_proj.restype = i32
@@ -453,3 +457,38 @@ def swimba_probe_mfma(sink: torch.Tensor, blocks: int, iters: int) -> None:
     assert sink.numel() >= blocks * 256
     _check(_load().swimba_probe_mfma(_ptr(sink, "sink", torch.float32), blocks, iters, _stream()),
            "swimba_probe_mfma")
+
+
+def swimba_step_multi_workspace_bytes(dims: swimba_dims) -> int:
+    return int(_load().swimba_step_multi_workspace_bytes(ctypes.byref(dims)))
+
+
+def swimba_step_multi(state, x, dt, A, D, B_experts, C_experts, router_logits, top_k: int, *,
+                      state_out=None, y=None, topk_idx=None, workspace=None, want_topk: bool = False) -> StepOut:
+    """L decode tokens per sequence in one call: state (B,H,P,N) fp32, x (B,L,H,P), dt (B,L,H),
+    B/C_experts (B,L,E,G,N), router_logits (B,L,E).  state_out defaults to `state` (in place)."""
+    B, L, H, P = x.shape
+    _, _, E, G, N = B_experts.shape
+    io = x.dtype
+    d = make_dims(B, L, H, P, N, G, E, top_k, 0, _io_code(x))
+    if state_out is None:
+        state_out = state
+    if y is None:
+        y = torch.empty_like(x)
+    if want_topk and topk_idx is None:
+        topk_idx = torch.empty((B, L, top_k), dtype=torch.int32, device=x.device)
+    if workspace is None:
+        n = swimba_step_multi_workspace_bytes(d)
+        if n == 0:
+            raise SwimbaError(4 if L > 0 else 2, "swimba_step_multi_workspace_bytes")
+        workspace = torch.empty(n, dtype=torch.uint8, device=x.device)
+    st = _load().swimba_step_multi(
+        ctypes.byref(d), _ptr(state, "state", torch.float32, (B, H, P, N)),
+        _ptr(state_out, "state_out", torch.float32, (B, H, P, N)), _ptr(x, "x", io, (B, L, H, P)),
+        _ptr(dt, "dt", io, (B, L, H)), _ptr(A, "A", torch.float32, (H,)), _ptr(D, "D", torch.float32, (H,)),
+        _ptr(B_experts, "B_experts", io, (B, L, E, G, N)), _ptr(C_experts, "C_experts", io, (B, L, E, G, N)),
+        _ptr(router_logits, "router_logits", io, (B, L, E)), _ptr(y, "y", io, (B, L, H, P)),
+        _ptr(topk_idx, "topk_idx", torch.int32, (B, L, top_k)),
+        _ptr(workspace, "workspace", torch.uint8), workspace.numel(), _stream())
+    _check(st, "swimba_step_multi")
+    return StepOut(y, state_out, topk_idx)

@@ -576,6 +576,33 @@ swimba_status swimba_step(const swimba_dims *dims, const float *state_in, float 
                        (hipStream_t)hip_stream);
 }
 
+size_t swimba_step_multi_workspace_bytes(const swimba_dims *dims)
+{
+    if (check_common(dims) != SWIMBA_OK || dims->seqlen < 1 || dims->seqlen > SWIMBA_MAX_STEP_TOKENS) return 0;
+    const size_t n = (size_t)dims->batch * dims->seqlen * dims->ngroups * dims->dstate * 2 * sizeof(float);
+    return align_up(n > 0 ? n : 1, 256);
+}
+
+swimba_status swimba_step_multi(const swimba_dims *dims, const float *state_in, float *state_out,
+                                const void *x, const void *dt, const float *A, const float *D,
+                                const void *B_experts, const void *C_experts, const void *router_logits,
+                                void *y, int32_t *topk_idx, void *workspace, size_t workspace_bytes,
+                                void *hip_stream)
+{
+    swimba_status st = check_common(dims);
+    if (st != SWIMBA_OK) return st;
+    if (dims->seqlen < 1) return SWIMBA_ERR_SHAPE;
+    if (dims->seqlen > SWIMBA_MAX_STEP_TOKENS) return SWIMBA_ERR_UNSUPPORTED;
+    if (dims->batch == 0) return SWIMBA_OK;
+    if (!workspace || workspace_bytes < swimba_step_multi_workspace_bytes(dims) || ((uintptr_t)workspace & 255u))
+        return SWIMBA_ERR_WORKSPACE;
+    if (!state_in || !state_out || !x || !dt || !A || !B_experts || !C_experts || !router_logits || !y)
+        return SWIMBA_ERR_NULL;
+    return launch_step_multi(make_shape(dims), dims->io_dtype, state_in, state_out, x, dt, A, D, B_experts,
+                             C_experts, router_logits, y, topk_idx, (float *)workspace,
+                             (hipStream_t)hip_stream);
+}
+
 const char *swimba_status_string(swimba_status s)
 {
     switch (s) {

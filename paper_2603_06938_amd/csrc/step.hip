@@ -100,25 +100,85 @@ step_update_n128_kernel(const float *state_in, float *state_out, const T *__rest
     }
 }
 
+// ---- several tokens per call, N = 128: same mapping; the state rows stay in registers while
+// ---- the L tokens are applied one after the other (one read and one write of the state).
+template <typename T>
+__global__ void __launch_bounds__(STEP_THREADS)
+step_multi_n128_kernel(const float *state_in, float *state_out, const T *__restrict__ x,
+                       const T *__restrict__ dt, const float *__restrict__ A,
+                       const float *__restrict__ D, const float *__restrict__ bc,
+                       T *__restrict__ y, Shape s, int slices)
+{
+    constexpr int N = 128;
+    const int sl = blockIdx.x % slices;
+    const int h = (blockIdx.x / slices) % s.H;
+    const int b = blockIdx.x / (slices * s.H);
+    const int g = (h * s.G) / s.H;
+    const int tid = threadIdx.x;
+    const int n4 = (tid & 31) * 4;
+    const int P = s.P, L = s.L;
+    const int p0 = sl * 16 + (tid >> 5), p1 = p0 + 8;
+    const bool ok0 = p0 < P, ok1 = p1 < P;
+    const int q0 = min(p0, P - 1), q1 = min(p1, P - 1);
+    const int64_t base = ((int64_t)b * s.H + h) * P * N;
+
+    f32x4_t v0 = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t *>(state_in + base + (int64_t)q0 * N + n4));
+    f32x4_t v1 = __builtin_nontemporal_load(reinterpret_cast<const f32x4_t *>(state_in + base + (int64_t)q1 * N + n4));
+    const float Ah = A[h];
+    const float dsk = D ? D[h] : 0.f;
+    for (int t = 0; t < L; ++t) {
+        const int64_t bt = (int64_t)b * L + t;
+        const float *mix = bc + (bt * s.G + g) * 2 * N + n4;
+        const f32x4_t bm = *reinterpret_cast<const f32x4_t *>(mix);
+        const f32x4_t cm = *reinterpret_cast<const f32x4_t *>(mix + N);
+        const float dtv = to_float(dt[bt * s.H + h]);
+        const T *xr = x + (bt * s.H + h) * P;
+        const float x0 = to_float(xr[q0]), x1 = to_float(xr[q1]);
+        const float decay = expf(dtv * Ah);
+        const float u0 = dtv * x0, u1 = dtv * x1;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            v0[q] = decay * v0[q] + u0 * bm[q];
+            v1[q] = decay * v1[q] + u1 * bm[q];
+        }
+        float part0 = (v0[0] * cm[0] + v0[1] * cm[1]) + (v0[2] * cm[2] + v0[3] * cm[3]);
+        float part1 = (v1[0] * cm[0] + v1[1] * cm[1]) + (v1[2] * cm[2] + v1[3] * cm[3]);
+#pragma unroll
+        for (int off = 16; off >= 1; off >>= 1) {
+            part0 += __shfl_xor(part0, off);
+            part1 += __shfl_xor(part1, off);
+        }
+        if ((tid & 31) == 0) {
+            T *yr = y + (bt * s.H + h) * P;
+            if (ok0) yr[p0] = from_float<T>(part0 + dsk * x0);
+            if (ok1) yr[p1] = from_float<T>(part1 + dsk * x1);
+        }
+    }
+    if (ok0) __builtin_nontemporal_store(v0, reinterpret_cast<f32x4_t *>(state_out + base + (int64_t)p0 * N + n4));
+    if (ok1) __builtin_nontemporal_store(v1, reinterpret_cast<f32x4_t *>(state_out + base + (int64_t)p1 * N + n4));
+}
+
 // ---- state update, any N: block = (b, h), a wave walks one state row at a time ------------
 template <typename T>
 __global__ void __launch_bounds__(STEP_THREADS)
 step_update_generic_kernel(const float *state_in, float *state_out, const T *__restrict__ x,
                            const T *__restrict__ dt, const float *__restrict__ A,
                            const float *__restrict__ D, const float *__restrict__ bc,
-                           T *__restrict__ y, Shape s)
+                           T *__restrict__ y, Shape s, int L, int t)
 {
+    // token t of L per sequence: x, dt, bc and y are indexed by bt = b * L + t
     const int b = blockIdx.x / s.H, h = blockIdx.x % s.H, g = (h * s.G) / s.H;
+    const int64_t bt = (int64_t)b * L + t;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int N = s.N, P = s.P;
     const int64_t base = ((int64_t)b * s.H + h) * P * N;
-    const float *bm = bc + ((int64_t)b * s.G + g) * 2 * N;
+    const float *bm = bc + (bt * s.G + g) * 2 * N;
     const float *cm = bm + N;
-    const float dtv = to_float(dt[(int64_t)b * s.H + h]);
+    const float dtv = to_float(dt[bt * s.H + h]);
     const float decay = expf(dtv * A[h]);
     const float dsk = D ? D[h] : 0.f;
     for (int p = wave; p < P; p += STEP_THREADS / 64) {
-        const float xv = to_float(x[((int64_t)b * s.H + h) * P + p]);
+        const float xv = to_float(x[(bt * s.H + h) * P + p]);
         const float u = dtv * xv;
         float part = 0.f;
         for (int n = lane; n < N; n += 64) {
@@ -128,7 +188,7 @@ step_update_generic_kernel(const float *state_in, float *state_out, const T *__r
         }
 #pragma unroll
         for (int off = 32; off >= 1; off >>= 1) part += __shfl_xor(part, off);
-        if (lane == 0) y[((int64_t)b * s.H + h) * P + p] = from_float<T>(part + dsk * xv);
+        if (lane == 0) y[(bt * s.H + h) * P + p] = from_float<T>(part + dsk * xv);
     }
 }
 
@@ -150,9 +210,52 @@ static swimba_status launch_step_t(const Shape &s, const float *state_in, float 
                            A, D, bc, (T *)y, s, slices);
     else
         hipLaunchKernelGGL(step_update_generic_kernel<T>, dim3((unsigned)blocks), dim3(STEP_THREADS), 0,
-                           st, state_in, state_out, (const T *)x, (const T *)dt, A, D, bc, (T *)y, s);
+                           st, state_in, state_out, (const T *)x, (const T *)dt, A, D, bc, (T *)y, s, 1, 0);
     SWIMBA_CHECK_LAUNCH();
     return SWIMBA_OK;
+}
+
+// L tokens per sequence: x (B,L,H,P), dt (B,L,H), Be/Ce (B,L,E,G,N), logits (B,L,E), y (B,L,H,P),
+// idx (B,L,k), bc (B,L,G,2N) fp32.  The token loop of the general-N path is a loop of launches.
+template <typename T>
+static swimba_status launch_step_multi_t(const Shape &s, const float *state_in, float *state_out,
+                                         const void *x, const void *dt, const float *A, const float *D,
+                                         const void *Be, const void *Ce, const void *logits, void *y,
+                                         int32_t *idx, float *bc, hipStream_t st)
+{
+    const int64_t blocks = (int64_t)s.B * s.H;
+    if (blocks == 0 || s.L == 0) return SWIMBA_OK;
+    Shape tok = s;                 // the mix kernel sees B*L independent tokens
+    tok.B = s.B * s.L;
+    tok.L = 1;
+    hipLaunchKernelGGL(step_mix_kernel<T>, dim3((unsigned)(tok.B * s.G)), dim3(128), 0, st, (const T *)Be,
+                       (const T *)Ce, (const T *)logits, bc, idx, tok);
+    SWIMBA_CHECK_LAUNCH();
+    const int slices = (s.P + 15) / 16;
+    if (s.N == 128 && blocks * slices < (1ll << 31)) {
+        hipLaunchKernelGGL(step_multi_n128_kernel<T>, dim3((unsigned)(blocks * slices)), dim3(STEP_THREADS), 0,
+                           st, state_in, state_out, (const T *)x, (const T *)dt, A, D, bc, (T *)y, s, slices);
+        SWIMBA_CHECK_LAUNCH();
+        return SWIMBA_OK;
+    }
+    // any N: one launch per token
+    for (int t = 0; t < s.L; ++t) {
+        hipLaunchKernelGGL(step_update_generic_kernel<T>, dim3((unsigned)blocks), dim3(STEP_THREADS), 0, st,
+                           t == 0 ? state_in : state_out, state_out, (const T *)x, (const T *)dt, A, D, bc,
+                           (T *)y, s, s.L, t);
+        SWIMBA_CHECK_LAUNCH();
+    }
+    return SWIMBA_OK;
+}
+
+swimba_status launch_step_multi(const Shape &s, int io_dtype, const float *state_in, float *state_out,
+                                const void *x, const void *dt, const float *A, const float *D,
+                                const void *Be, const void *Ce, const void *logits, void *y, int32_t *idx,
+                                float *bc, hipStream_t st)
+{
+    if (io_dtype == SWIMBA_BF16)
+        return launch_step_multi_t<bf16>(s, state_in, state_out, x, dt, A, D, Be, Ce, logits, y, idx, bc, st);
+    return launch_step_multi_t<float>(s, state_in, state_out, x, dt, A, D, Be, Ce, logits, y, idx, bc, st);
 }
 
 swimba_status launch_step(const Shape &s, int io_dtype, const float *state_in, float *state_out,

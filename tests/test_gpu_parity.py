@@ -249,3 +249,51 @@ def test_prefill_hands_its_state_to_decode():
     assert l2 <= TOL["bf16"] and linf <= TOL["bf16"], (l2, linf)
     l2, linf = rel_errors(host(state), ref["h_final"], (0, 1))
     assert l2 <= TOL["bf16"] and linf <= TOL["bf16"], (l2, linf)
+
+
+@pytest.mark.parametrize("cfg", [(3, 5, 4, 16, 16, 1, 4, 2, "f32"), (2, 7, 6, 24, 40, 3, 5, 5, "f32"),
+                                 (2, 4, 4, 64, 128, 2, 8, 2, "bf16"), (2, 8, 2, 48, 128, 1, 8, 1, "f32"),
+                                 (1, 1, 2, 64, 128, 1, 8, 2, "bf16")],
+                         ids=lambda c: "B%dL%dH%dP%dN%dG%dE%dk%d%s" % c)
+def test_step_multi_matches_oracle(cfg):
+    """L decode tokens in one call == the oracle's forward over those L tokens from the same state."""
+    B, L, H, P, N, G, E, k, io = cfg
+    w = synth.Workload("multi", B, L, H, P, N, G, E, k, 0, io, 7)
+    p = synth.make_decode_inputs(w, seed=hash(cfg[:8]) % 100000)
+    d = to_device(p, io)
+    state0 = d["state"].clone()
+    out = sw.swimba_step_multi(d["state"], d["x"], d["dt"], d["A"], d["D"], d["B_experts"], d["C_experts"],
+                               d["router_logits"], k, state_out=torch.empty_like(state0), want_topk=True)
+    torch.cuda.synchronize()
+    assert torch.equal(d["state"], state0)          # out of place: the input state is untouched
+    ref = oracle_fwd(p, k, h0=p["state"].astype(np.float64))
+    np.testing.assert_array_equal(out.topk_idx.cpu().numpy(), ref["topk_idx"])
+    l2, linf = rel_errors(host(out.y), ref["y"], (0, 2))
+    assert l2 <= TOL[io] and linf <= TOL[io], ("y", l2, linf)
+    l2, linf = rel_errors(host(out.state), ref["h_final"], (0, 1))
+    assert l2 <= 1e-5 and linf <= 1e-5, ("state", l2, linf)
+
+
+def test_step_multi_chain_equals_single_steps():
+    """64 tokens as 8 calls of 8 tokens, in place, against 64 single-token steps: same fp32
+    recurrence, so the states agree to rounding."""
+    w = synth.Workload("chain", 2, 64, 4, 64, 128, 1, 8, 2, 0, "bf16", 7)
+    p = synth.make_decode_inputs(w, seed=77)
+    d = to_device(p, "bf16")
+    s_multi, s_single = d["state"].clone(), d["state"].clone()
+    ys_m, ys_s = [], []
+    for c in range(0, 64, 8):
+        sl = slice(c, c + 8)
+        ys_m.append(sw.swimba_step_multi(s_multi, d["x"][:, sl].contiguous(), d["dt"][:, sl].contiguous(), d["A"], d["D"],
+                                         d["B_experts"][:, sl].contiguous(), d["C_experts"][:, sl].contiguous(),
+                                         d["router_logits"][:, sl].contiguous(), w.top_k).y)
+    for t in range(64):
+        ys_s.append(sw.swimba_step(s_single, d["x"][:, t].contiguous(), d["dt"][:, t].contiguous(), d["A"], d["D"],
+                                   d["B_experts"][:, t].contiguous(), d["C_experts"][:, t].contiguous(),
+                                   d["router_logits"][:, t].contiguous(), w.top_k).y)
+    torch.cuda.synchronize()
+    l2, linf = rel_errors(host(s_multi), host(s_single), (0, 1))
+    assert l2 <= 1e-6 and linf <= 1e-6, (l2, linf)
+    # y is rounded to bf16 on both sides: at most an occasional one-ulp difference
+    l2, linf = rel_errors(host(torch.cat(ys_m, dim=1)), host(torch.stack(ys_s, dim=1)), (0, 2))
+    assert l2 <= 1e-3 and linf <= 4e-3, (l2, linf)
