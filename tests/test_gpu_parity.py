@@ -118,6 +118,9 @@ SMALL = [
     (1, 520, 8, 64, 128, 2, 16, 1, 256, "bf16"),
     (1, 31, 2, 64, 128, 1, 4, 2, 256, "bf16"),
     (2, 257, 2, 64, 128, 1, 8, 3, 64, "bf16"),
+    # the limits of the routing tables: 256 experts, 16 active
+    (1, 70, 2, 64, 128, 1, 256, 16, 64, "bf16"),
+    (1, 40, 2, 8, 16, 2, 256, 16, 16, "f32"),
 ]
 
 
