@@ -21,6 +21,8 @@
 // the same permutation; this is used to read 16 contiguous bytes per operand.
 #include "common.hpp"
 
+#include <atomic>
+
 namespace swimba {
 
 typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
@@ -584,12 +586,18 @@ static swimba_status launch_cs_q(const Shape &s, const void *x, const void *dt, 
     if (total == 0) return SWIMBA_OK;
     const int nblocks = xcd_padded(total);
     const size_t shm = (size_t)2 * MP * (Q + 8) * 2 + 2 * Q * sizeof(float) + 8 * sizeof(float);
-    static bool attr_set = false;
-    if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)chunk_state_mfma_kernel<Q>,
-                                           hipFuncAttributeMaxDynamicSharedMemorySize, (int)shm);
+    // more than 64 KB of dynamic LDS has to be allowed once per device (a plain attribute call:
+    // legal under stream capture, but the first call on a device is best made before capturing)
+    static std::atomic<uint64_t> attr_set{0};            // one bit per device ordinal
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) { set_last_hip_error((int)e); return SWIMBA_ERR_HIP; }
+    const uint64_t bit = 1ull << (dev & 63);
+    if (!(attr_set.load(std::memory_order_acquire) & bit)) {
+        e = hipFuncSetAttribute((const void *)chunk_state_mfma_kernel<Q>,
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)shm);
         if (e != hipSuccess) { set_last_hip_error((int)e); return SWIMBA_ERR_HIP; }
-        attr_set = true;
+        attr_set.fetch_or(bit, std::memory_order_release);
     }
     hipLaunchKernelGGL(chunk_state_mfma_kernel<Q>, dim3(nblocks), dim3(MTHREADS), shm, st,
                        (const uint16_t *)x, (const uint16_t *)dt, A, (const uint16_t *)bmix_t8, cs,
