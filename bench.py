@@ -297,8 +297,27 @@ def main() -> int:
                     "ms": round(ms, 5), "mfma_TFLOPs": round(pflops / ms / 1e9, 1),
                     "mfma_frac": round(pflops / ms / 1e9 / PEAK_BF16_TFLOPS, 4),
                     "hbm_GBps": round(pbytes / ms / 1e6, 1), "hbm_frac": round(pbytes / ms / 1e6 / PEAK_HBM_GBS, 4)}
+        # token features -> y in one call, selected streams only (no tensor with an expert axis),
+        # against projection into the dense layout followed by the mixer forward
+        fws = torch.empty(sw.swimba_mixer_proj_workspace_bytes(dims, Dm), dtype=torch.uint8, device=dev)
+
+        def fused_step(i):
+            d = sets[i % nsets]
+            sw.swimba_mixer_fwd_proj(us[i % 3], WBs, WCs, d["x"], d["dt"], d["A"], d["D"], d["router_logits"],
+                                     w.top_k, w.chunk, y=d["y"], h_final=d["h_final"], workspace=fws)
+
+        def dense_step(i):
+            proj_step(i)
+            step(i)
+
+        time_loop(fused_step, 3)
+        fms = time_loop(fused_step, K)
+        time_loop(dense_step, 3)
+        dms = time_loop(dense_step, K)
+        proj_res["features_to_y"] = {"selected_streams_ms": round(fms, 5), "dense_streams_ms": round(dms, 5),
+                                     "tokens_per_s": round(T / fms * 1e3, 1)}
         # the projection overwrote the synthetic expert rows of every set with its own values
-        del us, WBs, WCs, pws
+        del us, WBs, WCs, pws, fws
 
     # ---- one input stream per expert: k rank-1 passes through the same kernels ------------------
     xe_res = None

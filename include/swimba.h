@@ -244,6 +244,46 @@ swimba_status swimba_expert_proj(const swimba_dims *dims, int32_t d_model, const
                                  size_t workspace_bytes, void *hip_stream);
 
 /*
+ * The same projection written per selected slot, so that no tensor with an expert axis is
+ * ever materialised (paper, MoE-parameterized SSM: only the active set K_t contributes):
+ *   B_sel, C_sel (B,L,k,G,N) io [out]: row r of token t is the stream of expert topk_idx[t][r].
+ * Every other argument, the arithmetic and the workspace are those of swimba_expert_proj.
+ */
+swimba_status swimba_expert_proj_selected(const swimba_dims *dims, int32_t d_model, const void *u,
+                                          const void *W_B, const void *W_C, const void *router_logits,
+                                          void *B_sel, void *C_sel, int32_t *topk_idx, float *topk_w,
+                                          void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * swimba_mixer_fwd on the streams of the selected experts only (paper: parameter-space
+ * mixing, Bmix_t = sum_{e in K_t} pi_{t,e} B_t^(e), likewise Cmix; one SSD recurrence):
+ *   B_sel, C_sel (B,L,k,G,N) io [in]  row r of a token = stream of its r-th selected expert
+ *   topk_w       (B,L,k) fp32  [in]  the router weights pi of those experts (softmax over all
+ *                                    E experts, not renormalised); no routing happens here
+ * x, dt, A, D, h0, y, h_final as in swimba_mixer_fwd; dims->nexperts only has to be >= top_k.
+ *   workspace >= swimba_mixer_workspace_bytes(dims), 256-byte aligned.
+ */
+swimba_status swimba_mixer_fwd_selected(const swimba_dims *dims, const void *x, const void *dt, const float *A,
+                                        const float *D, const void *B_sel, const void *C_sel,
+                                        const float *topk_w, const float *h0, void *y, float *h_final,
+                                        void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
+ * In-projection and forward in one call (paper, MoE-parameterized SSM followed by the mixed
+ * state update): swimba_expert_proj_selected into the workspace, then
+ * swimba_mixer_fwd_selected on it.  Arguments as in those two calls; u, W_B, W_C,
+ * router_logits, x, dt, A are inputs, y / h_final / topk_idx / topk_w outputs (the last three
+ * nullable).  Selected streams are rounded to the io dtype between the two steps.
+ *   workspace >= swimba_mixer_proj_workspace_bytes(dims, d_model), 256-byte aligned.
+ */
+size_t swimba_mixer_proj_workspace_bytes(const swimba_dims *dims, int32_t d_model);
+swimba_status swimba_mixer_fwd_proj(const swimba_dims *dims, int32_t d_model, const void *u, const void *W_B,
+                                    const void *W_C, const void *x, const void *dt, const float *A,
+                                    const float *D, const void *router_logits, const float *h0, void *y,
+                                    float *h_final, int32_t *topk_idx, float *topk_w, void *workspace,
+                                    size_t workspace_bytes, void *hip_stream);
+
+/*
  * Single-token recurrent decode step (paper: selective SSM recurrence, per
  * channel, with the mixed injection and readout of Theorem 1): for every
  * (b,h)

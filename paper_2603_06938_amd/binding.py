@@ -85,6 +85,14 @@ def _load():
         lib.swimba_expert_proj.restype = i32
         lib.swimba_expert_proj.argtypes = [dp, i32] + [vp] * 8 + [vp, sz, vp]
         lib.swimba_mixer_xe_workspace_bytes.restype = sz
+        lib.swimba_expert_proj_selected.restype = i32
+        lib.swimba_expert_proj_selected.argtypes = [dp, i32] + [vp] * 8 + [vp, sz, vp]
+        lib.swimba_mixer_fwd_selected.restype = i32
+        lib.swimba_mixer_fwd_selected.argtypes = [dp] + [vp] * 10 + [vp, sz, vp]
+        lib.swimba_mixer_proj_workspace_bytes.restype = sz
+        lib.swimba_mixer_proj_workspace_bytes.argtypes = [dp, i32]
+        lib.swimba_mixer_fwd_proj.restype = i32
+        lib.swimba_mixer_fwd_proj.argtypes = [dp, i32] + [vp] * 13 + [vp, sz, vp]
         lib.swimba_mixer_xe_workspace_bytes.argtypes = [dp]
         lib.swimba_mixer_fwd_xe.restype = i32
         lib.swimba_mixer_fwd_xe.argtypes = [dp] + [vp] * 12 + [vp, sz, vp]
@@ -268,6 +276,94 @@ def swimba_expert_proj(u, W_B, W_C, router_logits, top_k: int, *, B_experts=None
         _ptr(workspace, "workspace", torch.uint8), workspace.numel(), _stream())
     _check(st, "swimba_expert_proj")
     return ProjOut(B_experts, C_experts, topk_idx, topk_w)
+
+
+def swimba_expert_proj_selected(u, W_B, W_C, router_logits, top_k: int, *, B_sel=None, C_sel=None,
+                                workspace=None, want_topk: bool = True) -> ProjOut:
+    """Like swimba_expert_proj, but the outputs are (B,L,k,G,N): row r = stream of the r-th selected expert."""
+    B, L, Dm = u.shape
+    E, G, N, _ = W_B.shape
+    io, dev = u.dtype, u.device
+    d = make_dims(B, L, G, 1, N, G, E, top_k, 1, _io_code(u))
+    if workspace is None:
+        n = swimba_expert_proj_workspace_bytes(d, Dm)
+        if n == 0:
+            raise SwimbaError(2, "swimba_expert_proj_workspace_bytes")
+        workspace = torch.empty(n, dtype=torch.uint8, device=dev)
+    if B_sel is None:
+        B_sel = torch.empty((B, L, top_k, G, N), dtype=io, device=dev)
+    if C_sel is None:
+        C_sel = torch.empty((B, L, top_k, G, N), dtype=io, device=dev)
+    topk_idx = torch.empty((B, L, top_k), dtype=torch.int32, device=dev) if want_topk else None
+    topk_w = torch.empty((B, L, top_k), dtype=torch.float32, device=dev) if want_topk else None
+    st = _load().swimba_expert_proj_selected(
+        ctypes.byref(d), Dm, _ptr(u, "u", io, (B, L, Dm)), _ptr(W_B, "W_B", io, (E, G, N, Dm)),
+        _ptr(W_C, "W_C", io, (E, G, N, Dm)), _ptr(router_logits, "router_logits", io, (B, L, E)),
+        _ptr(B_sel, "B_sel", io, (B, L, top_k, G, N)), _ptr(C_sel, "C_sel", io, (B, L, top_k, G, N)),
+        _ptr(topk_idx, "topk_idx", torch.int32, (B, L, top_k)), _ptr(topk_w, "topk_w", torch.float32, (B, L, top_k)),
+        _ptr(workspace, "workspace", torch.uint8), workspace.numel(), _stream())
+    _check(st, "swimba_expert_proj_selected")
+    return ProjOut(B_sel, C_sel, topk_idx, topk_w)
+
+
+def swimba_mixer_fwd_selected(x, dt, A, D, B_sel, C_sel, topk_w, chunk: int, h0=None, *, y=None, h_final=None,
+                              workspace=None, want_h_final: bool = True) -> MixerOut:
+    """Mixer forward on the selected experts' streams B_sel/C_sel (B,L,k,G,N) with given weights (B,L,k)."""
+    B, L, H, P = x.shape
+    _, _, K, G, N = B_sel.shape
+    io, dev = x.dtype, x.device
+    d = make_dims(B, L, H, P, N, G, K, K, chunk, _io_code(x))
+    if workspace is None:
+        workspace = alloc_workspace(d, dev)
+    if y is None:
+        y = torch.empty_like(x)
+    if h_final is None and want_h_final:
+        h_final = torch.empty((B, H, P, N), dtype=torch.float32, device=dev)
+    st = _load().swimba_mixer_fwd_selected(
+        ctypes.byref(d), _ptr(x, "x", io, (B, L, H, P)), _ptr(dt, "dt", io, (B, L, H)),
+        _ptr(A, "A", torch.float32, (H,)), _ptr(D, "D", torch.float32, (H,)),
+        _ptr(B_sel, "B_sel", io, (B, L, K, G, N)), _ptr(C_sel, "C_sel", io, (B, L, K, G, N)),
+        _ptr(topk_w, "topk_w", torch.float32, (B, L, K)), _ptr(h0, "h0", torch.float32, (B, H, P, N)),
+        _ptr(y, "y", io, (B, L, H, P)), _ptr(h_final, "h_final", torch.float32, (B, H, P, N)),
+        _ptr(workspace, "workspace", torch.uint8), workspace.numel(), _stream())
+    _check(st, "swimba_mixer_fwd_selected")
+    return MixerOut(y, h_final, None, None)
+
+
+def swimba_mixer_proj_workspace_bytes(dims: swimba_dims, d_model: int) -> int:
+    return int(_load().swimba_mixer_proj_workspace_bytes(ctypes.byref(dims), d_model))
+
+
+def swimba_mixer_fwd_proj(u, W_B, W_C, x, dt, A, D, router_logits, top_k: int, chunk: int, h0=None, *, y=None,
+                          h_final=None, workspace=None, want_h_final: bool = True,
+                          want_topk: bool = False) -> MixerOut:
+    """In-projection of the selected experts and the mixer forward in one call; u (B,L,Dm), W (E,G,N,Dm)."""
+    B, L, H, P = x.shape
+    E, G, N, Dm = W_B.shape
+    io, dev = x.dtype, x.device
+    d = make_dims(B, L, H, P, N, G, E, top_k, chunk, _io_code(x))
+    if workspace is None:
+        n = swimba_mixer_proj_workspace_bytes(d, Dm)
+        if n == 0:
+            alloc_workspace(d, dev)   # raises with the status of the dims
+            raise SwimbaError(2, "swimba_mixer_proj_workspace_bytes")
+        workspace = torch.empty(n, dtype=torch.uint8, device=dev)
+    if y is None:
+        y = torch.empty_like(x)
+    if h_final is None and want_h_final:
+        h_final = torch.empty((B, H, P, N), dtype=torch.float32, device=dev)
+    topk_idx = torch.empty((B, L, top_k), dtype=torch.int32, device=dev) if want_topk else None
+    topk_w = torch.empty((B, L, top_k), dtype=torch.float32, device=dev) if want_topk else None
+    st = _load().swimba_mixer_fwd_proj(
+        ctypes.byref(d), Dm, _ptr(u, "u", io, (B, L, Dm)), _ptr(W_B, "W_B", io, (E, G, N, Dm)),
+        _ptr(W_C, "W_C", io, (E, G, N, Dm)), _ptr(x, "x", io, (B, L, H, P)), _ptr(dt, "dt", io, (B, L, H)),
+        _ptr(A, "A", torch.float32, (H,)), _ptr(D, "D", torch.float32, (H,)),
+        _ptr(router_logits, "router_logits", io, (B, L, E)), _ptr(h0, "h0", torch.float32, (B, H, P, N)),
+        _ptr(y, "y", io, (B, L, H, P)), _ptr(h_final, "h_final", torch.float32, (B, H, P, N)),
+        _ptr(topk_idx, "topk_idx", torch.int32, (B, L, top_k)), _ptr(topk_w, "topk_w", torch.float32, (B, L, top_k)),
+        _ptr(workspace, "workspace", torch.uint8), workspace.numel(), _stream())
+    _check(st, "swimba_mixer_fwd_proj")
+    return MixerOut(y, h_final, topk_idx, topk_w)
 
 
 def swimba_mixer_xe_workspace_bytes(dims: swimba_dims) -> int:

@@ -169,7 +169,7 @@ swimba_status swimba_stage_mix(const swimba_dims *dims, const void *B_experts,
     if (!B_experts || !C_experts || !router_logits) return SWIMBA_ERR_NULL;
     if (!use_mfma_path(dims)) return SWIMBA_OK;   // the fp32 chunk kernels mix while staging
     return launch_mix_rows_mfma(make_shape(dims), B_experts, C_experts, router_logits, ws.idx, ws.w,
-                                ws.cmix, ws.bmix_frag, ws.bmix_t8, -1, -1, (hipStream_t)hip_stream);
+                                ws.cmix, ws.bmix_frag, ws.bmix_t8, -1, -1, nullptr, (hipStream_t)hip_stream);
 }
 
 swimba_status swimba_stage_chunk_state(const swimba_dims *dims, const void *x, const void *dt,
@@ -341,7 +341,7 @@ swimba_status swimba_separated_fwd(const swimba_dims *dims, const void *x, const
     for (int e = 0; e < s.E; ++e) {
         if (mf) {
             st = launch_mix_rows_mfma(s, B_experts, C_experts, router_logits, ws.idx, ws.w, ws.cmix,
-                                      ws.bmix_frag, ws.bmix_t8, e, -1, stream);
+                                      ws.bmix_frag, ws.bmix_t8, e, -1, nullptr, stream);
             if (st != SWIMBA_OK) return st;
             st = launch_chunk_state_mfma(s, x, dt, A, ws.bmix_t8, ws.cs, ws.states_lp, stream);
             if (st != SWIMBA_OK) return st;
@@ -451,7 +451,7 @@ swimba_status swimba_mixer_fwd_xe(const swimba_dims *dims, const void *x_experts
         const float *skip_w = ws.w + r;
         if (mf) {
             st = launch_mix_rows_mfma(s, B_experts, C_experts, router_logits, ws.idx, ws.w, ws.cmix,
-                                      ws.bmix_frag, ws.bmix_t8, -1, r, stream);
+                                      ws.bmix_frag, ws.bmix_t8, -1, r, nullptr, stream);
             if (st != SWIMBA_OK) return st;
             st = launch_xe_gather(s, dims->io_dtype, r, x_experts, ws.idx, xg, stream);
             if (st != SWIMBA_OK) return st;
@@ -519,10 +519,10 @@ size_t swimba_expert_proj_workspace_bytes(const swimba_dims *dims, int32_t d_mod
     return proj_layout_of(dims, d_model, &pl) == SWIMBA_OK ? pl.total : 0;
 }
 
-swimba_status swimba_expert_proj(const swimba_dims *dims, int32_t d_model, const void *u, const void *W_B,
-                                 const void *W_C, const void *router_logits, void *B_experts,
-                                 void *C_experts, int32_t *topk_idx, float *topk_w, void *workspace,
-                                 size_t workspace_bytes, void *hip_stream)
+static swimba_status expert_proj_body(const swimba_dims *dims, int32_t d_model, const void *u, const void *W_B,
+                                      const void *W_C, const void *router_logits, void *B_experts,
+                                      void *C_experts, int32_t *topk_idx, float *topk_w, void *workspace,
+                                      size_t workspace_bytes, int compact, void *hip_stream)
 {
     ProjLayout pl;
     swimba_status st = proj_layout_of(dims, d_model, &pl);
@@ -537,7 +537,7 @@ swimba_status swimba_expert_proj(const swimba_dims *dims, int32_t d_model, const
     hipStream_t stream = (hipStream_t)hip_stream;
     st = launch_expert_proj(T, dims->nexperts, dims->top_k, dims->ngroups * dims->dstate, d_model, dims->io_dtype,
                             u, W_B, W_C, router_logits, B_experts, C_experts, idx, w,
-                            (int32_t *)(base + pl.counts), (int32_t *)(base + pl.lists), stream);
+                            (int32_t *)(base + pl.counts), (int32_t *)(base + pl.lists), compact, stream);
     if (st != SWIMBA_OK) return st;
     if (topk_idx || topk_w) {
         const size_t cnt = (size_t)T * dims->top_k;
@@ -548,6 +548,151 @@ swimba_status swimba_expert_proj(const swimba_dims *dims, int32_t d_model, const
         if (e != hipSuccess) { set_last_hip_error((int)e); return SWIMBA_ERR_HIP; }
     }
     return SWIMBA_OK;
+}
+
+swimba_status swimba_expert_proj(const swimba_dims *dims, int32_t d_model, const void *u, const void *W_B,
+                                 const void *W_C, const void *router_logits, void *B_experts,
+                                 void *C_experts, int32_t *topk_idx, float *topk_w, void *workspace,
+                                 size_t workspace_bytes, void *hip_stream)
+{
+    return expert_proj_body(dims, d_model, u, W_B, W_C, router_logits, B_experts, C_experts, topk_idx, topk_w,
+                            workspace, workspace_bytes, 0, hip_stream);
+}
+
+swimba_status swimba_expert_proj_selected(const swimba_dims *dims, int32_t d_model, const void *u,
+                                          const void *W_B, const void *W_C, const void *router_logits,
+                                          void *B_sel, void *C_sel, int32_t *topk_idx, float *topk_w,
+                                          void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    return expert_proj_body(dims, d_model, u, W_B, W_C, router_logits, B_sel, C_sel, topk_idx, topk_w,
+                            workspace, workspace_bytes, 1, hip_stream);
+}
+
+// ---- forward on the streams of the selected experts only ---------------------------------------
+// B_sel / C_sel (B,L,k,G,N), w_sel (B,L,k).  The fp32 kernels see them as E = k experts with
+// the identity selection; the bf16 mix kernel takes the weights instead of routing.
+static swimba_status mixer_selected_core(const swimba_dims *dims, const void *x, const void *dt, const float *A,
+                                         const float *D, const void *B_sel, const void *C_sel,
+                                         const float *w_sel, const float *h0, void *y, float *h_final,
+                                         const Ws &ws, hipStream_t stream)
+{
+    const int64_t T = (int64_t)dims->batch * dims->seqlen;
+    swimba_dims dk = *dims;
+    dk.nexperts = dims->top_k;
+    const Shape s = make_shape(&dk);
+    const bool mf = use_mfma_path(dims);
+    swimba_status st;
+    if (T > 0) {
+        if (mf) {
+            st = launch_mix_rows_mfma(s, B_sel, C_sel, nullptr, nullptr, nullptr, ws.cmix, ws.bmix_frag,
+                                      ws.bmix_t8, -1, -1, w_sel, stream);
+            if (st != SWIMBA_OK) return st;
+            st = launch_chunk_state_mfma(s, x, dt, A, ws.bmix_t8, ws.cs, ws.states_lp, stream);
+        } else {
+            st = launch_slot_ids(ws.idx, T, dims->top_k, stream);
+            if (st != SWIMBA_OK) return st;
+            st = launch_cumsum(s, dims->io_dtype, dt, A, ws.cs, stream);
+            if (st != SWIMBA_OK) return st;
+            st = launch_chunk_state_generic(s, dims->io_dtype, x, dt, B_sel, ws.idx, w_sel, ws.cs, ws.states,
+                                            stream);
+        }
+        if (st != SWIMBA_OK) return st;
+    }
+    if (dims->batch > 0 && (T > 0 || h_final)) {
+        st = mf ? launch_scan_cb_mfma(s, h0, h_final, ws.states_lp, ws.cs, ws.cmix, ws.bmix_frag, ws.cb, stream)
+                : launch_state_scan(s, h0, h_final, ws.states, nullptr, ws.cs, stream);
+        if (st != SWIMBA_OK) return st;
+    }
+    if (T > 0) {
+        st = mf ? launch_output_mfma(s, x, dt, D, ws.cmix, ws.cb, ws.cs, ws.states_lp, y, nullptr, 0, 0, stream)
+                : launch_output_generic(s, dims->io_dtype, x, dt, D, B_sel, C_sel, ws.idx, w_sel, w_sel, ws.cs,
+                                        ws.states, y, nullptr, 0, 0, stream);
+        if (st != SWIMBA_OK) return st;
+    }
+    return SWIMBA_OK;
+}
+
+swimba_status swimba_mixer_fwd_selected(const swimba_dims *dims, const void *x, const void *dt, const float *A,
+                                        const float *D, const void *B_sel, const void *C_sel,
+                                        const float *topk_w, const float *h0, void *y, float *h_final,
+                                        void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    Ws ws;
+    swimba_status st = carve(dims, workspace, workspace_bytes, &ws);
+    if (st != SWIMBA_OK) return st;
+    const int64_t T = (int64_t)dims->batch * dims->seqlen;
+    if (T > 0 && (!x || !dt || !A || !B_sel || !C_sel || !topk_w || !y)) return SWIMBA_ERR_NULL;
+    return mixer_selected_core(dims, x, dt, A, D, B_sel, C_sel, topk_w, h0, y, h_final, ws,
+                               (hipStream_t)hip_stream);
+}
+
+// ---- in-projection + forward, no tensor with an expert axis in between --------------------------
+struct MixProjLayout {
+    size_t mixer, bsel, csel, counts, lists, total;
+};
+static swimba_status mixproj_layout_of(const swimba_dims *d, int32_t d_model, MixProjLayout *o)
+{
+    swimba_status st = check_mixer(d);
+    if (st != SWIMBA_OK) return st;
+    ProjLayout pl;
+    st = proj_layout_of(d, d_model, &pl);   // limits on d_model and on the list sizes
+    if (st != SWIMBA_OK) return st;
+    swimba_ws_layout lo;
+    layout_of(d, &lo);
+    const size_t T = (size_t)d->batch * d->seqlen;
+    const size_t io = d->io_dtype == SWIMBA_BF16 ? 2 : 4;
+    const size_t sel = T * d->top_k * d->ngroups * d->dstate * io;
+    size_t off = 0;
+    o->mixer = off;  off = align_up(off + lo.total, 256);
+    o->bsel = off;   off = align_up(off + sel, 256);
+    o->csel = off;   off = align_up(off + sel, 256);
+    o->counts = off; off = align_up(off + SWIMBA_MAX_EXPERTS * sizeof(int32_t), 256);
+    o->lists = off;  off = align_up(off + T * d->nexperts * sizeof(int32_t), 256);
+    o->total = off;
+    return SWIMBA_OK;
+}
+
+size_t swimba_mixer_proj_workspace_bytes(const swimba_dims *dims, int32_t d_model)
+{
+    MixProjLayout ml;
+    return mixproj_layout_of(dims, d_model, &ml) == SWIMBA_OK ? ml.total : 0;
+}
+
+swimba_status swimba_mixer_fwd_proj(const swimba_dims *dims, int32_t d_model, const void *u, const void *W_B,
+                                    const void *W_C, const void *x, const void *dt, const float *A,
+                                    const float *D, const void *router_logits, const float *h0, void *y,
+                                    float *h_final, int32_t *topk_idx, float *topk_w, void *workspace,
+                                    size_t workspace_bytes, void *hip_stream)
+{
+    MixProjLayout ml;
+    swimba_status st = mixproj_layout_of(dims, d_model, &ml);
+    if (st != SWIMBA_OK) return st;
+    if (!workspace || workspace_bytes < ml.total || ((uintptr_t)workspace & 255u)) return SWIMBA_ERR_WORKSPACE;
+    char *base = (char *)workspace;
+    Ws ws;
+    st = carve(dims, base + ml.mixer, ml.bsel - ml.mixer, &ws);
+    if (st != SWIMBA_OK) return st;
+    const int64_t T = (int64_t)dims->batch * dims->seqlen;
+    if (T > 0 && (!u || !W_B || !W_C || !x || !dt || !A || !router_logits || !y)) return SWIMBA_ERR_NULL;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    void *bsel = base + ml.bsel, *csel = base + ml.csel;
+    if (T > 0) {
+        st = launch_expert_proj(T, dims->nexperts, dims->top_k, dims->ngroups * dims->dstate, d_model,
+                                dims->io_dtype, u, W_B, W_C, router_logits, bsel, csel, ws.idx, ws.w,
+                                (int32_t *)(base + ml.counts), (int32_t *)(base + ml.lists), 1, stream);
+        if (st != SWIMBA_OK) return st;
+        // the selection leaves the workspace before the fp32 kernels reuse its place for slot ids
+        if (topk_idx || topk_w) {
+            const size_t cnt = (size_t)T * dims->top_k;
+            hipError_t e = hipSuccess;
+            if (topk_idx)
+                e = hipMemcpyAsync(topk_idx, ws.idx, cnt * sizeof(int32_t), hipMemcpyDeviceToDevice, stream);
+            if (e == hipSuccess && topk_w)
+                e = hipMemcpyAsync(topk_w, ws.w, cnt * sizeof(float), hipMemcpyDeviceToDevice, stream);
+            if (e != hipSuccess) { set_last_hip_error((int)e); return SWIMBA_ERR_HIP; }
+        }
+    }
+    return mixer_selected_core(dims, x, dt, A, D, bsel, csel, ws.w, h0, y, h_final, ws, stream);
 }
 
 size_t swimba_step_workspace_bytes(const swimba_dims *dims)

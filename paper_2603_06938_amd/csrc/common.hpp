@@ -79,11 +79,13 @@ swimba_status launch_output_generic(const Shape &s, int io_dtype, const void *x,
                                     int skip_stride, int accumulate, hipStream_t st);
 swimba_status launch_mix_rows_mfma(const Shape &s, const void *Be, const void *Ce, const void *logits,
                                    int32_t *idx, float *w, void *cmix, void *bfrag, void *bmix_t8,
-                                   int sep_e, int slot, hipStream_t st);
+                                   int sep_e, int slot, const float *w_sel, hipStream_t st);
 // routed expert in-projection (expert_proj.hip)
 swimba_status launch_expert_proj(int64_t tokens, int E, int K, int GN, int Dm, int io_dtype, const void *u,
                                  const void *WB, const void *WC, const void *logits, void *Be, void *Ce,
-                                 int32_t *idx, float *w, int32_t *counts, int32_t *lists, hipStream_t st);
+                                 int32_t *idx, float *w, int32_t *counts, int32_t *lists, int compact,
+                                 hipStream_t st);
+swimba_status launch_slot_ids(int32_t *idx, int64_t tokens, int K, hipStream_t st);
 // expert-specific input streams (xe.hip)
 swimba_status launch_xe_gather(const Shape &s, int io_dtype, int slot, const void *x_experts,
                                const int32_t *idx, void *xg, hipStream_t st);

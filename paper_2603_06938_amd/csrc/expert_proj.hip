@@ -2,12 +2,13 @@
 // expert-specific linear projections of the same token features, and only the experts of the
 // active set K_t enter the mix): for every token t and every e in K_t
 //   B_t^(e)[c] = sum_d W_B[e][c][d] u_t[d],   C_t^(e)[c] = sum_d W_C[e][c][d] u_t[d],
-// written straight into the (B,L,E,G,N) layout the mixer gathers from.  Rows of inactive
-// experts are not touched (the mixer never reads them).
+// written either into the dense (B,L,E,G,N) layout (rows of inactive experts are not touched:
+// the mixer never reads them) or, with `compact`, into (B,L,k,G,N): row r of a token is the
+// stream of its r-th selected expert, so no buffer with an expert axis exists at all.
 //
-// Three launches: clear the per-expert counters; route every token and append it to the
-// token list of each of its k experts (LDS counters per block, one global atomic per block
-// and expert); a grouped GEMM over (expert, 64-token tile of its list, 256 output columns).
+// Three launches: clear the per-expert counters; route every token and append the entry
+// t*k + r to the list of its r-th expert (LDS counters per block, one global atomic per block
+// and expert); a grouped GEMM over (expert, 64-entry tile of its list, 256 output columns).
 // The GEMM is a dense contraction, so it runs on v_mfma_f32_32x32x16_bf16.  Both operands
 // are stored with the contraction index d contiguous (weights as (out, in), like a linear
 // layer), which is the 8-consecutive-k operand layout.  The product is computed transposed,
@@ -53,7 +54,7 @@ proj_route_kernel(const T *__restrict__ logits, int32_t *__restrict__ idx, float
     if (t < tokens) {
         for (int r = 0; r < K; ++r) {
             const int e = idx[t * K + r];
-            lists[(int64_t)e * tokens + s_base[e] + s_loc[tid * K + r]] = (int32_t)t;
+            lists[(int64_t)e * tokens + s_base[e] + s_loc[tid * K + r]] = (int32_t)(t * K + r);
         }
     }
 }
@@ -79,7 +80,7 @@ __global__ void __launch_bounds__(256)
 proj_mfma_kernel(const uint16_t *__restrict__ u, const uint16_t *__restrict__ WB,
                  const uint16_t *__restrict__ WC, const int32_t *__restrict__ counts,
                  const int32_t *__restrict__ lists, uint16_t *__restrict__ Be, uint16_t *__restrict__ Ce,
-                 int64_t tokens, int E, int GN, int Dm, int tiles_max)
+                 int64_t tokens, int E, int K, int GN, int Dm, int tiles_max, int compact)
 {
     __shared__ __align__(16) uint16_t sW[PJ_COLS * PJ_STR];
     __shared__ __align__(16) uint16_t sU[PJ_TOK * PJ_STR];
@@ -109,7 +110,7 @@ proj_mfma_kernel(const uint16_t *__restrict__ u, const uint16_t *__restrict__ WB
         wsrc[i] = (c < GN ? WB + ((int64_t)e * GN + c) * Dm : WC + ((int64_t)e * GN + c - GN) * Dm);
     }
 #pragma unroll
-    for (int i = 0; i < 2; ++i) usrc[i] = u + (int64_t)lst[min(row0 + 32 * i, nvalid - 1)] * Dm;
+    for (int i = 0; i < 2; ++i) usrc[i] = u + (int64_t)(lst[min(row0 + 32 * i, nvalid - 1)] / K) * Dm;
     // Register sets: the weight rows of stage i + 2 (L2 hits) and the token rows of stage i + PJ_UD
     // (scattered 128-byte reads that mostly come from HBM) are requested while stage i is
     // multiplied.  All loads are clamped and
@@ -200,10 +201,11 @@ proj_mfma_kernel(const uint16_t *__restrict__ u, const uint16_t *__restrict__ WB
 #pragma unroll
     for (int rt = 0; rt < 2; ++rt) {
         if (32 * rt + l32 < nvalid) {
-            const int64_t tok = lst[32 * rt + l32];
+            const int64_t ent = lst[32 * rt + l32];                       // t*K + r
+            const int64_t row = compact ? ent : (ent / K) * E + e;
 #pragma unroll
             for (int ct = 0; ct < 2; ++ct) {
-                uint16_t *dst = out + (tok * E + e) * GN + cc + 32 * ct + 16 * kg;
+                uint16_t *dst = out + row * GN + cc + 32 * ct + 16 * kg;
                 const pj_f32x16_t v = acc[ct][rt];
                 *reinterpret_cast<uint4 *>(dst) =
                     make_uint4(pj_pack(v[0], v[1]), pj_pack(v[2], v[3]), pj_pack(v[4], v[5]), pj_pack(v[6], v[7]));
@@ -220,11 +222,12 @@ template <typename T>
 __global__ void __launch_bounds__(256)
 proj_generic_kernel(const T *__restrict__ u, const T *__restrict__ WB, const T *__restrict__ WC,
                     const int32_t *__restrict__ idx, T *__restrict__ Be, T *__restrict__ Ce, int E, int K,
-                    int GN, int Dm)
+                    int GN, int Dm, int compact)
 {
     extern __shared__ float s_u[];
     const int64_t t = blockIdx.x / K;
     const int e = idx[blockIdx.x];
+    const int64_t row = compact ? (int64_t)blockIdx.x : t * E + e;
     for (int d = threadIdx.x; d < Dm; d += 256) s_u[d] = to_float(u[t * Dm + d]);
     __syncthreads();
     for (int c = threadIdx.x; c < 2 * GN; c += 256) {
@@ -233,15 +236,17 @@ proj_generic_kernel(const T *__restrict__ u, const T *__restrict__ WB, const T *
         const T *wr = (isB ? WB : WC) + ((int64_t)e * GN + cc) * Dm;
         float acc = 0.f;
         for (int d = 0; d < Dm; ++d) acc += to_float(wr[d]) * s_u[d];
-        (isB ? Be : Ce)[(t * E + e) * GN + cc] = from_float<T>(acc);
+        (isB ? Be : Ce)[row * GN + cc] = from_float<T>(acc);
     }
 }
 
 swimba_status launch_expert_proj(int64_t tokens, int E, int K, int GN, int Dm, int io_dtype, const void *u,
                                  const void *WB, const void *WC, const void *logits, void *Be, void *Ce,
-                                 int32_t *idx, float *w, int32_t *counts, int32_t *lists, hipStream_t st)
+                                 int32_t *idx, float *w, int32_t *counts, int32_t *lists, int compact,
+                                 hipStream_t st)
 {
     if (tokens == 0) return SWIMBA_OK;
+    if (tokens * K > 0x7fffffffll) return SWIMBA_ERR_UNSUPPORTED;   // list entries are 32-bit
     const bool mfma = io_dtype == SWIMBA_BF16 && Dm % 16 == 0 && GN % 64 == 0;
     const unsigned rgrid = (unsigned)((tokens + 255) / 256);
     if (!mfma) {
@@ -251,11 +256,11 @@ swimba_status launch_expert_proj(int64_t tokens, int E, int K, int GN, int Dm, i
         if (io_dtype == SWIMBA_BF16)
             hipLaunchKernelGGL(proj_generic_kernel<bf16>, dim3((unsigned)(tokens * K)), dim3(256), shm, st,
                                (const bf16 *)u, (const bf16 *)WB, (const bf16 *)WC, idx, (bf16 *)Be, (bf16 *)Ce, E,
-                               K, GN, Dm);
+                               K, GN, Dm, compact);
         else
             hipLaunchKernelGGL(proj_generic_kernel<float>, dim3((unsigned)(tokens * K)), dim3(256), shm, st,
                                (const float *)u, (const float *)WB, (const float *)WC, idx, (float *)Be,
-                               (float *)Ce, E, K, GN, Dm);
+                               (float *)Ce, E, K, GN, Dm, compact);
         SWIMBA_CHECK_LAUNCH();
         return SWIMBA_OK;
     }
@@ -267,8 +272,24 @@ swimba_status launch_expert_proj(int64_t tokens, int E, int K, int GN, int Dm, i
     const int tiles_max = (int)((tokens + PJ_TOK - 1) / PJ_TOK);
     const dim3 grid((unsigned)((int64_t)8 * ((E + 7) / 8) * tiles_max), (unsigned)((2 * GN + PJ_COLS - 1) / PJ_COLS));
     hipLaunchKernelGGL(proj_mfma_kernel, grid, dim3(256), 0, st, (const uint16_t *)u, (const uint16_t *)WB,
-                       (const uint16_t *)WC, counts, lists, (uint16_t *)Be, (uint16_t *)Ce, tokens, E, GN, Dm,
-                       tiles_max);
+                       (const uint16_t *)WC, counts, lists, (uint16_t *)Be, (uint16_t *)Ce, tokens, E, K, GN, Dm,
+                       tiles_max, compact);
+    SWIMBA_CHECK_LAUNCH();
+    return SWIMBA_OK;
+}
+
+// idx[t*K + r] = r: with streams stored per selected slot, slot r is "expert" r
+__global__ void slot_ids_kernel(int32_t *idx, int64_t n, int K)
+{
+    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (i < n) idx[i] = (int32_t)(i % K);
+}
+
+swimba_status launch_slot_ids(int32_t *idx, int64_t tokens, int K, hipStream_t st)
+{
+    const int64_t n = tokens * K;
+    if (n == 0) return SWIMBA_OK;
+    hipLaunchKernelGGL(slot_ids_kernel, dim3((unsigned)((n + 255) / 256)), dim3(256), 0, st, idx, n, K);
     SWIMBA_CHECK_LAUNCH();
     return SWIMBA_OK;
 }

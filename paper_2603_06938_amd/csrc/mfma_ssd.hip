@@ -141,7 +141,8 @@ __global__ void __launch_bounds__(MTHREADS)
 mix_rows_kernel(const uint16_t *__restrict__ Be, const uint16_t *__restrict__ Ce,
                 const uint16_t *__restrict__ logits, int32_t *__restrict__ idx_out,
                 float *__restrict__ w_out, uint16_t *__restrict__ cmix, uint16_t *__restrict__ bfrag,
-                uint16_t *__restrict__ bmix_t8, Shape s, int sep_e, int slot)
+                uint16_t *__restrict__ bmix_t8, Shape s, int sep_e, int slot,
+                const float *__restrict__ w_sel)
 {
     extern __shared__ __align__(16) unsigned char smem_raw[];
     const int Kr = s.K;                                             // experts kept by the router
@@ -169,13 +170,17 @@ mix_rows_kernel(const uint16_t *__restrict__ Be, const uint16_t *__restrict__ Ce
     const int64_t tok0 = (int64_t)b * s.L + (int64_t)c * s.Q + tile * 32;
     const int64_t last = (int64_t)b * s.L + min(s.L, (c + 1) * s.Q) - 1 - tok0;   // clamp for padded rows
     const int estride = s.G * MN;
-    const int tokstride = s.E * estride;                 // elements between tokens of B/C_experts
+    // Streams of the selected experts only (w_sel != nullptr): Be / Ce are (B,L,k,G,N), row r of
+    // a token belongs to its r-th selected expert and w_sel (B,L,k) holds the router weights.
+    const bool sel = (w_sel != nullptr);
+    const int rowsE = sel ? Kr : s.E;
+    const int tokstride = rowsE * estride;               // elements between tokens of B/C_experts
     const int64_t bcg = ((int64_t)b * s.nc + c) * s.G + g;
-    const uint16_t *Bg = Be + (tok0 * s.E * s.G + g) * MN;   // [token 0 of the tile][expert 0][g][0]
-    const uint16_t *Cg = Ce + (tok0 * s.E * s.G + g) * MN;
+    const uint16_t *Bg = Be + (tok0 * rowsE * s.G + g) * MN;   // [token 0 of the tile][expert 0][g][0]
+    const uint16_t *Cg = Ce + (tok0 * rowsE * s.G + g) * MN;
 
     // ---- routing of the tile's tokens: logits staged through LDS (one coalesced read) ----
-    {
+    if (!sel) {
         const int nlog = max(0, min(valid, 32)) * s.E;
         const uint16_t *gl = logits + tok0 * s.E;
         for (int i = tid; i < nlog; i += MTHREADS) s_log[(i / s.E) * (s.E + 1) + i % s.E] = to_float(bf16{gl[i]});
@@ -183,7 +188,12 @@ mix_rows_kernel(const uint16_t *__restrict__ Be, const uint16_t *__restrict__ Ce
     lds_barrier();
     if (tid < 32) {
         const int t = tid;
-        if (t < valid) {
+        if (sel) {
+            for (int rr = 0; rr < Kr; ++rr) {
+                s_idx[t * Kr + rr] = rr;
+                s_w[t * Kr + rr] = (t < valid) ? w_sel[(tok0 + t) * Kr + rr] : 0.f;
+            }
+        } else if (t < valid) {
             const float *gl = s_log + t * (s.E + 1);
             route_token([&](int e) { return gl[e]; }, s.E, Kr, s_idx + t * Kr, s_w + t * Kr);
             if (g == 0 && sep_e <= 0 && slot <= 0) {
@@ -377,16 +387,17 @@ scan_cb_kernel(uint16_t *__restrict__ lp, const float *__restrict__ h0, float *_
 
 swimba_status launch_mix_rows_mfma(const Shape &s, const void *Be, const void *Ce, const void *logits,
                                    int32_t *idx, float *w, void *cmix, void *bfrag, void *bmix_t8,
-                                   int sep_e, int slot, hipStream_t st)
+                                   int sep_e, int slot, const float *w_sel, hipStream_t st)
 {
     const int NT = s.Q / 32;
     const int64_t nbcg = (int64_t)s.B * s.nc * s.G;
     if (nbcg == 0) return SWIMBA_OK;
+    if (w_sel && (sep_e >= 0 || slot >= 0)) return SWIMBA_ERR_UNSUPPORTED;
     const size_t shm = (size_t)32 * s.K * 8 + 32 * 12 + (size_t)2 * 32 * (MN + 8) * 2 + (size_t)32 * (s.E + 1) * 4
                        + (size_t)32 * s.K * 4;
     hipLaunchKernelGGL(mix_rows_kernel, dim3((unsigned)(nbcg * NT)), dim3(MTHREADS), shm, st,
                        (const uint16_t *)Be, (const uint16_t *)Ce, (const uint16_t *)logits, idx, w,
-                       (uint16_t *)cmix, (uint16_t *)bfrag, (uint16_t *)bmix_t8, s, sep_e, slot);
+                       (uint16_t *)cmix, (uint16_t *)bfrag, (uint16_t *)bmix_t8, s, sep_e, slot, w_sel);
     SWIMBA_CHECK_LAUNCH();
     return SWIMBA_OK;
 }
