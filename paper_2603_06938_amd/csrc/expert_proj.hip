@@ -23,7 +23,6 @@ typedef __attribute__((ext_vector_type(2))) __bf16 pj_bf16x2_t;
 typedef __attribute__((ext_vector_type(2))) float pj_f32x2_t;
 typedef __attribute__((ext_vector_type(16))) float pj_f32x16_t;
 
-constexpr int PJ_TOK = 64;     // list entries (tokens) per workgroup tile
 constexpr int PJ_COLS = 256;   // output columns per workgroup: 4 waves x 64
 
 __global__ void proj_clear_kernel(int32_t *counts, int E)
@@ -66,151 +65,234 @@ __device__ __forceinline__ uint32_t pj_pack(float lo, float hi)
     return __builtin_bit_cast(uint32_t, h);
 }
 
-// Workgroup = (expert, 64-entry tile of its token list, block of 256 output columns);
-// wave w owns columns 64w..64w+63 of the block and all 64 entries: 2 x 2 MFMA tiles.
+// Workgroup = (share of one expert's list, block of 256 output columns), 8 waves: wave w owns
+// columns 64 (w & 3) .. + 63 of the block and one of two row groups.  The `nslots` workgroups
+// that fit on the chip at once (one per compute unit) are divided among the experts in
+// proportion to their list lengths (known on the device only), and a workgroup walks its share
+// in passes of up to 192 entries (6 row tiles of 32, at most 3 per row group): the whole launch
+// is one round of co-resident workgroups, whatever the routing.  (With fixed 64-entry tiles and
+// two workgroups per compute unit the 130M-shaped layer had 517 workgroups for 512 places, and
+// the second round of five cost 12 us; every workgroup also streamed the weights for 64 entries
+// only.)  Measured on that layer (29 us): everything but the k-steps 8.5 us, MFMAs alone + 10 us,
+// operand reads from LDS alone + 14 us (about 60 bytes per clock and compute unit, no bank
+// conflicts), both + 22 us: the operand reads are the limit.  One wave per SIMD with 4 x 3 tiles
+// (7 reads per 12 MFMAs instead of 5 per 6) measured slower (34 us): nothing hides its waits.
 // The contraction runs in stages of 64 features.  A stage of both operands (256 weight rows,
-// 64 token rows, 128 bytes each) is read with fully coalesced 16-byte loads (8 lanes per
+// 192 token rows, 128 bytes each) is read with fully coalesced 16-byte loads (8 lanes per
 // row), parked in registers while the previous stage is multiplied, and then passed through
 // LDS, from where the lanes read their operand registers.
+constexpr int PJ_THREADS = 512;
 constexpr int PJ_KT = 64;             // features per stage
 constexpr int PJ_STR = PJ_KT + 8;     // LDS row stride (elements): rows stay 16-byte aligned
-constexpr int PJ_UD = 2;              // stages the token-row loads run ahead (even); 6 measured no faster
+constexpr int PJ_UD = 2;              // stages the loads run ahead (even)
+constexpr int PJ_RT = 3;              // row tiles (of 32 list entries) per wave and pass
+constexpr int PJ_ROWS = 2 * 32 * PJ_RT;   // list entries per workgroup and pass
 
-__global__ void __launch_bounds__(256)
+// workgroups expert e gets out of nslots, given its list length
+__device__ __forceinline__ int proj_share(int cnt, int nslots, int64_t total)
+{
+    return cnt > 0 ? max(1, (int)((int64_t)nslots * cnt / total)) : 0;
+}
+
+__global__ void __launch_bounds__(PJ_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
 proj_mfma_kernel(const uint16_t *__restrict__ u, const uint16_t *__restrict__ WB,
                  const uint16_t *__restrict__ WC, const int32_t *__restrict__ counts,
                  const int32_t *__restrict__ lists, uint16_t *__restrict__ Be, uint16_t *__restrict__ Ce,
-                 int64_t tokens, int E, int K, int GN, int Dm, int tiles_max, int compact)
+                 int64_t tokens, int E, int K, int GN, int Dm, int nslots, int compact)
 {
     __shared__ __align__(16) uint16_t sW[PJ_COLS * PJ_STR];
-    __shared__ __align__(16) uint16_t sU[PJ_TOK * PJ_STR];
-    // Consecutive block ids go to consecutive XCDs (8 of them, each with its own L2).  Expert e
-    // is served by XCD e % 8 only, so that an XCD's L2 holds the weights of E/8 experts instead
-    // of all of them (3 MB of weights per 8 experts at 768 features would fill a 4 MB L2).
-    const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
-    const int e = xcd + 8 * (j / tiles_max), tile = j % tiles_max;
-    if (e >= E) return;
-    const int cnt = counts[e];
-    if (tile * PJ_TOK >= cnt) return;                        // whole workgroup: no barrier is skipped
+    __shared__ __align__(16) uint16_t sU[PJ_ROWS * PJ_STR];
+    __shared__ int32_t s_share[SWIMBA_MAX_EXPERTS];
+    __shared__ int32_t s_sel[2];
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int64_t total = tokens * K;
+
+    // ---- which expert, which part of its list: prefix sum of the shares (E <= 256 = 4 per lane) ----
+    if (tid < SWIMBA_MAX_EXPERTS) s_share[tid] = tid < E ? proj_share(counts[tid], nslots, total) : 0;
+    if (tid == 0) s_sel[0] = -1;
+    __syncthreads();
+    if (wave == 0) {
+        int v[4], sum = 0;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) { v[q] = s_share[4 * lane + q]; sum += v[q]; }
+        int incl = sum;
+#pragma unroll
+        for (int d = 1; d < 64; d <<= 1) {
+            const int t = __shfl_up(incl, d);
+            if (lane >= d) incl += t;
+        }
+        int r = (int)blockIdx.x - (incl - sum);
+        if (r >= 0 && r < sum) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                if (r >= 0 && r < v[q]) { s_sel[0] = 4 * lane + q; s_sel[1] = r; }
+                r -= v[q];          // negative from the match on: no later q matches
+            }
+        }
+    }
+    __syncthreads();
+    const int e = __builtin_amdgcn_readfirstlane(s_sel[0]);
+    if (e < 0) return;                                       // whole workgroup: no barrier is skipped
+    const int part = __builtin_amdgcn_readfirstlane(s_sel[1]);
+    const int cnt = counts[e];
+    const int nparts = proj_share(cnt, nslots, total);
+    const int n32 = (cnt + 31) / 32;
+    const int t_begin = (int)((int64_t)part * n32 / nparts), t_end = (int)((int64_t)(part + 1) * n32 / nparts);
+    const int nt = t_end - t_begin;
+    if (nt <= 0) return;
+    const int npass = (nt + 2 * PJ_RT - 1) / (2 * PJ_RT);
+
+    const int cw = wave & 3, rg = wave >> 2;                 // column group, row group of the wave
     const int colblk = blockIdx.y * PJ_COLS;                 // first column of the block in [B | C]
-    const int col0 = colblk + wave * 64;
+    const int col0 = colblk + cw * 64;
     const bool active = col0 < 2 * GN;                       // wave-uniform; idle waves still stage
     const int l32 = lane & 31, kg = lane >> 5;
-    const int nvalid = min(PJ_TOK, cnt - tile * PJ_TOK);
-    const int32_t *lst = lists + (int64_t)e * tokens + tile * PJ_TOK;
 
-    // ---- staging map: lane -> 16-byte piece `piece` of rows row0 + 32 i ----
-    const int piece = tid & 7, row0 = tid >> 3;
-    const uint16_t *wsrc[8], *usrc[2];
+    // ---- staging map: lane -> 16-byte piece `piece` of rows row0 + 64 i ----
+    const int piece = tid & 7, row0 = tid >> 3;              // row0 = 32 rg + (row inside a 32-block)
+    // G*N is a multiple of 32, so the 32 rows of a staging step of one wave lie in one of the two
+    // weight matrices: a uniform base (scalar registers) + one per-lane offset for all four.
+    const uint16_t *wbase[4];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) {
-        const int c = min(colblk + row0 + 32 * i, 2 * GN - 1);          // rows past [B | C] repeat the last one
-        wsrc[i] = (c < GN ? WB + ((int64_t)e * GN + c) * Dm : WC + ((int64_t)e * GN + c - GN) * Dm);
+    for (int i = 0; i < 4; ++i) {
+        const int c = min(colblk + 64 * i + 32 * rg, 2 * GN - 32);      // blocks past [B | C] repeat the last one
+        wbase[i] = (c < GN ? WB + ((int64_t)e * GN + c) * Dm : WC + ((int64_t)e * GN + c - GN) * Dm);
     }
-#pragma unroll
-    for (int i = 0; i < 2; ++i) usrc[i] = u + (int64_t)(lst[min(row0 + 32 * i, nvalid - 1)] / K) * Dm;
-    // Register sets: the weight rows of stage i + 2 (L2 hits) and the token rows of stage i + PJ_UD
-    // (scattered 128-byte reads that mostly come from HBM) are requested while stage i is
-    // multiplied.  All loads are clamped and
-    // unconditional, so that the waits on them stay exact counts; the issues past the last
-    // stage re-read it and are not used.
+    const int r32 = row0 & 31;
+    const int wlane = r32 * Dm;
     const int k_last = ((Dm - 1) / PJ_KT) * PJ_KT;
-    uint4 wreg[2][8], ureg[PJ_UD][2];
-    auto load_w = [&](uint4 (&wr)[8], int k0) __attribute__((always_inline)) {
-        const int kk = min(min(k0, k_last) + piece * 8, Dm - 8);   // a short last stage stays inside the row
-#pragma unroll
-        for (int i = 0; i < 8; ++i) wr[i] = *reinterpret_cast<const uint4 *>(wsrc[i] + kk);
-    };
-    auto load_u = [&](uint4 (&ur)[2], int k0) __attribute__((always_inline)) {
-        const int kk = min(min(k0, k_last) + piece * 8, Dm - 8);
-#pragma unroll
-        for (int i = 0; i < 2; ++i) ur[i] = *reinterpret_cast<const uint4 *>(usrc[i] + kk);
-    };
-
     // Operand row r of a 32-column weight tile must hold column 16*((r>>2)&1) + 4*(r>>3) + (r&3)
     // for accumulator register v of lane (l32, kg) to be column 16 kg + v of the tile.  The
     // permutation is applied when the rows are staged (column x goes to LDS row wrow), so the
     // lanes of a wave read consecutive LDS rows: no bank conflicts.
-    const int wrow = 8 * ((row0 >> 2) & 3) + 4 * ((row0 >> 4) & 1) + (row0 & 3);
-    const uint16_t *aop[2], *bop[2];
+    const int wrow = 8 * ((r32 >> 2) & 3) + 4 * ((r32 >> 4) & 1) + (r32 & 3) + 32 * rg;
+    const uint16_t *aop[2];
 #pragma unroll
-    for (int q = 0; q < 2; ++q) {
-        aop[q] = sW + (wave * 64 + 32 * q + l32) * PJ_STR + 8 * kg;
-        bop[q] = sU + (32 * q + l32) * PJ_STR + 8 * kg;
-    }
-    pj_f32x16_t acc[2][2];
-#pragma unroll
-    for (int ct = 0; ct < 2; ++ct)
-#pragma unroll
-        for (int rt = 0; rt < 2; ++rt) acc[ct][rt] = pj_f32x16_t{0};
-
-    // one stage: registers -> LDS, refill the registers two stages ahead, multiply from LDS
-    auto stage = [&](uint4 (&wr)[8], uint4 (&ur)[2], int k0) __attribute__((always_inline)) {
-        lds_barrier();                                       // every wave is done with the previous stage
-        // pieces past the end of a short last stage are staged as zeros: every stage is 4 k-steps
-        const bool inside = k0 + piece * 8 < Dm;
-#pragma unroll
-        for (int i = 0; i < 8; ++i)
-            *reinterpret_cast<uint4 *>(sW + (wrow + 32 * i) * PJ_STR + piece * 8) =
-                inside ? wr[i] : make_uint4(0, 0, 0, 0);
-#pragma unroll
-        for (int i = 0; i < 2; ++i)
-            *reinterpret_cast<uint4 *>(sU + (row0 + 32 * i) * PJ_STR + piece * 8) =
-                inside ? ur[i] : make_uint4(0, 0, 0, 0);
-        lds_barrier();
-        load_w(wr, k0 + 2 * PJ_KT);
-        load_u(ur, k0 + PJ_UD * PJ_KT);
-        if (active) {
-#pragma unroll
-            for (int s4 = 0; s4 < PJ_KT / 16; ++s4) {
-                uint4 a[2], b[2];
-#pragma unroll
-                for (int q = 0; q < 2; ++q) {
-                    a[q] = *reinterpret_cast<const uint4 *>(aop[q] + 16 * s4);
-                    b[q] = *reinterpret_cast<const uint4 *>(bop[q] + 16 * s4);
-                }
-#pragma unroll
-                for (int ct = 0; ct < 2; ++ct)
-#pragma unroll
-                    for (int rt = 0; rt < 2; ++rt)
-                        acc[ct][rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
-                            __builtin_bit_cast(pj_bf16x8_t, a[ct]), __builtin_bit_cast(pj_bf16x8_t, b[rt]),
-                            acc[ct][rt], 0, 0, 0);
-            }
-        }
-    };
-    // prologue in the order the loop consumes (scheduling barriers keep the issue order)
-#pragma unroll
-    for (int d = 0; d < PJ_UD; ++d) {
-        if (d < 2) load_w(wreg[d], d * PJ_KT);
-        load_u(ureg[d], d * PJ_KT);
-        __builtin_amdgcn_sched_barrier(0);
-    }
-    // straight-line groups of PJ_UD stages (a stage count that is not a multiple runs all-zero
-    // stages): no branch between the register sets
-    for (int k0 = 0; k0 < Dm; k0 += PJ_UD * PJ_KT) {
-#pragma unroll
-        for (int d = 0; d < PJ_UD; ++d) stage(wreg[d & 1], ureg[d], k0 + d * PJ_KT);
-    }
-    if (!active) return;
+    for (int q = 0; q < 2; ++q) aop[q] = sW + (cw * 64 + 32 * q + l32) * PJ_STR + 8 * kg;
     const bool isB = col0 < GN;
     const int cc = isB ? col0 : col0 - GN;                   // column inside the B (or C) row
     uint16_t *out = isB ? Be : Ce;
+
+    for (int pass = 0; pass < npass; ++pass) {
+        const int p_begin = t_begin + (int)((int64_t)pass * nt / npass);
+        const int p_end = t_begin + (int)((int64_t)(pass + 1) * nt / npass);
+        const int ptiles = p_end - p_begin;                              // 1..6 row tiles
+        const int half = (ptiles + 1) / 2;
+        const int tbase = rg ? half : 0;                                 // first tile of this wave's row group
+        const int nrt = rg ? ptiles - half : half;                       // its tiles: 0..3, wave-uniform
+        const int nvalid = min(32 * p_end, cnt) - 32 * p_begin;          // entries of this pass
+        const int32_t *lst = lists + (int64_t)e * tokens + 32 * p_begin;
+        const uint16_t *usrc[PJ_RT];
 #pragma unroll
-    for (int rt = 0; rt < 2; ++rt) {
-        if (32 * rt + l32 < nvalid) {
-            const int64_t ent = lst[32 * rt + l32];                       // t*K + r
-            const int64_t row = compact ? ent : (ent / K) * E + e;
+        for (int i = 0; i < PJ_RT; ++i) usrc[i] = u + (int64_t)(lst[min(row0 + 64 * i, nvalid - 1)] / K) * Dm;
+        const uint16_t *bop = sU + (32 * tbase + l32) * PJ_STR + 8 * kg;
+        // Register sets: the weight rows (L2 hits) and the token rows (scattered 128-byte reads
+        // that mostly come from HBM) of stage i + 2 are requested while stage i is multiplied.
+        // All loads are clamped and unconditional, so that the waits on them stay exact counts;
+        // the issues past the last stage re-read it and are not used.
+        uint4 wreg[2][4], ureg[PJ_UD][PJ_RT];
+        auto load_w = [&](uint4 (&wr)[4], int k0) __attribute__((always_inline)) {
+            const int kk = min(min(k0, k_last) + piece * 8, Dm - 8);   // a short last stage stays inside the row
 #pragma unroll
-            for (int ct = 0; ct < 2; ++ct) {
-                uint16_t *dst = out + row * GN + cc + 32 * ct + 16 * kg;
-                const pj_f32x16_t v = acc[ct][rt];
-                *reinterpret_cast<uint4 *>(dst) =
-                    make_uint4(pj_pack(v[0], v[1]), pj_pack(v[2], v[3]), pj_pack(v[4], v[5]), pj_pack(v[6], v[7]));
-                *reinterpret_cast<uint4 *>(dst + 8) =
-                    make_uint4(pj_pack(v[8], v[9]), pj_pack(v[10], v[11]), pj_pack(v[12], v[13]), pj_pack(v[14], v[15]));
+            for (int i = 0; i < 4; ++i) wr[i] = *reinterpret_cast<const uint4 *>(wbase[i] + (wlane + kk));
+        };
+        auto load_u = [&](uint4 (&ur)[PJ_RT], int k0) __attribute__((always_inline)) {
+            const int kk = min(min(k0, k_last) + piece * 8, Dm - 8);
+#pragma unroll
+            for (int i = 0; i < PJ_RT; ++i) ur[i] = *reinterpret_cast<const uint4 *>(usrc[i] + kk);
+        };
+        pj_f32x16_t acc[2][PJ_RT];
+#pragma unroll
+        for (int ct = 0; ct < 2; ++ct)
+#pragma unroll
+            for (int rt = 0; rt < PJ_RT; ++rt) acc[ct][rt] = pj_f32x16_t{0};
+
+        // the 4 k-steps of a stage; the operands of k-step s + 1 are read from LDS before the
+        // MFMAs of k-step s are issued (two operand sets rotated by name)
+        auto read_ops = [&](uint4 (&a)[2], uint4 (&b)[PJ_RT], int s4) __attribute__((always_inline)) {
+#pragma unroll
+            for (int q = 0; q < 2; ++q) a[q] = *reinterpret_cast<const uint4 *>(aop[q] + 16 * s4);
+#pragma unroll
+            for (int rt = 0; rt < PJ_RT; ++rt)
+                b[rt] = *reinterpret_cast<const uint4 *>(bop + 32 * rt * PJ_STR + 16 * s4);
+        };
+        auto mfmas = [&](const uint4 (&a)[2], const uint4 (&b)[PJ_RT]) __attribute__((always_inline)) {
+#pragma unroll
+            for (int rt = 0; rt < PJ_RT; ++rt)
+#pragma unroll
+                for (int ct = 0; ct < 2; ++ct)
+                    acc[ct][rt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                        __builtin_bit_cast(pj_bf16x8_t, a[ct]), __builtin_bit_cast(pj_bf16x8_t, b[rt]),
+                        acc[ct][rt], 0, 0, 0);
+        };
+        auto multiply = [&]() __attribute__((always_inline)) {
+            uint4 a0[2], b0[PJ_RT], a1[2], b1[PJ_RT];
+            read_ops(a0, b0, 0);
+            read_ops(a1, b1, 1);
+            __builtin_amdgcn_sched_barrier(0);
+            mfmas(a0, b0);
+            __builtin_amdgcn_sched_barrier(0);
+            read_ops(a0, b0, 2);
+            __builtin_amdgcn_sched_barrier(0);
+            mfmas(a1, b1);
+            __builtin_amdgcn_sched_barrier(0);
+            read_ops(a1, b1, 3);
+            __builtin_amdgcn_sched_barrier(0);
+            mfmas(a0, b0);
+            mfmas(a1, b1);
+        };
+        // one stage: registers -> LDS, refill the registers two stages ahead, multiply from LDS
+        auto stage = [&](uint4 (&wr)[4], uint4 (&ur)[PJ_RT], int k0) __attribute__((always_inline)) {
+            lds_barrier();                                       // every wave is done with the previous stage
+            // pieces past the end of a short last stage are staged as zeros: every stage is 4 k-steps
+            const bool inside = k0 + piece * 8 < Dm;
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+                *reinterpret_cast<uint4 *>(sW + (wrow + 64 * i) * PJ_STR + piece * 8) =
+                    inside ? wr[i] : make_uint4(0, 0, 0, 0);
+#pragma unroll
+            for (int i = 0; i < PJ_RT; ++i)
+                *reinterpret_cast<uint4 *>(sU + (row0 + 64 * i) * PJ_STR + piece * 8) =
+                    inside ? ur[i] : make_uint4(0, 0, 0, 0);
+            lds_barrier();
+            load_w(wr, k0 + 2 * PJ_KT);
+            load_u(ur, k0 + PJ_UD * PJ_KT);
+            // All three row tiles are multiplied whether the wave has that many or not (the rows are
+            // staged clamped, the epilogue skips them): a branch per row tile inside the k-steps made
+            // every pair of MFMAs wait for its own LDS read, and one code path per tile count spills.
+            if (active) multiply();
+        };
+        // prologue in the order the loop consumes (scheduling barriers keep the issue order)
+#pragma unroll
+        for (int d = 0; d < PJ_UD; ++d) {
+            load_w(wreg[d], d * PJ_KT);
+            load_u(ureg[d], d * PJ_KT);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        // straight-line groups of PJ_UD stages (a stage count that is not a multiple runs all-zero
+        // stages): no branch between the register sets
+        for (int k0 = 0; k0 < Dm; k0 += PJ_UD * PJ_KT) {
+#pragma unroll
+            for (int d = 0; d < PJ_UD; ++d) stage(wreg[d], ureg[d], k0 + d * PJ_KT);
+        }
+        if (active) {
+#pragma unroll
+            for (int rt = 0; rt < PJ_RT; ++rt) {
+                const int prow = 32 * (tbase + rt) + l32;                         // entry inside the pass
+                if (rt < nrt && prow < nvalid) {
+                    const int64_t ent = lst[prow];                                // t*K + r
+                    const int64_t row = compact ? ent : (ent / K) * E + e;
+#pragma unroll
+                    for (int ct = 0; ct < 2; ++ct) {
+                        uint16_t *dst = out + row * GN + cc + 32 * ct + 16 * kg;
+                        const pj_f32x16_t v = acc[ct][rt];
+                        *reinterpret_cast<uint4 *>(dst) =
+                            make_uint4(pj_pack(v[0], v[1]), pj_pack(v[2], v[3]), pj_pack(v[4], v[5]), pj_pack(v[6], v[7]));
+                        *reinterpret_cast<uint4 *>(dst + 8) = make_uint4(pj_pack(v[8], v[9]), pj_pack(v[10], v[11]),
+                                                                         pj_pack(v[12], v[13]), pj_pack(v[14], v[15]));
+                    }
+                }
             }
         }
     }
@@ -269,11 +351,18 @@ swimba_status launch_expert_proj(int64_t tokens, int E, int K, int GN, int Dm, i
     hipLaunchKernelGGL(proj_route_kernel<bf16>, dim3(rgrid), dim3(256), (size_t)256 * K * sizeof(int32_t), st,
                        (const bf16 *)logits, idx, w, counts, lists, tokens, E, K);
     SWIMBA_CHECK_LAUNCH();
-    const int tiles_max = (int)((tokens + PJ_TOK - 1) / PJ_TOK);
-    const dim3 grid((unsigned)((int64_t)8 * ((E + 7) / 8) * tiles_max), (unsigned)((2 * GN + PJ_COLS - 1) / PJ_COLS));
-    hipLaunchKernelGGL(proj_mfma_kernel, grid, dim3(256), 0, st, (const uint16_t *)u, (const uint16_t *)WB,
+    // one place per compute unit (a workgroup is 8 waves with up to 256 registers each), shared
+    // by the column blocks; the kernel divides them among the experts
+    int devid = 0, ncu = 0;
+    hipError_t he = hipGetDevice(&devid);
+    if (he == hipSuccess) he = hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, devid);
+    if (he != hipSuccess) { set_last_hip_error((int)he); return SWIMBA_ERR_HIP; }
+    const int colblocks = (2 * GN + PJ_COLS - 1) / PJ_COLS;
+    const int nslots = max(1, ncu / colblocks);
+    const dim3 grid((unsigned)(nslots + E), (unsigned)colblocks);   // the shares sum to at most nslots + E
+    hipLaunchKernelGGL(proj_mfma_kernel, grid, dim3(PJ_THREADS), 0, st, (const uint16_t *)u, (const uint16_t *)WB,
                        (const uint16_t *)WC, counts, lists, (uint16_t *)Be, (uint16_t *)Ce, tokens, E, K, GN, Dm,
-                       tiles_max, compact);
+                       nslots, compact);
     SWIMBA_CHECK_LAUNCH();
     return SWIMBA_OK;
 }
