@@ -50,6 +50,32 @@ def test_expert_proj_selected_matches_oracle(cfg):
         assert l2 <= TOL[io] and linf <= TOL[io], (name, l2, linf)
 
 
+@pytest.mark.parametrize("case", ["many_passes_8_column_blocks", "one_hot_expert", "long_lists"])
+def test_expert_proj_selected_list_shapes(case):
+    """The GEMM shares one round of workgroups out among the experts by list length and walks a
+    share in passes of up to 192 entries: cases with several passes per workgroup, with one expert
+    holding every token, and with lists far longer than a pass."""
+    if case == "many_passes_8_column_blocks":
+        B, L, Dm, E, G, N, k = 1, 4100, 64, 4, 8, 128, 2        # 2048 columns: few workgroups per column block
+    elif case == "one_hot_expert":
+        B, L, Dm, E, G, N, k = 2, 3000, 48, 8, 1, 128, 2
+    else:
+        B, L, Dm, E, G, N, k = 4, 8192, 32, 4, 1, 64, 2         # 65536 entries for 256 workgroups
+    u, WB, WC, g = make_problem(B, L, Dm, E, G, N, "bf16", seed=len(case))
+    if case == "one_hot_expert":
+        g[..., 3] = 8.0                                         # expert 3 is in every active set
+    ref = orc.expert_proj(u, WB, WC, g, k, fill=0.0)
+    out = sw.swimba_expert_proj_selected(dev(u, "bf16"), dev(WB, "bf16"), dev(WC, "bf16"), dev(g, "bf16"), k)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(out.topk_idx.cpu().numpy(), ref["topk_idx"])
+    for name, got, dense in (("B", host(out.B_experts), ref["B_experts"]), ("C", host(out.C_experts), ref["C_experts"])):
+        want = gather_selected(dense, ref["topk_idx"])
+        l2 = np.linalg.norm(got - want) / np.linalg.norm(want)
+        linf = np.abs(got - want).max() / np.abs(want).max()
+        print(case, name, "rel l2 %.3e linf %.3e" % (l2, linf), flush=True)
+        assert l2 <= TOL["bf16"] and linf <= TOL["bf16"], (name, l2, linf)
+
+
 MIX_SHAPES = [
     # B, L, H, P, N, G, E, k, Q, io
     (2, 96, 4, 16, 16, 2, 4, 2, 32, "f32"),
