@@ -11,7 +11,11 @@
  * Conventions that hold for every entry point
  *   - Every tensor pointer is a DEVICE pointer owned by the caller (the dims
  *     struct and the layout struct are HOST pointers).  Tensors are dense,
- *     row-major, last index contiguous, 16-byte aligned.
+ *     row-major, last index contiguous.  The large tensors (x, y, x_experts, u, the
+ *     B/C streams, projection weights, states) must be 16-byte aligned: they are moved
+ *     with 16-byte vector accesses; dt, router logits, A, D, topk_idx and topk_w need the
+ *     alignment of their element type only.  A misaligned pointer is refused
+ *     (SWIMBA_ERR_ALIGNMENT), never dereferenced.
  *   - "io" tensors have the element type dims->io_dtype (fp32 or bf16);
  *     A, D, states, weights are always fp32, indices int32.
  *   - The library allocates no device memory.  Scratch comes from the
@@ -48,7 +52,8 @@ typedef enum {
     SWIMBA_ERR_DTYPE = 3,       /* io_dtype is not a swimba_dtype */
     SWIMBA_ERR_UNSUPPORTED = 4, /* valid problem, but outside the kernels' limits */
     SWIMBA_ERR_WORKSPACE = 5,   /* workspace NULL or smaller than the query says */
-    SWIMBA_ERR_HIP = 6          /* a HIP call failed; see swimba_last_hip_error() */
+    SWIMBA_ERR_HIP = 6,         /* a HIP call failed; see swimba_last_hip_error() */
+    SWIMBA_ERR_ALIGNMENT = 7    /* a tensor pointer is misaligned (see the conventions above) */
 } swimba_status;
 
 typedef enum { SWIMBA_F32 = 0, SWIMBA_BF16 = 1 } swimba_dtype;

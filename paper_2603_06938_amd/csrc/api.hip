@@ -3,12 +3,31 @@
 
 #include <string.h>
 
+#include <initializer_list>
+
 namespace swimba {
 
 static thread_local int g_last_hip_error = 0;
 void set_last_hip_error(int e) { g_last_hip_error = e; }
 
 static inline size_t align_up(size_t v, size_t a) { return (v + a - 1) / a * a; }
+
+// Pointer alignment (NULL passes: whether a pointer may be NULL is checked elsewhere).  The
+// large tensors are read and written with 16-byte vector accesses; the small per-token and
+// per-head ones element by element.
+static swimba_status check_align(int io_dtype, std::initializer_list<const void *> vec16,
+                                 std::initializer_list<const void *> io_elems,
+                                 std::initializer_list<const void *> words)
+{
+    const uintptr_t io = io_dtype == SWIMBA_BF16 ? 2 : 4;
+    for (const void *q : vec16)
+        if ((uintptr_t)q & 15u) return SWIMBA_ERR_ALIGNMENT;
+    for (const void *q : io_elems)
+        if ((uintptr_t)q & (io - 1)) return SWIMBA_ERR_ALIGNMENT;
+    for (const void *q : words)
+        if ((uintptr_t)q & 3u) return SWIMBA_ERR_ALIGNMENT;
+    return SWIMBA_OK;
+}
 
 // Checks that hold for both entry points.
 static swimba_status check_common(const swimba_dims *d)
@@ -129,6 +148,7 @@ swimba_status swimba_router_topk(int64_t tokens, int32_t nexperts, int32_t top_k
         return SWIMBA_ERR_UNSUPPORTED;
     if (tokens == 0) return SWIMBA_OK;
     if (!logits || !topk_idx || !topk_w) return SWIMBA_ERR_NULL;
+    if (check_align(io_dtype, {}, {logits}, {topk_idx, topk_w}) != SWIMBA_OK) return SWIMBA_ERR_ALIGNMENT;
     return launch_router(tokens, nexperts, top_k, io_dtype, logits, topk_idx, topk_w,
                          (hipStream_t)hip_stream);
 }
@@ -142,6 +162,7 @@ swimba_status swimba_stage_router(const swimba_dims *dims, const void *router_lo
     const int64_t T = (int64_t)dims->batch * dims->seqlen;
     if (T == 0) return SWIMBA_OK;
     if (!router_logits) return SWIMBA_ERR_NULL;
+    if (check_align(dims->io_dtype, {}, {router_logits}, {}) != SWIMBA_OK) return SWIMBA_ERR_ALIGNMENT;
     return launch_router(T, dims->nexperts, dims->top_k, dims->io_dtype, router_logits, ws.idx, ws.w,
                          (hipStream_t)hip_stream);
 }
@@ -154,6 +175,7 @@ swimba_status swimba_stage_cumsum(const swimba_dims *dims, const void *dt, const
     if (st != SWIMBA_OK) return st;
     if ((int64_t)dims->batch * dims->seqlen == 0) return SWIMBA_OK;
     if (!dt || !A) return SWIMBA_ERR_NULL;
+    if (check_align(dims->io_dtype, {}, {dt}, {A}) != SWIMBA_OK) return SWIMBA_ERR_ALIGNMENT;
     if (use_mfma_path(dims)) return SWIMBA_OK;   // the MFMA chunk-state kernel computes cs itself
     return launch_cumsum(make_shape(dims), dims->io_dtype, dt, A, ws.cs, (hipStream_t)hip_stream);
 }
@@ -167,6 +189,8 @@ swimba_status swimba_stage_mix(const swimba_dims *dims, const void *B_experts,
     if (st != SWIMBA_OK) return st;
     if ((int64_t)dims->batch * dims->seqlen == 0) return SWIMBA_OK;
     if (!B_experts || !C_experts || !router_logits) return SWIMBA_ERR_NULL;
+    if (check_align(dims->io_dtype, {B_experts, C_experts}, {router_logits}, {}) != SWIMBA_OK)
+        return SWIMBA_ERR_ALIGNMENT;
     if (!use_mfma_path(dims)) return SWIMBA_OK;   // the fp32 chunk kernels mix while staging
     return launch_mix_rows_mfma(make_shape(dims), B_experts, C_experts, router_logits, ws.idx, ws.w,
                                 ws.cmix, ws.bmix_frag, ws.bmix_t8, -1, -1, nullptr, (hipStream_t)hip_stream);
@@ -181,6 +205,7 @@ swimba_status swimba_stage_chunk_state(const swimba_dims *dims, const void *x, c
     if (st != SWIMBA_OK) return st;
     if ((int64_t)dims->batch * dims->seqlen == 0) return SWIMBA_OK;
     if (!x || !dt || !A || !B_experts) return SWIMBA_ERR_NULL;
+    if (check_align(dims->io_dtype, {x, B_experts}, {dt}, {A}) != SWIMBA_OK) return SWIMBA_ERR_ALIGNMENT;
     const Shape s = make_shape(dims);
     if (use_mfma_path(dims))
         return launch_chunk_state_mfma(s, x, dt, A, ws.bmix_t8, ws.cs, ws.states_lp,
@@ -212,6 +237,8 @@ swimba_status swimba_stage_output(const swimba_dims *dims, const void *x, const 
     if (st != SWIMBA_OK) return st;
     if ((int64_t)dims->batch * dims->seqlen == 0) return SWIMBA_OK;
     if (!x || !dt || !B_experts || !C_experts || !y) return SWIMBA_ERR_NULL;
+    if (check_align(dims->io_dtype, {x, B_experts, C_experts, y}, {dt}, {D}) != SWIMBA_OK)
+        return SWIMBA_ERR_ALIGNMENT;
     const Shape s = make_shape(dims);
     if (use_mfma_path(dims))
         return launch_output_mfma(s, x, dt, D, ws.cmix, ws.cb, ws.cs, ws.states_lp, y, nullptr, 0, 0,
@@ -232,6 +259,9 @@ swimba_status swimba_mixer_fwd(const swimba_dims *dims, const void *x, const voi
     const int64_t T = (int64_t)dims->batch * dims->seqlen;
     if (T > 0 && (!x || !dt || !A || !B_experts || !C_experts || !router_logits || !y))
         return SWIMBA_ERR_NULL;
+    if (check_align(dims->io_dtype, {x, B_experts, C_experts, y, h0, h_final}, {dt, router_logits},
+                    {A, D, topk_idx, topk_w}) != SWIMBA_OK)
+        return SWIMBA_ERR_ALIGNMENT;
     hipStream_t stream = (hipStream_t)hip_stream;
     const Shape s = make_shape(dims);
     const bool mf = use_mfma_path(dims);
@@ -316,6 +346,9 @@ swimba_status swimba_separated_fwd(const swimba_dims *dims, const void *x, const
     const int64_t T = (int64_t)dims->batch * dims->seqlen;
     if (T == 0) return SWIMBA_OK;
     if (!x || !dt || !A || !B_experts || !C_experts || !router_logits || !y) return SWIMBA_ERR_NULL;
+    if (check_align(dims->io_dtype, {x, B_experts, C_experts, y}, {dt, router_logits}, {A, D, topk_idx, topk_w}) !=
+        SWIMBA_OK)
+        return SWIMBA_ERR_ALIGNMENT;
     char *base = (char *)workspace;
     Ws ws;
     swimba_ws_layout lo;
@@ -419,6 +452,9 @@ swimba_status swimba_mixer_fwd_xe(const swimba_dims *dims, const void *x_experts
     const int64_t T = (int64_t)dims->batch * dims->seqlen;
     if (T > 0 && (!x_experts || !dt || !A || !B_experts || !C_experts || !router_logits || !y))
         return SWIMBA_ERR_NULL;
+    if (check_align(dims->io_dtype, {x_experts, B_experts, C_experts, y, h0, h_final}, {dt, router_logits},
+                    {A, D, topk_idx, topk_w}) != SWIMBA_OK)
+        return SWIMBA_ERR_ALIGNMENT;
     char *base = (char *)workspace;
     Ws ws;
     swimba_ws_layout lo;
@@ -531,6 +567,9 @@ static swimba_status expert_proj_body(const swimba_dims *dims, int32_t d_model, 
     const int64_t T = (int64_t)dims->batch * dims->seqlen;
     if (T == 0) return SWIMBA_OK;
     if (!u || !W_B || !W_C || !router_logits || !B_experts || !C_experts) return SWIMBA_ERR_NULL;
+    if (check_align(dims->io_dtype, {u, W_B, W_C, B_experts, C_experts}, {router_logits}, {topk_idx, topk_w}) !=
+        SWIMBA_OK)
+        return SWIMBA_ERR_ALIGNMENT;
     char *base = (char *)workspace;
     int32_t *idx = (int32_t *)(base + pl.idx);
     float *w = (float *)(base + pl.w);
@@ -622,6 +661,8 @@ swimba_status swimba_mixer_fwd_selected(const swimba_dims *dims, const void *x, 
     if (st != SWIMBA_OK) return st;
     const int64_t T = (int64_t)dims->batch * dims->seqlen;
     if (T > 0 && (!x || !dt || !A || !B_sel || !C_sel || !topk_w || !y)) return SWIMBA_ERR_NULL;
+    if (check_align(dims->io_dtype, {x, B_sel, C_sel, y, h0, h_final}, {dt}, {A, D, topk_w}) != SWIMBA_OK)
+        return SWIMBA_ERR_ALIGNMENT;
     return mixer_selected_core(dims, x, dt, A, D, B_sel, C_sel, topk_w, h0, y, h_final, ws,
                                (hipStream_t)hip_stream);
 }
@@ -674,6 +715,9 @@ swimba_status swimba_mixer_fwd_proj(const swimba_dims *dims, int32_t d_model, co
     if (st != SWIMBA_OK) return st;
     const int64_t T = (int64_t)dims->batch * dims->seqlen;
     if (T > 0 && (!u || !W_B || !W_C || !x || !dt || !A || !router_logits || !y)) return SWIMBA_ERR_NULL;
+    if (check_align(dims->io_dtype, {u, W_B, W_C, x, y, h0, h_final}, {dt, router_logits},
+                    {A, D, topk_idx, topk_w}) != SWIMBA_OK)
+        return SWIMBA_ERR_ALIGNMENT;
     hipStream_t stream = (hipStream_t)hip_stream;
     void *bsel = base + ml.bsel, *csel = base + ml.csel;
     if (T > 0) {
@@ -716,6 +760,9 @@ swimba_status swimba_step(const swimba_dims *dims, const float *state_in, float 
         return SWIMBA_ERR_WORKSPACE;
     if (!state_in || !state_out || !x || !dt || !A || !B_experts || !C_experts || !router_logits || !y)
         return SWIMBA_ERR_NULL;
+    if (check_align(dims->io_dtype, {state_in, state_out, x, B_experts, C_experts, y}, {dt, router_logits},
+                    {A, D, topk_idx}) != SWIMBA_OK)
+        return SWIMBA_ERR_ALIGNMENT;
     return launch_step(make_shape(dims), dims->io_dtype, state_in, state_out, x, dt, A, D, B_experts,
                        C_experts, router_logits, y, topk_idx, (float *)workspace,
                        (hipStream_t)hip_stream);
@@ -743,6 +790,9 @@ swimba_status swimba_step_multi(const swimba_dims *dims, const float *state_in, 
         return SWIMBA_ERR_WORKSPACE;
     if (!state_in || !state_out || !x || !dt || !A || !B_experts || !C_experts || !router_logits || !y)
         return SWIMBA_ERR_NULL;
+    if (check_align(dims->io_dtype, {state_in, state_out, x, B_experts, C_experts, y}, {dt, router_logits},
+                    {A, D, topk_idx}) != SWIMBA_OK)
+        return SWIMBA_ERR_ALIGNMENT;
     return launch_step_multi(make_shape(dims), dims->io_dtype, state_in, state_out, x, dt, A, D, B_experts,
                              C_experts, router_logits, y, topk_idx, (float *)workspace,
                              (hipStream_t)hip_stream);
@@ -758,6 +808,7 @@ const char *swimba_status_string(swimba_status s)
     case SWIMBA_ERR_UNSUPPORTED: return "problem outside the kernels' limits";
     case SWIMBA_ERR_WORKSPACE: return "workspace missing, misaligned or too small";
     case SWIMBA_ERR_HIP: return "HIP runtime error";
+    case SWIMBA_ERR_ALIGNMENT: return "a tensor pointer is not aligned as the header requires";
     }
     return "unknown status";
 }

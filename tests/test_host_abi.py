@@ -96,6 +96,33 @@ def test_null_and_workspace_errors_enqueue_nothing():
     assert lib.swimba_last_hip_error() == 0
 
 
+def test_misaligned_pointers_are_refused_on_the_host():
+    """Pointer values only (never dereferenced: a refused call enqueues nothing).  Large tensors
+    need 16 bytes, per-token and per-head tensors the alignment of their elements."""
+    lib = sw._load()
+    d = dims()
+    ok = [0x10000 * (i + 1) for i in range(12)]    # x dt A D Be Ce logits h0 y h_final topk_idx topk_w
+    ws, wsb = 0x4000000, 1 << 30
+    for pos, off in [(0, 8), (4, 4), (5, 2), (8, 8), (7, 4), (9, 12),      # 16-byte tensors
+                     (1, 2), (6, 1), (2, 2), (10, 2), (11, 1)]:            # element alignment (fp32 io: 4 bytes)
+        args = list(ok)
+        args[pos] += off
+        assert lib.swimba_mixer_fwd(ctypes.byref(d), *args, ws, wsb, None) == 7, (pos, off)
+    # bf16 io: dt and logits need 2 bytes only -> refused at 1, and the big tensors still need 16
+    db = dims(io_dtype=1)
+    args = list(ok); args[1] += 1
+    assert lib.swimba_mixer_fwd(ctypes.byref(db), *args, ws, wsb, None) == 7
+    args = list(ok); args[0] += 2
+    assert lib.swimba_mixer_fwd(ctypes.byref(db), *args, ws, wsb, None) == 7
+    # decode step and router
+    d1 = dims(seqlen=1)
+    sargs = [0x10000 * (i + 1) for i in range(11)]  # state_in state_out x dt A D Be Ce logits y topk_idx
+    sargs[0] += 4
+    assert lib.swimba_step(ctypes.byref(d1), *sargs, ws, 1 << 20, None) == 7
+    assert lib.swimba_router_topk(10, 4, 2, 0, 0x10002, 0x20000, 0x30000, None) == 7
+    assert lib.swimba_status_string(7).decode().startswith("a tensor pointer is not aligned")
+
+
 def test_binding_refuses_cpu_tensors():
     import torch
     x = torch.zeros(1, 4, 2, 16)
