@@ -8,7 +8,7 @@
 //
 // Three launches: clear the per-expert counters; route every token and append the entry
 // t*k + r to the list of its r-th expert (LDS counters per block, one global atomic per block
-// and expert); a grouped GEMM over (expert, 64-entry tile of its list, 256 output columns).
+// and expert); a grouped GEMM over (share of an expert's list, 256 output columns).
 // The GEMM is a dense contraction, so it runs on v_mfma_f32_32x32x16_bf16.  Both operands
 // are stored with the contraction index d contiguous (weights as (out, in), like a linear
 // layer), which is the 8-consecutive-k operand layout.  The product is computed transposed,
@@ -23,7 +23,7 @@ typedef __attribute__((ext_vector_type(2))) __bf16 pj_bf16x2_t;
 typedef __attribute__((ext_vector_type(2))) float pj_f32x2_t;
 typedef __attribute__((ext_vector_type(16))) float pj_f32x16_t;
 
-constexpr int PJ_COLS = 256;   // output columns per workgroup: 4 waves x 64
+constexpr int PJ_COLS = 256;   // output columns per workgroup: 4 column groups of 64
 
 __global__ void proj_clear_kernel(int32_t *counts, int E)
 {
