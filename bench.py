@@ -246,6 +246,27 @@ def main() -> int:
                   "us_per_step": round(ms * 1e3, 2), "steps": S, "tokens_per_s": round(wd.batch / ms * 1e3, 1),
                   "bound": "hbm", "achieved": round(dbytes / ms / 1e6, 1), "peak": PEAK_HBM_GBS, "unit": "GB/s",
                   "frac": round(dbytes / ms / 1e6 / PEAK_HBM_GBS, 4), "state_buffers_rotated": 4}
+        # the same step with other router / group settings: G = 8 B/C groups (the long-sequence
+        # layer's grouping), and 4 experts with top-1 routing (the paper's large model); random
+        # device-side inputs of the same distributions, same state buffers
+        variants = {}
+        for vname, (vG, vE, vk) in {"G8_E8_top2": (8, 8, 2), "G1_E4_top1": (1, 4, 1)}.items():
+            gen = torch.Generator(device=dev)
+            gen.manual_seed(69384 + vG * 100 + vE)
+            vB = (torch.randn((wd.batch, vE, vG, wd.dstate), generator=gen, device=dev) / wd.dstate ** 0.5).to(io)
+            vC = (torch.randn((wd.batch, vE, vG, wd.dstate), generator=gen, device=dev) / wd.dstate ** 0.5).to(io)
+            vg = torch.randn((wd.batch, vE), generator=gen, device=dev).to(io)
+            vws = torch.empty(sw.swimba_step_workspace_bytes(
+                sw.make_dims(wd.batch, 1, wd.nheads, wd.headdim, wd.dstate, vG, vE, vk, 0, io)),
+                dtype=torch.uint8, device=dev)
+
+            def vstep(i):
+                sw.swimba_step(states[i % 4], xs[i % 8], dts[i % 8], dd["A"], dd["D"], vB, vC, vg, vk, y=yd, workspace=vws)
+
+            time_loop(vstep, 8)
+            vms = time_loop(vstep, S)
+            variants[vname] = {"us_per_step": round(vms * 1e3, 2), "frac": round(dbytes / vms / 1e6 / PEAK_HBM_GBS, 4)}
+        decode["variants"] = variants
         # several tokens per call (speculative / short-chunk decoding): same state bytes per call
         multi = {}
         for Lm in (4, 8):

@@ -184,7 +184,9 @@ def test_empty_inputs():
 
 @pytest.mark.parametrize("cfg", [(3, 4, 16, 16, 1, 4, 2, "f32"), (2, 6, 24, 40, 3, 5, 5, "f32"),
                                  (2, 4, 64, 128, 2, 8, 2, "bf16"), (2, 2, 48, 128, 1, 8, 1, "f32"),
-                                 (1, 2, 64, 128, 1, 8, 2, "f32")],
+                                 (1, 2, 64, 128, 1, 8, 2, "f32"),
+                                 (3, 8, 64, 128, 1, 4, 1, "bf16"),      # 4 experts, top-1 (the paper's large model)
+                                 (2, 16, 64, 128, 8, 8, 2, "bf16")],    # 8 B/C groups
                          ids=lambda c: "B%dH%dP%dN%dG%dE%dk%d%s" % c)
 def test_step_matches_oracle_over_a_few_tokens(cfg):
     B, H, P, N, G, E, k, io = cfg
