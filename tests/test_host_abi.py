@@ -123,6 +123,52 @@ def test_misaligned_pointers_are_refused_on_the_host():
     assert lib.swimba_status_string(7).decode().startswith("a tensor pointer is not aligned")
 
 
+def test_later_entry_points_validate_on_the_host():
+    """Separated, expert-X, projection, selected-stream and multi-token entry points: invalid dims,
+    missing workspace, NULL and misaligned pointers are all refused before anything is enqueued."""
+    lib = sw._load()
+    d = dims()
+    big = 1 << 30
+    ws = 0x4000000
+    p = [0x10000 * (i + 1) for i in range(16)]
+    # workspace queries: positive for valid dims, 0 for invalid ones
+    for q in (sw.swimba_separated_workspace_bytes, sw.swimba_mixer_xe_workspace_bytes):
+        assert q(d) >= sw.swimba_mixer_workspace_bytes(d) and q(dims(top_k=9)) == 0
+    assert sw.swimba_expert_proj_workspace_bytes(d, 64) > 0 and sw.swimba_expert_proj_workspace_bytes(d, 0) == 0
+    assert sw.swimba_mixer_proj_workspace_bytes(d, 64) > sw.swimba_mixer_workspace_bytes(d)
+    assert sw.swimba_mixer_proj_workspace_bytes(dims(chunk=0), 64) == 0
+    # separated: (dims, x dt A D Be Ce logits y idx w, ws, bytes, stream)
+    assert lib.swimba_separated_fwd(ctypes.byref(dims(ngroups=3)), *p[:10], ws, big, None) == 2
+    assert lib.swimba_separated_fwd(ctypes.byref(d), *p[:10], None, 0, None) == 5
+    assert lib.swimba_separated_fwd(ctypes.byref(d), None, *p[1:10], ws, big, None) == 1
+    assert lib.swimba_separated_fwd(ctypes.byref(d), p[0] + 8, *p[1:10], ws, big, None) == 7
+    # expert-X: (dims, xe dt A D Be Ce logits h0 y h_final idx w, ws, bytes, stream)
+    assert lib.swimba_mixer_fwd_xe(ctypes.byref(d), *p[:12], ws, 16, None) == 5
+    assert lib.swimba_mixer_fwd_xe(ctypes.byref(d), *p[:5], None, *p[6:12], ws, big, None) == 1
+    assert lib.swimba_mixer_fwd_xe(ctypes.byref(d), *p[:8], p[8] + 4, *p[9:12], ws, big, None) == 7
+    # projection, dense and per selected slot: (dims, d_model, u WB WC logits Bo Co idx w, ws, bytes, stream)
+    for fn in (lib.swimba_expert_proj, lib.swimba_expert_proj_selected):
+        assert fn(ctypes.byref(d), 0, *p[:8], ws, big, None) == 2
+        assert fn(ctypes.byref(d), 64, *p[:8], ws + 64, big, None) == 5
+        assert fn(ctypes.byref(d), 64, *p[:2], None, *p[3:8], ws, big, None) == 1
+        assert fn(ctypes.byref(d), 64, *p[:4], p[4] + 2, *p[5:8], ws, big, None) == 7
+    # forward on selected streams: (dims, x dt A D Bsel Csel w h0 y h_final, ws, bytes, stream)
+    assert lib.swimba_mixer_fwd_selected(ctypes.byref(d), *p[:10], None, 0, None) == 5
+    assert lib.swimba_mixer_fwd_selected(ctypes.byref(d), *p[:6], None, *p[7:10], ws, big, None) == 1
+    assert lib.swimba_mixer_fwd_selected(ctypes.byref(d), *p[:6], p[6] + 2, *p[7:10], ws, big, None) == 7
+    # projection + forward: (dims, d_model, u WB WC x dt A D logits h0 y h_final idx w, ws, bytes, stream)
+    assert lib.swimba_mixer_fwd_proj(ctypes.byref(d), 64, *p[:13], ws, 1024, None) == 5
+    assert lib.swimba_mixer_fwd_proj(ctypes.byref(d), 64, None, *p[1:13], ws, big, None) == 1
+    assert lib.swimba_mixer_fwd_proj(ctypes.byref(d), 64, *p[:3], p[3] + 8, *p[4:13], ws, big, None) == 7
+    assert lib.swimba_mixer_fwd_proj(ctypes.byref(dims(headdim=128, dstate=128)), 64, *p[:13], ws, big, None) == 4
+    # several decode tokens per call: at most 64, at least 1
+    assert sw.swimba_step_multi_workspace_bytes(dims(seqlen=65)) == 0
+    assert lib.swimba_step_multi(ctypes.byref(dims(seqlen=65)), *p[:11], ws, big, None) == 4
+    assert lib.swimba_step_multi(ctypes.byref(dims(seqlen=4)), *p[:11], None, 0, None) == 5
+    assert lib.swimba_step_multi(ctypes.byref(dims(seqlen=4)), *p[:2], None, *p[3:11], ws, big, None) == 1
+    assert lib.swimba_step_multi(ctypes.byref(dims(seqlen=4)), *p[:9], p[9] + 8, p[10], ws, big, None) == 7
+
+
 def test_binding_refuses_cpu_tensors():
     import torch
     x = torch.zeros(1, 4, 2, 16)
