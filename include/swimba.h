@@ -195,8 +195,10 @@ swimba_status swimba_stage_output(const swimba_dims *dims, const void *x, const 
  *   h_t^(e) = exp(dt_t A_h) h_{t-1}^(e) + dt_t B_t^(e) x_t^T,
  *   y_t = sum_{e in K_t} pi_{t,e} C_t^(e) . h_t^(e) + D_h x_t          (zero initial states).
  * Same tensors as swimba_mixer_fwd (no h0 / h_final).  It is E plain SSM passes through
- * the mixer's own kernels (one per expert) plus an fp32 accumulation of the per-expert
- * outputs: a measure of what replicating the recurrence costs, not a tuned path.
+ * the mixer's own kernels (one per expert); every pass adds its output to y in the io dtype
+ * (outside a token's active set a pass adds exact zeros, so a token's y sees top_k roundings;
+ * the skip term enters with the last pass): a measure of what replicating the recurrence
+ * costs, not a tuned path.
  *   workspace >= swimba_separated_workspace_bytes(dims), 256-byte aligned.
  */
 size_t swimba_separated_workspace_bytes(const swimba_dims *dims);

@@ -305,19 +305,15 @@ swimba_status swimba_mixer_fwd(const swimba_dims *dims, const void *x, const voi
 
 // ---- separated-SSM contrast ---------------------------------------------------------------
 struct SepLayout {
-    size_t mixer, y_e, acc, idx1, wb1, wc1, total;
+    size_t mixer, idx1, wb1, wc1, total;
 };
 static void sep_layout_of(const swimba_dims *d, SepLayout *o)
 {
     swimba_ws_layout lo;
     layout_of(d, &lo);
     const size_t T = (size_t)d->batch * d->seqlen;
-    const size_t n = T * d->nheads * d->headdim;
-    const size_t io = d->io_dtype == SWIMBA_BF16 ? 2 : 4;
     size_t off = 0;
     o->mixer = off; off = align_up(off + lo.total, 256);
-    o->y_e = off;   off = align_up(off + n * io, 256);
-    o->acc = off;   off = align_up(off + n * sizeof(float), 256);
     o->idx1 = off;  off = align_up(off + T * sizeof(int32_t), 256);
     o->wb1 = off;   off = align_up(off + T * sizeof(float), 256);
     o->wc1 = off;   off = align_up(off + T * sizeof(float), 256);
@@ -355,14 +351,11 @@ swimba_status swimba_separated_fwd(const swimba_dims *dims, const void *x, const
     layout_of(dims, &lo);
     st = carve(dims, base + sl.mixer, lo.total, &ws);
     if (st != SWIMBA_OK) return st;
-    void *y_e = base + sl.y_e;
-    float *acc = (float *)(base + sl.acc);
     int32_t *idx1 = (int32_t *)(base + sl.idx1);
     float *wb1 = (float *)(base + sl.wb1), *wc1 = (float *)(base + sl.wc1);
     hipStream_t stream = (hipStream_t)hip_stream;
     const Shape s = make_shape(dims);
     const bool mf = use_mfma_path(dims);
-    const int64_t n = T * dims->nheads * dims->headdim;
     Shape s1 = s;
     s1.K = 1;   // one expert at a time on the fp32 kernels
     if (!mf) {
@@ -371,7 +364,13 @@ swimba_status swimba_separated_fwd(const swimba_dims *dims, const void *x, const
         st = launch_cumsum(s, dims->io_dtype, dt, A, ws.cs, stream);
         if (st != SWIMBA_OK) return st;
     }
+    // Expert e's output is added to y by its own output kernel (in the io dtype).  A token's
+    // readout weight is zero outside its active set, where the pass adds exact zeros, so a
+    // token's y sees k roundings, not E; the skip term D x enters with the last pass, after the
+    // small state terms have been summed.
     for (int e = 0; e < s.E; ++e) {
+        const float *D_e = (e == s.E - 1) ? D : nullptr;
+        const int acc_e = e > 0;
         if (mf) {
             st = launch_mix_rows_mfma(s, B_experts, C_experts, router_logits, ws.idx, ws.w, ws.cmix,
                                       ws.bmix_frag, ws.bmix_t8, e, -1, nullptr, stream);
@@ -380,7 +379,7 @@ swimba_status swimba_separated_fwd(const swimba_dims *dims, const void *x, const
             if (st != SWIMBA_OK) return st;
             st = launch_scan_cb_mfma(s, nullptr, nullptr, ws.states_lp, ws.cs, ws.cmix, ws.bmix_frag, ws.cb, stream);
             if (st != SWIMBA_OK) return st;
-            st = launch_output_mfma(s, x, dt, nullptr, ws.cmix, ws.cb, ws.cs, ws.states_lp, y_e, nullptr, 0, 0,
+            st = launch_output_mfma(s, x, dt, D_e, ws.cmix, ws.cb, ws.cs, ws.states_lp, y, nullptr, 0, acc_e,
                                     stream);
             if (st != SWIMBA_OK) return st;
         } else {
@@ -391,15 +390,11 @@ swimba_status swimba_separated_fwd(const swimba_dims *dims, const void *x, const
             if (st != SWIMBA_OK) return st;
             st = launch_state_scan(s1, nullptr, nullptr, ws.states, nullptr, ws.cs, stream);
             if (st != SWIMBA_OK) return st;
-            st = launch_output_generic(s1, dims->io_dtype, x, dt, nullptr, B_experts, C_experts, idx1,
-                                       wb1, wc1, ws.cs, ws.states, y_e, nullptr, 0, 0, stream);
+            st = launch_output_generic(s1, dims->io_dtype, x, dt, D_e, B_experts, C_experts, idx1,
+                                       wb1, wc1, ws.cs, ws.states, y, nullptr, 0, acc_e, stream);
             if (st != SWIMBA_OK) return st;
         }
-        st = launch_sep_accumulate(dims->io_dtype, n, y_e, acc, e == 0, stream);
-        if (st != SWIMBA_OK) return st;
     }
-    st = launch_sep_finish(s, dims->io_dtype, acc, x, D, y, stream);
-    if (st != SWIMBA_OK) return st;
     if (topk_idx || topk_w) {
         const size_t cnt = (size_t)T * dims->top_k;
         hipError_t e = hipSuccess;

@@ -94,8 +94,6 @@ swimba_status launch_sep_prepare(const Shape &s, int e, const int32_t *idx, cons
                                  int32_t *idx1, float *wb1, float *wc1, hipStream_t st);
 swimba_status launch_sep_accumulate(int io_dtype, int64_t n, const void *y_e, float *acc, int first,
                                     hipStream_t st);
-swimba_status launch_sep_finish(const Shape &s, int io_dtype, const float *acc, const void *x,
-                                const float *D, void *y, hipStream_t st);
 swimba_status launch_chunk_state_mfma(const Shape &s, const void *x, const void *dt, const float *A,
                                       const void *bmix_t8, float *cs, void *states_lp, hipStream_t st);
 swimba_status launch_scan_cb_mfma(const Shape &s, const float *h0, float *h_final, void *states_lp,

@@ -2,8 +2,9 @@
 //   h_t^(e) = exp(dt_t A) h_{t-1}^(e) + dt_t B_t^(e) x_t^T  for every expert e,
 //   y_t = sum_{e in K_t} pi_{t,e} C_t^(e) . h_t^(e) + D x_t.
 // Each expert is one plain SSM pass through the mixer's own kernels with the streams
-// Bmix = B^(e), Cmix = gate_e * C^(e); these kernels build the per-expert routing
-// tables for the fp32 kernels and add the per-expert outputs up in fp32.
+// Bmix = B^(e), Cmix = gate_e * C^(e), whose output kernel adds to y; these kernels build the
+// per-expert routing tables of the fp32 kernels and add fp32 buffers (final states of the
+// passes of the forward with per-expert inputs).
 #include "common.hpp"
 
 namespace swimba {
@@ -33,17 +34,6 @@ sep_accumulate_kernel(const T *__restrict__ y_e, float *__restrict__ acc, int64_
     acc[i] = first ? v : acc[i] + v;
 }
 
-template <typename T>
-__global__ void __launch_bounds__(256)
-sep_finish_kernel(const float *__restrict__ acc, const T *__restrict__ x, const float *__restrict__ D,
-                  T *__restrict__ y, int64_t n, int H, int P)
-{
-    const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= n) return;
-    const int h = (int)((i / P) % H);
-    y[i] = from_float<T>(acc[i] + (D ? D[h] * to_float(x[i]) : 0.f));
-}
-
 swimba_status launch_sep_prepare(const Shape &s, int e, const int32_t *idx, const float *w,
                                  int32_t *idx1, float *wb1, float *wc1, hipStream_t st)
 {
@@ -64,22 +54,6 @@ swimba_status launch_sep_accumulate(int io_dtype, int64_t n, const void *y_e, fl
         hipLaunchKernelGGL(sep_accumulate_kernel<bf16>, grid, dim3(256), 0, st, (const bf16 *)y_e, acc, n, first);
     else
         hipLaunchKernelGGL(sep_accumulate_kernel<float>, grid, dim3(256), 0, st, (const float *)y_e, acc, n, first);
-    SWIMBA_CHECK_LAUNCH();
-    return SWIMBA_OK;
-}
-
-swimba_status launch_sep_finish(const Shape &s, int io_dtype, const float *acc, const void *x,
-                                const float *D, void *y, hipStream_t st)
-{
-    const int64_t n = (int64_t)s.B * s.L * s.H * s.P;
-    if (n == 0) return SWIMBA_OK;
-    const dim3 grid((unsigned)((n + 255) / 256));
-    if (io_dtype == SWIMBA_BF16)
-        hipLaunchKernelGGL(sep_finish_kernel<bf16>, grid, dim3(256), 0, st, acc, (const bf16 *)x, D, (bf16 *)y,
-                           n, s.H, s.P);
-    else
-        hipLaunchKernelGGL(sep_finish_kernel<float>, grid, dim3(256), 0, st, acc, (const float *)x, D,
-                           (float *)y, n, s.H, s.P);
     SWIMBA_CHECK_LAUNCH();
     return SWIMBA_OK;
 }
