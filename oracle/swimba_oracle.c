@@ -26,6 +26,8 @@
  *               + D_h x_t                       (separated-SSM equation)
  *   projection  B_t^(e), C_t^(e) for the active experts only, as expert-specific
  *               linear maps of the token features (swimba_oracle_expert_proj)
+ *   router map  g_t = W_g u_t, the routing logits as a linear function of the
+ *               token features (swimba_oracle_router_linear)
  *   expert x    the mixed state update in its full form, with one input stream
  *               per expert: h_t = exp(dt_t A_h) h_{t-1}
  *               + dt_t sum_{e in K_t} pi_{t,e} x_t^(e) (x) B_t^(e); same readout
@@ -51,7 +53,8 @@
  * expressivity theorem's proof, the geometric-series closed form, the
  * quadratic masked form Y = M X on tiny inputs, the E=1 / one-hot / identical
  * expert reductions to a plain selective SSM, linearity in x, the
- * separated-vs-mixed equality regime, the BIBO bound, brute-force top-k.
+ * separated-vs-mixed equality regime, the BIBO bound, brute-force top-k; the
+ * two linear maps against an independent library contraction and hand values.
  * Nothing here is "parity unpinned".
  */
 #include <math.h>
@@ -269,6 +272,27 @@ int swimba_oracle_expert_proj(int64_t T, int64_t Dm, int64_t E, int64_t k, int64
                 Be[(t * E + e) * GN + c] = sb;
                 Ce[(t * E + e) * GN + c] = sc;
             }
+        }
+    }
+    return 0;
+}
+
+/*
+ * Routing logits as a linear function of the token features (paper: the expressivity
+ * theorem assumes g a linear function of the features; the Swimba layer's router selects
+ * among the in-projection experts from the token's hidden state):
+ *   g_t[e] = sum_d Wg[e][d] u_t[d]        u (T,Dm)  Wg (E,Dm)  ->  g (T,E) double
+ * No bias, no temperature.
+ */
+int swimba_oracle_router_linear(int64_t T, int64_t Dm, int64_t E, const float *u, const float *Wg, double *g)
+{
+    if (T < 0 || Dm < 1 || E < 1) return 1;
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < T; ++t) {
+        for (int64_t e = 0; e < E; ++e) {
+            double sum = 0.0;
+            for (int64_t d = 0; d < Dm; ++d) sum += (double)Wg[e * Dm + d] * (double)u[t * Dm + d];
+            g[t * E + e] = sum;
         }
     }
     return 0;

@@ -162,6 +162,20 @@ def expert_proj(u, W_B, W_C, router_logits, top_k: int, fill=np.nan):
     return {"B_experts": Be, "C_experts": Ce, "topk_idx": idx, "topk_w": w}
 
 
+def router_linear(u, W_g) -> np.ndarray:
+    """Routing logits g = W_g u for every token: u (B,L,Dm), W_g (E,Dm) -> (B,L,E) float64."""
+    u = _f32(u); Wg = _f32(W_g)
+    B, L, Dm = u.shape
+    E, Dm2 = Wg.shape
+    assert Dm2 == Dm
+    g = np.zeros((B, L, E), dtype=np.float64)
+    i64 = ctypes.c_int64
+    rc = _load().swimba_oracle_router_linear(i64(B * L), i64(Dm), i64(E), _p(u), _p(Wg), _p(g))
+    if rc:
+        raise ValueError("oracle router_linear: bad arguments")
+    return g
+
+
 def separated_fwd(x, dt, A, D, B_experts, C_experts, router_logits, top_k: int) -> Dict[str, np.ndarray]:
     """MoE of separated SSMs (one trajectory per expert, zero initial states).
     Returns y (B,L,H,P), h_final (B,E,H,P,N), topk_idx, topk_w."""

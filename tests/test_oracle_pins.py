@@ -364,6 +364,39 @@ def test_expert_proj_feeds_the_mixer_like_a_dense_projection():
     np.testing.assert_allclose(a["y"], b["y"], rtol=1e-12, atol=1e-14)
 
 
+def test_router_linear_hand_values_and_library_contraction():
+    # hand values: u = (1, 2), W_g = [[3, 4], [5, 6], [-1, 0.5]] -> g = (11, 17, 0)
+    g = orc.router_linear(np.array([[[1.0, 2.0]]], dtype=np.float32),
+                          np.array([[3.0, 4.0], [5.0, 6.0], [-1.0, 0.5]], dtype=np.float32))
+    np.testing.assert_array_equal(g, np.array([[[11.0, 17.0, 0.0]]]))
+    # against an independent library contraction, odd sizes; rows and columns not interchangeable
+    rng = np.random.default_rng(41)
+    u = rng.standard_normal((2, 7, 13)).astype(np.float32)
+    W = rng.standard_normal((5, 13)).astype(np.float32)
+    g = orc.router_linear(u, W)
+    np.testing.assert_allclose(g, np.einsum("bld,ed->ble", u.astype(np.float64), W.astype(np.float64)),
+                               rtol=1e-13, atol=1e-13)
+    # a one-hot feature picks out a column of W_g; a one-hot row of W_g picks out a feature
+    e3 = np.zeros((1, 1, 13), dtype=np.float32); e3[0, 0, 3] = 1.0
+    np.testing.assert_array_equal(orc.router_linear(e3, W)[0, 0], W[:, 3].astype(np.float64))
+    W1 = np.zeros((5, 13), dtype=np.float32); W1[2, 9] = 1.0
+    got = orc.router_linear(u, W1)
+    np.testing.assert_array_equal(got[..., 2], u[..., 9].astype(np.float64))
+    assert np.count_nonzero(np.delete(got, 2, axis=-1)) == 0
+
+
+def test_router_linear_then_router_reproduces_the_sigmoid_example():
+    """One-step example of the expressivity theorem's proof with the logits made by the linear
+    router from a scalar feature: W_g = (0, 1)^T, u = g gives logits (0, g), so y = sigma(g)."""
+    for gval in (-3.0, -0.5, 0.0, 0.25, 2.0):
+        logits = orc.router_linear(np.array([[[gval]]], dtype=np.float32), np.array([[0.0], [1.0]], dtype=np.float32))
+        p = dict(x=np.ones((1, 1, 1, 1), np.float32), dt=np.ones((1, 1, 1), np.float32), A=-np.ones(1, np.float32),
+                 D=None, B_experts=np.array([0.0, 1.0], np.float32).reshape(1, 1, 2, 1, 1),
+                 C_experts=np.ones((1, 1, 2, 1, 1), np.float32), router_logits=logits.astype(np.float32))
+        y = call(p, 2)["y"][0, 0, 0, 0]
+        assert abs(y - 1.0 / (1.0 + np.exp(-np.float64(np.float32(gval))))) < 1e-15
+
+
 # --- P7: separated vs mixed (Theorem 4) -------------------------------------------------------
 
 def test_separated_equals_mixed_in_equality_regime():
