@@ -333,6 +333,13 @@ def main() -> int:
                     "ms": round(ms, 5), "mfma_TFLOPs": round(pflops / ms / 1e9, 1),
                     "mfma_frac": round(pflops / ms / 1e9 / PEAK_BF16_TFLOPS, 4),
                     "hbm_GBps": round(pbytes / ms / 1e6, 1), "hbm_frac": round(pbytes / ms / 1e6 / PEAK_HBM_GBS, 4)}
+        # the router's linear map on the same features
+        Wg = (torch.randn((E, Dm), generator=gen, device=dev) / Dm ** 0.5).to(io)
+        lg = torch.empty((w.batch, w.seqlen, E), dtype=io, device=dev)
+        time_loop(lambda i: sw.swimba_router_linear(us[i % 3], Wg, lg), 3)
+        rl_ms = time_loop(lambda i: sw.swimba_router_linear(us[i % 3], Wg, lg), K)
+        proj_res["router_linear"] = {"ms": round(rl_ms, 5),
+                                     "hbm_GBps": round(T * (Dm * 2 + E * 2) / rl_ms / 1e6, 1)}
         # token features -> y in one call, selected streams only (no tensor with an expert axis),
         # against projection into the dense layout followed by the mixer forward
         fws = torch.empty(sw.swimba_mixer_proj_workspace_bytes(dims, Dm), dtype=torch.uint8, device=dev)

@@ -227,6 +227,20 @@ swimba_status swimba_mixer_fwd_xe(const swimba_dims *dims, const void *x_experts
                                   void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * Routing logits as a linear function of the token features (paper: the expressivity theorem
+ * takes g a linear function of the features; the Swimba layer's router chooses among the
+ * in-projection experts from the token's hidden state):
+ *   g_t[e] = sum_d W_g[e][d] u_t[d]                    no bias, fp32 accumulation
+ *   u (tokens, d_model) io [in]   W_g (nexperts, d_model) io [in]   router_logits (tokens, nexperts) io [out]
+ * The logits are rounded to the io dtype when stored; routing (swimba_router_topk, the mixer,
+ * the projection) is defined on those stored values.  With d_model % 8 != 0 and bf16 io the rows
+ * of u and W_g are not 16-byte aligned past the first: only the base pointers are checked, the
+ * kernel then reads element by element.
+ */
+swimba_status swimba_router_linear(int64_t tokens, int32_t d_model, int32_t nexperts, int32_t io_dtype,
+                                   const void *u, const void *W_g, void *router_logits, void *hip_stream);
+
+/*
  * Routed expert in-projection, the step upstream of the mixer (paper, MoE-parameterized
  * SSM: the expert streams are expert-specific linear projections of the token features;
  * only the active set K_t enters the mix).  For every token t and every e in K_t:

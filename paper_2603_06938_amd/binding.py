@@ -85,6 +85,8 @@ def _load():
         lib.swimba_expert_proj.restype = i32
         lib.swimba_expert_proj.argtypes = [dp, i32] + [vp] * 8 + [vp, sz, vp]
         lib.swimba_mixer_xe_workspace_bytes.restype = sz
+        lib.swimba_router_linear.restype = i32
+        lib.swimba_router_linear.argtypes = [i64, i32, i32, i32, vp, vp, vp, vp]
         lib.swimba_expert_proj_selected.restype = i32
         lib.swimba_expert_proj_selected.argtypes = [dp, i32] + [vp] * 8 + [vp, sz, vp]
         lib.swimba_mixer_fwd_selected.restype = i32
@@ -236,6 +238,20 @@ def swimba_mixer_fwd(x, dt, A, D, B_experts, C_experts, router_logits, top_k: in
         _ptr(workspace, "workspace", torch.uint8), workspace.numel(), _stream())
     _check(st, "swimba_mixer_fwd")
     return MixerOut(y, h_final, topk_idx, topk_w)
+
+
+def swimba_router_linear(u, W_g, router_logits=None) -> torch.Tensor:
+    """u (..., Dm), W_g (E, Dm) -> routing logits (..., E) in the io dtype."""
+    Dm = u.shape[-1]
+    E = W_g.shape[0]
+    tokens = u.numel() // Dm if Dm else 0
+    if router_logits is None:
+        router_logits = torch.empty(tuple(u.shape[:-1]) + (E,), dtype=u.dtype, device=u.device)
+    st = _load().swimba_router_linear(tokens, Dm, E, _io_code(u), _ptr(u, "u"), _ptr(W_g, "W_g", u.dtype, (E, Dm)),
+                                      _ptr(router_logits, "router_logits", u.dtype, tuple(u.shape[:-1]) + (E,)),
+                                      _stream())
+    _check(st, "swimba_router_linear")
+    return router_logits
 
 
 def swimba_expert_proj_workspace_bytes(dims: swimba_dims, d_model: int) -> int:

@@ -153,6 +153,19 @@ swimba_status swimba_router_topk(int64_t tokens, int32_t nexperts, int32_t top_k
                          (hipStream_t)hip_stream);
 }
 
+swimba_status swimba_router_linear(int64_t tokens, int32_t d_model, int32_t nexperts, int32_t io_dtype,
+                                   const void *u, const void *W_g, void *router_logits, void *hip_stream)
+{
+    if (io_dtype != SWIMBA_F32 && io_dtype != SWIMBA_BF16) return SWIMBA_ERR_DTYPE;
+    if (tokens < 0 || d_model < 1 || nexperts < 1) return SWIMBA_ERR_SHAPE;
+    if (nexperts > SWIMBA_MAX_EXPERTS || d_model > 65536 || tokens > (1ll << 38)) return SWIMBA_ERR_UNSUPPORTED;
+    if (tokens == 0) return SWIMBA_OK;
+    if (!u || !W_g || !router_logits) return SWIMBA_ERR_NULL;
+    if (check_align(io_dtype, {u, W_g}, {router_logits}, {}) != SWIMBA_OK) return SWIMBA_ERR_ALIGNMENT;
+    return launch_router_linear(tokens, d_model, nexperts, io_dtype, u, W_g, router_logits,
+                                (hipStream_t)hip_stream);
+}
+
 swimba_status swimba_stage_router(const swimba_dims *dims, const void *router_logits,
                                   void *workspace, size_t workspace_bytes, void *hip_stream)
 {

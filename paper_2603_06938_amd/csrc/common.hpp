@@ -65,6 +65,8 @@ void set_last_hip_error(int e);
 // ---- kernel launchers (one per translation unit) ----------------------------------
 swimba_status launch_router(int64_t tokens, int E, int K, int io_dtype, const void *logits,
                             int32_t *idx, float *w, hipStream_t st);
+swimba_status launch_router_linear(int64_t tokens, int Dm, int E, int io_dtype, const void *u, const void *Wg,
+                                   void *logits, hipStream_t st);
 swimba_status launch_cumsum(const Shape &s, int io_dtype, const void *dt, const float *A, float *cs,
                             hipStream_t st);
 swimba_status launch_state_scan(const Shape &s, const float *h0, float *h_final, float *states,

@@ -64,6 +64,32 @@ def test_expert_proj_matches_oracle(cfg):
         assert l2 <= TOL[io] and linf <= TOL[io], (name, l2, linf)
 
 
+ROUTER_LINEAR_SHAPES = [
+    # B, L, Dm, E, io
+    (2, 37, 24, 4, "f32"), (1, 50, 33, 5, "f32"), (1, 3, 700, 256, "f32"),
+    (2, 40, 48, 4, "bf16"), (1, 130, 77, 8, "bf16"),          # 77 features: element-wise path
+    (2, 300, 768, 8, "bf16"), (1, 9, 1024, 16, "bf16"), (1, 1, 8, 1, "bf16"),
+]
+
+
+@pytest.mark.parametrize("cfg", ROUTER_LINEAR_SHAPES, ids=lambda c: "B%dL%dD%dE%d%s" % c)
+def test_router_linear_matches_oracle(cfg):
+    B, L, Dm, E, io = cfg
+    rng = np.random.default_rng(hash(cfg[:4]) % 100000)
+    rd = synth.round_to_bf16 if io == "bf16" else (lambda a: a)
+    u = rd(rng.standard_normal((B, L, Dm)).astype(np.float32))
+    Wg = rd((rng.standard_normal((E, Dm)) / np.sqrt(Dm)).astype(np.float32))
+    ref = orc.router_linear(u, Wg)
+    got = sw.swimba_router_linear(dev(u, io), dev(Wg, io))
+    torch.cuda.synchronize()
+    assert got.shape == (B, L, E) and got.dtype == IO[io]
+    g = host(got)
+    l2 = np.linalg.norm(g - ref) / np.linalg.norm(ref)
+    linf = np.abs(g - ref).max() / np.abs(ref).max()
+    print(cfg, "logits rel l2 %.3e linf %.3e" % (l2, linf), flush=True)
+    assert l2 <= TOL[io] and linf <= TOL[io], (l2, linf)
+
+
 def test_projection_then_mixer_end_to_end():
     """Token features -> routed projection -> mixer, all on the GPU, against the oracle chain
     (oracle projections are not rounded to bf16 in between)."""

@@ -161,6 +161,13 @@ def test_later_entry_points_validate_on_the_host():
     assert lib.swimba_mixer_fwd_proj(ctypes.byref(d), 64, None, *p[1:13], ws, big, None) == 1
     assert lib.swimba_mixer_fwd_proj(ctypes.byref(d), 64, *p[:3], p[3] + 8, *p[4:13], ws, big, None) == 7
     assert lib.swimba_mixer_fwd_proj(ctypes.byref(dims(headdim=128, dstate=128)), 64, *p[:13], ws, big, None) == 4
+    # router linear map: (tokens, d_model, nexperts, io_dtype, u, W_g, logits, stream)
+    assert lib.swimba_router_linear(10, 0, 4, 0, p[0], p[1], p[2], None) == 2
+    assert lib.swimba_router_linear(10, 16, 300, 0, p[0], p[1], p[2], None) == 4
+    assert lib.swimba_router_linear(10, 16, 4, 5, p[0], p[1], p[2], None) == 3
+    assert lib.swimba_router_linear(10, 16, 4, 0, p[0], None, p[2], None) == 1
+    assert lib.swimba_router_linear(10, 16, 4, 1, p[0] + 8, p[1], p[2], None) == 7
+    assert lib.swimba_router_linear(0, 16, 4, 1, None, None, None, None) == 0
     # several decode tokens per call: at most 64, at least 1
     assert sw.swimba_step_multi_workspace_bytes(dims(seqlen=65)) == 0
     assert lib.swimba_step_multi(ctypes.byref(dims(seqlen=65)), *p[:11], ws, big, None) == 4
