@@ -181,7 +181,7 @@ def main() -> int:
     T, H, P, N, G, E, k, Q = w.tokens, w.nheads, w.headdim, w.dstate, w.ngroups, w.nexperts, w.top_k, w.chunk
     nchunks = w.batch * ((w.seqlen + Q - 1) // Q)
     state_elems = nchunks * H * P * N
-    # algorithmic work per launch: (HBM bytes, MFMA flops); see DESIGN.md "Measurement"
+    # algorithmic work per launch: (HBM bytes, MFMA flops)
     NT = Q // 32
     cb_bytes = nchunks * G * (NT * (NT + 1) // 2) * 2048
     work = {
