@@ -128,9 +128,14 @@ output_generic_kernel(const T *__restrict__ x, const T *__restrict__ dt, const f
                       const float *__restrict__ skip_w, int skip_stride, int accumulate)
 {
     extern __shared__ float smem[];
-    float *sc = smem;                         // [GEN_TI][N] mixed C of the block's tokens
-    float *sb = sc + GEN_TI * s.N;            // [GEN_TI][N] mixed B of the current j tile
-    float *sx = sb + GEN_TI * s.N;            // [GEN_TI][P] dt_j * x_j of the current j tile
+    // rows of the two mixed tiles are padded by one float: the (i, j) dot products below read
+    // row ii of one and row jj of the other with the same n in every lane, and an unpadded
+    // power-of-two row length puts all those reads on one LDS bank (16-way conflicts: the kernel
+    // spent almost all of its time there)
+    const int NS = s.N + 1;
+    float *sc = smem;                         // [GEN_TI][NS] mixed C of the block's tokens
+    float *sb = sc + GEN_TI * NS;             // [GEN_TI][NS] mixed B of the current j tile
+    float *sx = sb + GEN_TI * NS;             // [GEN_TI][P] dt_j * x_j of the current j tile
     float *sm = sx + GEN_TI * s.P;            // [GEN_TI][GEN_TI] decay-masked C.B^T tile
     const int nib = (s.Q + GEN_TI - 1) / GEN_TI;
     const int ib = blockIdx.x % nib;
@@ -153,7 +158,7 @@ output_generic_kernel(const T *__restrict__ x, const T *__restrict__ dt, const f
             const int64_t bt = (int64_t)b * s.L + t;
             v = mix_elem(Ce + bt * s.E * s.G * s.N, idx + bt * s.K, wc + bt * s.K, s.K, s.G, s.N, g, n);
         }
-        sc[i] = v;
+        sc[ii * NS + n] = v;
     }
     __syncthreads();
 
@@ -168,7 +173,7 @@ output_generic_kernel(const T *__restrict__ x, const T *__restrict__ dt, const f
                 const int ii = o / s.P, p = o % s.P, q = i0 + ii;
                 if (q < s.Q) {
                     float a = 0.f;
-                    for (int n = 0; n < s.N; ++n) a += sc[ii * s.N + n] * Hc[p * s.N + n];
+                    for (int n = 0; n < s.N; ++n) a += sc[ii * NS + n] * Hc[p * s.N + n];
                     acc[r] = a * expf(csr[q]);
                 }
             }
@@ -185,7 +190,7 @@ output_generic_kernel(const T *__restrict__ x, const T *__restrict__ dt, const f
                 const int64_t bt = (int64_t)b * s.L + t;
                 v = mix_elem(Be + bt * s.E * s.G * s.N, idx + bt * s.K, w + bt * s.K, s.K, s.G, s.N, g, n);
             }
-            sb[i] = v;
+            sb[jj * NS + n] = v;
         }
         for (int i = tid; i < GEN_TI * s.P; i += GEN_THREADS) {
             const int jj = i / s.P, p = i % s.P, q = j0 + jj, t = c * s.Q + q;
@@ -203,7 +208,7 @@ output_generic_kernel(const T *__restrict__ x, const T *__restrict__ dt, const f
             float m = 0.f;
             if (qi < s.Q && qj <= qi) {
                 float dot = 0.f;
-                for (int n = 0; n < s.N; ++n) dot += sc[ii * s.N + n] * sb[jj * s.N + n];
+                for (int n = 0; n < s.N; ++n) dot += sc[ii * NS + n] * sb[jj * NS + n];
                 m = dot * expf(csr[qi] - csr[qj]);
             }
             sm[ii * GEN_TI + jj] = m;
@@ -251,7 +256,7 @@ swimba_status launch_output_generic(const Shape &s, int io_dtype, const void *x,
     const int nib = (s.Q + GEN_TI - 1) / GEN_TI;
     const int64_t blocks = (int64_t)s.B * s.nc * s.H * nib;
     if (blocks == 0) return SWIMBA_OK;
-    const size_t shm = sizeof(float) * (size_t)(2 * GEN_TI * s.N + GEN_TI * s.P + GEN_TI * GEN_TI);
+    const size_t shm = sizeof(float) * (size_t)(2 * GEN_TI * (s.N + 1) + GEN_TI * s.P + GEN_TI * GEN_TI);
     if (io_dtype == SWIMBA_BF16)
         hipLaunchKernelGGL(output_generic_kernel<bf16>, dim3((unsigned)blocks), dim3(GEN_THREADS), shm,
                            st, (const bf16 *)x, (const bf16 *)dt, D, (const bf16 *)Be,
