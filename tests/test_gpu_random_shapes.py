@@ -1,0 +1,85 @@
+"""Seeded random shapes through the bf16 MFMA path (P = 64, N = 128) and the projection in front
+of it: ragged lengths, every chunk size, group / head / expert / top-k combinations, with and
+without an initial state and a skip term.  Each case is checked element by element against the
+oracle like the fixed cases elsewhere; the point is coverage of combinations nobody wrote down."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import swimba_oracle as orc
+from paper_2603_06938_amd import binding as sw
+from paper_2603_06938_amd import synth
+from gpu_util import TOL, host, rel_errors, to_device
+
+pytestmark = pytest.mark.gpu
+
+
+def random_cases(n, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for i in range(n):
+        G = int(rng.choice([1, 1, 2, 4]))
+        H = G * int(rng.choice([1, 2, 3]))
+        Q = int(rng.choice([64, 128, 256]))
+        L = int(rng.integers(1, 3 * Q + 40))
+        B = int(rng.choice([1, 2, 3]))
+        E = int(rng.choice([1, 2, 3, 4, 8, 16, 33]))
+        k = int(rng.integers(1, min(E, 6) + 1))
+        cases.append((B, L, H, G, E, k, Q, bool(rng.integers(0, 2)), bool(rng.integers(0, 2)), 1000 + i))
+    return cases
+
+
+@pytest.mark.parametrize("case", random_cases(24, 20260311), ids=lambda c: "B%dL%dH%dG%dE%dk%dQ%d_h0%d_D%d_s%d" % c)
+def test_random_mfma_shapes_match_oracle(case):
+    B, L, H, G, E, k, Q, with_h0, with_D, seed = case
+    P, N = 64, 128
+    w = synth.Workload("rnd", B, L, H, P, N, G, E, k, Q, "bf16", 7)
+    p = synth.make_inputs(w, seed=seed)
+    rng = np.random.default_rng(seed)
+    p["D"] = rng.standard_normal(H).astype(np.float32)
+    h0 = (0.1 * rng.standard_normal((B, H, P, N))).astype(np.float32) if with_h0 else None
+    D = p["D"] if with_D else None
+    ref = orc.mixer_fwd(p["x"], p["dt"], p["A"], D, p["B_experts"], p["C_experts"], p["router_logits"], k, h0=h0)
+    d = to_device(p, "bf16")
+    out = sw.swimba_mixer_fwd(d["x"], d["dt"], d["A"], d["D"] if with_D else None, d["B_experts"], d["C_experts"],
+                              d["router_logits"], k, Q, None if h0 is None else torch.from_numpy(h0).to("cuda:0"),
+                              want_topk=True)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(out.topk_idx.cpu().numpy(), ref["topk_idx"])
+    np.testing.assert_allclose(host(out.topk_w), ref["topk_w"], rtol=1e-5, atol=1e-30)
+    l2, linf = rel_errors(host(out.y), ref["y"], (0, 2))
+    hl2, hlinf = rel_errors(host(out.h_final), ref["h_final"], (0, 1))
+    print(case, "y l2 %.2e linf %.2e  h_final l2 %.2e" % (l2, linf, hl2), flush=True)
+    assert l2 <= TOL["bf16"] and linf <= TOL["bf16"], (l2, linf)
+    assert hl2 <= TOL["bf16"] and hlinf <= TOL["bf16"], (hl2, hlinf)
+
+
+@pytest.mark.parametrize("case", random_cases(10, 77), ids=lambda c: "B%dL%dH%dG%dE%dk%dQ%d_h0%d_D%d_s%d" % c)
+def test_random_features_to_y_match_oracle_chain(case):
+    B, L, H, G, E, k, Q, with_h0, with_D, seed = case
+    P, N = 64, 128
+    rng = np.random.default_rng(seed + 5)
+    Dm = int(rng.choice([16, 48, 64, 80, 256]))
+    rd = synth.round_to_bf16
+    u = rd(rng.standard_normal((B, L, Dm)).astype(np.float32))
+    WB = rd((rng.standard_normal((E, G, N, Dm)) / np.sqrt(Dm)).astype(np.float32))
+    WC = rd((rng.standard_normal((E, G, N, Dm)) / np.sqrt(Dm)).astype(np.float32))
+    w = synth.Workload("rnd", B, L, H, P, N, G, E, k, Q, "bf16", 7)
+    p = synth.make_inputs(w, seed=seed)
+    g = p["router_logits"]
+    D = rng.standard_normal(H).astype(np.float32) if with_D else None
+    h0 = (0.1 * rng.standard_normal((B, H, P, N))).astype(np.float32) if with_h0 else None
+    rp = orc.expert_proj(u, WB, WC, g, k, fill=0.0)
+    ref = orc.mixer_fwd(p["x"], p["dt"], p["A"], D, rp["B_experts"].astype(np.float32),
+                        rp["C_experts"].astype(np.float32), g, k, h0=h0)
+    bf = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(torch.bfloat16).to("cuda:0")
+    out = sw.swimba_mixer_fwd_proj(bf(u), bf(WB), bf(WC), bf(p["x"]), bf(p["dt"]), torch.from_numpy(p["A"]).to("cuda:0"),
+                                   None if D is None else torch.from_numpy(D).to("cuda:0"), bf(g), k, Q,
+                                   None if h0 is None else torch.from_numpy(h0).to("cuda:0"), want_topk=True)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(out.topk_idx.cpu().numpy(), ref["topk_idx"])
+    l2, linf = rel_errors(host(out.y), ref["y"], (0, 2))
+    hl2, hlinf = rel_errors(host(out.h_final), ref["h_final"], (0, 1))
+    print(case, "Dm", Dm, "y l2 %.2e linf %.2e  h_final l2 %.2e" % (l2, linf, hl2), flush=True)
+    assert l2 <= TOL["bf16"] and linf <= TOL["bf16"], (l2, linf)
+    assert hl2 <= TOL["bf16"] and hlinf <= TOL["bf16"], (hl2, hlinf)
