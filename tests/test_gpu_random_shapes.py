@@ -83,3 +83,41 @@ def test_random_features_to_y_match_oracle_chain(case):
     print(case, "Dm", Dm, "y l2 %.2e linf %.2e  h_final l2 %.2e" % (l2, linf, hl2), flush=True)
     assert l2 <= TOL["bf16"] and linf <= TOL["bf16"], (l2, linf)
     assert hl2 <= TOL["bf16"] and hlinf <= TOL["bf16"], (hl2, hlinf)
+
+
+def random_generic_cases(n, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for i in range(n):
+        G = int(rng.choice([1, 2, 3]))
+        H = G * int(rng.choice([1, 2]))
+        P = int(rng.choice([1, 3, 8, 16, 24, 40]))
+        N = int(rng.choice([1, 5, 16, 33, 64, 70]))
+        Q = int(rng.choice([1, 7, 16, 32, 48, 100]))
+        L = int(rng.integers(1, 3 * Q + 9))
+        E = int(rng.choice([1, 2, 5, 8, 19]))
+        k = int(rng.integers(1, min(E, 4) + 1))
+        io = str(rng.choice(["f32", "bf16"]))
+        cases.append((int(rng.choice([1, 2])), L, H, P, N, G, E, k, Q, io, 2000 + i))
+    return cases
+
+
+@pytest.mark.parametrize("case", random_generic_cases(16, 5), ids=lambda c: "B%dL%dH%dP%dN%dG%dE%dk%dQ%d%s_s%d" % c)
+def test_random_shapes_on_the_fp32_kernels_match_oracle(case):
+    B, L, H, P, N, G, E, k, Q, io, seed = case
+    w = synth.Workload("rnd", B, L, H, P, N, G, E, k, Q, io, 7)
+    p = synth.make_inputs(w, seed=seed)
+    rng = np.random.default_rng(seed)
+    p["D"] = rng.standard_normal(H).astype(np.float32)
+    h0 = (0.1 * rng.standard_normal((B, H, P, N))).astype(np.float32)
+    ref = orc.mixer_fwd(p["x"], p["dt"], p["A"], p["D"], p["B_experts"], p["C_experts"], p["router_logits"], k, h0=h0)
+    d = to_device(p, io)
+    out = sw.swimba_mixer_fwd(d["x"], d["dt"], d["A"], d["D"], d["B_experts"], d["C_experts"], d["router_logits"],
+                              k, Q, torch.from_numpy(h0).to("cuda:0"), want_topk=True)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(out.topk_idx.cpu().numpy(), ref["topk_idx"])
+    l2, linf = rel_errors(host(out.y), ref["y"], (0, 2))
+    hl2, hlinf = rel_errors(host(out.h_final), ref["h_final"], (0, 1))
+    print(case, "y l2 %.2e linf %.2e  h_final l2 %.2e" % (l2, linf, hl2), flush=True)
+    assert l2 <= TOL[io] and linf <= TOL[io], (l2, linf)
+    assert hl2 <= 1e-4 and hlinf <= 1e-4, (hl2, hlinf)      # the state is fp32 arithmetic on both io types
