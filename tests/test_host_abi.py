@@ -176,6 +176,33 @@ def test_later_entry_points_validate_on_the_host():
     assert lib.swimba_step_multi(ctypes.byref(dims(seqlen=4)), *p[:9], p[9] + 8, p[10], ws, big, None) == 7
 
 
+def test_header_is_plain_c_and_links_against_the_library(tmp_path):
+    """include/swimba.h compiles as C99 with gcc (no C++ in the boundary), and a C program that
+    only uses host-side calls links against libswimba.so and runs without a GPU."""
+    import subprocess
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    src = tmp_path / "abi.c"
+    src.write_text(
+        '#include "swimba.h"\n#include <stdio.h>\n'
+        "int main(void) {\n"
+        "  swimba_dims d = {1, 256, 4, 16, 16, 1, 4, 2, 64, SWIMBA_F32};\n"
+        "  size_t n = swimba_mixer_workspace_bytes(&d);\n"
+        "  swimba_ws_layout lo;\n"
+        "  if (swimba_mixer_workspace_layout(&d, &lo) != SWIMBA_OK || lo.total != n || n == 0) return 1;\n"
+        "  if (swimba_mixer_fwd(&d, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0, 0) != SWIMBA_ERR_WORKSPACE) return 2;\n"
+        '  printf("%s\\n", swimba_status_string(SWIMBA_ERR_ALIGNMENT));\n'
+        "  return 0;\n}\n")
+    exe = tmp_path / "abi"
+    libdir = os.path.join(root, "paper_2603_06938_amd")
+    r = subprocess.run(["gcc", "-std=c99", "-Wall", "-Werror", "-pedantic", "-I", os.path.join(root, "include"),
+                        str(src), "-o", str(exe), "-L", libdir, "-l:libswimba.so", "-Wl,-rpath," + libdir],
+                       capture_output=True, text=True, timeout=120)
+    assert r.returncode == 0, r.stderr
+    r = subprocess.run([str(exe)], capture_output=True, text=True, timeout=60)
+    assert r.returncode == 0, (r.returncode, r.stderr)
+    assert "aligned" in r.stdout
+
+
 def test_binding_refuses_cpu_tensors():
     import torch
     x = torch.zeros(1, 4, 2, 16)
