@@ -67,11 +67,12 @@ static void layout_of(const swimba_dims *d, swimba_ws_layout *o)
     o->topk_idx = off; off = align_up(off + T * s.K * sizeof(int32_t), 256);
     o->topk_w = off;   off = align_up(off + T * s.K * sizeof(float), 256);
     o->cs = off;       off = align_up(off + (size_t)s.B * s.nc * s.H * s.Q * sizeof(float), 256);
-    const size_t nstate = (size_t)s.B * s.nc * s.H * s.P * s.N;
     const bool mf = use_mfma_path(d);
+    const size_t Nk = mf ? 128 : (size_t)s.N;   // the MFMA kernels pad the state size to 128
+    const size_t nstate = (size_t)s.B * s.nc * s.H * s.P * Nk;
     o->states = off;
     if (!mf) off = align_up(off + nstate * sizeof(float), 256);
-    const size_t mixed = (size_t)s.B * s.nc * s.Q * s.G * s.N * sizeof(uint16_t);
+    const size_t mixed = (size_t)s.B * s.nc * s.Q * s.G * Nk * sizeof(uint16_t);
     const size_t nt = (size_t)s.Q / 32;
     o->states_lp = off;
     if (mf) off = align_up(off + nstate * sizeof(uint16_t), 256);

@@ -47,7 +47,9 @@ inline Shape make_shape(const swimba_dims *d)
 // true when the bf16 MFMA kernels cover this problem
 inline bool use_mfma_path(const swimba_dims *d)
 {
-    return d->io_dtype == SWIMBA_BF16 && d->headdim == 64 && d->dstate == 128 &&
+    // state sizes below 128 (multiples of 8) run on the same kernels with the mixed rows and the
+    // states zero-padded to 128 columns
+    return d->io_dtype == SWIMBA_BF16 && d->headdim == 64 && d->dstate <= 128 && d->dstate % 8 == 0 &&
            (d->chunk == 64 || d->chunk == 128 || d->chunk == 256);
 }
 

@@ -1,4 +1,5 @@
-// bf16 MFMA SSD chunk kernels for P = 64, N = 128, Q in {64, 128, 256}
+// bf16 MFMA SSD chunk kernels for P = 64, N = 128 (smaller N, a multiple of 8, zero-padded to 128 when the
+// expert rows are mixed), Q in {64, 128, 256}
 // (paper, background section on SSD: matrix multiplications inside chunks;
 // Theorem 1: the mixed streams feed one plain SSM).
 //
@@ -169,15 +170,15 @@ mix_rows_kernel(const uint16_t *__restrict__ Be, const uint16_t *__restrict__ Ce
     const int valid = min(s.Q, s.L - c * s.Q) - tile * 32;     // tokens of this tile inside the sequence
     const int64_t tok0 = (int64_t)b * s.L + (int64_t)c * s.Q + tile * 32;
     const int64_t last = (int64_t)b * s.L + min(s.L, (c + 1) * s.Q) - 1 - tok0;   // clamp for padded rows
-    const int estride = s.G * MN;
+    const int estride = s.G * s.N;                       // rows of the inputs have the caller's N <= MN
     // Streams of the selected experts only (w_sel != nullptr): Be / Ce are (B,L,k,G,N), row r of
     // a token belongs to its r-th selected expert and w_sel (B,L,k) holds the router weights.
     const bool sel = (w_sel != nullptr);
     const int rowsE = sel ? Kr : s.E;
     const int tokstride = rowsE * estride;               // elements between tokens of B/C_experts
     const int64_t bcg = ((int64_t)b * s.nc + c) * s.G + g;
-    const uint16_t *Bg = Be + (tok0 * rowsE * s.G + g) * MN;   // [token 0 of the tile][expert 0][g][0]
-    const uint16_t *Cg = Ce + (tok0 * rowsE * s.G + g) * MN;
+    const uint16_t *Bg = Be + (tok0 * rowsE * s.G + g) * s.N;  // [token 0 of the tile][expert 0][g][0]
+    const uint16_t *Cg = Ce + (tok0 * rowsE * s.G + g) * s.N;
 
     // ---- routing of the tile's tokens: logits staged through LDS (one coalesced read) ----
     if (!sel) {
@@ -228,6 +229,8 @@ mix_rows_kernel(const uint16_t *__restrict__ Be, const uint16_t *__restrict__ Ce
     // ---- gather and mix: a lane owns one 16-byte piece (8 n) of tokens tg and tg+16, both
     // streams; 16 consecutive lanes read one whole 256-byte expert row.  Experts two at a time.
     const int piece = tid & 15, tg = tid >> 4;
+    const bool pin = piece * 8 < s.N;                    // pieces past the caller's N stay zero (padding)
+    const int pc = pin ? piece : 0;
     float accB[2][8], accC[2][8];
 #pragma unroll
     for (int jj = 0; jj < 2; ++jj)
@@ -238,7 +241,7 @@ mix_rows_kernel(const uint16_t *__restrict__ Be, const uint16_t *__restrict__ Ce
 #pragma unroll
         for (int jj = 0; jj < 2; ++jj) {
             const int j = tg + 16 * jj;
-            const int64_t rowoff = min((int64_t)j, last) * tokstride + piece * 8;
+            const int64_t rowoff = min((int64_t)j, last) * tokstride + pc * 8;
 #pragma unroll
             for (int q = 0; q < 2; ++q) {
                 const int eo = ixt[j * K + min(r0 + q, K - 1)] * estride;
@@ -251,7 +254,7 @@ mix_rows_kernel(const uint16_t *__restrict__ Be, const uint16_t *__restrict__ Ce
             const int j = tg + 16 * jj;
 #pragma unroll
             for (int q = 0; q < 2; ++q) {
-                const bool on = r0 + q < K;
+                const bool on = pin && r0 + q < K;
                 fma_bf16x8(accB[jj], vb[jj][q], on ? wtB[j * K + r0 + q] : 0.f);
                 fma_bf16x8(accC[jj], vc[jj][q], on ? wtC[j * K + r0 + q] : 0.f);
             }
@@ -345,17 +348,22 @@ scan_cb_kernel(uint16_t *__restrict__ lp, const float *__restrict__ h0, float *_
         if (bcg < nbcg && p < NT * (NT + 1) / 2) cb_pair(cmix, bfrag, cb, NT, bcg, p, threadIdx.x & 63);
         return;
     }
-    const int64_t per_bh = (int64_t)s.P * s.N / 8;
+    // chunk states are (MP, MN) tiles; h0 / h_final have the caller's N <= MN columns (the padded
+    // columns of the states are zero: the mixed B rows are zero there)
+    constexpr int64_t per_bh = (int64_t)MP * MN / 8;
     const int64_t gid = (int64_t)(blockIdx.x - ncb) * blockDim.x + threadIdx.x;
     if (gid >= per_bh * s.B * s.H) return;
     const int64_t bh = gid / per_bh;
     const int64_t pn = (gid % per_bh) * 8;
     const int b = (int)(bh / s.H), h = (int)(bh % s.H);
-    const int64_t PN = (int64_t)s.P * s.N;
+    constexpr int64_t PN = (int64_t)MP * MN;
+    const int pp = (int)(pn / MN), nn = (int)(pn % MN);
+    const bool real = nn < s.N;                          // 8 consecutive columns: all real or all padding
+    const int64_t user = bh * MP * s.N + (int64_t)pp * s.N + nn;
 
     float run[8];
 #pragma unroll
-    for (int v = 0; v < 8; ++v) run[v] = h0 ? h0[bh * PN + pn + v] : 0.f;
+    for (int v = 0; v < 8; ++v) run[v] = (h0 && real) ? h0[user + v] : 0.f;
 
     constexpr int UN = 4;  // chunks whose loads are issued together
     for (int c0 = 0; c0 < s.nc; c0 += UN) {
@@ -379,9 +387,9 @@ scan_cb_kernel(uint16_t *__restrict__ lp, const float *__restrict__ h0, float *_
             }
         }
     }
-    if (h_final) {
+    if (h_final && real) {
 #pragma unroll
-        for (int v = 0; v < 8; ++v) h_final[bh * PN + pn + v] = run[v];
+        for (int v = 0; v < 8; ++v) h_final[user + v] = run[v];
     }
 }
 
