@@ -140,8 +140,9 @@ swimba_status swimba_router_topk(int64_t tokens, int32_t nexperts, int32_t top_k
  * L need not be a multiple of Q (the last chunk is ragged).  B == 0 or L == 0
  * is valid: nothing is computed (h_final = h0 or zeros when L == 0).
  * Arithmetic: fp32 throughout for io_dtype fp32.  For bf16 io with
- * P = 64, N <= 128 (a multiple of 8; below 128 the mixed rows and the states are
- * zero-padded to 128 inside the workspace) and Q in {64,128,256} the contractions run on bf16 MFMA
+ * P <= 64 and N <= 128 (multiples of 8; below 64 x 128 the staged inputs, the mixed rows and the
+ * states are zero-padded inside the kernels and the workspace) and Q in {64,128,256} the
+ * contractions run on bf16 MFMA
  * with fp32 accumulation (mixed streams, decay-weighted x, the C.B^T block before and
  * after the decay mask, the chunk states and the carried states are rounded to bf16
  * as operands; the inter-chunk recurrence itself runs in fp32);

@@ -68,8 +68,9 @@ static void layout_of(const swimba_dims *d, swimba_ws_layout *o)
     o->topk_w = off;   off = align_up(off + T * s.K * sizeof(float), 256);
     o->cs = off;       off = align_up(off + (size_t)s.B * s.nc * s.H * s.Q * sizeof(float), 256);
     const bool mf = use_mfma_path(d);
-    const size_t Nk = mf ? 128 : (size_t)s.N;   // the MFMA kernels pad the state size to 128
-    const size_t nstate = (size_t)s.B * s.nc * s.H * s.P * Nk;
+    const size_t Nk = mf ? 128 : (size_t)s.N;   // the MFMA kernels pad the states to 64 x 128
+    const size_t Pk = mf ? 64 : (size_t)s.P;
+    const size_t nstate = (size_t)s.B * s.nc * s.H * Pk * Nk;
     o->states = off;
     if (!mf) off = align_up(off + nstate * sizeof(float), 256);
     const size_t mixed = (size_t)s.B * s.nc * s.Q * s.G * Nk * sizeof(uint16_t);

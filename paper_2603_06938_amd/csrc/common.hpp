@@ -47,9 +47,10 @@ inline Shape make_shape(const swimba_dims *d)
 // true when the bf16 MFMA kernels cover this problem
 inline bool use_mfma_path(const swimba_dims *d)
 {
-    // state sizes below 128 (multiples of 8) run on the same kernels with the mixed rows and the
-    // states zero-padded to 128 columns
-    return d->io_dtype == SWIMBA_BF16 && d->headdim == 64 && d->dstate <= 128 && d->dstate % 8 == 0 &&
+    // head dimensions below 64 and state sizes below 128 (multiples of 8) run on the same kernels:
+    // x is staged with zero channels, the mixed rows and the states are zero-padded to 64 x 128
+    return d->io_dtype == SWIMBA_BF16 && d->headdim <= 64 && d->headdim % 8 == 0 && d->dstate <= 128 &&
+           d->dstate % 8 == 0 &&
            (d->chunk == 64 || d->chunk == 128 || d->chunk == 256);
 }
 

@@ -1,5 +1,5 @@
-// bf16 MFMA SSD chunk kernels for P = 64, N = 128 (smaller N, a multiple of 8, zero-padded to 128 when the
-// expert rows are mixed), Q in {64, 128, 256}
+// bf16 MFMA SSD chunk kernels for P = 64, N = 128 (smaller P and N, multiples of 8, run zero-padded: x is
+// staged with zero channels, the mixed expert rows get zero columns), Q in {64, 128, 256}
 // (paper, background section on SSD: matrix multiplications inside chunks;
 // Theorem 1: the mixed streams feed one plain SSM).
 //
@@ -348,8 +348,8 @@ scan_cb_kernel(uint16_t *__restrict__ lp, const float *__restrict__ h0, float *_
         if (bcg < nbcg && p < NT * (NT + 1) / 2) cb_pair(cmix, bfrag, cb, NT, bcg, p, threadIdx.x & 63);
         return;
     }
-    // chunk states are (MP, MN) tiles; h0 / h_final have the caller's N <= MN columns (the padded
-    // columns of the states are zero: the mixed B rows are zero there)
+    // chunk states are (MP, MN) tiles; h0 / h_final have the caller's P <= MP rows and N <= MN columns
+    // (the padding of the states is zero: the mixed B rows and the staged x are zero there)
     constexpr int64_t per_bh = (int64_t)MP * MN / 8;
     const int64_t gid = (int64_t)(blockIdx.x - ncb) * blockDim.x + threadIdx.x;
     if (gid >= per_bh * s.B * s.H) return;
@@ -358,8 +358,8 @@ scan_cb_kernel(uint16_t *__restrict__ lp, const float *__restrict__ h0, float *_
     const int b = (int)(bh / s.H), h = (int)(bh % s.H);
     constexpr int64_t PN = (int64_t)MP * MN;
     const int pp = (int)(pn / MN), nn = (int)(pn % MN);
-    const bool real = nn < s.N;                          // 8 consecutive columns: all real or all padding
-    const int64_t user = bh * MP * s.N + (int64_t)pp * s.N + nn;
+    const bool real = nn < s.N && pp < s.P;              // 8 consecutive columns: all real or all padding
+    const int64_t user = (bh * s.P + pp) * s.N + nn;
 
     float run[8];
 #pragma unroll
@@ -470,8 +470,12 @@ chunk_state_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restri
     const int64_t tok0 = (int64_t)b * s.L + (int64_t)c * Q;
     const int valid = min(Q, s.L - c * Q);
     const int64_t bcg = ((int64_t)b * s.nc + c) * s.G + g;
-    const int tokstride = s.H * MP;
+    const int tokstride = s.H * s.P;                 // the caller's P <= MP channels per head
     const int tq = min(tid, Q - 1);
+    // a lane always stages the same two channels 2 p2, 2 p2 + 1; channels past P are staged as zeros
+    const bool pok = 2 * (tid & 31) < s.P;
+    const int pclamp = pok ? 2 * (tid & 31) : 0;
+    const int valid_x = pok ? valid : 0;
 
     // The tile is computed transposed, S^T[n][p] = Bmix^T . (coef x): the mixed B is the A
     // operand.  Operand row l32 holds column n = 32*wave + prow, so that accumulator row
@@ -490,7 +494,7 @@ chunk_state_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restri
     uint32_t xv[XU][8];
     // all global loads of one head, clamped and unconditional
     auto issue_loads = [&](int h) {
-        const uint16_t *xh = x + (tok0 * s.H + h) * MP;
+        const uint16_t *xh = x + (tok0 * s.H + h) * s.P + pclamp;
         dt_raw = dt[(tok0 + min(tq, valid - 1)) * s.H + h];
 #pragma unroll
         for (int it = 0; it < XU; ++it) {
@@ -501,7 +505,7 @@ chunk_state_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restri
                 const int j = jg * 8 + e;
                 // raw value: nothing may consume it here, or the loads would be waited for one by
                 // one right after their issue; rows past the sequence end are zeroed when staged
-                xv[it][e] = *reinterpret_cast<const uint32_t *>(xh + min(j, valid - 1) * tokstride + 2 * p2);
+                xv[it][e] = *reinterpret_cast<const uint32_t *>(xh + min(j, valid - 1) * tokstride);
             }
         }
     };
@@ -540,7 +544,7 @@ chunk_state_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restri
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
                 const float cf = s_coef[buf * Q + jg * 8 + e];
-                const uint32_t xr = (jg * 8 + e < valid) ? xv[it][e] : 0u;
+                const uint32_t xr = (jg * 8 + e < valid_x) ? xv[it][e] : 0u;
                 xa[e] = bf_lo(xr) * cf;
                 xb[e] = bf_hi(xr) * cf;
             }
@@ -690,9 +694,13 @@ output_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ 
     const int64_t tok0 = (int64_t)b * s.L + (int64_t)c * Q;
     const int valid = min(Q, s.L - c * Q);
     const int64_t bcg = ((int64_t)b * s.nc + c) * s.G + g;
-    const int tokstride = s.H * MP;                          // elements between tokens of x / y
-    const uint16_t *xh = x + (tok0 * s.H + h) * MP;          // x[token 0 of the chunk][h][0]
-    uint16_t *yh = y + (tok0 * s.H + h) * MP;
+    const int tokstride = s.H * s.P;                         // elements between tokens of x / y (P <= MP)
+    const uint16_t *xh = x + (tok0 * s.H + h) * s.P;         // x[token 0 of the chunk][h][0]
+    uint16_t *yh = y + (tok0 * s.H + h) * s.P;
+    // channels past the caller's P: staged as zeros, never stored
+    const bool pok = 2 * (tid & 31) < s.P;
+    const int pclamp = pok ? 2 * (tid & 31) : 0;
+    const int valid_x = pok ? valid : 0;
     // channel held by operand row l32 (see the header comment)
     const int prow = 16 * ((l32 >> 2) & 1) + 4 * (l32 >> 3) + (l32 & 3);
 
@@ -728,8 +736,8 @@ output_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ 
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
             const int j = 16 * t16 + 8 * (e >> 2) + 4 * kgx + (e & 3);
-            const uint32_t ld = *reinterpret_cast<const uint32_t *>(xh + min(j, valid - 1) * tokstride + 2 * p2);
-            xv[it][e] = (j < valid) ? ld : 0u;
+            const uint32_t ld = *reinterpret_cast<const uint32_t *>(xh + min(j, valid - 1) * tokstride + pclamp);
+            xv[it][e] = (j < valid_x) ? ld : 0u;
         }
     }
     // mixed C rows of the owned tiles (operand registers)
@@ -790,11 +798,13 @@ output_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ 
     {
         // x of the skip term, loaded the way y is stored: lane -> (token row, 16-byte piece)
         const int erow = lane >> 3, epiece = lane & 7;
+        const bool epok = epiece * 8 < s.P;
+        const int eoff = epok ? epiece * 8 : 0;
         uint4 xe[4];
 #pragma unroll
         for (int q4 = 0; q4 < 4; ++q4) {
             const int i = I * 32 + erow + 8 * q4;
-            xe[q4] = *reinterpret_cast<const uint4 *>(xh + min(i, valid - 1) * tokstride + epiece * 8);
+            xe[q4] = *reinterpret_cast<const uint4 *>(xh + min(i, valid - 1) * tokstride + eoff);
         }
         // keep these loads (first two G^T tiles, x of the skip term) in front of the MFMAs below:
         // moved behind them, the first tile pair would wait a full memory latency
@@ -895,7 +905,7 @@ output_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ 
 #pragma unroll
         for (int q4 = 0; q4 < 4; ++q4) {
             const int row = erow + 8 * q4, i = I * 32 + row;
-            if (i < valid) {
+            if (i < valid && epok) {
                 float a[8], xf[8];
                 unpack8(a, *reinterpret_cast<const uint4 *>(scr + row * YSTR + ((epiece ^ (row & 7)) << 3)));
                 unpack8(xf, xe[q4]);

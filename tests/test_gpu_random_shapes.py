@@ -29,6 +29,11 @@ def random_cases(n, seed, min_len=1):
     return cases
 
 
+def head_dim_of(seed):
+    """P = 64 is the kernels' own size; smaller multiples of 8 run on them with zero channels."""
+    return [64, 32, 64, 16, 8, 40, 64, 48, 24, 64, 56][seed % 11]
+
+
 def state_size_of(seed):
     """N = 128 is the kernels' own size; smaller multiples of 8 run on them zero-padded."""
     return [128, 128, 64, 16, 96, 8, 32, 120][seed % 8]
@@ -37,7 +42,7 @@ def state_size_of(seed):
 @pytest.mark.parametrize("case", random_cases(24, 20260311), ids=lambda c: "B%dL%dH%dG%dE%dk%dQ%d_h0%d_D%d_s%d" % c)
 def test_random_mfma_shapes_match_oracle(case):
     B, L, H, G, E, k, Q, with_h0, with_D, seed = case
-    P, N = 64, state_size_of(seed)
+    P, N = head_dim_of(seed), state_size_of(seed)
     w = synth.Workload("rnd", B, L, H, P, N, G, E, k, Q, "bf16", 7)
     p = synth.make_inputs(w, seed=seed)
     rng = np.random.default_rng(seed)
@@ -54,7 +59,7 @@ def test_random_mfma_shapes_match_oracle(case):
     np.testing.assert_allclose(host(out.topk_w), ref["topk_w"], rtol=1e-5, atol=1e-30)
     l2, linf = rel_errors(host(out.y), ref["y"], (0, 2))
     hl2, hlinf = rel_errors(host(out.h_final), ref["h_final"], (0, 1))
-    print(case, "N", N, "y l2 %.2e linf %.2e  h_final l2 %.2e" % (l2, linf, hl2), flush=True)
+    print(case, "P", P, "N", N, "y l2 %.2e linf %.2e  h_final l2 %.2e" % (l2, linf, hl2), flush=True)
     assert l2 <= TOL["bf16"] and linf <= TOL["bf16"], (l2, linf)
     assert hl2 <= TOL["bf16"] and hlinf <= TOL["bf16"], (hl2, hlinf)
 
@@ -65,7 +70,7 @@ def test_random_mfma_shapes_match_oracle(case):
 @pytest.mark.parametrize("case", random_cases(10, 77, min_len=16), ids=lambda c: "B%dL%dH%dG%dE%dk%dQ%d_h0%d_D%d_s%d" % c)
 def test_random_features_to_y_match_oracle_chain(case):
     B, L, H, G, E, k, Q, with_h0, with_D, seed = case
-    P, N = 64, state_size_of(seed + 1)
+    P, N = head_dim_of(seed + 3), state_size_of(seed + 1)
     rng = np.random.default_rng(seed + 5)
     Dm = int(rng.choice([16, 48, 64, 80, 256]))
     rd = synth.round_to_bf16
@@ -88,7 +93,7 @@ def test_random_features_to_y_match_oracle_chain(case):
     np.testing.assert_array_equal(out.topk_idx.cpu().numpy(), ref["topk_idx"])
     l2, linf = rel_errors(host(out.y), ref["y"], (0, 2))
     hl2, hlinf = rel_errors(host(out.h_final), ref["h_final"], (0, 1))
-    print(case, "N", N, "Dm", Dm, "y l2 %.2e linf %.2e  h_final l2 %.2e" % (l2, linf, hl2), flush=True)
+    print(case, "P", P, "N", N, "Dm", Dm, "y l2 %.2e linf %.2e  h_final l2 %.2e" % (l2, linf, hl2), flush=True)
     assert l2 <= TOL["bf16"] and linf <= TOL["bf16"], (l2, linf)
     assert hl2 <= TOL["bf16"] and hlinf <= TOL["bf16"], (hl2, hlinf)
 
