@@ -514,7 +514,8 @@ def workspace_views(dims: swimba_dims, workspace: torch.Tensor):
     }
     # chunk / carried states: fp32 on the fp32 path, bf16 on the bf16 MFMA path
     if lo.states_lp != lo.cmix:
-        out["states"] = view(lo.states_lp, B * nc * H * P * N, torch.bfloat16, (B, nc, H, P, N))
+        # stored as 64 x 128 tiles whatever P <= 64 and N <= 128 are; the view shows the caller's part
+        out["states"] = view(lo.states_lp, B * nc * H * 64 * 128, torch.bfloat16, (B, nc, H, 64, 128))[..., :P, :N]
     else:
         out["states"] = view(lo.states, B * nc * H * P * N, torch.float32, (B, nc, H, P, N))
     return out
