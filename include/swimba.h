@@ -65,6 +65,7 @@ typedef enum { SWIMBA_F32 = 0, SWIMBA_BF16 = 1 } swimba_dtype;
 #define SWIMBA_MAX_HEADDIM 256
 #define SWIMBA_MAX_CHUNK 256
 #define SWIMBA_MAX_STEP_TOKENS 64   /* tokens per sequence in one swimba_step_multi call */
+#define SWIMBA_MAX_DMODEL_GENERIC 16384 /* feature width of the projection outside its MFMA shapes */
 
 typedef struct {
     int32_t batch, seqlen, nheads, headdim, dstate, ngroups, nexperts, top_k;
@@ -104,8 +105,9 @@ swimba_status swimba_mixer_workspace_layout(const swimba_dims *dims, swimba_ws_l
  *   active set; their softmax values are kept and NOT renormalised.
  * Selection compares the raw stored logits (never the softmax values); equal
  * logits (including +0/-0) go to the lower expert index; the active set is
- * written in (logit descending, index ascending) order.  NaN logits are
- * outside the contract.
+ * written in (logit descending, index ascending) order.  NaN or +inf logits, and
+ * tokens whose logits are all -inf, are outside the contract: indices and weights are
+ * then unspecified, but every index stays inside [0, E), so no call reads out of bounds.
  *   logits   (tokens, E) io   [in]
  *   topk_idx (tokens, k) int32 [out]
  *   topk_w   (tokens, k) fp32  [out]
@@ -256,7 +258,9 @@ swimba_status swimba_router_linear(int64_t tokens, int32_t d_model, int32_t nexp
  *   topk_idx, topk_w (B,L,k) [out, nullable]
  * Uses dims->batch, seqlen, dstate, ngroups, nexperts, top_k, io_dtype.  bf16 io with
  * d_model % 16 == 0 and (G*N) % 64 == 0 runs as a grouped GEMM on bf16 MFMA (fp32
- * accumulation); anything else on plain fp32 arithmetic.  The router's linear layer is not
+ * accumulation); anything else on plain fp32 arithmetic, for d_model up to
+ * SWIMBA_MAX_DMODEL_GENERIC (the GEMM takes d_model up to 65536; beyond either limit the
+ * workspace query returns 0 and the call SWIMBA_ERR_UNSUPPORTED).  The router's linear layer is not
  * part of this call: the logits are an input, so that the routing decision is the caller's.
  *   workspace >= swimba_expert_proj_workspace_bytes(dims, d_model), 256-byte aligned.
  */

@@ -550,6 +550,9 @@ static swimba_status proj_layout_of(const swimba_dims *d, int32_t d_model, ProjL
     const int64_t T = (int64_t)d->batch * d->seqlen;
     if (d_model > 65536 || T * d->top_k > (1ll << 31) - 1 || T * d->nexperts > (1ll << 31) - 1)
         return SWIMBA_ERR_UNSUPPORTED;
+    // shapes outside the MFMA GEMM run on a kernel that keeps one token's features in LDS as fp32
+    const bool gemm = d->io_dtype == SWIMBA_BF16 && d_model % 16 == 0 && (d->ngroups * d->dstate) % 64 == 0;
+    if (!gemm && d_model > SWIMBA_MAX_DMODEL_GENERIC) return SWIMBA_ERR_UNSUPPORTED;
     size_t off = 0;
     o->idx = off;    off = align_up(off + (size_t)T * d->top_k * sizeof(int32_t), 256);
     o->w = off;      off = align_up(off + (size_t)T * d->top_k * sizeof(float), 256);

@@ -153,6 +153,9 @@ __device__ __forceinline__ void route_token(Load load, int E, int K, int32_t *id
             const bool after = (r == 0) || (v < pv) || (v == pv && e > pi);
             if (after && (best < 0 || v > bv)) { best = e; bv = v; }
         }
+        // Only logits outside the contract (NaN, +inf, all -inf) leave no candidate.  The result is
+        // undefined then, but the index stays a valid one: it addresses the expert rows.
+        if (best < 0) { best = (pi + 1) % E; bv = -INFINITY; }
         idx[r] = best;
         w[r] = route_exp(bv - m) * invZ;
         pv = bv;

@@ -28,8 +28,30 @@ def host(t):
     return t.detach().to("cpu").to(torch.float64).numpy()
 
 
+# Isolated-element guard of rel_errors: every element within ELEM_SLACK * tol * (|ref| + rms of its
+# slice).  The slack is there for rows that are small by cancellation (the readout Cmix_t . h_t of a
+# large state can nearly vanish): their error follows the size of the cancelling terms, not the
+# size of the result; measured up to 5.3 tol at the full benchmark sizes.  The sharp per-element
+# statement is componentwise_excess below; this guard needs no second oracle run, so every
+# comparison gets it, and an element wrong by a few slice rms fails it however long the slice.
+ELEM_SLACK = 8.0
+
+
+def elem_error(got, ref, slice_axes):
+    """max over elements of |got - ref| / (|ref| + rms(ref over the element's slice))"""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    if not ref.size:
+        return 0.0
+    red = tuple(a for a in range(ref.ndim) if a not in slice_axes)
+    rms = np.sqrt((ref ** 2).mean(axis=red, keepdims=True))
+    return float((np.abs(got - ref) / np.maximum(np.abs(ref) + rms, 1e-300)).max())
+
+
 def rel_errors(got, ref, slice_axes):
-    """(max over slices of ||got-ref||_2/||ref||_2, global ||.||_inf ratio).
+    """Two numbers, both held to the same tolerance by the tests:
+      * max over slices of ||got-ref||_2 / ||ref||_2;
+      * the larger of the global ||got-ref||_inf / ||ref||_inf and elem_error / ELEM_SLACK.
     slice_axes: the axes that index a slice (e.g. batch and head)."""
     got = np.asarray(got, dtype=np.float64)
     ref = np.asarray(ref, dtype=np.float64)
@@ -38,7 +60,51 @@ def rel_errors(got, ref, slice_axes):
     den = np.sqrt((ref ** 2).sum(axis=red))
     l2 = float((num / np.maximum(den, 1e-300)).max()) if num.size else 0.0
     linf = float(np.abs(got - ref).max() / max(np.abs(ref).max(), 1e-300)) if ref.size else 0.0
-    return l2, linf
+    return l2, max(linf, elem_error(got, ref, slice_axes) / ELEM_SLACK)
+
+
+# ---- componentwise bound ------------------------------------------------------------------
+# Every output element is a sum of products of inputs, sum_j a_j b_j ...; computing it with
+# operands rounded r times to a format of unit roundoff u changes it by at most
+# ((1+u)^r - 1) * sum_j |a_j b_j ...| (the standard forward error bound of an inner product).
+# The sum of absolute values is the oracle itself run on the absolute values of x, B_e, C_e,
+# h0 and D (router weights, dt and the decays are positive, so every term of the linear map
+# turns into its absolute value, and sum_e pi_e |B_e| >= |Bmix|).  The bound holds element by
+# element, for any length, and does not care whether the terms cancel in the true result.
+# bf16 (8 significant bits) has u = 2^-8.  On the bf16 MFMA path a term passes through at most 5
+# roundings (the mixed B row, the coefficient-weighted x or the C.B^T tile, the chunk state, the
+# carried state or the masked tile, the stored y; the mixed C row replaces one of them in the
+# readout terms): 5 u = 1.95e-2, which is the 2e-2 bar of bf16 io with fp32 accumulation taken
+# element by element.  Streams that were themselves projected and stored in bf16 add one
+# rounding on each side of the product (7 u).  Sums of many terms stay far below the bound
+# (about 0.6 u for y at the benchmark sizes); an element made of a single product (a one-token
+# sequence) does come close to it (3 u seen on h_final, which passes 3 roundings).
+U_BF16 = 2.0 ** -8
+
+
+def comp_tol(io_dtype, roundings=5):
+    return roundings * U_BF16 if io_dtype == "bf16" else TOL["f32"]
+
+
+def abs_inputs(p):
+    """the inputs with x, the expert streams and D replaced by their absolute values"""
+    q = dict(p)
+    for k in ("x", "x_experts", "B_experts", "C_experts", "D"):
+        if q.get(k) is not None:
+            q[k] = np.abs(q[k])
+    return q
+
+
+def componentwise_excess(got, ref, absref):
+    """max over elements of |got - ref| / absref (absref: the oracle on absolute values)"""
+    got = np.asarray(got, dtype=np.float64)
+    ref = np.asarray(ref, dtype=np.float64)
+    absref = np.asarray(absref, dtype=np.float64)
+    if not ref.size:
+        return 0.0
+    d = np.abs(got - ref)
+    # where no term contributes at all (absref == 0) the result has to be exactly zero
+    return float(np.where(absref > 0, d / np.maximum(absref, 1e-300), np.where(d > 0, np.inf, 0.0)).max())
 
 
 def run_mixer(p, top_k, chunk, io_dtype, h0=None, d_none=False, want_topk=True):

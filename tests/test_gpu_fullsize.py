@@ -8,7 +8,7 @@ import torch
 from oracle import swimba_oracle as orc
 from paper_2603_06938_amd import binding as sw
 from paper_2603_06938_amd import synth
-from gpu_util import TOL, host, rel_errors, run_mixer, to_device
+from gpu_util import TOL, abs_inputs, comp_tol, componentwise_excess, host, rel_errors, run_mixer, to_device
 
 pytestmark = pytest.mark.gpu
 
@@ -19,6 +19,9 @@ def test_prefill_workload_full_size(wi):
     print("workload", w, flush=True)
     p = synth.make_inputs(w)
     tol = TOL[w.io_dtype]
+    # the sums of absolute values behind every output element (the componentwise bound's scale)
+    q = abs_inputs(p)
+    aref = orc.mixer_fwd(q["x"], q["dt"], q["A"], None, q["B_experts"], q["C_experts"], q["router_logits"], w.top_k)
     for d_none in (True, False):
         out = run_mixer(p, w.top_k, w.chunk, w.io_dtype, d_none=d_none)
         ref = orc.mixer_fwd(p["x"], p["dt"], p["A"], None if d_none else p["D"], p["B_experts"],
@@ -31,7 +34,12 @@ def test_prefill_workload_full_size(wi):
         l2, linf = rel_errors(host(out.h_final), ref["h_final"], (0, 1))
         print("      h_final rel l2 %.3e linf %.3e" % (l2, linf), flush=True)
         assert l2 <= tol and linf <= tol, (l2, linf)
-        del out, ref
+        ay = aref["y"] if d_none else aref["y"] + np.abs(p["D"])[None, None, :, None] * q["x"]
+        ey = componentwise_excess(host(out.y), ref["y"], ay)
+        eh = componentwise_excess(host(out.h_final), ref["h_final"], aref["h_final"])
+        print("      componentwise: y %.3e h_final %.3e (bound %.3e)" % (ey, eh, comp_tol(w.io_dtype)), flush=True)
+        assert ey <= comp_tol(w.io_dtype) and eh <= comp_tol(w.io_dtype), (d_none, ey, eh)
+        del out, ref, ay
 
 
 @pytest.mark.parametrize("G", [1, 8])

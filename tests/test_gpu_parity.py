@@ -7,7 +7,7 @@ import torch
 from oracle import swimba_oracle as orc
 from paper_2603_06938_amd import binding as sw
 from paper_2603_06938_amd import synth
-from gpu_util import TOL, host, rel_errors, run_mixer, to_device
+from gpu_util import TOL, abs_inputs, comp_tol, componentwise_excess, host, rel_errors, run_mixer, to_device
 
 pytestmark = pytest.mark.gpu
 
@@ -17,6 +17,15 @@ def oracle_fwd(p, top_k, h0=None, d_none=False, **kw):
                          p["C_experts"], p["router_logits"], top_k, h0=h0, **kw)
 
 
+def check_componentwise(out, ref, p, w, h0=None, d_none=False, tag=""):
+    """every element of y and h_final within the forward error bound of its own sum of products"""
+    aref = oracle_fwd(abs_inputs(p), w.top_k, h0=None if h0 is None else np.abs(h0), d_none=d_none)
+    ctol = comp_tol(w.io_dtype)
+    ey = componentwise_excess(host(out.y), ref["y"], aref["y"])
+    eh = componentwise_excess(host(out.h_final), ref["h_final"], aref["h_final"])
+    assert ey <= ctol and eh <= ctol, (tag, "componentwise", d_none, ey, eh, ctol)
+
+
 def check_fwd(p, w, h0=None, tag=""):
     """y with D as given, y with D = NULL (so the SSM term is not hidden behind the
     skip term), final state, and bit-exact active sets."""
@@ -24,6 +33,7 @@ def check_fwd(p, w, h0=None, tag=""):
     for d_none in (False, True):
         ref = oracle_fwd(p, w.top_k, h0=h0, d_none=d_none)
         out = run_mixer(p, w.top_k, w.chunk, w.io_dtype, h0=h0, d_none=d_none)
+        check_componentwise(out, ref, p, w, h0=h0, d_none=d_none, tag=tag)
         np.testing.assert_array_equal(out.topk_idx.cpu().numpy(), ref["topk_idx"], err_msg=tag)
         np.testing.assert_allclose(host(out.topk_w), ref["topk_w"], rtol=1e-5, atol=1e-30, err_msg=tag)
         l2, linf = rel_errors(host(out.y), ref["y"], (0, 2))
@@ -147,6 +157,76 @@ def test_chunk_size_invariance_and_extreme_decay():
         assert torch.isfinite(out.y).all()
         l2, linf = rel_errors(host(out.y), ref["y"], (0, 2))
         assert l2 <= 1e-4 and linf <= 1e-4, (Q, l2, linf)
+
+
+@pytest.mark.parametrize("Q", [64, 128, 256])
+def test_extreme_decay_on_the_mfma_kernels(Q):
+    """bf16 io at the MFMA shape with A = -16 and dt = 1 over stretches of tokens, one inside a
+    chunk and one across a chunk boundary for every Q: the per-chunk cumsum reaches about -640,
+    far below the fp32 exponent range of exp(cs_i) * exp(-cs_j).  The decay has to be formed
+    from differences only; the output must be finite and within the bf16 bar."""
+    w = synth.Workload("decay", 2, 600, 4, 64, 128, 2, 8, 2, Q, "bf16", 7)
+    p = synth.make_inputs(w, seed=1212)
+    p["dt"][:, 100:140] = 1.0
+    p["dt"][:, 250:262] = 1.0
+    p["dt"][:, 500:530, 1] = 4.0            # dt * A = -64 per token on one head
+    p["A"][:] = np.array([-16, -16, -1, -8], np.float32)
+    rng = np.random.default_rng(5)
+    h0 = rng.standard_normal((2, 4, 64, 128)).astype(np.float32) * 0.1
+    for d_none in (True, False):
+        ref = oracle_fwd(p, w.top_k, h0=h0, d_none=d_none)
+        out = run_mixer(p, w.top_k, Q, "bf16", h0=h0, d_none=d_none)
+        assert torch.isfinite(out.y).all() and torch.isfinite(out.h_final).all()
+        check_componentwise(out, ref, p, w, h0=h0, d_none=d_none, tag="Q%d" % Q)
+        l2, linf = rel_errors(host(out.y), ref["y"], (0, 2))
+        assert l2 <= TOL["bf16"] and linf <= TOL["bf16"], (Q, d_none, l2, linf)
+        l2, linf = rel_errors(host(out.h_final), ref["h_final"], (0, 1))
+        assert l2 <= TOL["bf16"] and linf <= TOL["bf16"], (Q, "h_final", l2, linf)
+
+
+@pytest.mark.parametrize("Q,io,P,N", [(256, "bf16", 64, 128), (64, "bf16", 64, 128), (128, "bf16", 32, 64),
+                                      (64, "f32", 16, 16)])
+def test_causality_is_bitwise(Q, io, P, N):
+    """Changing every input at tokens >= s leaves y at tokens < s bitwise unchanged (paper: the
+    recurrence is causal; in the chunked form nothing a token's output reads may depend on later
+    tokens of its chunk or tile).  s inside a 32-token tile, at a tile edge, at a chunk edge."""
+    w = synth.Workload("causal", 2, 2 * Q + 50, 4, P, N, 2, 8, 2, Q, io, 7)
+    p = synth.make_inputs(w, seed=99)
+    q = synth.make_inputs(w, seed=100)
+    base = run_mixer(p, w.top_k, Q, io).y.clone()
+    for s in (1, 37, 64, Q - 1, Q, Q + 32 + 5, 2 * Q + 49):
+        mod = {}
+        for name, v in p.items():
+            if name in ("x", "dt", "B_experts", "C_experts", "router_logits"):
+                mod[name] = np.concatenate([v[:, :s], q[name][:, s:]], axis=1)
+            else:
+                mod[name] = v
+        got = run_mixer(mod, w.top_k, Q, io).y
+        assert torch.equal(got[:, :s], base[:, :s]), s
+        assert not torch.equal(got[:, s:], base[:, s:]), s
+
+
+@pytest.mark.parametrize("io,P,N,Q", [("bf16", 64, 128, 256), ("f32", 16, 16, 64)])
+def test_linearity_in_x(io, P, N, Q):
+    """y(a x1 + b x2) = a y(x1) + b y(x2) with everything else fixed (paper: for given router
+    weights and streams the layer is a linear map of x), to the path's tolerance; D = NULL and
+    D given.  a and b are powers of two, so the combined input is rounded once."""
+    w = synth.Workload("lin", 2, Q + 70, 4, P, N, 1, 4, 2, Q, io, 7)
+    p = synth.make_inputs(w, seed=31)
+    x2 = synth.make_inputs(w, seed=32)["x"]
+    a, b = 0.5, -2.0
+    comb = dict(p)
+    comb["x"] = synth.to_storage(a * p["x"] + b * x2, io)
+    for d_none in (True, False):
+        ref = oracle_fwd(comb, w.top_k, d_none=d_none)["y"]
+        y1 = host(run_mixer(p, w.top_k, Q, io, d_none=d_none).y)
+        y2 = host(run_mixer(dict(p, x=x2), w.top_k, Q, io, d_none=d_none).y)
+        yc = host(run_mixer(comb, w.top_k, Q, io, d_none=d_none).y)
+        l2, linf = rel_errors(yc, ref, (0, 2))
+        assert l2 <= TOL[io] and linf <= TOL[io], (d_none, l2, linf)
+        # the linear combination of two GPU outputs carries both outputs' rounding errors
+        l2, linf = rel_errors(a * y1 + b * y2, ref, (0, 2))
+        assert l2 <= 2 * TOL[io] and linf <= 2 * TOL[io], (d_none, l2, linf)
 
 
 def test_split_sequence_resume_and_determinism():

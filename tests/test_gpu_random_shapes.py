@@ -9,7 +9,7 @@ import torch
 from oracle import swimba_oracle as orc
 from paper_2603_06938_amd import binding as sw
 from paper_2603_06938_amd import synth
-from gpu_util import TOL, host, rel_errors, to_device
+from gpu_util import TOL, abs_inputs, comp_tol, componentwise_excess, host, rel_errors, to_device
 
 pytestmark = pytest.mark.gpu
 
@@ -27,6 +27,22 @@ def random_cases(n, seed, min_len=1):
         k = int(rng.integers(1, min(E, 6) + 1))
         cases.append((B, L, H, G, E, k, Q, bool(rng.integers(0, 2)), bool(rng.integers(0, 2)), 1000 + i))
     return cases
+
+
+# Slices of fewer tokens than this are held to the componentwise bound only.  The norm of such a
+# slice of y is made of a handful of scalars Cmix_t . Bmix_s, each a sum of N products of either
+# sign whose value can come out far below the size of its terms, while the rounding error
+# follows the terms: error / norm is then a ratio with a heavy tail (for one scalar,
+# P(ratio > 10 x typical) is about 8 %), whatever the kernel does.  Seen on the case
+# B3 L2 H8 G4 E4 k3 Q128 (P 24, N 120, projected from 48 features): worst slice 1.84e-2 against a
+# typical 4e-3, while every element sits at 8e-4 of its own sum of absolute products.
+MIN_TOKENS_NORMWISE = 16
+
+
+def assert_normwise(L, l2, linf, hl2, hlinf):
+    if L >= MIN_TOKENS_NORMWISE:
+        assert l2 <= TOL["bf16"] and linf <= TOL["bf16"], (l2, linf)
+    assert hl2 <= TOL["bf16"] and hlinf <= TOL["bf16"], (hl2, hlinf)
 
 
 def head_dim_of(seed):
@@ -59,15 +75,18 @@ def test_random_mfma_shapes_match_oracle(case):
     np.testing.assert_allclose(host(out.topk_w), ref["topk_w"], rtol=1e-5, atol=1e-30)
     l2, linf = rel_errors(host(out.y), ref["y"], (0, 2))
     hl2, hlinf = rel_errors(host(out.h_final), ref["h_final"], (0, 1))
-    print(case, "P", P, "N", N, "y l2 %.2e linf %.2e  h_final l2 %.2e" % (l2, linf, hl2), flush=True)
-    assert l2 <= TOL["bf16"] and linf <= TOL["bf16"], (l2, linf)
-    assert hl2 <= TOL["bf16"] and hlinf <= TOL["bf16"], (hl2, hlinf)
+    q = abs_inputs(p)
+    aref = orc.mixer_fwd(q["x"], q["dt"], q["A"], None if D is None else np.abs(D), q["B_experts"], q["C_experts"],
+                         q["router_logits"], k, h0=None if h0 is None else np.abs(h0))
+    ey = componentwise_excess(host(out.y), ref["y"], aref["y"])
+    eh = componentwise_excess(host(out.h_final), ref["h_final"], aref["h_final"])
+    print(case, "P", P, "N", N, "y l2 %.2e linf %.2e  h_final l2 %.2e  componentwise %.2e %.2e" % (l2, linf, hl2, ey, eh),
+          flush=True)
+    assert ey <= comp_tol("bf16") and eh <= comp_tol("bf16"), (ey, eh)
+    assert_normwise(L, l2, linf, hl2, hlinf)
 
 
-# at least 16 tokens: the projected streams are rounded to bf16 on the way (two more roundings per
-# product than with given streams), and the worst (batch, head) slice of a 2-token output is a
-# noisy statistic right at the bar
-@pytest.mark.parametrize("case", random_cases(10, 77, min_len=16), ids=lambda c: "B%dL%dH%dG%dE%dk%dQ%d_h0%d_D%d_s%d" % c)
+@pytest.mark.parametrize("case", random_cases(10, 77), ids=lambda c: "B%dL%dH%dG%dE%dk%dQ%d_h0%d_D%d_s%d" % c)
 def test_random_features_to_y_match_oracle_chain(case):
     B, L, H, G, E, k, Q, with_h0, with_D, seed = case
     P, N = head_dim_of(seed + 3), state_size_of(seed + 1)
@@ -93,9 +112,67 @@ def test_random_features_to_y_match_oracle_chain(case):
     np.testing.assert_array_equal(out.topk_idx.cpu().numpy(), ref["topk_idx"])
     l2, linf = rel_errors(host(out.y), ref["y"], (0, 2))
     hl2, hlinf = rel_errors(host(out.h_final), ref["h_final"], (0, 1))
-    print(case, "P", P, "N", N, "Dm", Dm, "y l2 %.2e linf %.2e  h_final l2 %.2e" % (l2, linf, hl2), flush=True)
-    assert l2 <= TOL["bf16"] and linf <= TOL["bf16"], (l2, linf)
-    assert hl2 <= TOL["bf16"] and hlinf <= TOL["bf16"], (hl2, hlinf)
+    aB, aC = np.abs(rp["B_experts"]).astype(np.float32), np.abs(rp["C_experts"]).astype(np.float32)
+    aref = orc.mixer_fwd(np.abs(p["x"]), p["dt"], p["A"], None if D is None else np.abs(D), aB, aC, g, k,
+                         h0=None if h0 is None else np.abs(h0))
+    # the projected streams are stored in bf16 before they are mixed: one more rounding on each
+    # side of every product than with given streams
+    ctol = comp_tol("bf16", roundings=7)
+    ey = componentwise_excess(host(out.y), ref["y"], aref["y"])
+    eh = componentwise_excess(host(out.h_final), ref["h_final"], aref["h_final"])
+    print(case, "P", P, "N", N, "Dm", Dm, "y l2 %.2e linf %.2e  h_final l2 %.2e  componentwise %.2e %.2e"
+          % (l2, linf, hl2, ey, eh), flush=True)
+    assert ey <= ctol and eh <= ctol, (ey, eh)
+    assert_normwise(L, l2, linf, hl2, hlinf)
+
+
+@pytest.mark.parametrize("L", [1, 2, 3, 5, 8, 15])
+def test_short_sequences_hold_the_componentwise_bound(L):
+    """Sequences shorter than MIN_TOKENS_NORMWISE through both the forward on given streams and the
+    features-to-y call: every element of y and h_final within the forward error bound of its own sum
+    of products (5 roundings with given streams, 7 with projected ones), active sets exact."""
+    for seed in range(4):
+        B, H, G, E, k, Q = 3, 8, 4, 4, 3, (64, 128, 256)[seed % 3]
+        P, N = head_dim_of(seed + 3), state_size_of(seed + 1)
+        rng = np.random.default_rng(900 + 10 * L + seed)
+        Dm = int(rng.choice([16, 48, 64]))
+        rd = synth.round_to_bf16
+        u = rd(rng.standard_normal((B, L, Dm)).astype(np.float32))
+        WB = rd((rng.standard_normal((E, G, N, Dm)) / np.sqrt(Dm)).astype(np.float32))
+        WC = rd((rng.standard_normal((E, G, N, Dm)) / np.sqrt(Dm)).astype(np.float32))
+        w = synth.Workload("short", B, L, H, P, N, G, E, k, Q, "bf16", 7)
+        p = synth.make_inputs(w, seed=700 + seed)
+        g = p["router_logits"]
+        D = rng.standard_normal(H).astype(np.float32)
+        h0 = (0.1 * rng.standard_normal((B, H, P, N))).astype(np.float32) if seed % 2 else None
+        ah0 = None if h0 is None else np.abs(h0)
+        h0d = None if h0 is None else torch.from_numpy(h0).to("cuda:0")
+        bf = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(torch.bfloat16).to("cuda:0")
+        # given streams
+        d = to_device(p, "bf16")
+        out = sw.swimba_mixer_fwd(d["x"], d["dt"], d["A"], torch.from_numpy(D).to("cuda:0"), d["B_experts"],
+                                  d["C_experts"], d["router_logits"], k, Q, h0d, want_topk=True)
+        torch.cuda.synchronize()
+        ref = orc.mixer_fwd(p["x"], p["dt"], p["A"], D, p["B_experts"], p["C_experts"], g, k, h0=h0)
+        q = abs_inputs(p)
+        aref = orc.mixer_fwd(q["x"], q["dt"], q["A"], np.abs(D), q["B_experts"], q["C_experts"], g, k, h0=ah0)
+        np.testing.assert_array_equal(out.topk_idx.cpu().numpy(), ref["topk_idx"])
+        ey = componentwise_excess(host(out.y), ref["y"], aref["y"])
+        eh = componentwise_excess(host(out.h_final), ref["h_final"], aref["h_final"])
+        assert ey <= comp_tol("bf16") and eh <= comp_tol("bf16"), ("given", L, seed, ey, eh)
+        # projected streams
+        rp = orc.expert_proj(u, WB, WC, g, k, fill=0.0)
+        rB, rC = rp["B_experts"].astype(np.float32), rp["C_experts"].astype(np.float32)
+        ref = orc.mixer_fwd(p["x"], p["dt"], p["A"], D, rB, rC, g, k, h0=h0)
+        aref = orc.mixer_fwd(q["x"], q["dt"], q["A"], np.abs(D), np.abs(rB), np.abs(rC), g, k, h0=ah0)
+        out = sw.swimba_mixer_fwd_proj(bf(u), bf(WB), bf(WC), d["x"], d["dt"], d["A"], torch.from_numpy(D).to("cuda:0"),
+                                       d["router_logits"], k, Q, h0d, want_topk=True)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(out.topk_idx.cpu().numpy(), ref["topk_idx"])
+        ey2 = componentwise_excess(host(out.y), ref["y"], aref["y"])
+        eh2 = componentwise_excess(host(out.h_final), ref["h_final"], aref["h_final"])
+        print("L", L, "seed", seed, "given %.2e %.2e  projected %.2e %.2e" % (ey, eh, ey2, eh2), flush=True)
+        assert ey2 <= comp_tol("bf16", 7) and eh2 <= comp_tol("bf16", 7), ("projected", L, seed, ey2, eh2)
 
 
 def random_generic_cases(n, seed):

@@ -152,6 +152,14 @@ def test_later_entry_points_validate_on_the_host():
         assert fn(ctypes.byref(d), 64, *p[:8], ws + 64, big, None) == 5
         assert fn(ctypes.byref(d), 64, *p[:2], None, *p[3:8], ws, big, None) == 1
         assert fn(ctypes.byref(d), 64, *p[:4], p[4] + 2, *p[5:8], ws, big, None) == 7
+        # outside the MFMA GEMM's shapes (here fp32 io) one token's features sit in LDS: width limit
+        assert fn(ctypes.byref(d), 16400, *p[:8], ws, big, None) == 4
+    assert sw.swimba_expert_proj_workspace_bytes(d, 16384) > 0 and sw.swimba_expert_proj_workspace_bytes(d, 16400) == 0
+    # the GEMM's shapes (bf16, d_model % 16 == 0, (G*N) % 64 == 0) take up to 65536 features
+    dg = dims(io_dtype=1, dstate=64)
+    assert sw.swimba_expert_proj_workspace_bytes(dg, 65536) > 0 and sw.swimba_expert_proj_workspace_bytes(dg, 65552) == 0
+    assert sw.swimba_expert_proj_workspace_bytes(dg, 16392) == 0       # not a multiple of 16: generic kernel
+    assert sw.swimba_mixer_proj_workspace_bytes(d, 16400) == 0
     # forward on selected streams: (dims, x dt A D Bsel Csel w h0 y h_final, ws, bytes, stream)
     assert lib.swimba_mixer_fwd_selected(ctypes.byref(d), *p[:10], None, 0, None) == 5
     assert lib.swimba_mixer_fwd_selected(ctypes.byref(d), *p[:6], None, *p[7:10], ws, big, None) == 1
