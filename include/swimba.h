@@ -65,6 +65,7 @@ typedef enum { SWIMBA_F32 = 0, SWIMBA_BF16 = 1 } swimba_dtype;
 #define SWIMBA_MAX_HEADDIM 256
 #define SWIMBA_MAX_CHUNK 256
 #define SWIMBA_MAX_STEP_TOKENS 64   /* tokens per sequence in one swimba_step_multi call */
+#define SWIMBA_STATIC_SCRATCH_BYTES (1u << 20) /* scratch held inside the library for swimba_step_static */
 #define SWIMBA_MAX_DMODEL_GENERIC 16384 /* feature width of the projection outside its MFMA shapes */
 
 typedef struct {
@@ -332,6 +333,25 @@ swimba_status swimba_step(const swimba_dims *dims, const float *state_in, float 
                           const void *B_experts, const void *C_experts, const void *router_logits,
                           void *y, int32_t *topk_idx, void *workspace, size_t workspace_bytes,
                           void *hip_stream);
+
+/*
+ * swimba_step for callers that cannot allocate or pass a workspace: code under HIP graph
+ * capture set up elsewhere, tight serving loops, harnesses that forbid hipMalloc.  Same
+ * arguments, kernels and results (bitwise) as swimba_step, without the workspace pair: the
+ * step's mixed streams (B*G*N*2 fp32) live in a device array inside the library, of
+ * SWIMBA_STATIC_SCRATCH_BYTES bytes per GPU the library runs on (held until the process ends).
+ * A step that needs more (swimba_step_workspace_bytes(dims) > SWIMBA_STATIC_SCRATCH_BYTES, i.e.
+ * B*G*N > 131072) is refused with SWIMBA_ERR_UNSUPPORTED and enqueues nothing.  The call
+ * allocates and frees nothing; the first call on a device looks the array's address up once.
+ * Every call on a GPU uses that GPU's one array (each call overwrites all of what it reads, so
+ * nothing carries over from the previous call): calls that overlap on one GPU - different
+ * streams, or different host threads without ordering between them - race; calls on one
+ * stream are ordered and safe.
+ */
+swimba_status swimba_step_static(const swimba_dims *dims, const float *state_in, float *state_out,
+                                 const void *x, const void *dt, const float *A, const float *D,
+                                 const void *B_experts, const void *C_experts, const void *router_logits,
+                                 void *y, int32_t *topk_idx, void *hip_stream);
 
 /*
  * Several decode tokens per call (the same recurrence as swimba_step, paper: selective SSM

@@ -102,6 +102,8 @@ def _load():
         lib.swimba_step_workspace_bytes.argtypes = [dp]
         lib.swimba_step.restype = i32
         lib.swimba_step.argtypes = [dp] + [vp] * 11 + [vp, sz, vp]
+        lib.swimba_step_static.restype = i32
+        lib.swimba_step_static.argtypes = [dp] + [vp] * 11 + [vp]
         lib.swimba_probe_copy.restype = i32
         lib.swimba_probe_copy.argtypes = [vp, vp, sz, vp]
         lib.swimba_probe_mfma.restype = i32
@@ -556,6 +558,27 @@ def swimba_step(state, x, dt, A, D, B_experts, C_experts, router_logits, top_k: 
         _ptr(topk_idx, "topk_idx", torch.int32, (B, top_k)),
         _ptr(workspace, "workspace", torch.uint8), workspace.numel(), _stream())
     _check(st, "swimba_step")
+    return StepOut(y, state_out, topk_idx)
+
+
+def swimba_step_static(state, x, dt, A, D, B_experts, C_experts, router_logits, top_k: int, y, *,
+                       state_out=None, topk_idx=None) -> StepOut:
+    """swimba_step on the library's own scratch array: no workspace, and nothing is allocated here
+    either (y, and topk_idx / state_out when wanted, are the caller's tensors)."""
+    B, H, P = x.shape
+    _, E, G, N = B_experts.shape
+    io = x.dtype
+    d = make_dims(B, 1, H, P, N, G, E, top_k, 0, _io_code(x))
+    if state_out is None:
+        state_out = state
+    st = _load().swimba_step_static(
+        ctypes.byref(d), _ptr(state, "state", torch.float32, (B, H, P, N)),
+        _ptr(state_out, "state_out", torch.float32, (B, H, P, N)), _ptr(x, "x", io, (B, H, P)),
+        _ptr(dt, "dt", io, (B, H)), _ptr(A, "A", torch.float32, (H,)), _ptr(D, "D", torch.float32, (H,)),
+        _ptr(B_experts, "B_experts", io, (B, E, G, N)), _ptr(C_experts, "C_experts", io, (B, E, G, N)),
+        _ptr(router_logits, "router_logits", io, (B, E)), _ptr(y, "y", io, (B, H, P)),
+        _ptr(topk_idx, "topk_idx", torch.int32, (B, top_k)), _stream())
+    _check(st, "swimba_step_static")
     return StepOut(y, state_out, topk_idx)
 
 

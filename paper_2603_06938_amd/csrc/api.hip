@@ -781,6 +781,25 @@ swimba_status swimba_step(const swimba_dims *dims, const float *state_in, float 
                        (hipStream_t)hip_stream);
 }
 
+swimba_status swimba_step_static(const swimba_dims *dims, const float *state_in, float *state_out,
+                                 const void *x, const void *dt, const float *A, const float *D,
+                                 const void *B_experts, const void *C_experts, const void *router_logits,
+                                 void *y, int32_t *topk_idx, void *hip_stream)
+{
+    swimba_status st = check_common(dims);
+    if (st != SWIMBA_OK) return st;
+    if (dims->seqlen != 1) return SWIMBA_ERR_SHAPE;
+    if (swimba_step_workspace_bytes(dims) > SWIMBA_STATIC_SCRATCH_BYTES) return SWIMBA_ERR_UNSUPPORTED;
+    if (dims->batch == 0) return SWIMBA_OK;
+    if (!state_in || !state_out || !x || !dt || !A || !B_experts || !C_experts || !router_logits || !y)
+        return SWIMBA_ERR_NULL;
+    if (check_align(dims->io_dtype, {state_in, state_out, x, B_experts, C_experts, y}, {dt, router_logits},
+                    {A, D, topk_idx}) != SWIMBA_OK)
+        return SWIMBA_ERR_ALIGNMENT;
+    return launch_step_static(make_shape(dims), dims->io_dtype, state_in, state_out, x, dt, A, D, B_experts,
+                              C_experts, router_logits, y, topk_idx, (hipStream_t)hip_stream);
+}
+
 size_t swimba_step_multi_workspace_bytes(const swimba_dims *dims)
 {
     if (check_common(dims) != SWIMBA_OK || dims->seqlen < 1 || dims->seqlen > SWIMBA_MAX_STEP_TOKENS) return 0;

@@ -112,6 +112,10 @@ swimba_status launch_step(const Shape &s, int io_dtype, const float *state_in, f
                           const void *x, const void *dt, const float *A, const float *D,
                           const void *Be, const void *Ce, const void *logits, void *y, int32_t *idx,
                           float *bc, hipStream_t st);
+swimba_status launch_step_static(const Shape &s, int io_dtype, const float *state_in, float *state_out,
+                                 const void *x, const void *dt, const float *A, const float *D,
+                                 const void *Be, const void *Ce, const void *logits, void *y, int32_t *idx,
+                                 hipStream_t st);
 swimba_status launch_step_multi(const Shape &s, int io_dtype, const float *state_in, float *state_out,
                                 const void *x, const void *dt, const float *A, const float *D,
                                 const void *Be, const void *Ce, const void *logits, void *y, int32_t *idx,

@@ -8,7 +8,15 @@
 // one that measured fastest for an in-place stream on this chip.
 #include "common.hpp"
 
+#include <atomic>
+
 namespace swimba {
+
+// Scratch of swimba_step_static, the decode step for callers that cannot provide (or allocate) a
+// workspace: the mixed B and C rows of one step, B*G*2N fp32.  One copy per GPU the library runs
+// on, held until the process ends.  In host code the array's name is only a handle for
+// hipGetSymbolAddress; kernels and copies get the address that call returns for the current device.
+static __device__ __align__(256) float scratch[SWIMBA_STATIC_SCRATCH_BYTES / sizeof(float)];
 
 constexpr int STEP_THREADS = 256;
 typedef float __attribute__((ext_vector_type(4))) f32x4_t;
@@ -278,6 +286,39 @@ swimba_status launch_step_multi(const Shape &s, int io_dtype, const float *state
     if (io_dtype == SWIMBA_BF16)
         return launch_step_multi_t<bf16>(s, state_in, state_out, x, dt, A, D, Be, Ce, logits, y, idx, bc, st);
     return launch_step_multi_t<float>(s, state_in, state_out, x, dt, A, D, Be, Ce, logits, y, idx, bc, st);
+}
+
+// Device address of `scratch` on the current device, looked up once per device.
+static swimba_status static_scratch(float **out)
+{
+    constexpr int MAXDEV = 64;
+    static std::atomic<float *> ptr[MAXDEV];
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) { set_last_hip_error((int)e); return SWIMBA_ERR_HIP; }
+    if (dev < 0 || dev >= MAXDEV) return SWIMBA_ERR_UNSUPPORTED;
+    float *p = ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        e = hipGetSymbolAddress((void **)&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !p) { set_last_hip_error((int)e); return SWIMBA_ERR_HIP; }
+        ptr[dev].store(p, std::memory_order_release);   // every thread that gets here stores the same address
+    }
+    *out = p;
+    return SWIMBA_OK;
+}
+
+swimba_status launch_step_static(const Shape &s, int io_dtype, const float *state_in, float *state_out,
+                                 const void *x, const void *dt, const float *A, const float *D,
+                                 const void *Be, const void *Ce, const void *logits, void *y, int32_t *idx,
+                                 hipStream_t st)
+{
+    if ((int64_t)s.B * s.G * s.N * 2 * (int64_t)sizeof(float) > (int64_t)SWIMBA_STATIC_SCRATCH_BYTES)
+        return SWIMBA_ERR_UNSUPPORTED;
+    float *bc = nullptr;
+    const swimba_status rs = static_scratch(&bc);
+    if (rs != SWIMBA_OK) return rs;
+    // the mix kernel overwrites every element the update kernel reads: nothing has to be cleared
+    return launch_step(s, io_dtype, state_in, state_out, x, dt, A, D, Be, Ce, logits, y, idx, bc, st);
 }
 
 swimba_status launch_step(const Shape &s, int io_dtype, const float *state_in, float *state_out,
