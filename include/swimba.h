@@ -90,6 +90,10 @@ typedef struct {
     size_t bmix_frag; /* (B,nc,G,Q/32,8,64,8) bf16 : mixed B rows, MFMA operand layout   */
     size_t cb;        /* (B,nc,G,NP,2,64,8) bf16 : causal 32x32 tiles of Bmix.Cmix^T in
                          MFMA accumulator layout, NP = (Q/32)(Q/32+1)/2               */
+    size_t cs2;       /* (B,nc,H,Q) fp32 : log2(e) * cs, table of the single-pass kernel */
+    size_t fdec;      /* (B,nc,H,Q) fp32 : dt_j exp(R_J - cs_j), R_J = cs at the end of j's
+                         32-token tile; table of the single-pass kernel                  */
+    size_t cdec;      /* (B,nc,H,Q) fp32 : dt_j exp(cs_last - cs_j); table of the single-pass kernel */
     size_t total;
 } swimba_ws_layout;
 
@@ -146,9 +150,9 @@ swimba_status swimba_router_topk(int64_t tokens, int32_t nexperts, int32_t top_k
  * P <= 64 and N <= 128 (multiples of 8; below 64 x 128 the staged inputs, the mixed rows and the
  * states are zero-padded inside the kernels and the workspace) and Q in {64,128,256} the
  * contractions run on bf16 MFMA
- * with fp32 accumulation (mixed streams, decay-weighted x, the C.B^T block before and
- * after the decay mask, the chunk states and the carried states are rounded to bf16
- * as operands; the inter-chunk recurrence itself runs in fp32);
+ * with fp32 accumulation (mixed streams, decay-weighted x, the C.B^T block, on the diagonal
+ * tiles also after the decay mask, and the state carried into a chunk are rounded to bf16
+ * as operands; the recurrence between chunks itself runs in fp32 registers);
  * other bf16 shapes use the fp32 kernels.
  */
 swimba_status swimba_mixer_fwd(const swimba_dims *dims, const void *x, const void *dt,
@@ -160,7 +164,9 @@ swimba_status swimba_mixer_fwd(const swimba_dims *dims, const void *x, const voi
 /*
  * The stages of swimba_mixer_fwd, one call each, on the same workspace (for
  * per-kernel measurement and stage-level tests).  Running router, cumsum, mix,
- * chunk_state, state_scan, output in this order equals swimba_mixer_fwd.
+ * chunk_state, state_scan, output in this order computes what swimba_mixer_fwd computes
+ * (on the bf16 MFMA path swimba_mixer_fwd itself runs mix, prep, pass: the single-pass
+ * evaluation below, same operands and roundings, another summation order).
  *   router      : logits -> ws.topk_idx, ws.topk_w     (no-op on the bf16 MFMA path: mix routes)
  *   cumsum      : dt, A  -> ws.cs   (per-chunk cumsum of dt*A; no-op on the bf16 MFMA path:
  *                 chunk_state computes it)
@@ -175,7 +181,17 @@ swimba_status swimba_mixer_fwd(const swimba_dims *dims, const void *x, const voi
  *   output      : x, dt, D, B/C_experts, ws.* -> y
  *                 y_i = sum_{j<=i} (Cmix_i.Bmix_j) exp(cs_i - cs_j) dt_j x_j
  *                       + exp(cs_i) Cmix_i . H_c + D x_i
+ * bf16 MFMA path only (SWIMBA_ERR_UNSUPPORTED otherwise), after mix:
+ *   prep        : dt, A, ws.cmix, ws.bmix_frag ->  ws.cb (tiles of Bmix.Cmix^T), ws.cs2, ws.fdec, ws.cdec
+ *   pass        : x, dt, D, h0, ws.{cmix,bmix_t8,cb,cs2,fdec,cdec} -> y, h_final.  One workgroup per
+ *                 (batch, head, 32 channels) walks the chunks in order with the running state
+ *                 in registers: chunk states never reach memory and x is read once.
  */
+swimba_status swimba_stage_prep(const swimba_dims *dims, const void *dt, const float *A, void *workspace,
+                                size_t workspace_bytes, void *hip_stream);
+swimba_status swimba_stage_pass(const swimba_dims *dims, const void *x, const void *dt, const float *D,
+                                const float *h0, void *y, float *h_final, void *workspace,
+                                size_t workspace_bytes, void *hip_stream);
 swimba_status swimba_stage_router(const swimba_dims *dims, const void *router_logits,
                                   void *workspace, size_t workspace_bytes, void *hip_stream);
 swimba_status swimba_stage_cumsum(const swimba_dims *dims, const void *dt, const float *A,

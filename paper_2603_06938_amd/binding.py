@@ -39,7 +39,7 @@ class swimba_dims(ctypes.Structure):
 
 class swimba_ws_layout(ctypes.Structure):
     _fields_ = [(n, ctypes.c_size_t) for n in
-                ("topk_idx", "topk_w", "cs", "states", "states_lp", "cmix", "bmix_t8", "bmix_frag", "cb", "total")]
+                ("topk_idx", "topk_w", "cs", "states", "states_lp", "cmix", "bmix_t8", "bmix_frag", "cb", "cs2", "fdec", "cdec", "total")]
 
 
 def _load():
@@ -72,6 +72,10 @@ def _load():
         lib.swimba_stage_state_scan.argtypes = [dp, vp, vp, vp, sz, vp]
         lib.swimba_stage_output.restype = i32
         lib.swimba_stage_output.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        lib.swimba_stage_prep.restype = i32
+        lib.swimba_stage_prep.argtypes = [dp, vp, vp, vp, sz, vp]
+        lib.swimba_stage_pass.restype = i32
+        lib.swimba_stage_pass.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         lib.swimba_separated_workspace_bytes.restype = sz
         lib.swimba_separated_workspace_bytes.argtypes = [dp]
         lib.swimba_separated_fwd.restype = i32
@@ -496,6 +500,20 @@ def swimba_stage_output(dims, x, dt, D, B_experts, C_experts, y, workspace):
                                        _ptr(C_experts, "C_experts"), _ptr(y, "y"),
                                        _ptr(workspace, "workspace", torch.uint8), workspace.numel(),
                                        _stream()), "swimba_stage_output")
+
+
+def swimba_stage_prep(dims, dt, A, workspace):
+    _check(_load().swimba_stage_prep(ctypes.byref(dims), _ptr(dt, "dt"), _ptr(A, "A", torch.float32),
+                                     _ptr(workspace, "workspace", torch.uint8), workspace.numel(), _stream()),
+           "swimba_stage_prep")
+
+
+def swimba_stage_pass(dims, x, dt, D, h0, y, h_final, workspace):
+    _check(_load().swimba_stage_pass(ctypes.byref(dims), _ptr(x, "x"), _ptr(dt, "dt"), _ptr(D, "D", torch.float32),
+                                     _ptr(h0, "h0", torch.float32), _ptr(y, "y"),
+                                     _ptr(h_final, "h_final", torch.float32),
+                                     _ptr(workspace, "workspace", torch.uint8), workspace.numel(), _stream()),
+           "swimba_stage_pass")
 
 
 def workspace_views(dims: swimba_dims, workspace: torch.Tensor):

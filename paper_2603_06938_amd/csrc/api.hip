@@ -3,6 +3,7 @@
 
 #include <string.h>
 
+#include <atomic>
 #include <initializer_list>
 
 namespace swimba {
@@ -85,7 +86,35 @@ static void layout_of(const swimba_dims *d, swimba_ws_layout *o)
     if (mf) off = align_up(off + mixed, 256);
     o->cb = off;
     if (mf) off = align_up(off + (size_t)s.B * s.nc * s.G * (nt * (nt + 1) / 2) * 2048, 256);
+    o->cs2 = off;
+    if (mf) off = align_up(off + (size_t)s.B * s.nc * s.H * s.Q * sizeof(float), 256);
+    o->fdec = off;
+    if (mf) off = align_up(off + (size_t)s.B * s.nc * s.H * s.Q * sizeof(float), 256);
+    o->cdec = off;
+    if (mf) off = align_up(off + (size_t)s.B * s.nc * s.H * s.Q * sizeof(float), 256);
     o->total = off > 0 ? off : 256;
+}
+
+// Which evaluation of the SSD part swimba_mixer_fwd takes on the bf16 MFMA path.  The single pass
+// keeps one workgroup per (batch, head, 32 channels) busy for the whole sequence: it needs about
+// one such chain per compute unit and enough chunks per chain to pay off; with fewer chains most
+// of the chip idles, with more they run in rounds and the staged kernels (which also parallelise
+// over chunks) are faster.  Measured on MI355X: 342 us against 454 us at B2 L16384 H64 (256 chains,
+// 64 chunks), 195 against 190 at B8 L4096 H32 (512 chains), 97 against 75 at B8 L2048 H24 (384).
+static bool use_single_pass(const swimba_dims *d)
+{
+    static std::atomic<int> ncu_cache{0};
+    int ncu = ncu_cache.load(std::memory_order_relaxed);
+    if (ncu == 0) {
+        int dev = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || ncu <= 0)
+            return false;
+        ncu_cache.store(ncu, std::memory_order_relaxed);
+    }
+    const int64_t chains = (int64_t)d->batch * d->nheads * ((d->headdim + 31) / 32);
+    const int64_t nc = ((int64_t)d->seqlen + d->chunk - 1) / d->chunk;
+    return chains <= ncu && 4 * chains >= 3 * (int64_t)ncu && nc >= 16;
 }
 
 struct Ws {
@@ -94,6 +123,7 @@ struct Ws {
     float *cs;
     float *states;
     void *states_lp, *cmix, *bmix_t8, *bmix_frag, *cb;
+    float *cs2, *fdec, *cdec;
 };
 
 static swimba_status carve(const swimba_dims *d, void *workspace, size_t bytes, Ws *ws)
@@ -114,6 +144,9 @@ static swimba_status carve(const swimba_dims *d, void *workspace, size_t bytes, 
     ws->bmix_t8 = mf ? (void *)(p + lo.bmix_t8) : nullptr;
     ws->bmix_frag = mf ? (void *)(p + lo.bmix_frag) : nullptr;
     ws->cb = mf ? (void *)(p + lo.cb) : nullptr;
+    ws->cs2 = mf ? (float *)(p + lo.cs2) : nullptr;
+    ws->fdec = mf ? (float *)(p + lo.fdec) : nullptr;
+    ws->cdec = mf ? (float *)(p + lo.cdec) : nullptr;
     return SWIMBA_OK;
 }
 
@@ -262,6 +295,35 @@ swimba_status swimba_stage_output(const swimba_dims *dims, const void *x, const 
                                  ws.w, ws.cs, ws.states, y, nullptr, 0, 0, (hipStream_t)hip_stream);
 }
 
+swimba_status swimba_stage_prep(const swimba_dims *dims, const void *dt, const float *A, void *workspace,
+                                size_t workspace_bytes, void *hip_stream)
+{
+    Ws ws;
+    swimba_status st = carve(dims, workspace, workspace_bytes, &ws);
+    if (st != SWIMBA_OK) return st;
+    if (!use_mfma_path(dims)) return SWIMBA_ERR_UNSUPPORTED;
+    if ((int64_t)dims->batch * dims->seqlen == 0) return SWIMBA_OK;
+    if (!dt || !A) return SWIMBA_ERR_NULL;
+    if (check_align(dims->io_dtype, {}, {dt}, {A}) != SWIMBA_OK) return SWIMBA_ERR_ALIGNMENT;
+    return launch_prep_mfma(make_shape(dims), dt, A, ws.cmix, ws.bmix_frag, ws.cb, ws.cs2, ws.fdec, ws.cdec,
+                            (hipStream_t)hip_stream);
+}
+
+swimba_status swimba_stage_pass(const swimba_dims *dims, const void *x, const void *dt, const float *D,
+                                const float *h0, void *y, float *h_final, void *workspace,
+                                size_t workspace_bytes, void *hip_stream)
+{
+    Ws ws;
+    swimba_status st = carve(dims, workspace, workspace_bytes, &ws);
+    if (st != SWIMBA_OK) return st;
+    if (!use_mfma_path(dims)) return SWIMBA_ERR_UNSUPPORTED;
+    if ((int64_t)dims->batch * dims->seqlen == 0) return SWIMBA_OK;
+    if (!x || !dt || !y) return SWIMBA_ERR_NULL;
+    if (check_align(dims->io_dtype, {x, y, h0, h_final}, {dt}, {D}) != SWIMBA_OK) return SWIMBA_ERR_ALIGNMENT;
+    return launch_pass_mfma(make_shape(dims), x, dt, D, ws.cmix, ws.bmix_t8, ws.cb, ws.cs2, ws.fdec, ws.cdec, h0, h_final,
+                            y, (hipStream_t)hip_stream);
+}
+
 swimba_status swimba_mixer_fwd(const swimba_dims *dims, const void *x, const void *dt,
                                const float *A, const float *D, const void *B_experts,
                                const void *C_experts, const void *router_logits, const float *h0,
@@ -300,6 +362,14 @@ swimba_status swimba_mixer_fwd(const swimba_dims *dims, const void *x, const voi
             if (e == hipSuccess && topk_w)
                 e = hipMemcpyAsync(topk_w, ws.w, n * sizeof(float), hipMemcpyDeviceToDevice, stream);
             if (e != hipSuccess) { set_last_hip_error((int)e); return SWIMBA_ERR_HIP; }
+        }
+        if (mf && use_single_pass(dims)) {
+            // single pass: G^T tiles and cumsum tables, then one walk over the chunks per
+            // (batch, head, 32 channels) with the state in registers
+            st = launch_prep_mfma(s, dt, A, ws.cmix, ws.bmix_frag, ws.cb, ws.cs2, ws.fdec, ws.cdec, stream);
+            if (st != SWIMBA_OK) return st;
+            return launch_pass_mfma(s, x, dt, D, ws.cmix, ws.bmix_t8, ws.cb, ws.cs2, ws.fdec, ws.cdec, h0, h_final, y,
+                                    stream);
         }
         st = swimba_stage_chunk_state(dims, x, dt, A, B_experts, workspace, workspace_bytes, hip_stream);
         if (st != SWIMBA_OK) return st;
@@ -639,6 +709,12 @@ static swimba_status mixer_selected_core(const swimba_dims *dims, const void *x,
             st = launch_mix_rows_mfma(s, B_sel, C_sel, nullptr, nullptr, nullptr, ws.cmix, ws.bmix_frag,
                                       ws.bmix_t8, -1, -1, w_sel, stream);
             if (st != SWIMBA_OK) return st;
+            if (use_single_pass(dims)) {
+                st = launch_prep_mfma(s, dt, A, ws.cmix, ws.bmix_frag, ws.cb, ws.cs2, ws.fdec, ws.cdec, stream);
+                if (st != SWIMBA_OK) return st;
+                return launch_pass_mfma(s, x, dt, D, ws.cmix, ws.bmix_t8, ws.cb, ws.cs2, ws.fdec, ws.cdec, h0, h_final, y,
+                                        stream);
+            }
             st = launch_chunk_state_mfma(s, x, dt, A, ws.bmix_t8, ws.cs, ws.states_lp, stream);
         } else {
             st = launch_slot_ids(ws.idx, T, dims->top_k, stream);

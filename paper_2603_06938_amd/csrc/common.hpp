@@ -108,6 +108,12 @@ swimba_status launch_output_mfma(const Shape &s, const void *x, const void *dt, 
                                  const void *cmix, const void *cb, const float *cs,
                                  const void *states_lp, void *y, const float *skip_w, int skip_stride,
                                  int accumulate, hipStream_t st);
+// single-pass forward (fused_pass.hip)
+swimba_status launch_prep_mfma(const Shape &s, const void *dt, const float *A, const void *cmix, const void *bfrag,
+                               void *cb, float *cs2, float *fdec, float *cdec, hipStream_t st);
+swimba_status launch_pass_mfma(const Shape &s, const void *x, const void *dt, const float *D, const void *cmix,
+                               const void *bt8, const void *cb, const float *cs2, const float *fdec,
+                               const float *cdec, const float *h0, float *h_final, void *y, hipStream_t st);
 swimba_status launch_step(const Shape &s, int io_dtype, const float *state_in, float *state_out,
                           const void *x, const void *dt, const float *A, const float *D,
                           const void *Be, const void *Ce, const void *logits, void *y, int32_t *idx,

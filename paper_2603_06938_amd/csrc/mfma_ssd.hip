@@ -21,81 +21,11 @@
 // The k index of a contraction may be permuted freely as long as A and B use
 // the same permutation; this is used to read 16 contiguous bytes per operand.
 #include "common.hpp"
+#include "mfma_util.hpp"
 
 #include <atomic>
 
 namespace swimba {
-
-typedef __attribute__((ext_vector_type(8))) __bf16 bf16x8_t;
-typedef __attribute__((ext_vector_type(2))) __bf16 bf16x2_t;
-typedef __attribute__((ext_vector_type(2))) float f32x2_t;
-typedef __attribute__((ext_vector_type(16))) float f32x16_t;
-
-constexpr int MP = 64;    // headdim
-constexpr int MN = 128;   // state size
-constexpr int MTHREADS = 256;
-
-__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi)
-{
-    f32x2_t f = {lo, hi};
-    bf16x2_t h = __builtin_convertvector(f, bf16x2_t);   // round to nearest even
-    return __builtin_bit_cast(uint32_t, h);
-}
-__device__ __forceinline__ float bf_lo(uint32_t u) { return __uint_as_float(u << 16); }
-__device__ __forceinline__ float bf_hi(uint32_t u) { return __uint_as_float(u & 0xffff0000u); }
-
-__device__ __forceinline__ f32x16_t mfma32(uint4 a, uint4 b, f32x16_t c)
-{
-    return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8_t, a),
-                                                   __builtin_bit_cast(bf16x8_t, b), c, 0, 0, 0);
-}
-
-// acc[0..7] += wgt * (8 bf16 values packed in u)
-__device__ __forceinline__ void fma_bf16x8(float *acc, uint4 u, float wgt)
-{
-    acc[0] += wgt * bf_lo(u.x); acc[1] += wgt * bf_hi(u.x);
-    acc[2] += wgt * bf_lo(u.y); acc[3] += wgt * bf_hi(u.y);
-    acc[4] += wgt * bf_lo(u.z); acc[5] += wgt * bf_hi(u.z);
-    acc[6] += wgt * bf_lo(u.w); acc[7] += wgt * bf_hi(u.w);
-}
-__device__ __forceinline__ void unpack8(float *a, uint4 u)
-{
-    a[0] = bf_lo(u.x); a[1] = bf_hi(u.x); a[2] = bf_lo(u.y); a[3] = bf_hi(u.y);
-    a[4] = bf_lo(u.z); a[5] = bf_hi(u.z); a[6] = bf_lo(u.w); a[7] = bf_hi(u.w);
-}
-__device__ __forceinline__ uint4 pack8(const float *a)
-{
-    return make_uint4(pack_bf16x2(a[0], a[1]), pack_bf16x2(a[2], a[3]), pack_bf16x2(a[4], a[5]),
-                      pack_bf16x2(a[6], a[7]));
-}
-
-// Workgroups are handed to the 8 XCDs round-robin by block id.  This maps a
-// block id to a logical id such that each XCD works on one contiguous range of
-// logical ids (neighbouring heads of one chunk share the group's tiles in that
-// XCD's L2).  The grid is padded to a multiple of 8; ids >= total do nothing.
-__device__ __forceinline__ int xcd_logical_id(int bid, int nblocks)
-{
-    const int per = nblocks >> 3;
-    return (bid & 7) * per + (bid >> 3);
-}
-static inline int xcd_padded(int64_t total) { return (int)((total + 7) / 8 * 8); }
-
-// 16-byte accesses that are not worth caching (read once / written once by this kernel)
-typedef unsigned int __attribute__((ext_vector_type(4))) u32x4_t;
-__device__ __forceinline__ uint4 load_nt(const uint16_t *p)
-{
-    const u32x4_t v = __builtin_nontemporal_load(reinterpret_cast<const u32x4_t *>(p));
-    return make_uint4(v.x, v.y, v.z, v.w);
-}
-__device__ __forceinline__ void store_nt(uint16_t *p, uint4 v)
-{
-    const u32x4_t pv = {v.x, v.y, v.z, v.w};
-    __builtin_nontemporal_store(pv, reinterpret_cast<u32x4_t *>(p));
-}
-
-__device__ __forceinline__ float fast_exp2(float v) { return __builtin_amdgcn_exp2f(v); }
-
-constexpr float LOG2E = 1.4426950408889634f;
 
 // Mixed row of one token for MFMA use: lane (row, kg) gets, for ks = 0..7, the 8
 // values n = 64*kg + 8*ks + 0..7 of  sum_r w_r * S[e_r][g][n]  as packed bf16.
@@ -136,7 +66,9 @@ __device__ __forceinline__ void gather_mix_row(uint4 *frag, const uint16_t *tok,
 // slot-th active expert, Bmix = pi_{t,e_slot} B^(e_slot); Cmix is the full mix.
 //   cmix, bfrag (B, nc, G, NT, 8, 64, 8) bf16, mixed rows of tile I as operand registers:
 //           [ks][lane][e] = mix[32I + lane%32][64*(lane/32) + 8ks + e]
-//   bmix_t8 (B, nc, G, Q/8, N, 8)    bf16, mixed B with 8 consecutive tokens innermost
+//   bmix_t8 (B, nc, G, Q/8, N, 8)    bf16, mixed B with 8 tokens innermost: position 8 o + e of a
+//           chunk holds token t8_token(8 o + e) (tokens 4..7 and 8..11 of every 16 swapped), the
+//           order in which an accumulator tile hands its rows to the next contraction
 // =========================================================================================
 __global__ void __launch_bounds__(MTHREADS)
 mix_rows_kernel(const uint16_t *__restrict__ Be, const uint16_t *__restrict__ Ce,
@@ -277,53 +209,22 @@ mix_rows_kernel(const uint16_t *__restrict__ Be, const uint16_t *__restrict__ Ce
         for (int ks = 0; ks < 8; ++ks)
             *reinterpret_cast<uint4 *>(dst + ks * 64 * 8) = *reinterpret_cast<const uint4 *>(src + ks * 8);
     } else {
-        // mixed B, 8 tokens innermost: lane = state index n, one 16-byte store per token octet
+        // mixed B, 8 tokens innermost (in the operand order of t8_token): lane = state index n,
+        // one 16-byte store per token octet
         const int n = tid - 128;
 #pragma unroll
         for (int jgl = 0; jgl < 4; ++jgl) {
             uint32_t pk[4];
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                const uint32_t lo = s_mix[(jgl * 8 + 2 * q) * MIXROW + n];
-                const uint32_t hi = s_mix[(jgl * 8 + 2 * q + 1) * MIXROW + n];
+                const uint32_t lo = s_mix[t8_token(jgl * 8 + 2 * q) * MIXROW + n];
+                const uint32_t hi = s_mix[t8_token(jgl * 8 + 2 * q + 1) * MIXROW + n];
                 pk[q] = lo | (hi << 16);
             }
             *reinterpret_cast<uint4 *>(bmix_t8 + ((bcg * (s.Q / 8) + tile * 4 + jgl) * MN + n) * 8) =
                 make_uint4(pk[0], pk[1], pk[2], pk[3]);
         }
     }
-}
-
-// =========================================================================================
-// cb tile of one wave: pair p = I(I+1)/2 + J, J <= I, of one (batch, chunk, group):
-//   cb (B, nc, G, NP, 2, 64, 8) bf16: the accumulator registers v = 8t..8t+7 of lane l
-//   of G^T[j][i] = Bmix_j . Cmix_i  (32 x 32 tile)
-// Both operands are read as the register images mix_rows stored.
-// =========================================================================================
-__device__ __forceinline__ void cb_pair(const uint16_t *__restrict__ cmix, const uint16_t *__restrict__ bfrag,
-                                        uint16_t *__restrict__ cb, int NT, int64_t bcg, int p, int lane)
-{
-    const int NP = NT * (NT + 1) / 2;
-    int I = 0;
-    while ((I + 1) * (I + 2) / 2 <= p) ++I;
-    const int J = p - I * (I + 1) / 2;
-    const uint16_t *cs = cmix + (((bcg * NT + I) * 8) * 64 + lane) * 8;
-    const uint16_t *bs = bfrag + (((bcg * NT + J) * 8) * 64 + lane) * 8;
-    uint4 cf[8], bf[8];
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks) {
-        cf[ks] = *reinterpret_cast<const uint4 *>(cs + ks * 64 * 8);
-        bf[ks] = *reinterpret_cast<const uint4 *>(bs + ks * 64 * 8);
-    }
-    f32x16_t acc = {0};
-#pragma unroll
-    for (int ks = 0; ks < 8; ++ks) acc = mfma32(bf[ks], cf[ks], acc);
-    float m[16];
-#pragma unroll
-    for (int v = 0; v < 16; ++v) m[v] = acc[v];
-    uint16_t *dst = cb + ((bcg * NP + p) * 2 * 64 + lane) * 8;
-    *reinterpret_cast<uint4 *>(dst) = pack8(m);
-    *reinterpret_cast<uint4 *>(dst + 64 * 8) = pack8(m + 8);
 }
 
 // =========================================================================================
@@ -502,7 +403,7 @@ chunk_state_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restri
             const int p2 = u & 31, jg = u >> 5;
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                const int j = jg * 8 + e;
+                const int j = t8_token(jg * 8 + e);
                 // raw value: nothing may consume it here, or the loads would be waited for one by
                 // one right after their issue; rows past the sequence end are zeroed when staged
                 xv[it][e] = *reinterpret_cast<const uint32_t *>(xh + min(j, valid - 1) * tokstride);
@@ -543,8 +444,9 @@ chunk_state_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restri
             float xa[8], xb[8];
 #pragma unroll
             for (int e = 0; e < 8; ++e) {
-                const float cf = s_coef[buf * Q + jg * 8 + e];
-                const uint32_t xr = (jg * 8 + e < valid_x) ? xv[it][e] : 0u;
+                const int j = t8_token(jg * 8 + e);
+                const float cf = s_coef[buf * Q + j];
+                const uint32_t xr = (j < valid_x) ? xv[it][e] : 0u;
                 xa[e] = bf_lo(xr) * cf;
                 xb[e] = bf_hi(xr) * cf;
             }

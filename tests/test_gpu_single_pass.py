@@ -1,0 +1,114 @@
+"""The single-pass evaluation (mix, prep, pass through the C ABI) against the oracle on shapes the
+forward's own heuristic would send to the staged kernels: every chunk size, ragged lengths, head
+dimensions and state sizes below the kernels' 64 x 128, groups, initial state, with and without
+the skip term; and against the staged evaluation of the same inputs."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import swimba_oracle as orc
+from paper_2603_06938_amd import binding as sw
+from paper_2603_06938_amd import synth
+from gpu_util import TOL, abs_inputs, comp_tol, componentwise_excess, host, rel_errors, to_device
+
+pytestmark = pytest.mark.gpu
+
+CASES = [
+    # B, L, H, P, N, G, E, k, Q, h0, D
+    (2, 600, 4, 64, 128, 2, 8, 2, 256, True, True),
+    (1, 1100, 6, 64, 128, 1, 8, 2, 256, False, False),     # several chunks, ragged tail
+    (2, 300, 4, 64, 128, 2, 8, 2, 128, True, False),
+    (2, 257, 2, 64, 128, 1, 8, 3, 64, False, True),
+    (1, 31, 2, 64, 128, 1, 4, 2, 256, True, True),          # one short chunk
+    (1, 1, 2, 64, 128, 1, 4, 1, 64, False, True),           # one token
+    (2, 520, 3, 32, 64, 3, 4, 4, 256, True, True),          # one 32-channel slice, padded state
+    (1, 400, 4, 40, 96, 2, 16, 1, 128, False, True),        # second slice partly past P
+    (2, 700, 2, 8, 16, 1, 5, 5, 256, True, False),
+    (1, 2100, 8, 64, 128, 8, 16, 2, 256, False, True),      # the long-sequence layer's grouping, 9 chunks
+]
+
+
+def single_pass(d, dims, D, h0, k, Q):
+    ws = sw.alloc_workspace(dims, "cuda:0")
+    y = torch.full_like(d["x"], float("nan"))
+    hf = torch.full((dims.batch, dims.nheads, dims.headdim, dims.dstate), float("nan"), device="cuda:0")
+    sw.swimba_stage_mix(dims, d["B_experts"], d["C_experts"], d["router_logits"], ws)
+    sw.swimba_stage_prep(dims, d["dt"], d["A"], ws)
+    sw.swimba_stage_pass(dims, d["x"], d["dt"], D, h0, y, hf, ws)
+    torch.cuda.synchronize()
+    return y, hf, ws
+
+
+@pytest.mark.parametrize("case", CASES, ids=lambda c: "B%dL%dH%dP%dN%dG%dE%dk%dQ%d_h0%d_D%d" % c)
+def test_single_pass_matches_oracle(case):
+    B, L, H, P, N, G, E, k, Q, with_h0, with_D = case
+    w = synth.Workload("sp", B, L, H, P, N, G, E, k, Q, "bf16", 7)
+    p = synth.make_inputs(w, seed=hash(case) % 100000)
+    rng = np.random.default_rng(11)
+    p["D"] = rng.standard_normal(H).astype(np.float32)
+    h0 = (0.1 * rng.standard_normal((B, H, P, N))).astype(np.float32) if with_h0 else None
+    D = p["D"] if with_D else None
+    d = to_device(p, "bf16")
+    dims = sw.dims_of(d["x"], d["B_experts"], k, Q)
+    y, hf, ws = single_pass(d, dims, d["D"] if with_D else None,
+                            None if h0 is None else torch.from_numpy(h0).to("cuda:0"), k, Q)
+    ref = orc.mixer_fwd(p["x"], p["dt"], p["A"], D, p["B_experts"], p["C_experts"], p["router_logits"], k, h0=h0)
+    idx = sw.workspace_views(dims, ws)["topk_idx"]
+    np.testing.assert_array_equal(idx.cpu().numpy(), ref["topk_idx"])
+    assert torch.isfinite(y).all() and torch.isfinite(hf).all()
+    q = abs_inputs(p)
+    aref = orc.mixer_fwd(q["x"], q["dt"], q["A"], None if D is None else np.abs(D), q["B_experts"], q["C_experts"],
+                         q["router_logits"], k, h0=None if h0 is None else np.abs(h0))
+    ey = componentwise_excess(host(y), ref["y"], aref["y"])
+    eh = componentwise_excess(host(hf), ref["h_final"], aref["h_final"])
+    l2, linf = rel_errors(host(y), ref["y"], (0, 2))
+    hl2, hlinf = rel_errors(host(hf), ref["h_final"], (0, 1))
+    print(case, "y l2 %.2e linf %.2e  h_final l2 %.2e  componentwise %.2e %.2e" % (l2, linf, hl2, ey, eh), flush=True)
+    assert ey <= comp_tol("bf16") and eh <= comp_tol("bf16"), (ey, eh)
+    if L >= 16:
+        assert l2 <= TOL["bf16"] and linf <= TOL["bf16"], (l2, linf)
+    assert hl2 <= TOL["bf16"] and hlinf <= TOL["bf16"], (hl2, hlinf)
+    # the staged evaluation of the same inputs (the same operands and roundings, another order of
+    # summation): far closer to each other than either is to the exact result
+    out = torch.empty_like(d["x"])
+    hf2 = torch.empty_like(hf)
+    ws2 = sw.alloc_workspace(dims, "cuda:0")
+    sw.swimba_stage_mix(dims, d["B_experts"], d["C_experts"], d["router_logits"], ws2)
+    sw.swimba_stage_chunk_state(dims, d["x"], d["dt"], d["A"], d["B_experts"], ws2)
+    sw.swimba_stage_state_scan(dims, None if h0 is None else torch.from_numpy(h0).to("cuda:0"), hf2, ws2)
+    sw.swimba_stage_output(dims, d["x"], d["dt"], d["D"] if with_D else None, d["B_experts"], d["C_experts"], out, ws2)
+    torch.cuda.synchronize()
+    if L >= 16:
+        l2, linf = rel_errors(host(y), host(out), (0, 2))
+        assert l2 <= TOL["bf16"] and linf <= TOL["bf16"], ("staged", l2, linf)
+    l2, linf = rel_errors(host(hf), host(hf2), (0, 1))
+    assert l2 <= TOL["bf16"] and linf <= TOL["bf16"], ("staged h_final", l2, linf)
+
+
+def test_single_pass_is_deterministic_and_causal():
+    w = synth.Workload("sp", 2, 600, 4, 64, 128, 2, 8, 2, 256, "bf16", 7)
+    p = synth.make_inputs(w, seed=5)
+    q = synth.make_inputs(w, seed=6)
+    d = to_device(p, "bf16")
+    dims = sw.dims_of(d["x"], d["B_experts"], 2, 256)
+    y1, h1, _ = single_pass(d, dims, d["D"], None, 2, 256)
+    y2, h2, _ = single_pass(d, dims, d["D"], None, 2, 256)
+    assert torch.equal(y1, y2) and torch.equal(h1, h2)
+    for s in (37, 256, 300, 599):
+        mod = {kk: (np.concatenate([v[:, :s], q[kk][:, s:]], axis=1) if kk in ("x", "dt", "B_experts", "C_experts",
+                                                                                 "router_logits") else v)
+               for kk, v in p.items()}
+        dm = to_device(mod, "bf16")
+        ym, _, _ = single_pass(dm, dims, dm["D"], None, 2, 256)
+        assert torch.equal(ym[:, :s], y1[:, :s]), s
+
+
+def test_stage_calls_refuse_the_fp32_path():
+    dev = "cuda:0"
+    x = torch.zeros((1, 64, 2, 16), device=dev)
+    Be = torch.zeros((1, 64, 3, 1, 16), device=dev)
+    dims = sw.dims_of(x, Be, 2, 32)
+    ws = sw.alloc_workspace(dims, dev)
+    with pytest.raises(sw.SwimbaError) as e:
+        sw.swimba_stage_prep(dims, torch.ones((1, 64, 2), device=dev), -torch.ones(2, device=dev), ws)
+    assert e.value.status == 4
