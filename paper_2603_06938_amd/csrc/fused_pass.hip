@@ -35,31 +35,72 @@
 namespace swimba {
 
 // =========================================================================================
-// prep: blocks [0, ncb) compute the G^T tiles (one wave per tile pair); blocks [ncb, ...) the
-// cumsum tables, workgroup = (batch, chunk, block of 16 heads).
+// prep: blocks [0, ncb) compute the G^T tiles (two forms, see the launcher); the blocks behind
+// them the cumsum tables, workgroup = (batch, chunk, block of 16 heads).
 // =========================================================================================
 template <int Q>
 __global__ void __launch_bounds__(MTHREADS)
 prep_kernel(const uint16_t *__restrict__ dt, const float *__restrict__ A, const uint16_t *__restrict__ cmix,
             const uint16_t *__restrict__ bfrag, uint16_t *__restrict__ cb, float *__restrict__ cs2,
-            float *__restrict__ fdec, float *__restrict__ cdec, Shape s, int ncb, int64_t nbcg)
+            float *__restrict__ fdec, float *__restrict__ cdec, Shape s, int64_t nbcg, int64_t ncb, int fine)
 {
     constexpr int NT = Q / 32;
-    if ((int)blockIdx.x < ncb) {
-        constexpr int PB = (NT * (NT + 1) / 2 + 3) / 4;
-        const int64_t id = xcd_logical_id(blockIdx.x, ncb);
-        const int64_t bcg = id / PB;
-        const int p = (int)(id % PB) * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-        if (bcg < nbcg && p < NT * (NT + 1) / 2) cb_pair(cmix, bfrag, cb, NT, bcg, p, threadIdx.x & 63);
-        return;
-    }
+    constexpr int NP = NT * (NT + 1) / 2;
     constexpr int HB = 16;                       // heads per workgroup
     constexpr int NSEG = MTHREADS / HB;          // segments a head's tokens are scanned in
-    __shared__ float s_a[Q][HB + 1];             // dt*A, then its cumsum (token-major: conflict-free both ways)
-    __shared__ float s_d[Q][HB + 1];             // dt
-    __shared__ float s_tot[NSEG][HB];
+    // one LDS area for both kinds of workgroup
+    constexpr size_t LDS_CB = (size_t)NT * 8 * 64 * 16;                       // mixed B rows of the chunk
+    constexpr size_t LDS_CUM = (size_t)(2 * Q * (HB + 1) + NSEG * HB) * sizeof(float);
+    __shared__ __align__(16) unsigned char s_raw[LDS_CB > LDS_CUM ? LDS_CB : LDS_CUM];
+    if (fine && (int64_t)blockIdx.x < ncb) {
+        // ---- G^T tiles, one wave per tile pair (few (batch, chunk, group) triples: this form
+        // ---- spreads them over the whole chip) ----
+        constexpr int PB = (NP + 3) / 4;
+        const int64_t id = xcd_logical_id(blockIdx.x, (int)ncb);
+        const int64_t bcg = id / PB;
+        const int p = (int)(id % PB) * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+        if (bcg < nbcg && p < NP) cb_pair(cmix, bfrag, cb, NT, bcg, p, threadIdx.x & 63);
+        return;
+    }
+    if (!fine && (int64_t)blockIdx.x < ncb) {
+        // ---- G^T tiles of one (batch, chunk, group).  The mixed B rows of the whole chunk go
+        // ---- through LDS once (they are the A operand of every pair of their column of tiles);
+        // ---- with eight tiles wave w computes the rows of tiles w and 7-w: nine pairs for every wave.
+        const int64_t bcg = blockIdx.x;
+        const int tid = threadIdx.x, lane = tid & 63;
+        const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+        uint4 *sB = reinterpret_cast<uint4 *>(s_raw);                                    // [NT][8][64]
+        const uint4 *gB = reinterpret_cast<const uint4 *>(bfrag) + bcg * (NT * 8 * 64);
+#pragma unroll
+        for (int i = 0; i < NT * 8 * 64 / MTHREADS; ++i) sB[tid + i * MTHREADS] = gB[tid + i * MTHREADS];
+        __syncthreads();
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            const int I = t == 0 ? wave : NT - 1 - wave;
+            if (I >= NT || (t == 1 && NT < 8)) continue;          // at most four tiles: one per wave
+            uint4 cf[8];
+            const uint16_t *cs = cmix + (((bcg * NT + I) * 8) * 64 + lane) * 8;
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks) cf[ks] = *reinterpret_cast<const uint4 *>(cs + ks * 64 * 8);
+            for (int J = 0; J <= I; ++J) {
+                f32x16_t acc = {0};
+#pragma unroll
+                for (int ks = 0; ks < 8; ++ks) acc = mfma32(sB[(J * 8 + ks) * 64 + lane], cf[ks], acc);
+                float m[16];
+#pragma unroll
+                for (int v = 0; v < 16; ++v) m[v] = acc[v];
+                uint16_t *dst = cb + ((bcg * NP + I * (I + 1) / 2 + J) * 2 * 64 + lane) * 8;
+                *reinterpret_cast<uint4 *>(dst) = pack8(m);
+                *reinterpret_cast<uint4 *>(dst + 64 * 8) = pack8(m + 8);
+            }
+        }
+        return;
+    }
+    float (*s_a)[HB + 1] = reinterpret_cast<float (*)[HB + 1]>(s_raw);                   // dt*A, then its cumsum
+    float (*s_d)[HB + 1] = reinterpret_cast<float (*)[HB + 1]>(s_raw) + Q;               // dt
+    float (*s_tot)[HB] = reinterpret_cast<float (*)[HB]>(reinterpret_cast<float *>(s_raw) + 2 * Q * (HB + 1));
     const int nhb = (s.H + HB - 1) / HB;
-    const int id = blockIdx.x - ncb;
+    const int id = (int)((int64_t)blockIdx.x - ncb);
     const int hb = id % nhb;
     const int c = (id / nhb) % s.nc;
     const int b = id / (nhb * s.nc);
@@ -606,11 +647,15 @@ static swimba_status launch_prep_q(const Shape &s, const void *dt, const float *
     constexpr int NT = Q / 32;
     const int64_t nbcg = (int64_t)s.B * s.nc * s.G;
     if (nbcg == 0) return SWIMBA_OK;
-    const int ncb = xcd_padded(nbcg * ((NT * (NT + 1) / 2 + 3) / 4));
+    // G^T tiles: one workgroup per (batch, chunk, group) with the mixed B rows shared through LDS
+    // where there are enough of them to fill the chip (49 against 55 us on the long-sequence
+    // workload, 1024 triples), one wave per tile pair otherwise (12 against 17 us with 64 triples)
+    const int fine = nbcg < 512;
+    const int64_t ncb = fine ? xcd_padded(nbcg * ((NT * (NT + 1) / 2 + 3) / 4)) : nbcg;
     const int64_t ncum = (int64_t)s.B * s.nc * ((s.H + 15) / 16);
     hipLaunchKernelGGL(prep_kernel<Q>, dim3((unsigned)(ncb + ncum)), dim3(MTHREADS), 0, st, (const uint16_t *)dt, A,
-                       (const uint16_t *)cmix, (const uint16_t *)bfrag, (uint16_t *)cb, cs2, fdec, cdec, s, ncb,
-                       nbcg);
+                       (const uint16_t *)cmix, (const uint16_t *)bfrag, (uint16_t *)cb, cs2, fdec, cdec, s, nbcg, ncb,
+                       fine);
     SWIMBA_CHECK_LAUNCH();
     return SWIMBA_OK;
 }
