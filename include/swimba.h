@@ -192,6 +192,19 @@ swimba_status swimba_stage_prep(const swimba_dims *dims, const void *dt, const f
 swimba_status swimba_stage_pass(const swimba_dims *dims, const void *x, const void *dt, const float *D,
                                 const float *h0, void *y, float *h_final, void *workspace,
                                 size_t workspace_bytes, void *hip_stream);
+
+/* Which kernels swimba_mixer_fwd (and the _selected/_proj forms) run for these dims on the
+ * current device: SWIMBA_PATH_GENERIC (fp32-capable kernels, any shape), SWIMBA_PATH_STAGED
+ * (bf16 MFMA: mix, chunk_state, state_scan, output) or SWIMBA_PATH_SINGLE_PASS (bf16 MFMA: mix,
+ * prep, pass).  The single pass is taken when its (batch, head, 32-channel) chains number between
+ * 3/4 of and all of the device's compute units and the sequence has at least 16 chunks; results
+ * of the two MFMA paths agree to the rounding of their bf16 operands.  Returns minus the
+ * swimba_status for invalid dims.  Host only; launches nothing. */
+#define SWIMBA_PATH_GENERIC 0
+#define SWIMBA_PATH_STAGED 1
+#define SWIMBA_PATH_SINGLE_PASS 2
+int swimba_prefill_path(const swimba_dims *dims);
+
 swimba_status swimba_stage_router(const swimba_dims *dims, const void *router_logits,
                                   void *workspace, size_t workspace_bytes, void *hip_stream);
 swimba_status swimba_stage_cumsum(const swimba_dims *dims, const void *dt, const float *A,

@@ -74,6 +74,8 @@ def _load():
         lib.swimba_stage_output.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         lib.swimba_stage_prep.restype = i32
         lib.swimba_stage_prep.argtypes = [dp, vp, vp, vp, sz, vp]
+        lib.swimba_prefill_path.restype = ctypes.c_int
+        lib.swimba_prefill_path.argtypes = [dp]
         lib.swimba_stage_pass.restype = i32
         lib.swimba_stage_pass.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         lib.swimba_separated_workspace_bytes.restype = sz
@@ -500,6 +502,17 @@ def swimba_stage_output(dims, x, dt, D, B_experts, C_experts, y, workspace):
                                        _ptr(C_experts, "C_experts"), _ptr(y, "y"),
                                        _ptr(workspace, "workspace", torch.uint8), workspace.numel(),
                                        _stream()), "swimba_stage_output")
+
+
+PATH_GENERIC, PATH_STAGED, PATH_SINGLE_PASS = 0, 1, 2
+
+
+def swimba_prefill_path(dims) -> int:
+    """Kernels the forward runs for these dims on the current device (PATH_* values)."""
+    r = _load().swimba_prefill_path(ctypes.byref(dims))
+    if r < 0:
+        _check(-r, "swimba_prefill_path")
+    return r
 
 
 def swimba_stage_prep(dims, dt, A, workspace):

@@ -295,6 +295,14 @@ swimba_status swimba_stage_output(const swimba_dims *dims, const void *x, const 
                                  ws.w, ws.cs, ws.states, y, nullptr, 0, 0, (hipStream_t)hip_stream);
 }
 
+int swimba_prefill_path(const swimba_dims *dims)
+{
+    swimba_status st = check_mixer(dims);
+    if (st != SWIMBA_OK) return -(int)st;
+    if (!use_mfma_path(dims)) return SWIMBA_PATH_GENERIC;
+    return use_single_pass(dims) ? SWIMBA_PATH_SINGLE_PASS : SWIMBA_PATH_STAGED;
+}
+
 swimba_status swimba_stage_prep(const swimba_dims *dims, const void *dt, const float *A, void *workspace,
                                 size_t workspace_bytes, void *hip_stream)
 {

@@ -113,7 +113,10 @@ mix_rows_kernel(const uint16_t *__restrict__ Be, const uint16_t *__restrict__ Ce
     const uint16_t *Cg = Ce + (tok0 * rowsE * s.G + g) * s.N;
 
     // ---- routing of the tile's tokens: logits staged through LDS (one coalesced read) ----
-    if (!sel) {
+    // separated-SSM contrast: the pass of expert 0 routes and stores the routing, the passes of the
+    // other experts read it back instead of repeating softmax and top-k E times per token
+    const bool reuse = sep_e > 0;
+    if (!sel && !reuse) {
         const int nlog = max(0, min(valid, 32)) * s.E;
         const uint16_t *gl = logits + tok0 * s.E;
         for (int i = tid; i < nlog; i += MTHREADS) s_log[(i / s.E) * (s.E + 1) + i % s.E] = to_float(bf16{gl[i]});
@@ -125,6 +128,11 @@ mix_rows_kernel(const uint16_t *__restrict__ Be, const uint16_t *__restrict__ Ce
             for (int rr = 0; rr < Kr; ++rr) {
                 s_idx[t * Kr + rr] = rr;
                 s_w[t * Kr + rr] = (t < valid) ? w_sel[(tok0 + t) * Kr + rr] : 0.f;
+            }
+        } else if (t < valid && reuse) {
+            for (int rr = 0; rr < Kr; ++rr) {
+                s_idx[t * Kr + rr] = idx_out[(tok0 + t) * Kr + rr];
+                s_w[t * Kr + rr] = w_out[(tok0 + t) * Kr + rr];
             }
         } else if (t < valid) {
             const float *gl = s_log + t * (s.E + 1);
