@@ -419,7 +419,7 @@ def main() -> int:
         # the projection overwrote the synthetic expert rows of every set with its own values
         del us, WBs, WCs, pws, fws
 
-    # ---- one input stream per expert: k rank-1 passes through the same kernels ------------------
+    # ---- one input stream per expert (rank-k injection) -------------------------------------------
     xe_res = None
     if args.xe and not args.stage:
         gen = torch.Generator(device=dev)
@@ -436,10 +436,32 @@ def main() -> int:
 
         time_loop(xe_step, 3)
         ms = time_loop(xe_step, max(5, K // 2))
-        xe_res = {"what": "mixed forward with one x stream per expert (rank-%d injection), %d passes" % (k, k),
-                  "ms_per_step": round(ms, 4), "tokens_per_s": round(w.tokens / ms * 1e3, 1),
-                  "slowdown_vs_shared_x": round(ms / ev_ms, 2)}
         del xes, xws
+        # the same forward on the rows of the selected experts only, (B,L,k,...) as a projection
+        # restricted to the active set leaves them: no gather
+        xss = [torch.randn((w.batch, w.seqlen, k, H, P), generator=gen, device=dev, dtype=torch.float32).to(io)
+               for _ in range(2)]
+        Bs_ = [torch.randn((w.batch, w.seqlen, k, G, N), generator=gen, device=dev, dtype=torch.float32).mul_(N ** -0.5).to(io)
+               for _ in range(4)]
+        wsel = torch.rand((w.batch, w.seqlen, k), generator=gen, device=dev, dtype=torch.float32).mul_(0.5)
+        sdims = sw.make_dims(w.batch, w.seqlen, H, P, N, G, k, k, w.chunk, head.dims.io_dtype)
+        sws = torch.empty(sw.swimba_mixer_xe_selected_workspace_bytes(sdims), dtype=torch.uint8, device=dev)
+
+        def xs_step(i):
+            d = head.sets[i % head.nsets]
+            sw.swimba_mixer_fwd_xe_selected(xss[i % 2], d["dt"], d["A"], d["D"], Bs_[i % 2], Bs_[2 + i % 2], wsel,
+                                            w.chunk, None, y=d["y"], h_final=d["h_final"], workspace=sws)
+
+        time_loop(xs_step, 3)
+        sms = time_loop(xs_step, max(5, K // 2))
+        xe_res = {"what": "mixed forward with one x stream per expert (rank-%d injection)" % k,
+                  "dense_input": {"what": "x_experts (B,L,E,H,P), routed inside, rows gathered once",
+                                  "ms_per_step": round(ms, 4), "tokens_per_s": round(w.tokens / ms * 1e3, 1),
+                                  "slowdown_vs_shared_x": round(ms / ev_ms, 2)},
+                  "selected_input": {"what": "x_sel (B,L,k,H,P), B_sel, C_sel, weights given",
+                                     "ms_per_step": round(sms, 4), "tokens_per_s": round(w.tokens / sms * 1e3, 1),
+                                     "slowdown_vs_shared_x": round(sms / ev_ms, 2)}}
+        del xss, Bs_, sws
 
     p_head = head.p
     head_desc, head_nsets, head_path = head.describe(), head.nsets, head.path_name

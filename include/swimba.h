@@ -248,10 +248,21 @@ swimba_status swimba_separated_fwd(const swimba_dims *dims, const void *x, const
  *   h_t = exp(dt_t A_h) h_{t-1} + dt_t sum_{e in K_t} pi_{t,e} x_t^(e) (x) B_t^(e)
  *   y_t = Cmix_t . h_t + D_h xbar_t,   xbar_t = sum_{e in K_t} pi_{t,e} x_t^(e)
  * x_experts (B,L,E,H,P) io; every other argument as in swimba_mixer_fwd.  One state
- * trajectory; the rank-k injection is evaluated as k rank-1 passes through the mixer's
- * kernels (the state is linear in the injection): pass r adds its output to y (in the io
- * dtype) and its final state to h_final (fp32); about k times the time of swimba_mixer_fwd.
+ * trajectory (the state is linear in the injection).  On the bf16 MFMA shapes with
+ * top_k <= 4 the selected rows x^(e_r) are gathered once into (B,L,k,H,P) and every kernel
+ * takes all k slots in one launch: one weighted B image per slot, the chunk states of the
+ * slots summed in fp32 by the scan, one readout of the carried state and one store of y, the
+ * skip term as a contraction with diag(D pi) in two bf16 terms.  Other shapes: k rank-1
+ * passes through the one-stream kernels, pass r adding its output to y (in the io dtype) and
+ * its final state to h_final (fp32), about k times the time of swimba_mixer_fwd.
  *   workspace >= swimba_mixer_xe_workspace_bytes(dims), 256-byte aligned.
+ *
+ * swimba_mixer_fwd_xe_selected: the same forward on the rows of the selected experts only, as
+ * a projection restricted to the active set produces them (no tensor with an expert axis):
+ *   x_sel (B,L,k,H,P) io, B_sel / C_sel (B,L,k,G,N) io, topk_w (B,L,k) fp32 [in]: row r of a
+ *   token belongs to its r-th selected expert, topk_w holds the router weights pi_{t,e_r}.
+ * No gather; otherwise as above (bf16 MFMA shapes with top_k > 4 run on the plain-arithmetic
+ * kernels).  workspace >= swimba_mixer_xe_selected_workspace_bytes(dims), 256-byte aligned.
  */
 size_t swimba_mixer_xe_workspace_bytes(const swimba_dims *dims);
 swimba_status swimba_mixer_fwd_xe(const swimba_dims *dims, const void *x_experts, const void *dt,
@@ -259,6 +270,11 @@ swimba_status swimba_mixer_fwd_xe(const swimba_dims *dims, const void *x_experts
                                   const void *C_experts, const void *router_logits, const float *h0,
                                   void *y, float *h_final, int32_t *topk_idx, float *topk_w,
                                   void *workspace, size_t workspace_bytes, void *hip_stream);
+size_t swimba_mixer_xe_selected_workspace_bytes(const swimba_dims *dims);
+swimba_status swimba_mixer_fwd_xe_selected(const swimba_dims *dims, const void *x_sel, const void *dt,
+                                           const float *A, const float *D, const void *B_sel, const void *C_sel,
+                                           const float *topk_w, const float *h0, void *y, float *h_final,
+                                           void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
  * Routing logits as a linear function of the token features (paper: the expressivity theorem

@@ -104,6 +104,10 @@ def _load():
         lib.swimba_mixer_xe_workspace_bytes.argtypes = [dp]
         lib.swimba_mixer_fwd_xe.restype = i32
         lib.swimba_mixer_fwd_xe.argtypes = [dp] + [vp] * 12 + [vp, sz, vp]
+        lib.swimba_mixer_xe_selected_workspace_bytes.restype = sz
+        lib.swimba_mixer_xe_selected_workspace_bytes.argtypes = [dp]
+        lib.swimba_mixer_fwd_xe_selected.restype = i32
+        lib.swimba_mixer_fwd_xe_selected.argtypes = [dp] + [vp] * 10 + [vp, sz, vp]
         lib.swimba_step_workspace_bytes.restype = sz
         lib.swimba_step_workspace_bytes.argtypes = [dp]
         lib.swimba_step.restype = i32
@@ -428,6 +432,37 @@ def swimba_mixer_fwd_xe(x_experts, dt, A, D, B_experts, C_experts, router_logits
         _ptr(workspace, "workspace", torch.uint8), workspace.numel(), _stream())
     _check(st, "swimba_mixer_fwd_xe")
     return MixerOut(y, h_final, topk_idx, topk_w)
+
+
+def swimba_mixer_xe_selected_workspace_bytes(dims: swimba_dims) -> int:
+    return int(_load().swimba_mixer_xe_selected_workspace_bytes(ctypes.byref(dims)))
+
+
+def swimba_mixer_fwd_xe_selected(x_sel, dt, A, D, B_sel, C_sel, topk_w, chunk: int, h0=None, *, y=None,
+                                 h_final=None, workspace=None, want_h_final: bool = True) -> MixerOut:
+    """Expert-X forward on the selected experts' rows: x_sel (B,L,k,H,P), B_sel/C_sel (B,L,k,G,N), topk_w (B,L,k)."""
+    B, L, K, H, P = x_sel.shape
+    _, _, _, G, N = B_sel.shape
+    io, dev = x_sel.dtype, x_sel.device
+    d = make_dims(B, L, H, P, N, G, K, K, chunk, _io_code(x_sel))
+    if workspace is None:
+        n = swimba_mixer_xe_selected_workspace_bytes(d)
+        if n == 0:
+            alloc_workspace(d, dev)   # raises with the status of the dims
+        workspace = torch.empty(n, dtype=torch.uint8, device=dev)
+    if y is None:
+        y = torch.empty((B, L, H, P), dtype=io, device=dev)
+    if h_final is None and want_h_final:
+        h_final = torch.empty((B, H, P, N), dtype=torch.float32, device=dev)
+    st = _load().swimba_mixer_fwd_xe_selected(
+        ctypes.byref(d), _ptr(x_sel, "x_sel", io, (B, L, K, H, P)), _ptr(dt, "dt", io, (B, L, H)),
+        _ptr(A, "A", torch.float32, (H,)), _ptr(D, "D", torch.float32, (H,)),
+        _ptr(B_sel, "B_sel", io, (B, L, K, G, N)), _ptr(C_sel, "C_sel", io, (B, L, K, G, N)),
+        _ptr(topk_w, "topk_w", torch.float32, (B, L, K)), _ptr(h0, "h0", torch.float32, (B, H, P, N)),
+        _ptr(y, "y", io, (B, L, H, P)), _ptr(h_final, "h_final", torch.float32, (B, H, P, N)),
+        _ptr(workspace, "workspace", torch.uint8), workspace.numel(), _stream())
+    _check(st, "swimba_mixer_fwd_xe_selected")
+    return MixerOut(y, h_final, None, None)
 
 
 def swimba_separated_workspace_bytes(dims: swimba_dims) -> int:

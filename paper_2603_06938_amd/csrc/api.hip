@@ -500,21 +500,42 @@ swimba_status swimba_separated_fwd(const swimba_dims *dims, const void *x, const
 }
 
 // ---- mixed forward with one input stream per expert -----------------------------------------
+// Two evaluations.  bf16 MFMA shapes with top_k <= MIX_ALL_SLOTS_MAX: every kernel handles all
+// slots in one launch (the mix writes one weighted B image per slot, the chunk-state grid
+// carries the slot, the scan sums the slots' chunk states in fp32, the output kernel reads the
+// carried state once and walks the slots).  Anything else: k rank-1 passes through the
+// one-stream kernels, pass r adding its output to y.
 struct XeLayout {
-    size_t mixer, xg, wslot, hf, total;
+    size_t mixer, xg, wslot, hf, bfragK, t8K, cbK, statesK, total;
+    bool slots;
 };
-static void xe_layout_of(const swimba_dims *d, XeLayout *o)
+static void xe_layout_of(const swimba_dims *d, XeLayout *o, bool selected)
 {
     swimba_ws_layout lo;
     layout_of(d, &lo);
     const size_t T = (size_t)d->batch * d->seqlen;
     const size_t n = T * d->nheads * d->headdim;
     const size_t io = d->io_dtype == SWIMBA_BF16 ? 2 : 4;
+    const size_t K = d->top_k;
+    o->slots = use_mfma_path(d) && d->top_k <= MIX_ALL_SLOTS_MAX;
     size_t off = 0;
     o->mixer = off; off = align_up(off + lo.total, 256);
-    o->xg = off;    off = align_up(off + n * io, 256);
-    o->wslot = off; off = align_up(off + T * d->top_k * sizeof(float), 256);
+    // rows of the selected experts: all slots (B,L,k,H,P) for the slot kernels unless the caller
+    // brings them, one slot at a time otherwise
+    o->xg = off;    off = align_up(off + (o->slots ? (selected ? 0 : n * K * io) : n * io), 256);
+    o->wslot = off; off = align_up(off + T * K * sizeof(float), 256);
     o->hf = off;    off = align_up(off + (size_t)d->batch * d->nheads * d->headdim * d->dstate * sizeof(float), 256);
+    o->bfragK = o->t8K = o->cbK = o->statesK = off;
+    if (o->slots) {
+        const size_t nc = ((size_t)d->seqlen + d->chunk - 1) / d->chunk;
+        const size_t nbcg = (size_t)d->batch * nc * d->ngroups;
+        const size_t NT = d->chunk / 32, NP = NT * (NT + 1) / 2;
+        const size_t image = nbcg * d->chunk * 128 * 2;                       // one mixed-B image, bytes
+        o->bfragK = off;  off = align_up(off + K * image, 256);
+        o->t8K = off;     off = align_up(off + K * image, 256);
+        o->cbK = off;     off = align_up(off + K * nbcg * NP * 2048, 256);
+        o->statesK = off; off = align_up(off + K * (size_t)d->batch * nc * d->nheads * 64 * 128 * 2, 256);
+    }
     o->total = off;
 }
 
@@ -522,8 +543,112 @@ size_t swimba_mixer_xe_workspace_bytes(const swimba_dims *dims)
 {
     if (check_mixer(dims) != SWIMBA_OK) return 0;
     XeLayout xl;
-    xe_layout_of(dims, &xl);
+    xe_layout_of(dims, &xl, false);
     return xl.total;
+}
+
+size_t swimba_mixer_xe_selected_workspace_bytes(const swimba_dims *dims)
+{
+    if (check_mixer(dims) != SWIMBA_OK) return 0;
+    XeLayout xl;
+    xe_layout_of(dims, &xl, true);
+    return xl.total;
+}
+
+// x_src: (B,L,E,H,P) with the routing taken from router_logits, or, with w_sel != nullptr, the
+// rows of the selected experts (B,L,k,H,P) beside B_src / C_src (B,L,k,G,N) and their weights
+static swimba_status xe_core(const swimba_dims *dims, const void *x_src, const void *dt, const float *A,
+                             const float *D, const void *B_src, const void *C_src, const void *router_logits,
+                             const float *w_sel, const float *h0, void *y, float *h_final, char *base,
+                             const XeLayout &xl, hipStream_t stream)
+{
+    const bool selected = (w_sel != nullptr);
+    const int64_t T = (int64_t)dims->batch * dims->seqlen;
+    Ws ws;
+    swimba_ws_layout lo;
+    layout_of(dims, &lo);
+    swimba_status st = carve(dims, base + xl.mixer, lo.total, &ws);
+    if (st != SWIMBA_OK) return st;
+    swimba_dims dk = *dims;
+    if (selected) dk.nexperts = dims->top_k;        // the kernels see k "experts" with the identity selection
+    const Shape s = make_shape(&dk);
+    const bool mf = use_mfma_path(dims);
+    if (T == 0) {
+        // nothing to inject: the final state is the initial one
+        if (dims->batch > 0 && h_final)
+            return mf ? launch_scan_cb_mfma(s, h0, h_final, ws.states_lp, ws.cs, ws.cmix, ws.bmix_frag, ws.cb, stream)
+                      : launch_state_scan(s, h0, h_final, ws.states, nullptr, ws.cs, stream);
+        return SWIMBA_OK;
+    }
+    void *xg = base + xl.xg;
+    if (xl.slots) {
+        void *bfragK = base + xl.bfragK, *t8K = base + xl.t8K, *cbK = base + xl.cbK, *statesK = base + xl.statesK;
+        st = launch_mix_rows_mfma(s, B_src, C_src, router_logits, ws.idx, ws.w, ws.cmix, bfragK, t8K, -1,
+                                  MIX_ALL_SLOTS, w_sel, stream);
+        if (st != SWIMBA_OK) return st;
+        const void *xs = x_src;
+        if (!selected) {
+            st = launch_xe_gather(s, dims->io_dtype, -1, x_src, ws.idx, xg, stream);
+            if (st != SWIMBA_OK) return st;
+            xs = xg;
+        }
+        st = launch_chunk_state_mfma(s, xs, dt, A, t8K, ws.cs, statesK, stream, s.K);
+        if (st != SWIMBA_OK) return st;
+        st = launch_scan_cb_mfma(s, h0, h_final, statesK, ws.cs, ws.cmix, bfragK, cbK, stream, s.K);
+        if (st != SWIMBA_OK) return st;
+        return launch_output_slots_mfma(s, xs, dt, D, ws.cmix, cbK, ws.cs, statesK, y, selected ? w_sel : ws.w,
+                                        s.K, stream);
+    }
+    float *wslot = (float *)(base + xl.wslot), *hf_tmp = (float *)(base + xl.hf);
+    const int64_t nstate = (int64_t)dims->batch * dims->nheads * dims->headdim * dims->dstate;
+    // the selected form runs on the plain-arithmetic kernels (the per-slot MFMA mix routes by itself)
+    const bool mfl = mf && !selected;
+    const float *wsrc = selected ? w_sel : ws.w;
+    if (!mfl) {
+        st = selected ? launch_slot_ids(ws.idx, T, dims->top_k, stream)
+                      : launch_router(T, s.E, s.K, dims->io_dtype, router_logits, ws.idx, ws.w, stream);
+        if (st != SWIMBA_OK) return st;
+        st = launch_cumsum(s, dims->io_dtype, dt, A, ws.cs, stream);
+        if (st != SWIMBA_OK) return st;
+    }
+    for (int r = 0; r < s.K; ++r) {
+        const float *h0_r = (r == 0) ? h0 : nullptr;       // the initial state enters the sum once
+        float *hf_r = !h_final ? nullptr : (r == 0 ? h_final : hf_tmp);
+        // pass r adds its output to y; its skip term is D pi_{t,e_r} x_t^(e_r)
+        const float *skip_w = wsrc + r;
+        if (mfl) {
+            st = launch_mix_rows_mfma(s, B_src, C_src, router_logits, ws.idx, ws.w, ws.cmix,
+                                      ws.bmix_frag, ws.bmix_t8, -1, r, nullptr, stream);
+            if (st != SWIMBA_OK) return st;
+            st = launch_xe_gather(s, dims->io_dtype, r, x_src, ws.idx, xg, stream);
+            if (st != SWIMBA_OK) return st;
+            st = launch_chunk_state_mfma(s, xg, dt, A, ws.bmix_t8, ws.cs, ws.states_lp, stream);
+            if (st != SWIMBA_OK) return st;
+            st = launch_scan_cb_mfma(s, h0_r, hf_r, ws.states_lp, ws.cs, ws.cmix, ws.bmix_frag, ws.cb, stream);
+            if (st != SWIMBA_OK) return st;
+            st = launch_output_mfma(s, xg, dt, D, ws.cmix, ws.cb, ws.cs, ws.states_lp, y, skip_w, s.K, r > 0,
+                                    stream);
+            if (st != SWIMBA_OK) return st;
+        } else {
+            st = launch_xe_slot_weights(s, r, wsrc, wslot, stream);
+            if (st != SWIMBA_OK) return st;
+            st = launch_xe_gather(s, dims->io_dtype, r, x_src, ws.idx, xg, stream);
+            if (st != SWIMBA_OK) return st;
+            st = launch_chunk_state_generic(s, dims->io_dtype, xg, dt, B_src, ws.idx, wslot, ws.cs,
+                                            ws.states, stream);
+            if (st != SWIMBA_OK) return st;
+            st = launch_state_scan(s, h0_r, hf_r, ws.states, nullptr, ws.cs, stream);
+            if (st != SWIMBA_OK) return st;
+            st = launch_output_generic(s, dims->io_dtype, xg, dt, D, B_src, C_src, ws.idx, wslot,
+                                       wsrc, ws.cs, ws.states, y, skip_w, s.K, r > 0, stream);
+            if (st != SWIMBA_OK) return st;
+        }
+        if (h_final && r > 0) {
+            st = launch_sep_accumulate(SWIMBA_F32, nstate, hf_tmp, h_final, 0, stream);
+            if (st != SWIMBA_OK) return st;
+        }
+    }
+    return SWIMBA_OK;
 }
 
 swimba_status swimba_mixer_fwd_xe(const swimba_dims *dims, const void *x_experts, const void *dt,
@@ -535,7 +660,7 @@ swimba_status swimba_mixer_fwd_xe(const swimba_dims *dims, const void *x_experts
     swimba_status st = check_mixer(dims);
     if (st != SWIMBA_OK) return st;
     XeLayout xl;
-    xe_layout_of(dims, &xl);
+    xe_layout_of(dims, &xl, false);
     if (!workspace || workspace_bytes < xl.total || ((uintptr_t)workspace & 255u)) return SWIMBA_ERR_WORKSPACE;
     const int64_t T = (int64_t)dims->batch * dims->seqlen;
     if (T > 0 && (!x_experts || !dt || !A || !B_experts || !C_experts || !router_logits || !y))
@@ -543,77 +668,43 @@ swimba_status swimba_mixer_fwd_xe(const swimba_dims *dims, const void *x_experts
     if (check_align(dims->io_dtype, {x_experts, B_experts, C_experts, y, h0, h_final}, {dt, router_logits},
                     {A, D, topk_idx, topk_w}) != SWIMBA_OK)
         return SWIMBA_ERR_ALIGNMENT;
-    char *base = (char *)workspace;
-    Ws ws;
-    swimba_ws_layout lo;
-    layout_of(dims, &lo);
-    st = carve(dims, base + xl.mixer, lo.total, &ws);
-    if (st != SWIMBA_OK) return st;
     hipStream_t stream = (hipStream_t)hip_stream;
-    const Shape s = make_shape(dims);
-    const bool mf = use_mfma_path(dims);
-    if (T == 0) {
-        // nothing to inject: the final state is the initial one
-        if (dims->batch > 0 && h_final)
-            return mf ? launch_scan_cb_mfma(s, h0, h_final, ws.states_lp, ws.cs, ws.cmix, ws.bmix_frag, ws.cb, stream)
-                      : launch_state_scan(s, h0, h_final, ws.states, nullptr, ws.cs, stream);
-        return SWIMBA_OK;
-    }
-    void *xg = base + xl.xg;
-    float *wslot = (float *)(base + xl.wslot), *hf_tmp = (float *)(base + xl.hf);
-    const int64_t nstate = (int64_t)dims->batch * dims->nheads * dims->headdim * dims->dstate;
-    if (!mf) {
-        st = launch_router(T, s.E, s.K, dims->io_dtype, router_logits, ws.idx, ws.w, stream);
-        if (st != SWIMBA_OK) return st;
-        st = launch_cumsum(s, dims->io_dtype, dt, A, ws.cs, stream);
-        if (st != SWIMBA_OK) return st;
-    }
-    for (int r = 0; r < s.K; ++r) {
-        const float *h0_r = (r == 0) ? h0 : nullptr;       // the initial state enters the sum once
-        float *hf_r = !h_final ? nullptr : (r == 0 ? h_final : hf_tmp);
-        // pass r adds its output to y; its skip term is D pi_{t,e_r} x_t^(e_r)
-        const float *skip_w = ws.w + r;
-        if (mf) {
-            st = launch_mix_rows_mfma(s, B_experts, C_experts, router_logits, ws.idx, ws.w, ws.cmix,
-                                      ws.bmix_frag, ws.bmix_t8, -1, r, nullptr, stream);
-            if (st != SWIMBA_OK) return st;
-            st = launch_xe_gather(s, dims->io_dtype, r, x_experts, ws.idx, xg, stream);
-            if (st != SWIMBA_OK) return st;
-            st = launch_chunk_state_mfma(s, xg, dt, A, ws.bmix_t8, ws.cs, ws.states_lp, stream);
-            if (st != SWIMBA_OK) return st;
-            st = launch_scan_cb_mfma(s, h0_r, hf_r, ws.states_lp, ws.cs, ws.cmix, ws.bmix_frag, ws.cb, stream);
-            if (st != SWIMBA_OK) return st;
-            st = launch_output_mfma(s, xg, dt, D, ws.cmix, ws.cb, ws.cs, ws.states_lp, y, skip_w, s.K, r > 0,
-                                    stream);
-            if (st != SWIMBA_OK) return st;
-        } else {
-            st = launch_xe_slot_weights(s, r, ws.w, wslot, stream);
-            if (st != SWIMBA_OK) return st;
-            st = launch_xe_gather(s, dims->io_dtype, r, x_experts, ws.idx, xg, stream);
-            if (st != SWIMBA_OK) return st;
-            st = launch_chunk_state_generic(s, dims->io_dtype, xg, dt, B_experts, ws.idx, wslot, ws.cs,
-                                            ws.states, stream);
-            if (st != SWIMBA_OK) return st;
-            st = launch_state_scan(s, h0_r, hf_r, ws.states, nullptr, ws.cs, stream);
-            if (st != SWIMBA_OK) return st;
-            st = launch_output_generic(s, dims->io_dtype, xg, dt, D, B_experts, C_experts, ws.idx, wslot,
-                                       ws.w, ws.cs, ws.states, y, skip_w, s.K, r > 0, stream);
-            if (st != SWIMBA_OK) return st;
-        }
-        if (h_final && r > 0) {
-            st = launch_sep_accumulate(SWIMBA_F32, nstate, hf_tmp, h_final, 0, stream);
-            if (st != SWIMBA_OK) return st;
-        }
-    }
-    if (topk_idx || topk_w) {
+    char *base = (char *)workspace;
+    st = xe_core(dims, x_experts, dt, A, D, B_experts, C_experts, router_logits, nullptr, h0, y, h_final, base, xl,
+                 stream);
+    if (st != SWIMBA_OK) return st;
+    if (T > 0 && (topk_idx || topk_w)) {
+        swimba_ws_layout lo;
+        layout_of(dims, &lo);
         const size_t cnt = (size_t)T * dims->top_k;
         hipError_t e = hipSuccess;
-        if (topk_idx) e = hipMemcpyAsync(topk_idx, ws.idx, cnt * sizeof(int32_t), hipMemcpyDeviceToDevice, stream);
+        if (topk_idx)
+            e = hipMemcpyAsync(topk_idx, base + xl.mixer + lo.topk_idx, cnt * sizeof(int32_t), hipMemcpyDeviceToDevice,
+                               stream);
         if (e == hipSuccess && topk_w)
-            e = hipMemcpyAsync(topk_w, ws.w, cnt * sizeof(float), hipMemcpyDeviceToDevice, stream);
+            e = hipMemcpyAsync(topk_w, base + xl.mixer + lo.topk_w, cnt * sizeof(float), hipMemcpyDeviceToDevice,
+                               stream);
         if (e != hipSuccess) { set_last_hip_error((int)e); return SWIMBA_ERR_HIP; }
     }
     return SWIMBA_OK;
+}
+
+swimba_status swimba_mixer_fwd_xe_selected(const swimba_dims *dims, const void *x_sel, const void *dt,
+                                           const float *A, const float *D, const void *B_sel, const void *C_sel,
+                                           const float *topk_w, const float *h0, void *y, float *h_final,
+                                           void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    swimba_status st = check_mixer(dims);
+    if (st != SWIMBA_OK) return st;
+    XeLayout xl;
+    xe_layout_of(dims, &xl, true);
+    if (!workspace || workspace_bytes < xl.total || ((uintptr_t)workspace & 255u)) return SWIMBA_ERR_WORKSPACE;
+    const int64_t T = (int64_t)dims->batch * dims->seqlen;
+    if (T > 0 && (!x_sel || !dt || !A || !B_sel || !C_sel || !topk_w || !y)) return SWIMBA_ERR_NULL;
+    if (check_align(dims->io_dtype, {x_sel, B_sel, C_sel, y, h0, h_final}, {dt}, {A, D, topk_w}) != SWIMBA_OK)
+        return SWIMBA_ERR_ALIGNMENT;
+    return xe_core(dims, x_sel, dt, A, D, B_sel, C_sel, nullptr, topk_w, h0, y, h_final, (char *)workspace, xl,
+                   (hipStream_t)hip_stream);
 }
 
 // ---- routed expert in-projection --------------------------------------------------------------

@@ -100,10 +100,18 @@ swimba_status launch_sep_prepare(const Shape &s, int e, const int32_t *idx, cons
 swimba_status launch_sep_accumulate(int io_dtype, int64_t n, const void *y_e, float *acc, int first,
                                     hipStream_t st);
 swimba_status launch_chunk_state_mfma(const Shape &s, const void *x, const void *dt, const float *A,
-                                      const void *bmix_t8, float *cs, void *states_lp, hipStream_t st);
+                                      const void *bmix_t8, float *cs, void *states_lp, hipStream_t st,
+                                      int nslots = 1);
 swimba_status launch_scan_cb_mfma(const Shape &s, const float *h0, float *h_final, void *states_lp,
                                   const float *cs, const void *cmix, const void *bfrag, void *cb,
-                                  hipStream_t st);
+                                  hipStream_t st, int nslots = 1);
+swimba_status launch_output_slots_mfma(const Shape &s, const void *x, const void *dt, const float *D,
+                                       const void *cmix, const void *cb, const float *cs,
+                                       const void *states_lp, void *y, const float *w, int nslots,
+                                       hipStream_t st);
+// launch_mix_rows_mfma, slot argument: every slot's weighted B rows as images of their own
+constexpr int MIX_ALL_SLOTS = -2;
+constexpr int MIX_ALL_SLOTS_MAX = 4;   // most slots the slot-image kernels take
 swimba_status launch_output_mfma(const Shape &s, const void *x, const void *dt, const float *D,
                                  const void *cmix, const void *cb, const float *cs,
                                  const void *states_lp, void *y, const float *skip_w, int skip_stride,

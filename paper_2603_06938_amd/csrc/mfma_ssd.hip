@@ -63,7 +63,9 @@ __device__ __forceinline__ void gather_mix_row(uint4 *frag, const uint16_t *tok,
 // prepares the streams of ONE expert for the separated-SSM contrast instead:
 // Bmix = B^(e), Cmix = gate * C^(e), gate = pi_{t,e} if e is in the active set, else 0.
 // With slot >= 0 (one input stream per expert) Bmix keeps only the term of the token's
-// slot-th active expert, Bmix = pi_{t,e_slot} B^(e_slot); Cmix is the full mix.
+// slot-th active expert, Bmix = pi_{t,e_slot} B^(e_slot); Cmix is the full mix.  With
+// slot == MIX_ALL_SLOTS every slot's term is written, image r of bfrag / bmix_t8 (each
+// B*nc*G*Q*MN elements) holding pi_{t,e_r} B^(e_r); the summed B mix is not formed.
 //   cmix, bfrag (B, nc, G, NT, 8, 64, 8) bf16, mixed rows of tile I as operand registers:
 //           [ks][lane][e] = mix[32I + lane%32][64*(lane/32) + 8ks + e]
 //   bmix_t8 (B, nc, G, Q/8, N, 8)    bf16, mixed B with 8 tokens innermost: position 8 o + e of a
@@ -90,6 +92,9 @@ mix_rows_kernel(const uint16_t *__restrict__ Be, const uint16_t *__restrict__ Ce
     float *s_log = reinterpret_cast<float *>(s_mix + 2 * 32 * MIXROW);   // [32][E + 1]
     // expert-specific input streams (slot >= 0): B keeps the weight of active expert `slot` only
     float *s_wslot = s_log + 32 * (s.E + 1);                             // [32][K]
+    // every slot's weighted B row on its own (slot == MIX_ALL_SLOTS): [K][32][MIXROW]
+    uint16_t *s_slots = reinterpret_cast<uint16_t *>(s_wslot + 32 * Kr);
+    const bool all_slots = (slot == MIX_ALL_SLOTS);
 
     const int NT = s.Q / 32;
     const int tile = blockIdx.x % NT;
@@ -195,7 +200,15 @@ mix_rows_kernel(const uint16_t *__restrict__ Be, const uint16_t *__restrict__ Ce
 #pragma unroll
             for (int q = 0; q < 2; ++q) {
                 const bool on = pin && r0 + q < K;
-                fma_bf16x8(accB[jj], vb[jj][q], on ? wtB[j * K + r0 + q] : 0.f);
+                if (all_slots) {
+                    if (r0 + q < K) {
+                        float one[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+                        fma_bf16x8(one, vb[jj][q], on ? wtB[j * K + r0 + q] : 0.f);
+                        *reinterpret_cast<uint4 *>(s_slots + ((r0 + q) * 32 + j) * MIXROW + piece * 8) = pack8(one);
+                    }
+                } else {
+                    fma_bf16x8(accB[jj], vb[jj][q], on ? wtB[j * K + r0 + q] : 0.f);
+                }
                 fma_bf16x8(accC[jj], vc[jj][q], on ? wtC[j * K + r0 + q] : 0.f);
             }
         }
@@ -209,28 +222,41 @@ mix_rows_kernel(const uint16_t *__restrict__ Be, const uint16_t *__restrict__ Ce
     }
     lds_barrier();
 
-    if (wave < 2) {
+    const int nimg = all_slots ? Kr : 1;                 // B images written by this launch
+    const int64_t img = (int64_t)s.B * s.nc * s.G * s.Q * MN;   // elements per image
+    if (wave == 0) {
         // operand registers: lane (l32, kg) holds n = 64 kg + 8 ks .. + 7 of token l32
-        const uint16_t *src = s_mix + ((wave == 0 ? 32 : 0) + l32) * MIXROW + 64 * kg;
-        uint16_t *dst = (wave == 0 ? cmix : bfrag) + (((bcg * NT + tile) * 8) * 64 + lane) * 8;
+        const uint16_t *src = s_mix + (32 + l32) * MIXROW + 64 * kg;
+        uint16_t *dst = cmix + (((bcg * NT + tile) * 8) * 64 + lane) * 8;
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks)
             *reinterpret_cast<uint4 *>(dst + ks * 64 * 8) = *reinterpret_cast<const uint4 *>(src + ks * 8);
+    } else if (wave == 1) {
+        for (int r = 0; r < nimg; ++r) {
+            const uint16_t *src = (all_slots ? s_slots + r * 32 * MIXROW : s_mix) + l32 * MIXROW + 64 * kg;
+            uint16_t *dst = bfrag + r * img + (((bcg * NT + tile) * 8) * 64 + lane) * 8;
+#pragma unroll
+            for (int ks = 0; ks < 8; ++ks)
+                *reinterpret_cast<uint4 *>(dst + ks * 64 * 8) = *reinterpret_cast<const uint4 *>(src + ks * 8);
+        }
     } else {
         // mixed B, 8 tokens innermost (in the operand order of t8_token): lane = state index n,
         // one 16-byte store per token octet
         const int n = tid - 128;
+        for (int r = 0; r < nimg; ++r) {
+            const uint16_t *src = all_slots ? s_slots + r * 32 * MIXROW : s_mix;
 #pragma unroll
-        for (int jgl = 0; jgl < 4; ++jgl) {
-            uint32_t pk[4];
+            for (int jgl = 0; jgl < 4; ++jgl) {
+                uint32_t pk[4];
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const uint32_t lo = s_mix[t8_token(jgl * 8 + 2 * q) * MIXROW + n];
-                const uint32_t hi = s_mix[t8_token(jgl * 8 + 2 * q + 1) * MIXROW + n];
-                pk[q] = lo | (hi << 16);
+                for (int q = 0; q < 4; ++q) {
+                    const uint32_t lo = src[t8_token(jgl * 8 + 2 * q) * MIXROW + n];
+                    const uint32_t hi = src[t8_token(jgl * 8 + 2 * q + 1) * MIXROW + n];
+                    pk[q] = lo | (hi << 16);
+                }
+                *reinterpret_cast<uint4 *>(bmix_t8 + r * img + ((bcg * (s.Q / 8) + tile * 4 + jgl) * MN + n) * 8) =
+                    make_uint4(pk[0], pk[1], pk[2], pk[3]);
             }
-            *reinterpret_cast<uint4 *>(bmix_t8 + ((bcg * (s.Q / 8) + tile * 4 + jgl) * MN + n) * 8) =
-                make_uint4(pk[0], pk[1], pk[2], pk[3]);
         }
     }
 }
@@ -242,19 +268,30 @@ mix_rows_kernel(const uint16_t *__restrict__ Be, const uint16_t *__restrict__ Ce
 // not scan: each of their waves computes one cb tile (see cb_pair), work that only
 // depends on the mixed rows and is needed by the output kernel alone, so it rides in
 // this launch instead of paying for one of its own.
+// With nslots > 1 (one input stream per expert) the chunk states of the slots, images of
+// B*nc*H*MP*MN elements behind each other in lp, are summed in fp32 on the way (the state is
+// linear in the injection) and the carried states land in image 0; the tiles are computed
+// per slot from the slot's B image (cb image r behind image r - 1).  NS >= nslots is the
+// number of slot loads kept in flight per chunk.
 // =========================================================================================
+template <int NS>
 __global__ void __launch_bounds__(MTHREADS)
 scan_cb_kernel(uint16_t *__restrict__ lp, const float *__restrict__ h0, float *__restrict__ h_final,
                const float *__restrict__ cs, const uint16_t *__restrict__ cmix,
-               const uint16_t *__restrict__ bfrag, uint16_t *__restrict__ cb, Shape s, int ncb, int64_t nbcg)
+               const uint16_t *__restrict__ bfrag, uint16_t *__restrict__ cb, Shape s, int ncb, int64_t nbcg,
+               int nslots)
 {
     if ((int)blockIdx.x < ncb) {
-        const int NT = s.Q / 32, PB = (NT * (NT + 1) / 2 + 3) / 4;
+        const int NT = s.Q / 32, NPAIR = NT * (NT + 1) / 2, PB = (NPAIR + 3) / 4;
         // consecutive logical ids (the pairs of one (batch, chunk, group)) share an XCD and its L2
         const int64_t id = xcd_logical_id(blockIdx.x, ncb);
-        const int64_t bcg = id / PB;
+        const int64_t sbcg = id / PB;                    // (slot, batch, chunk, group)
+        const int64_t bcg = sbcg % nbcg;
+        const int slot = (int)(sbcg / nbcg);
         const int p = (int)(id % PB) * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-        if (bcg < nbcg && p < NT * (NT + 1) / 2) cb_pair(cmix, bfrag, cb, NT, bcg, p, threadIdx.x & 63);
+        if (slot < nslots && p < NPAIR)
+            cb_pair(cmix, bfrag + slot * (nbcg * s.Q * MN), cb + slot * (nbcg * NPAIR * 1024), NT, bcg, p,
+                    threadIdx.x & 63);
         return;
     }
     // chunk states are (MP, MN) tiles; h0 / h_final have the caller's P <= MP rows and N <= MN columns
@@ -274,14 +311,18 @@ scan_cb_kernel(uint16_t *__restrict__ lp, const float *__restrict__ h0, float *_
 #pragma unroll
     for (int v = 0; v < 8; ++v) run[v] = (h0 && real) ? h0[user + v] : 0.f;
 
-    constexpr int UN = 4;  // chunks whose loads are issued together
+    constexpr int UN = (NS > 2) ? 2 : 4;  // chunks whose loads are issued together
+    const int64_t simg = (int64_t)s.B * s.nc * s.H * PN;   // elements per slot image
     for (int c0 = 0; c0 < s.nc; c0 += UN) {
-        uint4 S[UN];
+        uint4 S[UN][NS];
         float decay[UN];
 #pragma unroll
         for (int u = 0; u < UN; ++u) {
             const int c = min(c0 + u, s.nc - 1);
-            S[u] = *reinterpret_cast<const uint4 *>(lp + (((int64_t)b * s.nc + c) * s.H + h) * PN + pn);
+#pragma unroll
+            for (int r = 0; r < NS; ++r)
+                S[u][r] = *reinterpret_cast<const uint4 *>(lp + min(r, nslots - 1) * simg +
+                                                           (((int64_t)b * s.nc + c) * s.H + h) * PN + pn);
             decay[u] = fast_exp2(cs[(((int64_t)b * s.nc + c) * s.H + h) * s.Q + s.Q - 1] * LOG2E);
         }
 #pragma unroll
@@ -290,7 +331,16 @@ scan_cb_kernel(uint16_t *__restrict__ lp, const float *__restrict__ h0, float *_
             if (c < s.nc) {
                 *reinterpret_cast<uint4 *>(lp + (((int64_t)b * s.nc + c) * s.H + h) * PN + pn) = pack8(run);
                 float sv[8];
-                unpack8(sv, S[u]);
+                unpack8(sv, S[u][0]);
+#pragma unroll
+                for (int r = 1; r < NS; ++r) {
+                    float sr[8];
+                    unpack8(sr, S[u][r]);
+                    if (r < nslots) {
+#pragma unroll
+                        for (int v = 0; v < 8; ++v) sv[v] += sr[v];
+                    }
+                }
 #pragma unroll
                 for (int v = 0; v < 8; ++v) run[v] = decay[u] * run[v] + sv[v];
             }
@@ -310,8 +360,9 @@ swimba_status launch_mix_rows_mfma(const Shape &s, const void *Be, const void *C
     const int64_t nbcg = (int64_t)s.B * s.nc * s.G;
     if (nbcg == 0) return SWIMBA_OK;
     if (w_sel && (sep_e >= 0 || slot >= 0)) return SWIMBA_ERR_UNSUPPORTED;
+    if (slot == MIX_ALL_SLOTS && (sep_e >= 0 || s.K > MIX_ALL_SLOTS_MAX)) return SWIMBA_ERR_UNSUPPORTED;
     const size_t shm = (size_t)32 * s.K * 8 + 32 * 12 + (size_t)2 * 32 * (MN + 8) * 2 + (size_t)32 * (s.E + 1) * 4
-                       + (size_t)32 * s.K * 4;
+                       + (size_t)32 * s.K * 4 + (slot == MIX_ALL_SLOTS ? (size_t)s.K * 32 * (MN + 8) * 2 : 0);
     hipLaunchKernelGGL(mix_rows_kernel, dim3((unsigned)(nbcg * NT)), dim3(MTHREADS), shm, st,
                        (const uint16_t *)Be, (const uint16_t *)Ce, (const uint16_t *)logits, idx, w,
                        (uint16_t *)cmix, (uint16_t *)bfrag, (uint16_t *)bmix_t8, s, sep_e, slot, w_sel);
@@ -321,16 +372,22 @@ swimba_status launch_mix_rows_mfma(const Shape &s, const void *Be, const void *C
 
 swimba_status launch_scan_cb_mfma(const Shape &s, const float *h0, float *h_final, void *states_lp,
                                   const float *cs, const void *cmix, const void *bfrag, void *cb,
-                                  hipStream_t st)
+                                  hipStream_t st, int nslots)
 {
     const int64_t elems = (int64_t)s.B * s.H * MP * MN;
     const int64_t nbcg = (int64_t)s.B * s.nc * s.G;
     if (elems == 0) return SWIMBA_OK;
+    if (nslots < 1 || nslots > MIX_ALL_SLOTS_MAX) return SWIMBA_ERR_UNSUPPORTED;
     const int NT = s.Q / 32;
-    const int ncb = xcd_padded(nbcg * ((NT * (NT + 1) / 2 + 3) / 4));   // 0 for an empty sequence
+    const int ncb = xcd_padded(nslots * nbcg * ((NT * (NT + 1) / 2 + 3) / 4));   // 0 for an empty sequence
     const unsigned grid = (unsigned)(ncb + (elems / 8 + MTHREADS - 1) / MTHREADS);
-    hipLaunchKernelGGL(scan_cb_kernel, dim3(grid), dim3(MTHREADS), 0, st, (uint16_t *)states_lp, h0, h_final, cs,
-                       (const uint16_t *)cmix, (const uint16_t *)bfrag, (uint16_t *)cb, s, ncb, nbcg);
+#define SWIMBA_SCAN_LAUNCH(NS)                                                                                    \
+    hipLaunchKernelGGL(scan_cb_kernel<NS>, dim3(grid), dim3(MTHREADS), 0, st, (uint16_t *)states_lp, h0, h_final, \
+                       cs, (const uint16_t *)cmix, (const uint16_t *)bfrag, (uint16_t *)cb, s, ncb, nbcg, nslots)
+    if (nslots == 1) SWIMBA_SCAN_LAUNCH(1);
+    else if (nslots == 2) SWIMBA_SCAN_LAUNCH(2);
+    else SWIMBA_SCAN_LAUNCH(4);
+#undef SWIMBA_SCAN_LAUNCH
     SWIMBA_CHECK_LAUNCH();
     return SWIMBA_OK;
 }
@@ -347,13 +404,16 @@ swimba_status launch_scan_cb_mfma(const Shape &s, const float *h0, float *h_fina
 // scan) and stores it for the scan and output kernels.
 // The coefficient-weighted x tile is staged transposed ([p][j]); wave w owns columns
 // n = 32w..32w+31 and both 32-channel halves of p.  The chunk state is stored in bf16.
+// With nslots > 1 (one input stream per expert) the grid carries the slot as its slowest
+// index: slot r reads x rows r*H*P elements into a token (xts elements between tokens), the
+// r-th mixed-B image, and writes the r-th chunk-state image; the scan sums the images.
 // =========================================================================================
 template <int Q>
-__global__ void __launch_bounds__(MTHREADS)
+__global__ void __launch_bounds__(MTHREADS, 2)   // two waves per SIMD: 256 registers, two workgroups per compute unit
 chunk_state_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ dt,
                         const float *__restrict__ A, const uint16_t *__restrict__ bmix_t8,
                         float *__restrict__ cs, uint16_t *__restrict__ states_lp, Shape s, int ipw,
-                        int nruns, int total, int nblocks)
+                        int nruns, int total, int nblocks, int xts, int nslots)
 {
     constexpr int STR = Q + 8;                    // row stride of the transposed x tile (elements)
     constexpr int KS = Q / 16;
@@ -369,7 +429,11 @@ chunk_state_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restri
     const int run = lid % nruns;
     const int g = (lid / nruns) % s.G;
     const int c = (lid / (nruns * s.G)) % s.nc;
-    const int b = lid / (nruns * s.G * s.nc);
+    const int b = (lid / (nruns * s.G * s.nc)) % s.B;
+    const int slot = lid / (nruns * s.G * s.nc * s.B);
+    x += (int64_t)slot * s.H * s.P;
+    bmix_t8 += (int64_t)slot * s.B * s.nc * s.G * Q * MN;
+    states_lp += (int64_t)slot * s.B * s.nc * s.H * MP * MN;
     const int hpg = s.H / s.G;
     const int h0 = g * hpg + run * ipw;
     const int count = min(ipw, hpg - run * ipw);
@@ -379,7 +443,7 @@ chunk_state_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restri
     const int64_t tok0 = (int64_t)b * s.L + (int64_t)c * Q;
     const int valid = min(Q, s.L - c * Q);
     const int64_t bcg = ((int64_t)b * s.nc + c) * s.G + g;
-    const int tokstride = s.H * s.P;                 // the caller's P <= MP channels per head
+    const int tokstride = xts;                       // elements between tokens of x
     const int tq = min(tid, Q - 1);
     // a lane always stages the same two channels 2 p2, 2 p2 + 1; channels past P are staged as zeros
     const bool pok = 2 * (tid & 31) < s.P;
@@ -403,7 +467,7 @@ chunk_state_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restri
     uint32_t xv[XU][8];
     // all global loads of one head, clamped and unconditional
     auto issue_loads = [&](int h) {
-        const uint16_t *xh = x + (tok0 * s.H + h) * s.P + pclamp;
+        const uint16_t *xh = x + tok0 * xts + h * s.P + pclamp;
         dt_raw = dt[(tok0 + min(tq, valid - 1)) * s.H + h];
 #pragma unroll
         for (int it = 0; it < XU; ++it) {
@@ -508,15 +572,17 @@ chunk_state_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restri
 
 template <int Q>
 static swimba_status launch_cs_q(const Shape &s, const void *x, const void *dt, const float *A,
-                                 const void *bmix_t8, float *cs, void *states_lp, hipStream_t st)
+                                 const void *bmix_t8, float *cs, void *states_lp, hipStream_t st, int xts,
+                                 int nslots)
 {
     const int hpg = s.H / s.G;
     // heads per workgroup: as many as possible while at least ~2 workgroups per CU remain
     int ipw = hpg;
     while (ipw > 1 && (int64_t)s.B * s.nc * s.G * ((hpg + ipw - 1) / ipw) < 512) ipw = (ipw + 1) / 2;
     const int nruns = (hpg + ipw - 1) / ipw;
-    const int64_t total = (int64_t)s.B * s.nc * s.G * nruns;
+    const int64_t total = (int64_t)s.B * s.nc * s.G * nruns * nslots;
     if (total == 0) return SWIMBA_OK;
+    if (total > (int64_t)1 << 30) return SWIMBA_ERR_UNSUPPORTED;
     const int nblocks = xcd_padded(total);
     const size_t shm = (size_t)2 * MP * (Q + 8) * 2 + 2 * Q * sizeof(float) + 8 * sizeof(float);
     // more than 64 KB of dynamic LDS has to be allowed once per device (a plain attribute call:
@@ -534,18 +600,21 @@ static swimba_status launch_cs_q(const Shape &s, const void *x, const void *dt, 
     }
     hipLaunchKernelGGL(chunk_state_mfma_kernel<Q>, dim3(nblocks), dim3(MTHREADS), shm, st,
                        (const uint16_t *)x, (const uint16_t *)dt, A, (const uint16_t *)bmix_t8, cs,
-                       (uint16_t *)states_lp, s, ipw, nruns, (int)total, nblocks);
+                       (uint16_t *)states_lp, s, ipw, nruns, (int)total, nblocks, xts, nslots);
     SWIMBA_CHECK_LAUNCH();
     return SWIMBA_OK;
 }
 
+// x is (B, L, nslots, H, P) for nslots > 1 (rows of the selected experts), (B, L, H, P) otherwise
 swimba_status launch_chunk_state_mfma(const Shape &s, const void *x, const void *dt, const float *A,
-                                      const void *bmix_t8, float *cs, void *states_lp, hipStream_t st)
+                                      const void *bmix_t8, float *cs, void *states_lp, hipStream_t st,
+                                      int nslots)
 {
+    const int xts = nslots * s.H * s.P;
     switch (s.Q) {
-    case 64: return launch_cs_q<64>(s, x, dt, A, bmix_t8, cs, states_lp, st);
-    case 128: return launch_cs_q<128>(s, x, dt, A, bmix_t8, cs, states_lp, st);
-    case 256: return launch_cs_q<256>(s, x, dt, A, bmix_t8, cs, states_lp, st);
+    case 64: return launch_cs_q<64>(s, x, dt, A, bmix_t8, cs, states_lp, st, xts, nslots);
+    case 128: return launch_cs_q<128>(s, x, dt, A, bmix_t8, cs, states_lp, st, xts, nslots);
+    case 256: return launch_cs_q<256>(s, x, dt, A, bmix_t8, cs, states_lp, st, xts, nslots);
     }
     return SWIMBA_ERR_UNSUPPORTED;
 }
@@ -572,25 +641,50 @@ swimba_status launch_chunk_state_mfma(const Shape &s, const void *x, const void 
 // bf16, passed through LDS and stored as full 128-byte rows (D x is added on the way).
 // cs is kept multiplied by log2(e): every exponential is one v_exp_f32.
 // =========================================================================================
-// XE (passes of the forward with one input stream per expert): the skip term carries the
+// MODE 1 (one pass per expert or per slot, the results added up in y): the skip term carries the
 // per-token factor skip_w[token * skip_stride], and with `accumulate` the result is added to
 // what y already holds.
-template <int Q, bool XE>
-__global__ void __launch_bounds__(64 * (Q / 32))
+// MODE 2 (one input stream per expert, all slots in one launch): x is (B, L, nslots, H, P); the
+// carried state is read out once, then slot after slot the x tile of the slot is staged and its
+// tile pairs, taken from the slot's G^T image, go into the same accumulators.  The skip term
+// D sum_r pi_r x^(r) is one more contraction per slot, x^T . diag(D pi_{i,r}) with the factor
+// split into two bf16 terms, so the epilogue reads no x; pi_{i,r} = skip_w[token * skip_stride + r].
+template <int Q, int MODE>
+__global__ void __launch_bounds__(64 * (Q / 32), (Q == 256 ? 4 : 1))   // Q = 256: two workgroups per compute unit
 output_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ dt,
                    const float *__restrict__ D, const uint16_t *__restrict__ cmix,
                    const uint16_t *__restrict__ cb, const float *__restrict__ cs,
                    const uint16_t *__restrict__ Hlp, uint16_t *__restrict__ y, Shape s, int total,
-                   int nblocks, const float *__restrict__ skip_w, int skip_stride, int accumulate)
+                   int nblocks, const float *__restrict__ skip_w, int skip_stride, int accumulate,
+                   int nslots)
 {
+    constexpr bool XE = (MODE == 1);
+    constexpr bool SLOTS = (MODE == 2);
     constexpr int NT = Q / 32;                 // 32-token tiles in the chunk
     constexpr int NP = NT * (NT + 1) / 2;
     constexpr int NTHR = 64 * NT;              // one wave per output tile
     constexpr int HSTR = MN + 8;               // row stride of the carried-state tile
     constexpr int XSTR = Q + 8;                // row stride of the transposed x tile
-    __shared__ __align__(16) uint16_t sX[MP * XSTR];
-    __shared__ __align__(16) uint16_t sH[MP * HSTR];
-    __shared__ float s_cs[Q], s_dt[Q], s_f[Q];
+    // MODE 2 keeps the x tiles of two slots: the second one takes the place of the carried-state tile,
+    // which is dead once the state has been read out, and runs past it (dynamic LDS, more than 64 KB
+    // at Q = 256); the other modes keep their fixed layout.
+    uint16_t *sX, *sH, *sX1;
+    float *s_cs, *s_dt, *s_f;
+    if constexpr (SLOTS) {
+        extern __shared__ __align__(16) unsigned char smem_slots[];
+        sX = reinterpret_cast<uint16_t *>(smem_slots);
+        sX1 = sX + MP * XSTR;
+        sH = sX1;
+        s_cs = reinterpret_cast<float *>(sX1 + MP * (XSTR > HSTR ? XSTR : HSTR));
+        s_dt = s_cs + Q;
+        s_f = s_dt + Q;
+    } else {
+        __shared__ __align__(16) uint16_t sX_[MP * XSTR];
+        __shared__ __align__(16) uint16_t sH_[MP * HSTR];
+        __shared__ float s_cs_[Q], s_dt_[Q], s_f_[Q];
+        sX = sX_; sH = sH_; sX1 = sX_;
+        s_cs = s_cs_; s_dt = s_dt_; s_f = s_f_;
+    }
 
     const int lid = xcd_logical_id(blockIdx.x, nblocks);
     if (lid >= total) return;
@@ -604,8 +698,9 @@ output_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ 
     const int64_t tok0 = (int64_t)b * s.L + (int64_t)c * Q;
     const int valid = min(Q, s.L - c * Q);
     const int64_t bcg = ((int64_t)b * s.nc + c) * s.G + g;
-    const int tokstride = s.H * s.P;                         // elements between tokens of x / y (P <= MP)
-    const uint16_t *xh = x + (tok0 * s.H + h) * s.P;         // x[token 0 of the chunk][h][0]
+    const int tokstride = s.H * s.P;                         // elements between tokens of y (P <= MP)
+    const int xts = SLOTS ? nslots * tokstride : tokstride;  // ... of x
+    const uint16_t *xh = x + tok0 * xts + h * s.P;           // x[token 0 of the chunk][slot 0][h][0]
     uint16_t *yh = y + (tok0 * s.H + h) * s.P;
     // channels past the caller's P: staged as zeros, never stored
     const bool pok = 2 * (tid & 31) < s.P;
@@ -637,19 +732,24 @@ output_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ 
     }
     // x staging: unit = (8 tokens in operand order) x (2 channels)
     constexpr int XU = (Q / 8) * 32 / NTHR;
-    uint32_t xv[XU][8];
+    uint32_t xv[XU][8], xw[SLOTS ? XU : 1][8];   // xw: the second slot of a pair (MODE 2)
+    auto load_x = [&](uint32_t (*xd)[8], const uint16_t *xs, int xts, int vlast) __attribute__((always_inline)) {
 #pragma unroll
-    for (int it = 0; it < XU; ++it) {
-        const int u = tid + it * NTHR;
-        const int p2 = u & 31, gi = u >> 5;
-        const int t16 = gi >> 1, kgx = gi & 1;
+        for (int it = 0; it < XU; ++it) {
+            const int u = tid + it * NTHR;
+            const int gi = u >> 5;
+            const int t16 = gi >> 1, kgx = gi & 1;
 #pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const int j = 16 * t16 + 8 * (e >> 2) + 4 * kgx + (e & 3);
-            const uint32_t ld = *reinterpret_cast<const uint32_t *>(xh + min(j, valid - 1) * tokstride + pclamp);
-            xv[it][e] = (j < valid_x) ? ld : 0u;
+            for (int e = 0; e < 8; ++e) {
+                const int j = 16 * t16 + 8 * (e >> 2) + 4 * kgx + (e & 3);
+                // raw value: rows past the end of the sequence and channels past P are zeroed when staged
+                // (a select here would put a wait behind every single load)
+                xd[it][e] = *reinterpret_cast<const uint32_t *>(xs + min(j, vlast) * xts + pclamp);
+            }
         }
-    }
+    };
+    load_x(xv, xh, xts, valid - 1);
+    if constexpr (SLOTS) load_x(xw, xh + min(1, nslots - 1) * tokstride, xts, valid - 1);
     // mixed C rows of the owned tiles (operand registers)
     uint4 cfrag[8];
     {
@@ -671,23 +771,31 @@ output_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ 
         const int row = (tid >> 4) + (NTHR / 16) * pass, piece = tid & 15;
         *reinterpret_cast<uint4 *>(sH + row * HSTR + piece * 8) = hreg[pass];
     }
+    auto stage_x = [&](uint32_t (*xv)[8], uint16_t *sX) __attribute__((always_inline)) {
 #pragma unroll
-    for (int it = 0; it < XU; ++it) {
-        const int u = tid + it * NTHR;
-        const int p2 = u & 31, gi = u >> 5;
-        const int t16 = gi >> 1, kgx = gi & 1;
-        uint4 lo, hi;   // channel 2*p2 and 2*p2+1 of the unit's 8 tokens
-        lo.x = __builtin_amdgcn_perm(xv[it][1], xv[it][0], 0x05040100u);
-        lo.y = __builtin_amdgcn_perm(xv[it][3], xv[it][2], 0x05040100u);
-        lo.z = __builtin_amdgcn_perm(xv[it][5], xv[it][4], 0x05040100u);
-        lo.w = __builtin_amdgcn_perm(xv[it][7], xv[it][6], 0x05040100u);
-        hi.x = __builtin_amdgcn_perm(xv[it][1], xv[it][0], 0x07060302u);
-        hi.y = __builtin_amdgcn_perm(xv[it][3], xv[it][2], 0x07060302u);
-        hi.z = __builtin_amdgcn_perm(xv[it][5], xv[it][4], 0x07060302u);
-        hi.w = __builtin_amdgcn_perm(xv[it][7], xv[it][6], 0x07060302u);
-        *reinterpret_cast<uint4 *>(sX + (2 * p2) * XSTR + 16 * t16 + 8 * kgx) = lo;
-        *reinterpret_cast<uint4 *>(sX + (2 * p2 + 1) * XSTR + 16 * t16 + 8 * kgx) = hi;
-    }
+        for (int it = 0; it < XU; ++it) {
+            const int u = tid + it * NTHR;
+            const int p2 = u & 31, gi = u >> 5;
+            const int t16 = gi >> 1, kgx = gi & 1;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const int j = 16 * t16 + 8 * (e >> 2) + 4 * kgx + (e & 3);
+                xv[it][e] = (j < valid_x) ? xv[it][e] : 0u;
+            }
+            uint4 lo, hi;   // channel 2*p2 and 2*p2+1 of the unit's 8 tokens
+            lo.x = __builtin_amdgcn_perm(xv[it][1], xv[it][0], 0x05040100u);
+            lo.y = __builtin_amdgcn_perm(xv[it][3], xv[it][2], 0x05040100u);
+            lo.z = __builtin_amdgcn_perm(xv[it][5], xv[it][4], 0x05040100u);
+            lo.w = __builtin_amdgcn_perm(xv[it][7], xv[it][6], 0x05040100u);
+            hi.x = __builtin_amdgcn_perm(xv[it][1], xv[it][0], 0x07060302u);
+            hi.y = __builtin_amdgcn_perm(xv[it][3], xv[it][2], 0x07060302u);
+            hi.z = __builtin_amdgcn_perm(xv[it][5], xv[it][4], 0x07060302u);
+            hi.w = __builtin_amdgcn_perm(xv[it][7], xv[it][6], 0x07060302u);
+            *reinterpret_cast<uint4 *>(sX + (2 * p2) * XSTR + 16 * t16 + 8 * kgx) = lo;
+            *reinterpret_cast<uint4 *>(sX + (2 * p2 + 1) * XSTR + 16 * t16 + 8 * kgx) = hi;
+        }
+    };
+    stage_x(xv, sX);
     lds_barrier();
 
     const float dsk = D ? D[h] : 0.f;
@@ -697,24 +805,29 @@ output_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ 
     // G^T tiles are streamed two pairs ahead of their use (tile index clamped to I, so the
     // loads are unconditional and the wait counters stay exact).
     const uint16_t *tile0 = cb + ((bcg * NP + I * (I + 1) / 2) * 2 * 64 + lane) * 8;
+    const int64_t cbimg = (int64_t)s.B * s.nc * s.G * NP * 1024;   // elements per slot image of the tiles
     auto load_tile = [&](int J, uint4 &u0, uint4 &u1) {
         const uint16_t *t = tile0 + min(J, I) * (2 * 64 * 8);
         u0 = *reinterpret_cast<const uint4 *>(t);
         u1 = *reinterpret_cast<const uint4 *>(t + 64 * 8);
     };
     uint4 uA0, uA1, uB0, uB1;
-    load_tile(0, uA0, uA1);
-    load_tile(1, uB0, uB1);
+    if constexpr (!SLOTS) {
+        load_tile(0, uA0, uA1);
+        load_tile(1, uB0, uB1);
+    }
     {
         // x of the skip term, loaded the way y is stored: lane -> (token row, 16-byte piece)
         const int erow = lane >> 3, epiece = lane & 7;
         const bool epok = epiece * 8 < s.P;
         const int eoff = epok ? epiece * 8 : 0;
         uint4 xe[4];
+        if (!SLOTS) {
 #pragma unroll
-        for (int q4 = 0; q4 < 4; ++q4) {
-            const int i = I * 32 + erow + 8 * q4;
-            xe[q4] = *reinterpret_cast<const uint4 *>(xh + min(i, valid - 1) * tokstride + eoff);
+            for (int q4 = 0; q4 < 4; ++q4) {
+                const int i = I * 32 + erow + 8 * q4;
+                xe[q4] = *reinterpret_cast<const uint4 *>(xh + min(i, valid - 1) * tokstride + eoff);
+            }
         }
         // keep these loads (first two G^T tiles, x of the skip term) in front of the MFMAs below:
         // moved behind them, the first tile pair would wait a full memory latency
@@ -735,7 +848,7 @@ output_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ 
             for (int v = 0; v < 16; ++v) { y0[v] *= sc; y1[v] *= sc; }
         }
         // ---- intra-chunk part ----
-        auto pair = [&](int J, uint4 u0, uint4 u1) {
+        auto pair = [&](int J, uint4 u0, uint4 u1, int xoff) __attribute__((always_inline)) {
             float m[16];
             unpack8(m, u0);
             unpack8(m + 8, u1);
@@ -772,25 +885,116 @@ output_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ 
 #pragma unroll
             for (int t = 0; t < 2; ++t) {
                 const uint4 mfrag = pack8(m + 8 * t);
-                const uint4 x0 = *reinterpret_cast<const uint4 *>(sXr0 + J * 32 + 16 * t);
-                const uint4 x1 = *reinterpret_cast<const uint4 *>(sXr1 + J * 32 + 16 * t);
+                const uint4 x0 = *reinterpret_cast<const uint4 *>(sXr0 + xoff + J * 32 + 16 * t);
+                const uint4 x1 = *reinterpret_cast<const uint4 *>(sXr1 + xoff + J * 32 + 16 * t);
                 y0 = mfma32(x0, mfrag, y0);
                 y1 = mfma32(x1, mfrag, y1);
             }
         };
-        {   // three tile buffers rotate by name, so no register moves sit behind the loads
+        if constexpr (!SLOTS) {
+            // three tile buffers rotate by name, so no register moves sit behind the loads
             uint4 uC0, uC1;
             int J = 0;
             while (true) {
                 load_tile(J + 2, uC0, uC1);
-                pair(J, uA0, uA1);
+                pair(J, uA0, uA1, 0);
                 if (++J > I) break;
                 load_tile(J + 2, uA0, uA1);
-                pair(J, uB0, uB1);
+                pair(J, uB0, uB1, 0);
                 if (++J > I) break;
                 load_tile(J + 2, uB0, uB1);
-                pair(J, uC0, uC1);
+                pair(J, uC0, uC1, 0);
                 if (++J > I) break;
+            }
+        } else {
+            // Slots two at a time, their x tiles side by side in LDS.  The first pair's tiles were
+            // loaded in the prologue; the second tile of a pair is staged once every wave has read
+            // the carried state out of the space it takes.
+            const int iw = I * 32 + l32;                       // this lane's token (column of the tile)
+            const float *wtok = skip_w + (tok0 + min(iw, valid - 1)) * skip_stride;
+            lds_barrier();
+            stage_x(xw, sX1);
+            lds_barrier();
+            for (int g0 = 0; g0 < nslots; g0 += 2) {
+                const int ns = min(2, nslots - g0);
+                // router weights of the two slots for the skip term
+                const float w0 = wtok[g0], w1 = wtok[min(g0 + 1, nslots - 1)];
+                if (g0 > 0) {
+                    // stride and last row go through opaque copies: the row addresses are rebuilt here instead
+                    // of living in registers (or scratch memory) across the whole kernel
+                    int xts_r = xts, vlast_r = valid - 1;
+                    asm volatile("" : "+s"(xts_r), "+s"(vlast_r));
+                    load_x(xv, xh + g0 * tokstride, xts_r, vlast_r);
+                    load_x(xw, xh + min(g0 + 1, nslots - 1) * tokstride, xts_r, vlast_r);
+                    lds_barrier();                              // every wave is done with the previous pair of slots
+                    stage_x(xv, sX);
+                    stage_x(xw, sX1);
+                    lds_barrier();
+                }
+                // the (slot, J) steps of the pair of slots as one sequence; three tile buffers rotate by
+                // name and the loads run two steps ahead, across the change of slot
+                const uint16_t *tileg = tile0 + g0 * cbimg;
+                int pj = 0, psl = 0;
+                auto fetch = [&](uint4 &u0, uint4 &u1) __attribute__((always_inline)) {
+                    const uint16_t *t = tileg + psl * cbimg + pj * (2 * 64 * 8);
+                    u0 = *reinterpret_cast<const uint4 *>(t);
+                    u1 = *reinterpret_cast<const uint4 *>(t + 64 * 8);
+                    // next tile; past the last step the counters stay on the last tile (plain selects: a
+                    // conditional store to one of two counters would put both in scratch memory)
+                    const bool more = pj < I, wrap = !more && psl + 1 < ns;
+                    pj = more ? pj + 1 : (wrap ? 0 : pj);
+                    psl = wrap ? psl + 1 : psl;
+                };
+                int cj = 0, csl = 0;
+                auto step = [&](uint4 u0, uint4 u1) __attribute__((always_inline)) {
+                    pair(cj, u0, u1, csl * (MP * XSTR));
+                    const bool last = (cj == I);
+                    const int slot_now = csl;
+                    cj = last ? 0 : cj + 1;
+                    csl = last ? csl + 1 : csl;
+                    if (!last) return;
+                    // that was the last tile of the slot; now its skip term: Y^T += x^T . diag(D pi_{i,r}); the B operand
+                    // of k-step t holds rows j = 16t + 8(e>>2) + 4kg + (e&3) of column i = l32, non-zero
+                    // where j == i
+                    const float dv = (iw < valid) ? dsk * (slot_now ? w1 : w0) : 0.f;
+                    const uint32_t dh = bf16_bits_rne(dv);
+                    const uint32_t dl = bf16_bits_rne(dv - __uint_as_float(dh << 16));
+#pragma unroll
+                    for (int t = 0; t < 2; ++t) {
+                        uint32_t wh[4], wl[4];
+#pragma unroll
+                        for (int e2 = 0; e2 < 4; ++e2) {
+                            const int e = 2 * e2;
+                            const int j0 = 16 * t + 8 * (e >> 2) + 4 * kg + (e & 3), j1 = j0 + 1;
+                            wh[e2] = (j0 == l32 ? dh : 0u) | (j1 == l32 ? dh << 16 : 0u);
+                            wl[e2] = (j0 == l32 ? dl : 0u) | (j1 == l32 ? dl << 16 : 0u);
+                        }
+                        const uint4 mh = make_uint4(wh[0], wh[1], wh[2], wh[3]);
+                        const uint4 ml = make_uint4(wl[0], wl[1], wl[2], wl[3]);
+                        const uint4 x0 = *reinterpret_cast<const uint4 *>(sXr0 + slot_now * (MP * XSTR) + I * 32 + 16 * t);
+                        const uint4 x1 = *reinterpret_cast<const uint4 *>(sXr1 + slot_now * (MP * XSTR) + I * 32 + 16 * t);
+                        y0 = mfma32(x0, mh, y0);
+                        y1 = mfma32(x1, mh, y1);
+                        y0 = mfma32(x0, ml, y0);
+                        y1 = mfma32(x1, ml, y1);
+                    }
+                };
+                const int steps = ns * (I + 1);
+                uint4 uC0, uC1;
+                fetch(uA0, uA1);
+                fetch(uB0, uB1);
+                int q = 0;
+                while (true) {
+                    fetch(uC0, uC1);
+                    step(uA0, uA1);
+                    if (++q >= steps) break;
+                    fetch(uA0, uA1);
+                    step(uB0, uB1);
+                    if (++q >= steps) break;
+                    fetch(uB0, uB1);
+                    step(uC0, uC1);
+                    if (++q >= steps) break;
+                }
             }
         }
         // ---- y = acc + D x.  The wave's 32 x 64 tile goes through LDS (the x^T tile is
@@ -816,22 +1020,27 @@ output_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ 
         for (int q4 = 0; q4 < 4; ++q4) {
             const int row = erow + 8 * q4, i = I * 32 + row;
             if (i < valid && epok) {
-                float a[8], xf[8];
-                unpack8(a, *reinterpret_cast<const uint4 *>(scr + row * YSTR + ((epiece ^ (row & 7)) << 3)));
-                unpack8(xf, xe[q4]);
-                float dski = dsk;
-                if (XE) {
-                    if (skip_w) dski *= skip_w[(tok0 + i) * skip_stride];
-                    if (accumulate) {
-                        float prev[8];
-                        unpack8(prev, *reinterpret_cast<const uint4 *>(yh + i * tokstride + epiece * 8));
+                const uint4 tile_row = *reinterpret_cast<const uint4 *>(scr + row * YSTR + ((epiece ^ (row & 7)) << 3));
+                if (SLOTS) {
+                    store_nt(yh + i * tokstride + epiece * 8, tile_row);   // the skip term is in the tile already
+                } else {
+                    float a[8], xf[8];
+                    unpack8(a, tile_row);
+                    unpack8(xf, xe[q4]);
+                    float dski = dsk;
+                    if (XE) {
+                        if (skip_w) dski *= skip_w[(tok0 + i) * skip_stride];
+                        if (accumulate) {
+                            float prev[8];
+                            unpack8(prev, *reinterpret_cast<const uint4 *>(yh + i * tokstride + epiece * 8));
 #pragma unroll
-                        for (int e = 0; e < 8; ++e) a[e] += prev[e];
+                            for (int e = 0; e < 8; ++e) a[e] += prev[e];
+                        }
                     }
-                }
 #pragma unroll
-                for (int e = 0; e < 8; ++e) a[e] += dski * xf[e];
-                store_nt(yh + i * tokstride + epiece * 8, pack8(a));
+                    for (int e = 0; e < 8; ++e) a[e] += dski * xf[e];
+                    store_nt(yh + i * tokstride + epiece * 8, pack8(a));
+                }
             }
         }
     }
@@ -840,22 +1049,38 @@ output_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ 
 template <int Q>
 static swimba_status launch_out_q(const Shape &s, const void *x, const void *dt, const float *D,
                                   const void *cmix, const void *cb, const float *cs, const void *Hlp,
-                                  void *y, const float *skip_w, int skip_stride, int accumulate,
+                                  void *y, const float *skip_w, int skip_stride, int accumulate, int nslots,
                                   hipStream_t st)
 {
     const int64_t total = (int64_t)s.B * s.nc * s.H;
     if (total == 0) return SWIMBA_OK;
     const int nblocks = xcd_padded(total);
-    if (skip_w || accumulate)
-        hipLaunchKernelGGL((output_mfma_kernel<Q, true>), dim3(nblocks), dim3(64 * (Q / 32)), 0, st,
-                           (const uint16_t *)x, (const uint16_t *)dt, D, (const uint16_t *)cmix,
-                           (const uint16_t *)cb, cs, (const uint16_t *)Hlp, (uint16_t *)y, s, (int)total,
-                           nblocks, skip_w, skip_stride, accumulate);
-    else
-        hipLaunchKernelGGL((output_mfma_kernel<Q, false>), dim3(nblocks), dim3(64 * (Q / 32)), 0, st,
-                           (const uint16_t *)x, (const uint16_t *)dt, D, (const uint16_t *)cmix,
-                           (const uint16_t *)cb, cs, (const uint16_t *)Hlp, (uint16_t *)y, s, (int)total,
-                           nblocks, nullptr, 0, 0);
+#define SWIMBA_OUT_LAUNCH(MODE, SHM, SW, SS, ACC, NSL)                                                             \
+    hipLaunchKernelGGL((output_mfma_kernel<Q, MODE>), dim3(nblocks), dim3(64 * (Q / 32)), SHM, st,                \
+                       (const uint16_t *)x, (const uint16_t *)dt, D, (const uint16_t *)cmix, (const uint16_t *)cb, \
+                       cs, (const uint16_t *)Hlp, (uint16_t *)y, s, (int)total, nblocks, SW, SS, ACC, NSL)
+    if (nslots > 0) {
+        // two x tiles (the second in the place of the carried-state tile) and the three tables
+        constexpr int XSTR = Q + 8, HSTR = MN + 8;
+        constexpr size_t shm = (size_t)(MP * XSTR + MP * (XSTR > HSTR ? XSTR : HSTR)) * 2 + 3 * Q * sizeof(float);
+        static std::atomic<uint64_t> attr_set{0};            // one bit per device ordinal
+        int dev = 0;
+        hipError_t e = hipGetDevice(&dev);
+        if (e != hipSuccess) { set_last_hip_error((int)e); return SWIMBA_ERR_HIP; }
+        const uint64_t bit = 1ull << (dev & 63);
+        if (!(attr_set.load(std::memory_order_acquire) & bit)) {
+            e = hipFuncSetAttribute((const void *)output_mfma_kernel<Q, 2>, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                    (int)shm);
+            if (e != hipSuccess) { set_last_hip_error((int)e); return SWIMBA_ERR_HIP; }
+            attr_set.fetch_or(bit, std::memory_order_release);
+        }
+        SWIMBA_OUT_LAUNCH(2, shm, skip_w, skip_stride, 0, nslots);
+    } else if (skip_w || accumulate) {
+        SWIMBA_OUT_LAUNCH(1, 0, skip_w, skip_stride, accumulate, 1);
+    } else {
+        SWIMBA_OUT_LAUNCH(0, 0, nullptr, 0, 0, 1);
+    }
+#undef SWIMBA_OUT_LAUNCH
     SWIMBA_CHECK_LAUNCH();
     return SWIMBA_OK;
 }
@@ -866,9 +1091,24 @@ swimba_status launch_output_mfma(const Shape &s, const void *x, const void *dt, 
                                  int accumulate, hipStream_t st)
 {
     switch (s.Q) {
-    case 64: return launch_out_q<64>(s, x, dt, D, cmix, cb, cs, states_lp, y, skip_w, skip_stride, accumulate, st);
-    case 128: return launch_out_q<128>(s, x, dt, D, cmix, cb, cs, states_lp, y, skip_w, skip_stride, accumulate, st);
-    case 256: return launch_out_q<256>(s, x, dt, D, cmix, cb, cs, states_lp, y, skip_w, skip_stride, accumulate, st);
+    case 64: return launch_out_q<64>(s, x, dt, D, cmix, cb, cs, states_lp, y, skip_w, skip_stride, accumulate, 0, st);
+    case 128: return launch_out_q<128>(s, x, dt, D, cmix, cb, cs, states_lp, y, skip_w, skip_stride, accumulate, 0, st);
+    case 256: return launch_out_q<256>(s, x, dt, D, cmix, cb, cs, states_lp, y, skip_w, skip_stride, accumulate, 0, st);
+    }
+    return SWIMBA_ERR_UNSUPPORTED;
+}
+
+// all slots of the forward with one input stream per expert in one launch: x (B, L, nslots, H, P),
+// cb = nslots images of G^T tiles, w (B, L, nslots) router weights of the slots
+swimba_status launch_output_slots_mfma(const Shape &s, const void *x, const void *dt, const float *D,
+                                       const void *cmix, const void *cb, const float *cs,
+                                       const void *states_lp, void *y, const float *w, int nslots, hipStream_t st)
+{
+    if (nslots < 1 || !w) return SWIMBA_ERR_UNSUPPORTED;
+    switch (s.Q) {
+    case 64: return launch_out_q<64>(s, x, dt, D, cmix, cb, cs, states_lp, y, w, nslots, 0, nslots, st);
+    case 128: return launch_out_q<128>(s, x, dt, D, cmix, cb, cs, states_lp, y, w, nslots, 0, nslots, st);
+    case 256: return launch_out_q<256>(s, x, dt, D, cmix, cb, cs, states_lp, y, w, nslots, 0, nslots, st);
     }
     return SWIMBA_ERR_UNSUPPORTED;
 }

@@ -9,7 +9,8 @@
 
 namespace swimba {
 
-// xg[t][:] = x_experts[t][idx[t][slot]][:], 16 bytes per lane when the row length allows
+// xg[t][:] = x_experts[t][idx[t][slot]][:], 16 bytes per lane when the row length allows;
+// with slot < 0 every slot: xg[t][r][:] = x_experts[t][idx[t][r]][:]
 template <int BYTES>
 __global__ void __launch_bounds__(256)
 xe_gather_kernel(const unsigned char *__restrict__ xe, const int32_t *__restrict__ idx,
@@ -17,11 +18,13 @@ xe_gather_kernel(const unsigned char *__restrict__ xe, const int32_t *__restrict
 {
     const int64_t per_tok = row_bytes / BYTES;
     const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (i >= tokens * per_tok) return;
-    const int64_t t = i / per_tok, o = (i % per_tok) * BYTES;
-    const int e = idx[t * K + slot];
+    const int64_t rows = (slot < 0) ? tokens * K : tokens;
+    if (i >= rows * per_tok) return;
+    const int64_t row = i / per_tok, o = (i % per_tok) * BYTES;
+    const int64_t t = (slot < 0) ? row / K : row;
+    const int e = idx[(slot < 0) ? row : t * K + slot];
     const unsigned char *src = xe + (t * E + e) * row_bytes + o;
-    unsigned char *dst = xg + t * row_bytes + o;
+    unsigned char *dst = xg + row * row_bytes + o;
     if (BYTES == 16)
         *reinterpret_cast<uint4 *>(dst) = *reinterpret_cast<const uint4 *>(src);
     else if (BYTES == 4)
@@ -46,7 +49,8 @@ swimba_status launch_xe_gather(const Shape &s, int io_dtype, int slot, const voi
     if (T == 0) return SWIMBA_OK;
     // rows start at multiples of row_bytes from 16-byte aligned bases
     const int bytes = (row_bytes % 16 == 0) ? 16 : (row_bytes % 4 == 0) ? 4 : 2;
-    const dim3 grid((unsigned)((T * (row_bytes / bytes) + 255) / 256));
+    const int64_t rows = (slot < 0) ? T * s.K : T;
+    const dim3 grid((unsigned)((rows * (row_bytes / bytes) + 255) / 256));
     const unsigned char *src = (const unsigned char *)x_experts;
     unsigned char *dst = (unsigned char *)xg;
     if (bytes == 16)

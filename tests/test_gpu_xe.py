@@ -7,7 +7,8 @@ import torch
 from oracle import swimba_oracle as orc
 from paper_2603_06938_amd import binding as sw
 from paper_2603_06938_amd import synth
-from gpu_util import IO, TOL, host, rel_errors, run_mixer, to_device
+from gpu_util import (IO, TOL, abs_inputs, comp_tol, componentwise_excess, host, rel_errors, run_mixer,
+                      to_device)
 
 pytestmark = pytest.mark.gpu
 
@@ -43,7 +44,29 @@ SHAPES = [
     (2, 300, 4, 64, 128, 2, 8, 2, 128, "bf16"),  # MFMA kernels, ragged tail, groups
     (1, 257, 2, 64, 128, 1, 4, 3, 64, "bf16"),
     (1, 520, 4, 64, 128, 2, 16, 1, 256, "bf16"),
+    (2, 700, 8, 64, 128, 2, 8, 2, 256, "bf16"),  # several full chunks of 256 and a tail, two slots
+    (1, 333, 4, 24, 120, 2, 6, 4, 128, "bf16"),  # padded P and N, the most slots the slot kernels take
+    (1, 200, 2, 64, 128, 1, 6, 5, 64, "bf16"),   # more slots than that: one MFMA pass per slot
 ]
+
+
+def selected_rows(p, topk_idx, topk_w):
+    """rows of the k selected experts per token, as a projection restricted to the active set leaves them"""
+    idx = np.asarray(topk_idx).astype(np.int64)
+    take = lambda a: np.take_along_axis(a, idx.reshape(idx.shape + (1,) * (a.ndim - 3)), axis=2)
+    return take(p["x_experts"]), take(p["B_experts"]), take(p["C_experts"]), np.asarray(topk_w, dtype=np.float32)
+
+
+def run_xe_selected(p, topk_idx, topk_w, chunk, io, h0=None, d_none=False):
+    xs, bs, cs, w = selected_rows(p, topk_idx, topk_w)
+    dev = "cuda:0"
+    t = lambda a: torch.from_numpy(np.ascontiguousarray(a)).to(IO[io]).to(dev)
+    d = to_device(p, io)
+    h0d = None if h0 is None else torch.from_numpy(np.asarray(h0, dtype=np.float32)).to(dev)
+    out = sw.swimba_mixer_fwd_xe_selected(t(xs), d["dt"], d["A"], None if d_none else d["D"], t(bs), t(cs),
+                                          torch.from_numpy(w).to(dev), chunk, h0d)
+    torch.cuda.synchronize()
+    return out
 
 
 @pytest.mark.parametrize("cfg", SHAPES, ids=lambda c: "B%dL%dH%dP%dN%dG%dE%dk%dQ%d%s" % c)
@@ -62,6 +85,24 @@ def test_xe_matches_oracle(cfg):
         assert l2 <= TOL[io] and linf <= TOL[io], ("y", d_none, l2, linf)
         l2, linf = rel_errors(host(out.h_final), ref["h_final"], (0, 1))
         assert l2 <= TOL[io] and linf <= TOL[io], ("h_final", d_none, l2, linf)
+        # every element within the forward-error bound of its own sum of term magnitudes
+        q = abs_inputs(p)
+        aref = orc.mixer_fwd_xe(q["x_experts"], p["dt"], p["A"], None if d_none else q["D"], q["B_experts"],
+                                q["C_experts"], p["router_logits"], k, h0=None if h0v is None else np.abs(h0v))
+        ex_y = componentwise_excess(host(out.y), ref["y"], aref["y"])
+        ex_h = componentwise_excess(host(out.h_final), ref["h_final"], aref["h_final"])
+        print("   componentwise y %.3e h_final %.3e" % (ex_y, ex_h), flush=True)
+        assert ex_y <= comp_tol(io) and ex_h <= comp_tol(io), (ex_y, ex_h)
+        # the same forward on the rows of the selected experts only
+        # (selection and weights as the routed call returned them, so both calls mix with the same bits)
+        sel = run_xe_selected(p, out.topk_idx.cpu().numpy(), out.topk_w.cpu().numpy(), Q, io, h0=h0v, d_none=d_none)
+        l2, linf = rel_errors(host(sel.y), ref["y"], (0, 2))
+        assert l2 <= TOL[io] and linf <= TOL[io], ("selected y", d_none, l2, linf)
+        l2, linf = rel_errors(host(sel.h_final), ref["h_final"], (0, 1))
+        assert l2 <= TOL[io] and linf <= TOL[io], ("selected h_final", d_none, l2, linf)
+        if io == "bf16" and P % 8 == 0 and N % 8 == 0 and Q in (64, 128, 256) and k <= 4:
+            # slot kernels: both entries run the same launches on the same rows
+            assert torch.equal(sel.y, out.y) and torch.equal(sel.h_final, out.h_final)
 
 
 def test_xe_with_one_shared_stream_is_the_shared_x_forward():
