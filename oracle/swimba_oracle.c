@@ -25,7 +25,9 @@
  *               every expert e, y_t = sum_{e in K_t} pi_{t,e} C_t^(e) . h_t^(e)
  *               + D_h x_t                       (separated-SSM equation)
  *   projection  B_t^(e), C_t^(e) for the active experts only, as expert-specific
- *               linear maps of the token features (swimba_oracle_expert_proj)
+ *               linear maps of the token features (swimba_oracle_expert_proj), and the
+ *               input streams x_t^(e) of the active experts the same way, stored per
+ *               selected slot (swimba_oracle_expert_proj_x)
  *   router map  g_t = W_g u_t, the routing logits as a linear function of the
  *               token features (swimba_oracle_router_linear)
  *   expert x    the mixed state update in its full form, with one input stream
@@ -271,6 +273,35 @@ int swimba_oracle_expert_proj(int64_t T, int64_t Dm, int64_t E, int64_t k, int64
                 }
                 Be[(t * E + e) * GN + c] = sb;
                 Ce[(t * E + e) * GN + c] = sc;
+            }
+        }
+    }
+    return 0;
+}
+
+/*
+ * Routed in-projection of the input streams (paper, MoE-parameterized SSM: the experts also emit
+ * X^(e), an expert-specific linear map of the token features, and the mixed state update injects
+ * the products B^(e) X^(e) of the active set):
+ *   x_t^(e_r)[c] = sum_d WX[e_r][c][d] u_t[d]     for the token's r-th active expert e_r
+ *   u (T,Dm)  WX (E, HP, Dm)  logits (T,E)  ->  Xsel (T, k, HP) double, row r of a token belongs
+ *   to its r-th active expert in router order (no array with an expert axis is formed).
+ */
+int swimba_oracle_expert_proj_x(int64_t T, int64_t Dm, int64_t E, int64_t k, int64_t HP,
+                                const float *u, const float *WX, const float *logits,
+                                double *Xsel, int32_t *idx, double *w)
+{
+    if (T < 0 || Dm < 1 || HP < 1 || E < 1 || k < 1 || k > E) return 1;
+    if (swimba_oracle_router(logits, T, E, k, idx, w)) return 1;
+#pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < T; ++t) {
+        for (int64_t r = 0; r < k; ++r) {
+            const int64_t e = idx[t * k + r];
+            for (int64_t c = 0; c < HP; ++c) {
+                const float *wx = WX + (e * HP + c) * Dm;
+                double sx = 0.0;
+                for (int64_t d = 0; d < Dm; ++d) sx += (double)wx[d] * (double)u[t * Dm + d];
+                Xsel[(t * k + r) * HP + c] = sx;
             }
         }
     }

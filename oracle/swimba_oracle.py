@@ -162,6 +162,24 @@ def expert_proj(u, W_B, W_C, router_logits, top_k: int, fill=np.nan):
     return {"B_experts": Be, "C_experts": Ce, "topk_idx": idx, "topk_w": w}
 
 
+def expert_proj_x(u, W_X, router_logits, top_k: int):
+    """Routed in-projection of the input streams.  u (B,L,Dm), W_X (E,H,P,Dm), router_logits (B,L,E)
+    -> x_sel (B,L,k,H,P) float64, row r = the token's r-th active expert; topk_idx, topk_w."""
+    u = _f32(u); WX = _f32(W_X); g = _f32(router_logits)
+    B, L, Dm = u.shape
+    E, H, P, Dm2 = WX.shape
+    assert Dm2 == Dm and g.shape == (B, L, E)
+    xs = np.zeros((B, L, top_k, H, P), dtype=np.float64)
+    idx = np.zeros((B, L, top_k), dtype=np.int32)
+    w = np.zeros((B, L, top_k), dtype=np.float64)
+    i64 = ctypes.c_int64
+    rc = _load().swimba_oracle_expert_proj_x(i64(B * L), i64(Dm), i64(E), i64(top_k), i64(H * P), _p(u), _p(WX),
+                                             _p(g), _p(xs), _p(idx), _p(w))
+    if rc:
+        raise ValueError("oracle expert_proj_x: bad arguments")
+    return {"x_sel": xs, "topk_idx": idx, "topk_w": w}
+
+
 def router_linear(u, W_g) -> np.ndarray:
     """Routing logits g = W_g u for every token: u (B,L,Dm), W_g (E,Dm) -> (B,L,E) float64."""
     u = _f32(u); Wg = _f32(W_g)

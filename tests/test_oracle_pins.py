@@ -364,6 +364,54 @@ def test_expert_proj_feeds_the_mixer_like_a_dense_projection():
     np.testing.assert_allclose(a["y"], b["y"], rtol=1e-12, atol=1e-14)
 
 
+def test_expert_proj_x_hand_values_and_library_contraction():
+    # hand values: u = (1, -2); expert 0 maps to (u0 + u1, 3 u0), expert 1 to (2 u1, u0 - u1);
+    # logits (0, 1) pick expert 1 first, then expert 0
+    u = np.array([[[1.0, -2.0]]], dtype=np.float32)
+    WX = np.array([[[[1.0, 1.0], [3.0, 0.0]]], [[[0.0, 2.0], [1.0, -1.0]]]], dtype=np.float32)   # (E=2, H=1, P=2, Dm=2)
+    r = orc.expert_proj_x(u, WX, np.array([[[0.0, 1.0]]], dtype=np.float32), 2)
+    np.testing.assert_array_equal(r["topk_idx"], [[[1, 0]]])
+    np.testing.assert_array_equal(r["x_sel"], [[[[[-4.0, 3.0]], [[-1.0, 3.0]]]]])
+    # against a dense library contraction of every expert, gathered in router order; odd sizes so
+    # that no two axes can be interchanged unnoticed
+    rng = np.random.default_rng(41)
+    B, L, Dm, E, H, P, k = 2, 7, 11, 5, 3, 4, 3
+    u = rng.standard_normal((B, L, Dm)).astype(np.float32)
+    WX = rng.standard_normal((E, H, P, Dm)).astype(np.float32)
+    g = rng.standard_normal((B, L, E)).astype(np.float32)
+    r = orc.expert_proj_x(u, WX, g, k)
+    dX = np.einsum("bld,ehpd->blehp", u.astype(np.float64), WX.astype(np.float64))
+    wts, order = dense_router_weights(g, k)
+    np.testing.assert_array_equal(r["topk_idx"], order)
+    want = np.take_along_axis(dX, order[..., None, None], axis=2)
+    assert r["x_sel"].shape == (B, L, k, H, P)
+    np.testing.assert_allclose(r["x_sel"], want, rtol=1e-12, atol=1e-13)
+    np.testing.assert_allclose(r["topk_w"], np.take_along_axis(wts, order, axis=2), rtol=1e-12)
+    # one-hot features pick out single weight columns
+    onehot = np.zeros((1, 1, Dm), dtype=np.float32)
+    onehot[0, 0, 4] = 1.0
+    r1 = orc.expert_proj_x(onehot, WX, g[:1, :1], 1)
+    np.testing.assert_array_equal(r1["x_sel"][0, 0, 0], WX[r1["topk_idx"][0, 0, 0], :, :, 4].astype(np.float64))
+
+
+def test_expert_proj_x_feeds_the_expert_x_forward_like_a_dense_projection():
+    # the forward only reads the rows of the active experts: scattering the selected rows back
+    # into a (B,L,E,H,P) array of zeros gives the same result as projecting every expert
+    rng = np.random.default_rng(42)
+    p = small_problem(42, B=1, L=10, H=2, P=3, N=4, G=1, E=4)
+    Dm = 5
+    u = rng.standard_normal((1, 10, Dm)).astype(np.float32)
+    WX = (rng.standard_normal((4, 2, 3, Dm)) / 3).astype(np.float32)
+    sel = orc.expert_proj_x(u, WX, p["router_logits"], 2)
+    dense = np.einsum("bld,ehpd->blehp", u.astype(np.float64), WX.astype(np.float64))
+    scattered = np.zeros_like(dense)
+    np.put_along_axis(scattered, sel["topk_idx"].astype(np.int64)[..., None, None], sel["x_sel"], axis=2)
+    a = call_xe(dict(p, x_experts=scattered.astype(np.float32)), 2)
+    b = call_xe(dict(p, x_experts=dense.astype(np.float32)), 2)
+    np.testing.assert_allclose(a["y"], b["y"], rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(a["h_final"], b["h_final"], rtol=1e-12, atol=1e-14)
+
+
 def test_router_linear_hand_values_and_library_contraction():
     # hand values: u = (1, 2), W_g = [[3, 4], [5, 6], [-1, 0.5]] -> g = (11, 17, 0)
     g = orc.router_linear(np.array([[[1.0, 2.0]]], dtype=np.float32),
