@@ -416,8 +416,35 @@ def main() -> int:
         dms = time_loop(dense_step, K)
         proj_res["features_to_y"] = {"selected_streams_ms": round(fms, 5), "dense_streams_ms": round(dms, 5),
                                      "tokens_per_s": round(T / fms * 1e3, 1)}
+        # the same with the experts' input streams as a third block of columns, [B | C | X], and the
+        # expert-X forward on the projected rows
+        WXs = (torch.randn((E, H, P, Dm), generator=gen, device=dev) / Dm ** 0.5).to(io)
+        xpw = torch.empty(sw.swimba_expert_proj_x_workspace_bytes(head.dims, Dm), dtype=torch.uint8, device=dev)
+
+        def projx_step(i):
+            d = head.sets[i % head.nsets]
+            sw.swimba_expert_proj_x_selected(us[i % 3], WBs, WCs, WXs, d["router_logits"], w.top_k, workspace=xpw,
+                                             want_topk=False)
+
+        time_loop(projx_step, 3)
+        xms = time_loop(projx_step, K)
+        xflops = 2.0 * T * k * Dm * (2 * G * N + H * P)
+        xfw = torch.empty(sw.swimba_mixer_xe_proj_workspace_bytes(head.dims, Dm), dtype=torch.uint8, device=dev)
+
+        def fused_x_step(i):
+            d = head.sets[i % head.nsets]
+            sw.swimba_mixer_fwd_xe_proj(us[i % 3], WBs, WCs, WXs, d["dt"], d["A"], d["D"], d["router_logits"],
+                                        w.top_k, w.chunk, y=d["y"], h_final=d["h_final"], workspace=xfw)
+
+        time_loop(fused_x_step, 3)
+        fxms = time_loop(fused_x_step, K)
+        proj_res["with_input_streams"] = {
+            "what": "[B | C | X] rows of the top-%d experts, %d output columns" % (k, 2 * G * N + H * P),
+            "ms": round(xms, 5), "mfma_TFLOPs": round(xflops / xms / 1e9, 1),
+            "mfma_frac": round(xflops / xms / 1e9 / PEAK_BF16_TFLOPS, 4),
+            "features_to_y_ms": round(fxms, 5), "tokens_per_s": round(T / fxms * 1e3, 1)}
         # the projection overwrote the synthetic expert rows of every set with its own values
-        del us, WBs, WCs, pws, fws
+        del us, WBs, WCs, WXs, pws, fws, xpw, xfw
 
     # ---- one input stream per expert (rank-k injection) -------------------------------------------
     xe_res = None

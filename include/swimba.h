@@ -328,6 +328,36 @@ swimba_status swimba_expert_proj_selected(const swimba_dims *dims, int32_t d_mod
                                           void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /*
+ * The projection with the experts' input streams as a third block of output columns (paper,
+ * MoE-parameterized SSM: every expert emits X^(e), B^(e), C^(e) from the token features; the
+ * mixed state update as printed injects sum_{e in K_t} pi_{t,e} B^(e) X^(e)):
+ *   x_t^(e)[h][p] = sum_d W_X[e][h][p][d] u_t[d]
+ *   W_X   (E,H,P,d_model) io [in]    input index d contiguous
+ *   x_sel (B,L,k,H,P) io [out]       row r of token t is the stream of expert topk_idx[t][r]
+ * B_sel, C_sel and every other argument as in swimba_expert_proj_selected; the three blocks are
+ * columns of one grouped GEMM.  The GEMM path additionally needs (H*P) % 64 == 0; dims->nheads
+ * and headdim are used.  The outputs feed swimba_mixer_fwd_xe_selected.
+ *   workspace >= swimba_expert_proj_x_workspace_bytes(dims, d_model), 256-byte aligned.
+ *
+ * swimba_mixer_fwd_xe_proj: this projection into the workspace and swimba_mixer_fwd_xe_selected
+ * on its outputs in one call, token features -> y with nothing that has an expert axis except
+ * the weights.  dt, A, D, h0, y, h_final, topk_idx, topk_w as in swimba_mixer_fwd.
+ *   workspace >= swimba_mixer_xe_proj_workspace_bytes(dims, d_model), 256-byte aligned.
+ */
+size_t swimba_expert_proj_x_workspace_bytes(const swimba_dims *dims, int32_t d_model);
+swimba_status swimba_expert_proj_x_selected(const swimba_dims *dims, int32_t d_model, const void *u,
+                                            const void *W_B, const void *W_C, const void *W_X,
+                                            const void *router_logits, void *B_sel, void *C_sel, void *x_sel,
+                                            int32_t *topk_idx, float *topk_w, void *workspace,
+                                            size_t workspace_bytes, void *hip_stream);
+size_t swimba_mixer_xe_proj_workspace_bytes(const swimba_dims *dims, int32_t d_model);
+swimba_status swimba_mixer_fwd_xe_proj(const swimba_dims *dims, int32_t d_model, const void *u, const void *W_B,
+                                       const void *W_C, const void *W_X, const void *dt, const float *A,
+                                       const float *D, const void *router_logits, const float *h0, void *y,
+                                       float *h_final, int32_t *topk_idx, float *topk_w, void *workspace,
+                                       size_t workspace_bytes, void *hip_stream);
+
+/*
  * swimba_mixer_fwd on the streams of the selected experts only (paper: parameter-space
  * mixing, Bmix_t = sum_{e in K_t} pi_{t,e} B_t^(e), likewise Cmix; one SSD recurrence):
  *   B_sel, C_sel (B,L,k,G,N) io [in]  row r of a token = stream of its r-th selected expert

@@ -5,7 +5,8 @@ recipe.  Nothing here falls back to the CPU."""
 _BINDING_NAMES = (
     "swimba_mixer_fwd", "swimba_expert_proj", "swimba_expert_proj_workspace_bytes",
     "swimba_expert_proj_selected", "swimba_mixer_fwd_selected", "swimba_mixer_fwd_proj",
-    "swimba_mixer_proj_workspace_bytes", "swimba_router_linear", "swimba_mixer_fwd_xe", "swimba_mixer_fwd_xe_selected", "swimba_mixer_xe_selected_workspace_bytes", "swimba_mixer_xe_workspace_bytes", "swimba_separated_fwd", "swimba_separated_workspace_bytes", "swimba_step", "swimba_step_multi", "swimba_step_multi_workspace_bytes", "swimba_step_workspace_bytes", "swimba_router_topk", "swimba_mixer_workspace_bytes",
+    "swimba_mixer_proj_workspace_bytes", "swimba_router_linear", "swimba_mixer_fwd_xe", "swimba_mixer_fwd_xe_selected", "swimba_expert_proj_x_selected", "swimba_expert_proj_x_workspace_bytes",
+    "swimba_mixer_fwd_xe_proj", "swimba_mixer_xe_proj_workspace_bytes", "swimba_mixer_xe_selected_workspace_bytes", "swimba_mixer_xe_workspace_bytes", "swimba_separated_fwd", "swimba_separated_workspace_bytes", "swimba_step", "swimba_step_multi", "swimba_step_multi_workspace_bytes", "swimba_step_workspace_bytes", "swimba_router_topk", "swimba_mixer_workspace_bytes",
     "swimba_mixer_workspace_layout", "swimba_stage_router", "swimba_stage_cumsum",
     "swimba_stage_mix", "swimba_stage_chunk_state", "swimba_stage_state_scan", "swimba_stage_output",
     "swimba_stage_prep", "swimba_stage_pass", "swimba_prefill_path", "swimba_step_static",

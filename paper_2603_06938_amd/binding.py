@@ -99,6 +99,14 @@ def _load():
         lib.swimba_mixer_fwd_selected.argtypes = [dp] + [vp] * 10 + [vp, sz, vp]
         lib.swimba_mixer_proj_workspace_bytes.restype = sz
         lib.swimba_mixer_proj_workspace_bytes.argtypes = [dp, i32]
+        lib.swimba_expert_proj_x_workspace_bytes.restype = sz
+        lib.swimba_expert_proj_x_workspace_bytes.argtypes = [dp, i32]
+        lib.swimba_expert_proj_x_selected.restype = i32
+        lib.swimba_expert_proj_x_selected.argtypes = [dp, i32] + [vp] * 10 + [vp, sz, vp]
+        lib.swimba_mixer_xe_proj_workspace_bytes.restype = sz
+        lib.swimba_mixer_xe_proj_workspace_bytes.argtypes = [dp, i32]
+        lib.swimba_mixer_fwd_xe_proj.restype = i32
+        lib.swimba_mixer_fwd_xe_proj.argtypes = [dp, i32] + [vp] * 13 + [vp, sz, vp]
         lib.swimba_mixer_fwd_proj.restype = i32
         lib.swimba_mixer_fwd_proj.argtypes = [dp, i32] + [vp] * 13 + [vp, sz, vp]
         lib.swimba_mixer_xe_workspace_bytes.argtypes = [dp]
@@ -332,6 +340,77 @@ def swimba_expert_proj_selected(u, W_B, W_C, router_logits, top_k: int, *, B_sel
         _ptr(workspace, "workspace", torch.uint8), workspace.numel(), _stream())
     _check(st, "swimba_expert_proj_selected")
     return ProjOut(B_sel, C_sel, topk_idx, topk_w)
+
+
+def swimba_expert_proj_x_workspace_bytes(dims: swimba_dims, d_model: int) -> int:
+    return int(_load().swimba_expert_proj_x_workspace_bytes(ctypes.byref(dims), d_model))
+
+
+def swimba_expert_proj_x_selected(u, W_B, W_C, W_X, router_logits, top_k: int, *, workspace=None,
+                                  want_topk: bool = True):
+    """Routed projection of the B, C and input streams of the selected experts:
+    u (B,L,Dm), W_B/W_C (E,G,N,Dm), W_X (E,H,P,Dm) -> B_sel, C_sel (B,L,k,G,N), x_sel (B,L,k,H,P), topk_idx, topk_w."""
+    B, L, Dm = u.shape
+    E, G, N, _ = W_B.shape
+    _, H, P, _ = W_X.shape
+    io, dev = u.dtype, u.device
+    d = make_dims(B, L, H, P, N, G, E, top_k, 1, _io_code(u))
+    if workspace is None:
+        n = swimba_expert_proj_x_workspace_bytes(d, Dm)
+        if n == 0:
+            raise SwimbaError(2, "swimba_expert_proj_x_workspace_bytes")
+        workspace = torch.empty(n, dtype=torch.uint8, device=dev)
+    B_sel = torch.empty((B, L, top_k, G, N), dtype=io, device=dev)
+    C_sel = torch.empty((B, L, top_k, G, N), dtype=io, device=dev)
+    x_sel = torch.empty((B, L, top_k, H, P), dtype=io, device=dev)
+    topk_idx = torch.empty((B, L, top_k), dtype=torch.int32, device=dev) if want_topk else None
+    topk_w = torch.empty((B, L, top_k), dtype=torch.float32, device=dev) if want_topk else None
+    st = _load().swimba_expert_proj_x_selected(
+        ctypes.byref(d), Dm, _ptr(u, "u", io, (B, L, Dm)), _ptr(W_B, "W_B", io, (E, G, N, Dm)),
+        _ptr(W_C, "W_C", io, (E, G, N, Dm)), _ptr(W_X, "W_X", io, (E, H, P, Dm)),
+        _ptr(router_logits, "router_logits", io, (B, L, E)),
+        _ptr(B_sel, "B_sel", io, (B, L, top_k, G, N)), _ptr(C_sel, "C_sel", io, (B, L, top_k, G, N)),
+        _ptr(x_sel, "x_sel", io, (B, L, top_k, H, P)),
+        _ptr(topk_idx, "topk_idx", torch.int32, (B, L, top_k)), _ptr(topk_w, "topk_w", torch.float32, (B, L, top_k)),
+        _ptr(workspace, "workspace", torch.uint8), workspace.numel(), _stream())
+    _check(st, "swimba_expert_proj_x_selected")
+    return B_sel, C_sel, x_sel, topk_idx, topk_w
+
+
+def swimba_mixer_xe_proj_workspace_bytes(dims: swimba_dims, d_model: int) -> int:
+    return int(_load().swimba_mixer_xe_proj_workspace_bytes(ctypes.byref(dims), d_model))
+
+
+def swimba_mixer_fwd_xe_proj(u, W_B, W_C, W_X, dt, A, D, router_logits, top_k: int, chunk: int, h0=None, *, y=None,
+                             h_final=None, workspace=None, want_h_final: bool = True,
+                             want_topk: bool = False) -> MixerOut:
+    """Token features -> y with one projected input stream per expert (projection + expert-X forward in one call)."""
+    B, L, Dm = u.shape
+    E, G, N, _ = W_B.shape
+    _, H, P, _ = W_X.shape
+    io, dev = u.dtype, u.device
+    d = make_dims(B, L, H, P, N, G, E, top_k, chunk, _io_code(u))
+    if workspace is None:
+        n = swimba_mixer_xe_proj_workspace_bytes(d, Dm)
+        if n == 0:
+            raise SwimbaError(2, "swimba_mixer_xe_proj_workspace_bytes")
+        workspace = torch.empty(n, dtype=torch.uint8, device=dev)
+    if y is None:
+        y = torch.empty((B, L, H, P), dtype=io, device=dev)
+    if h_final is None and want_h_final:
+        h_final = torch.empty((B, H, P, N), dtype=torch.float32, device=dev)
+    topk_idx = torch.empty((B, L, top_k), dtype=torch.int32, device=dev) if want_topk else None
+    topk_w = torch.empty((B, L, top_k), dtype=torch.float32, device=dev) if want_topk else None
+    st = _load().swimba_mixer_fwd_xe_proj(
+        ctypes.byref(d), Dm, _ptr(u, "u", io, (B, L, Dm)), _ptr(W_B, "W_B", io, (E, G, N, Dm)),
+        _ptr(W_C, "W_C", io, (E, G, N, Dm)), _ptr(W_X, "W_X", io, (E, H, P, Dm)), _ptr(dt, "dt", io, (B, L, H)),
+        _ptr(A, "A", torch.float32, (H,)), _ptr(D, "D", torch.float32, (H,)),
+        _ptr(router_logits, "router_logits", io, (B, L, E)), _ptr(h0, "h0", torch.float32, (B, H, P, N)),
+        _ptr(y, "y", io, (B, L, H, P)), _ptr(h_final, "h_final", torch.float32, (B, H, P, N)),
+        _ptr(topk_idx, "topk_idx", torch.int32, (B, L, top_k)), _ptr(topk_w, "topk_w", torch.float32, (B, L, top_k)),
+        _ptr(workspace, "workspace", torch.uint8), workspace.numel(), _stream())
+    _check(st, "swimba_mixer_fwd_xe_proj")
+    return MixerOut(y, h_final, topk_idx, topk_w)
 
 
 def swimba_mixer_fwd_selected(x, dt, A, D, B_sel, C_sel, topk_w, chunk: int, h0=None, *, y=None, h_final=None,

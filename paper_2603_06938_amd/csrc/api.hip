@@ -711,7 +711,7 @@ swimba_status swimba_mixer_fwd_xe_selected(const swimba_dims *dims, const void *
 struct ProjLayout {
     size_t idx, w, counts, lists, total;
 };
-static swimba_status proj_layout_of(const swimba_dims *d, int32_t d_model, ProjLayout *o)
+static swimba_status proj_layout_of(const swimba_dims *d, int32_t d_model, ProjLayout *o, bool with_x = false)
 {
     swimba_status st = check_common(d);
     if (st != SWIMBA_OK) return st;
@@ -720,7 +720,8 @@ static swimba_status proj_layout_of(const swimba_dims *d, int32_t d_model, ProjL
     if (d_model > 65536 || T * d->top_k > (1ll << 31) - 1 || T * d->nexperts > (1ll << 31) - 1)
         return SWIMBA_ERR_UNSUPPORTED;
     // shapes outside the MFMA GEMM run on a kernel that keeps one token's features in LDS as fp32
-    const bool gemm = d->io_dtype == SWIMBA_BF16 && d_model % 16 == 0 && (d->ngroups * d->dstate) % 64 == 0;
+    const bool gemm = expert_proj_on_mfma(d->io_dtype, d->ngroups * d->dstate, with_x ? d->nheads * d->headdim : 0,
+                                          d_model);
     if (!gemm && d_model > SWIMBA_MAX_DMODEL_GENERIC) return SWIMBA_ERR_UNSUPPORTED;
     size_t off = 0;
     o->idx = off;    off = align_up(off + (size_t)T * d->top_k * sizeof(int32_t), 256);
@@ -740,17 +741,19 @@ size_t swimba_expert_proj_workspace_bytes(const swimba_dims *dims, int32_t d_mod
 static swimba_status expert_proj_body(const swimba_dims *dims, int32_t d_model, const void *u, const void *W_B,
                                       const void *W_C, const void *router_logits, void *B_experts,
                                       void *C_experts, int32_t *topk_idx, float *topk_w, void *workspace,
-                                      size_t workspace_bytes, int compact, void *hip_stream)
+                                      size_t workspace_bytes, int compact, void *hip_stream,
+                                      bool with_x = false, const void *W_X = nullptr, void *x_out = nullptr)
 {
     ProjLayout pl;
-    swimba_status st = proj_layout_of(dims, d_model, &pl);
+    swimba_status st = proj_layout_of(dims, d_model, &pl, with_x);
     if (st != SWIMBA_OK) return st;
     if (!workspace || workspace_bytes < pl.total || ((uintptr_t)workspace & 255u)) return SWIMBA_ERR_WORKSPACE;
     const int64_t T = (int64_t)dims->batch * dims->seqlen;
     if (T == 0) return SWIMBA_OK;
     if (!u || !W_B || !W_C || !router_logits || !B_experts || !C_experts) return SWIMBA_ERR_NULL;
-    if (check_align(dims->io_dtype, {u, W_B, W_C, B_experts, C_experts}, {router_logits}, {topk_idx, topk_w}) !=
-        SWIMBA_OK)
+    if (with_x && (!W_X || !x_out)) return SWIMBA_ERR_NULL;
+    if (check_align(dims->io_dtype, {u, W_B, W_C, B_experts, C_experts, W_X, x_out}, {router_logits},
+                    {topk_idx, topk_w}) != SWIMBA_OK)
         return SWIMBA_ERR_ALIGNMENT;
     char *base = (char *)workspace;
     int32_t *idx = (int32_t *)(base + pl.idx);
@@ -758,7 +761,8 @@ static swimba_status expert_proj_body(const swimba_dims *dims, int32_t d_model, 
     hipStream_t stream = (hipStream_t)hip_stream;
     st = launch_expert_proj(T, dims->nexperts, dims->top_k, dims->ngroups * dims->dstate, d_model, dims->io_dtype,
                             u, W_B, W_C, router_logits, B_experts, C_experts, idx, w,
-                            (int32_t *)(base + pl.counts), (int32_t *)(base + pl.lists), compact, stream);
+                            (int32_t *)(base + pl.counts), (int32_t *)(base + pl.lists), compact, stream,
+                            with_x ? W_X : nullptr, with_x ? x_out : nullptr, dims->nheads * dims->headdim);
     if (st != SWIMBA_OK) return st;
     if (topk_idx || topk_w) {
         const size_t cnt = (size_t)T * dims->top_k;
@@ -787,6 +791,22 @@ swimba_status swimba_expert_proj_selected(const swimba_dims *dims, int32_t d_mod
 {
     return expert_proj_body(dims, d_model, u, W_B, W_C, router_logits, B_sel, C_sel, topk_idx, topk_w,
                             workspace, workspace_bytes, 1, hip_stream);
+}
+
+size_t swimba_expert_proj_x_workspace_bytes(const swimba_dims *dims, int32_t d_model)
+{
+    ProjLayout pl;
+    return proj_layout_of(dims, d_model, &pl, true) == SWIMBA_OK ? pl.total : 0;
+}
+
+swimba_status swimba_expert_proj_x_selected(const swimba_dims *dims, int32_t d_model, const void *u,
+                                            const void *W_B, const void *W_C, const void *W_X,
+                                            const void *router_logits, void *B_sel, void *C_sel, void *x_sel,
+                                            int32_t *topk_idx, float *topk_w, void *workspace,
+                                            size_t workspace_bytes, void *hip_stream)
+{
+    return expert_proj_body(dims, d_model, u, W_B, W_C, router_logits, B_sel, C_sel, topk_idx, topk_w,
+                            workspace, workspace_bytes, 1, hip_stream, true, W_X, x_sel);
 }
 
 // ---- forward on the streams of the selected experts only ---------------------------------------
@@ -925,6 +945,80 @@ swimba_status swimba_mixer_fwd_proj(const swimba_dims *dims, int32_t d_model, co
         }
     }
     return mixer_selected_core(dims, x, dt, A, D, bsel, csel, ws.w, h0, y, h_final, ws, stream);
+}
+
+// ---- token features -> y with one projected input stream per expert ------------------------------
+struct XeProjLayout {
+    size_t xe, bsel, csel, xsel, idx, w, counts, lists, total;
+};
+static swimba_status xeproj_layout_of(const swimba_dims *d, int32_t d_model, XeProjLayout *o, XeLayout *xl)
+{
+    ProjLayout pl;
+    swimba_status st = proj_layout_of(d, d_model, &pl, true);
+    if (st != SWIMBA_OK) return st;
+    st = check_mixer(d);
+    if (st != SWIMBA_OK) return st;
+    xe_layout_of(d, xl, true);
+    const size_t T = (size_t)d->batch * d->seqlen;
+    const size_t io = d->io_dtype == SWIMBA_BF16 ? 2 : 4;
+    const size_t sel = T * d->top_k * d->ngroups * d->dstate * io;
+    size_t off = 0;
+    o->xe = off;     off = align_up(off + xl->total, 256);
+    o->bsel = off;   off = align_up(off + sel, 256);
+    o->csel = off;   off = align_up(off + sel, 256);
+    o->xsel = off;   off = align_up(off + T * d->top_k * d->nheads * d->headdim * io, 256);
+    o->idx = off;    off = align_up(off + T * d->top_k * sizeof(int32_t), 256);
+    o->w = off;      off = align_up(off + T * d->top_k * sizeof(float), 256);
+    o->counts = off; off = align_up(off + SWIMBA_MAX_EXPERTS * sizeof(int32_t), 256);
+    o->lists = off;  off = align_up(off + T * d->nexperts * sizeof(int32_t), 256);
+    o->total = off;
+    return SWIMBA_OK;
+}
+
+size_t swimba_mixer_xe_proj_workspace_bytes(const swimba_dims *dims, int32_t d_model)
+{
+    XeProjLayout ml;
+    XeLayout xl;
+    return xeproj_layout_of(dims, d_model, &ml, &xl) == SWIMBA_OK ? ml.total : 0;
+}
+
+swimba_status swimba_mixer_fwd_xe_proj(const swimba_dims *dims, int32_t d_model, const void *u, const void *W_B,
+                                       const void *W_C, const void *W_X, const void *dt, const float *A,
+                                       const float *D, const void *router_logits, const float *h0, void *y,
+                                       float *h_final, int32_t *topk_idx, float *topk_w, void *workspace,
+                                       size_t workspace_bytes, void *hip_stream)
+{
+    XeProjLayout ml;
+    XeLayout xl;
+    swimba_status st = xeproj_layout_of(dims, d_model, &ml, &xl);
+    if (st != SWIMBA_OK) return st;
+    if (!workspace || workspace_bytes < ml.total || ((uintptr_t)workspace & 255u)) return SWIMBA_ERR_WORKSPACE;
+    char *base = (char *)workspace;
+    const int64_t T = (int64_t)dims->batch * dims->seqlen;
+    if (T > 0 && (!u || !W_B || !W_C || !W_X || !dt || !A || !router_logits || !y)) return SWIMBA_ERR_NULL;
+    if (check_align(dims->io_dtype, {u, W_B, W_C, W_X, y, h0, h_final}, {dt, router_logits},
+                    {A, D, topk_idx, topk_w}) != SWIMBA_OK)
+        return SWIMBA_ERR_ALIGNMENT;
+    hipStream_t stream = (hipStream_t)hip_stream;
+    void *bsel = base + ml.bsel, *csel = base + ml.csel, *xsel = base + ml.xsel;
+    int32_t *idx = (int32_t *)(base + ml.idx);
+    float *w = (float *)(base + ml.w);
+    if (T > 0) {
+        st = launch_expert_proj(T, dims->nexperts, dims->top_k, dims->ngroups * dims->dstate, d_model,
+                                dims->io_dtype, u, W_B, W_C, router_logits, bsel, csel, idx, w,
+                                (int32_t *)(base + ml.counts), (int32_t *)(base + ml.lists), 1, stream, W_X, xsel,
+                                dims->nheads * dims->headdim);
+        if (st != SWIMBA_OK) return st;
+        if (topk_idx || topk_w) {
+            const size_t cnt = (size_t)T * dims->top_k;
+            hipError_t e = hipSuccess;
+            if (topk_idx) e = hipMemcpyAsync(topk_idx, idx, cnt * sizeof(int32_t), hipMemcpyDeviceToDevice, stream);
+            if (e == hipSuccess && topk_w)
+                e = hipMemcpyAsync(topk_w, w, cnt * sizeof(float), hipMemcpyDeviceToDevice, stream);
+            if (e != hipSuccess) { set_last_hip_error((int)e); return SWIMBA_ERR_HIP; }
+        }
+    }
+    return xe_core(dims, xsel, dt, A, D, bsel, csel, nullptr, w, h0, y, h_final, base + ml.xe, xl, stream);
 }
 
 size_t swimba_step_workspace_bytes(const swimba_dims *dims)

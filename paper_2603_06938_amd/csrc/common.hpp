@@ -89,7 +89,8 @@ swimba_status launch_mix_rows_mfma(const Shape &s, const void *Be, const void *C
 swimba_status launch_expert_proj(int64_t tokens, int E, int K, int GN, int Dm, int io_dtype, const void *u,
                                  const void *WB, const void *WC, const void *logits, void *Be, void *Ce,
                                  int32_t *idx, float *w, int32_t *counts, int32_t *lists, int compact,
-                                 hipStream_t st);
+                                 hipStream_t st, const void *WX = nullptr, void *Xo = nullptr, int HP = 0);
+bool expert_proj_on_mfma(int io_dtype, int GN, int HP, int Dm);
 swimba_status launch_slot_ids(int32_t *idx, int64_t tokens, int K, hipStream_t st);
 // expert-specific input streams (xe.hip)
 swimba_status launch_xe_gather(const Shape &s, int io_dtype, int slot, const void *x_experts,

@@ -5,6 +5,10 @@
 // written either into the dense (B,L,E,G,N) layout (rows of inactive experts are not touched:
 // the mixer never reads them) or, with `compact`, into (B,L,k,G,N): row r of a token is the
 // stream of its r-th selected expert, so no buffer with an expert axis exists at all.
+// The experts' input streams X^(e) (the mixed state update in its full form injects
+// sum_e pi_e x^(e) (x) B^(e)) are a third block of output columns of the same product,
+//   x_t^(e)[c] = sum_d W_X[e][c][d] u_t[d],  c over (head, channel),
+// written the same way into (B,L,E,H,P) or (B,L,k,H,P).
 //
 // Three launches: clear the per-expert counters; route every token and append the entry
 // t*k + r to the list of its r-th expert (LDS counters per block, one global atomic per block
@@ -24,6 +28,22 @@ typedef __attribute__((ext_vector_type(2))) float pj_f32x2_t;
 typedef __attribute__((ext_vector_type(16))) float pj_f32x16_t;
 
 constexpr int PJ_COLS = 256;   // output columns per workgroup: 4 column groups of 64
+
+// The output columns of the product are the concatenation [B | C | X] of up to three blocks, each
+// with its own weight tensor (E, n, Dm) and its own output tensor (rows of n columns).
+struct ProjBlocks {
+    const void *W[3];
+    void *out[3];
+    int n[3];       // columns of the block (0: absent); multiples of 64 on the MFMA path
+    int tot;        // n[0] + n[1] + n[2]
+};
+// block of column c and the column inside it
+__device__ __forceinline__ int proj_block_of(const ProjBlocks &pb, int c, int &local)
+{
+    const int s = (c >= pb.n[0]) + (c >= pb.n[0] + pb.n[1]);
+    local = c - (s > 0 ? pb.n[0] : 0) - (s > 1 ? pb.n[1] : 0);
+    return s;
+}
 
 __global__ void proj_clear_kernel(int32_t *counts, int E)
 {
@@ -95,10 +115,9 @@ __device__ __forceinline__ int proj_share(int cnt, int nslots, int64_t total)
 }
 
 __global__ void __launch_bounds__(PJ_THREADS) __attribute__((amdgpu_waves_per_eu(2, 2)))
-proj_mfma_kernel(const uint16_t *__restrict__ u, const uint16_t *__restrict__ WB,
-                 const uint16_t *__restrict__ WC, const int32_t *__restrict__ counts,
-                 const int32_t *__restrict__ lists, uint16_t *__restrict__ Be, uint16_t *__restrict__ Ce,
-                 int64_t tokens, int E, int K, int GN, int Dm, int nslots, int compact)
+proj_mfma_kernel(const uint16_t *__restrict__ u, ProjBlocks pb, const int32_t *__restrict__ counts,
+                 const int32_t *__restrict__ lists, int64_t tokens, int E, int K, int Dm, int nslots,
+                 int compact)
 {
     __shared__ __align__(16) uint16_t sW[PJ_COLS * PJ_STR];
     __shared__ __align__(16) uint16_t sU[PJ_ROWS * PJ_STR];
@@ -144,20 +163,21 @@ proj_mfma_kernel(const uint16_t *__restrict__ u, const uint16_t *__restrict__ WB
     const int npass = (nt + 2 * PJ_RT - 1) / (2 * PJ_RT);
 
     const int cw = wave & 3, rg = wave >> 2;                 // column group, row group of the wave
-    const int colblk = blockIdx.y * PJ_COLS;                 // first column of the block in [B | C]
+    const int colblk = blockIdx.y * PJ_COLS;                 // first column of the workgroup in [B | C | X]
     const int col0 = colblk + cw * 64;
-    const bool active = col0 < 2 * GN;                       // wave-uniform; idle waves still stage
+    const bool active = col0 < pb.tot;                       // wave-uniform; idle waves still stage
     const int l32 = lane & 31, kg = lane >> 5;
 
     // ---- staging map: lane -> 16-byte piece `piece` of rows row0 + 64 i ----
     const int piece = tid & 7, row0 = tid >> 3;              // row0 = 32 rg + (row inside a 32-block)
-    // G*N is a multiple of 32, so the 32 rows of a staging step of one wave lie in one of the two
-    // weight matrices: a uniform base (scalar registers) + one per-lane offset for all four.
+    // Every block has a multiple of 32 columns, so the 32 rows of a staging step of one wave lie in
+    // one weight tensor: a uniform base (scalar registers) + one per-lane offset for all four.
     const uint16_t *wbase[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        const int c = min(colblk + 64 * i + 32 * rg, 2 * GN - 32);      // blocks past [B | C] repeat the last one
-        wbase[i] = (c < GN ? WB + ((int64_t)e * GN + c) * Dm : WC + ((int64_t)e * GN + c - GN) * Dm);
+        int cl;
+        const int sb = proj_block_of(pb, min(colblk + 64 * i + 32 * rg, pb.tot - 32), cl);   // past the end: the last rows again
+        wbase[i] = (const uint16_t *)pb.W[sb] + ((int64_t)e * pb.n[sb] + cl) * Dm;
     }
     const int r32 = row0 & 31;
     const int wlane = r32 * Dm;
@@ -170,9 +190,10 @@ proj_mfma_kernel(const uint16_t *__restrict__ u, const uint16_t *__restrict__ WB
     const uint16_t *aop[2];
 #pragma unroll
     for (int q = 0; q < 2; ++q) aop[q] = sW + (cw * 64 + 32 * q + l32) * PJ_STR + 8 * kg;
-    const bool isB = col0 < GN;
-    const int cc = isB ? col0 : col0 - GN;                   // column inside the B (or C) row
-    uint16_t *out = isB ? Be : Ce;
+    int cc;                                                  // column inside the row of the wave's block
+    const int ob = proj_block_of(pb, min(col0, pb.tot - 64), cc);
+    uint16_t *out = (uint16_t *)pb.out[ob];
+    const int ncol = pb.n[ob];                               // row length of that output
 
     for (int pass = 0; pass < npass; ++pass) {
         const int p_begin = t_begin + (int)((int64_t)pass * nt / npass);
@@ -285,7 +306,7 @@ proj_mfma_kernel(const uint16_t *__restrict__ u, const uint16_t *__restrict__ WB
                     const int64_t row = compact ? ent : (ent / K) * E + e;
 #pragma unroll
                     for (int ct = 0; ct < 2; ++ct) {
-                        uint16_t *dst = out + row * GN + cc + 32 * ct + 16 * kg;
+                        uint16_t *dst = out + row * ncol + cc + 32 * ct + 16 * kg;
                         const pj_f32x16_t v = acc[ct][rt];
                         *reinterpret_cast<uint4 *>(dst) =
                             make_uint4(pj_pack(v[0], v[1]), pj_pack(v[2], v[3]), pj_pack(v[4], v[5]), pj_pack(v[6], v[7]));
@@ -302,9 +323,8 @@ proj_mfma_kernel(const uint16_t *__restrict__ u, const uint16_t *__restrict__ WB
 // per output column of [B | C]
 template <typename T>
 __global__ void __launch_bounds__(256)
-proj_generic_kernel(const T *__restrict__ u, const T *__restrict__ WB, const T *__restrict__ WC,
-                    const int32_t *__restrict__ idx, T *__restrict__ Be, T *__restrict__ Ce, int E, int K,
-                    int GN, int Dm, int compact)
+proj_generic_kernel(const T *__restrict__ u, ProjBlocks pb, const int32_t *__restrict__ idx, int E, int K,
+                    int Dm, int compact)
 {
     extern __shared__ float s_u[];
     const int64_t t = blockIdx.x / K;
@@ -312,24 +332,35 @@ proj_generic_kernel(const T *__restrict__ u, const T *__restrict__ WB, const T *
     const int64_t row = compact ? (int64_t)blockIdx.x : t * E + e;
     for (int d = threadIdx.x; d < Dm; d += 256) s_u[d] = to_float(u[t * Dm + d]);
     __syncthreads();
-    for (int c = threadIdx.x; c < 2 * GN; c += 256) {
-        const bool isB = c < GN;
-        const int cc = isB ? c : c - GN;
-        const T *wr = (isB ? WB : WC) + ((int64_t)e * GN + cc) * Dm;
+    for (int c = threadIdx.x; c < pb.tot; c += 256) {
+        int cc;
+        const int sb = proj_block_of(pb, c, cc);
+        const T *wr = (const T *)pb.W[sb] + ((int64_t)e * pb.n[sb] + cc) * Dm;
         float acc = 0.f;
         for (int d = 0; d < Dm; ++d) acc += to_float(wr[d]) * s_u[d];
-        (isB ? Be : Ce)[row * GN + cc] = from_float<T>(acc);
+        ((T *)pb.out[sb])[row * pb.n[sb] + cc] = from_float<T>(acc);
     }
 }
 
+bool expert_proj_on_mfma(int io_dtype, int GN, int HP, int Dm)
+{
+    return io_dtype == SWIMBA_BF16 && Dm % 16 == 0 && GN % 64 == 0 && HP % 64 == 0;
+}
+
+// WX / Xo / HP: the third block of columns (input streams), nullptr / nullptr / 0 when not wanted
 swimba_status launch_expert_proj(int64_t tokens, int E, int K, int GN, int Dm, int io_dtype, const void *u,
                                  const void *WB, const void *WC, const void *logits, void *Be, void *Ce,
                                  int32_t *idx, float *w, int32_t *counts, int32_t *lists, int compact,
-                                 hipStream_t st)
+                                 hipStream_t st, const void *WX, void *Xo, int HP)
 {
     if (tokens == 0) return SWIMBA_OK;
     if (tokens * K > 0x7fffffffll) return SWIMBA_ERR_UNSUPPORTED;   // list entries are 32-bit
-    const bool mfma = io_dtype == SWIMBA_BF16 && Dm % 16 == 0 && GN % 64 == 0;
+    ProjBlocks pb;
+    pb.W[0] = WB; pb.W[1] = WC; pb.W[2] = WX;
+    pb.out[0] = Be; pb.out[1] = Ce; pb.out[2] = Xo;
+    pb.n[0] = GN; pb.n[1] = GN; pb.n[2] = WX ? HP : 0;
+    pb.tot = 2 * GN + pb.n[2];
+    const bool mfma = expert_proj_on_mfma(io_dtype, GN, pb.n[2], Dm);
     const unsigned rgrid = (unsigned)((tokens + 255) / 256);
     if (!mfma) {
         swimba_status rs = launch_router(tokens, E, K, io_dtype, logits, idx, w, st);
@@ -337,12 +368,10 @@ swimba_status launch_expert_proj(int64_t tokens, int E, int K, int GN, int Dm, i
         const size_t shm = (size_t)Dm * sizeof(float);
         if (io_dtype == SWIMBA_BF16)
             hipLaunchKernelGGL(proj_generic_kernel<bf16>, dim3((unsigned)(tokens * K)), dim3(256), shm, st,
-                               (const bf16 *)u, (const bf16 *)WB, (const bf16 *)WC, idx, (bf16 *)Be, (bf16 *)Ce, E,
-                               K, GN, Dm, compact);
+                               (const bf16 *)u, pb, idx, E, K, Dm, compact);
         else
             hipLaunchKernelGGL(proj_generic_kernel<float>, dim3((unsigned)(tokens * K)), dim3(256), shm, st,
-                               (const float *)u, (const float *)WB, (const float *)WC, idx, (float *)Be,
-                               (float *)Ce, E, K, GN, Dm, compact);
+                               (const float *)u, pb, idx, E, K, Dm, compact);
         SWIMBA_CHECK_LAUNCH();
         return SWIMBA_OK;
     }
@@ -357,12 +386,11 @@ swimba_status launch_expert_proj(int64_t tokens, int E, int K, int GN, int Dm, i
     hipError_t he = hipGetDevice(&devid);
     if (he == hipSuccess) he = hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, devid);
     if (he != hipSuccess) { set_last_hip_error((int)he); return SWIMBA_ERR_HIP; }
-    const int colblocks = (2 * GN + PJ_COLS - 1) / PJ_COLS;
+    const int colblocks = (pb.tot + PJ_COLS - 1) / PJ_COLS;
     const int nslots = max(1, ncu / colblocks);
     const dim3 grid((unsigned)(nslots + E), (unsigned)colblocks);   // the shares sum to at most nslots + E
-    hipLaunchKernelGGL(proj_mfma_kernel, grid, dim3(PJ_THREADS), 0, st, (const uint16_t *)u, (const uint16_t *)WB,
-                       (const uint16_t *)WC, counts, lists, (uint16_t *)Be, (uint16_t *)Ce, tokens, E, K, GN, Dm,
-                       nslots, compact);
+    hipLaunchKernelGGL(proj_mfma_kernel, grid, dim3(PJ_THREADS), 0, st, (const uint16_t *)u, pb, counts, lists,
+                       tokens, E, K, Dm, nslots, compact);
     SWIMBA_CHECK_LAUNCH();
     return SWIMBA_OK;
 }
