@@ -52,6 +52,12 @@ def work_model(w):
         # rows and the mixed B rows in two layouts (bf16)
         "mix": {"moved": T * (E * 2 + k * 8 + 2 * k * G * N * 2 + 3 * G * N * 2),
                 "irreducible": T * (E * 2 + 2 * k * G * N * 2), "flops": 0.0},
+        # router + mixing + C.B^T tiles per whole chunk in one persistent kernel: reads logits and the
+        # selected rows; writes top-k, the mixed C rows, the mixed B rows once, and the tiles
+        "mix_chunk": {"moved": T * (E * 2 + k * 8 + 2 * k * G * N * 2 + 2 * G * N * 2) + cb_bytes,
+                      "irreducible": T * (E * 2 + 2 * k * G * N * 2), "flops": 2.0 * T * Q * N * G},
+        # the cumsum tables alone
+        "tables": {"moved": T * (H * 2 + 3 * H * 4), "irreducible": T * H * 2, "flops": 0.0},
         # C.B^T tiles from the mixed rows, cumsum tables from dt
         "prep": {"moved": T * (2 * G * N * 2 + H * 2 + H * 8) + cb_bytes,
                  "irreducible": T * H * 2, "flops": 2.0 * T * Q * N * G},
@@ -97,7 +103,7 @@ def main() -> int:
                     help="mixed against separated forward for E in {1,2,4,8,16} on the headline shape")
     ap.add_argument("--stage", default=None,
                     help="run only this stage in the timed loop (for profilers): "
-                         "fwd|mix|prep|pass|chunk_state|state_scan|output|step|copy")
+                         "fwd|mix|mix_chunk|tables|prep|pass|chunk_state|state_scan|output|step|copy")
     ap.add_argument("--staged", action="store_true",
                     help="also time the kernels of the evaluation the forward does not take for the headline shape "
                          "(chunk states through memory against the single pass)")
@@ -188,6 +194,12 @@ def main() -> int:
                     "prep": lambda d: sw.swimba_stage_prep(dims, d["dt"], d["A"], d["ws"]),
                     "pass": lambda d: sw.swimba_stage_pass(dims, d["x"], d["dt"], d["D"], None, d["y"], d["h_final"], d["ws"]),
                 },
+                sw.PATH_SINGLE_PASS_CHUNK_MIX: {
+                    "mix_chunk": lambda d: sw.swimba_stage_mix_chunk(dims, d["B_experts"], d["C_experts"],
+                                                                     d["router_logits"], d["ws"]),
+                    "tables": lambda d: sw.swimba_stage_tables(dims, d["dt"], d["A"], d["ws"]),
+                    "pass": lambda d: sw.swimba_stage_pass(dims, d["x"], d["dt"], d["D"], None, d["y"], d["h_final"], d["ws"]),
+                },
                 sw.PATH_STAGED: {
                     "mix": mix,
                     "chunk_state": lambda d: sw.swimba_stage_chunk_state(dims, d["x"], d["dt"], d["A"], d["B_experts"], d["ws"]),
@@ -197,8 +209,9 @@ def main() -> int:
                 },
             }
             self.path = sw.swimba_prefill_path(dims)
-            self.path_name = {sw.PATH_SINGLE_PASS: "single_pass", sw.PATH_STAGED: "staged"}[self.path]
-            self.other = sw.PATH_STAGED if self.path == sw.PATH_SINGLE_PASS else sw.PATH_SINGLE_PASS
+            self.path_name = {sw.PATH_SINGLE_PASS: "single_pass", sw.PATH_STAGED: "staged",
+                              sw.PATH_SINGLE_PASS_CHUNK_MIX: "single_pass_chunk_mix"}[self.path]
+            self.other = sw.PATH_SINGLE_PASS if self.path == sw.PATH_STAGED else sw.PATH_STAGED
 
         def step(self, i):
             d, w = self.sets[i % self.nsets], self.w
@@ -267,7 +280,9 @@ def main() -> int:
     if args.stage:
         for i in range(head.nsets):
             head.step(i)   # every workspace holds valid router/cumsum/state data
-            for fns in head.paths.values():
+            for pth, fns in head.paths.items():
+                if pth == sw.PATH_SINGLE_PASS_CHUNK_MIX and head.path != pth:
+                    continue   # the chunk-level kernel takes few experts only
                 for fn in fns.values():
                     fn(head.sets[i])
         torch.cuda.synchronize()
@@ -283,7 +298,8 @@ def main() -> int:
             print(json.dumps({"stage": "fwd", "workload": w.name, "ms": ms}))
             return 0
         if args.stage != "step":
-            fn = head.paths[sw.PATH_SINGLE_PASS].get(args.stage) or head.paths[sw.PATH_STAGED][args.stage]
+            fn = (head.paths[sw.PATH_SINGLE_PASS].get(args.stage) or head.paths[sw.PATH_STAGED].get(args.stage)
+                  or head.paths[sw.PATH_SINGLE_PASS_CHUNK_MIX][args.stage])
             ms = time_loop(lambda i: fn(head.sets[i % head.nsets]), K)
             print(json.dumps({"stage": args.stage, "workload": w.name, "ms": ms}))
             return 0
@@ -638,7 +654,7 @@ def main() -> int:
                                            "ridge 312): at the HBM floor the contractions would sit at %.2f of MFMA peak"
                                            % (round(call["flops"] / call["irreducible_bytes"]),
                                               call["flops"] / call["irreducible_bytes"] / 312.5)},
-        "mixing_hbm_frac": {"target": 0.6, "value": kernels["mix"]["hbm_frac"] if "mix" in kernels else None},
+        "mixing_hbm_frac": {"target": 0.6, "value": (kernels.get("mix") or kernels.get("mix_chunk") or {}).get("hbm_frac")},
         "scan_hbm_frac": ({"target": 0.6, "value": kernels["state_scan"]["hbm_frac_with_intermediates"],
                            "note": "on the chunk states it reads and writes (intermediates of the staged path)"}
                           if "state_scan" in kernels else

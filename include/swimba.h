@@ -195,15 +195,30 @@ swimba_status swimba_stage_pass(const swimba_dims *dims, const void *x, const vo
 
 /* Which kernels swimba_mixer_fwd (and the _selected/_proj forms) run for these dims on the
  * current device: SWIMBA_PATH_GENERIC (fp32-capable kernels, any shape), SWIMBA_PATH_STAGED
- * (bf16 MFMA: mix, chunk_state, state_scan, output) or SWIMBA_PATH_SINGLE_PASS (bf16 MFMA: mix,
- * prep, pass).  The single pass is taken when its (batch, head, 32-channel) chains number between
+ * (bf16 MFMA: mix, chunk_state, state_scan, output), SWIMBA_PATH_SINGLE_PASS (bf16 MFMA: mix,
+ * prep, pass) or SWIMBA_PATH_SINGLE_PASS_CHUNK_MIX (see below).  The single pass is taken when its (batch, head, 32-channel) chains number between
  * 3/4 of and all of the device's compute units and the sequence has at least 16 chunks; results
  * of the two MFMA paths agree to the rounding of their bf16 operands.  Returns minus the
  * swimba_status for invalid dims.  Host only; launches nothing. */
 #define SWIMBA_PATH_GENERIC 0
 #define SWIMBA_PATH_STAGED 1
 #define SWIMBA_PATH_SINGLE_PASS 2
+#define SWIMBA_PATH_SINGLE_PASS_CHUNK_MIX 3
 int swimba_prefill_path(const swimba_dims *dims);
+
+/* Single pass with the router, the mixing and the tiles of Bmix.Cmix^T done per whole chunk in one
+ * persistent kernel (SWIMBA_PATH_SINGLE_PASS_CHUNK_MIX: mix_chunk, tables, pass).  Taken by the forward
+ * on single-pass shapes with at most 16 experts, top_k <= 2 and at least two (batch, chunk, group)
+ * triples per compute unit; same results as mix + prep, bit for bit.
+ *   mix_chunk : B/C_experts, logits -> ws.topk_*, ws.cmix, ws.bmix_t8, ws.cb   (ws.bmix_frag is not written)
+ *   tables    : dt, A -> ws.cs2, ws.fdec, ws.cdec                              (prep without the tiles)
+ * swimba_stage_mix_chunk runs for any bf16 MFMA shape with nexperts <= 16 and top_k <= 2
+ * (SWIMBA_ERR_UNSUPPORTED otherwise). */
+swimba_status swimba_stage_mix_chunk(const swimba_dims *dims, const void *B_experts, const void *C_experts,
+                                     const void *router_logits, void *workspace, size_t workspace_bytes,
+                                     void *hip_stream);
+swimba_status swimba_stage_tables(const swimba_dims *dims, const void *dt, const float *A, void *workspace,
+                                  size_t workspace_bytes, void *hip_stream);
 
 swimba_status swimba_stage_router(const swimba_dims *dims, const void *router_logits,
                                   void *workspace, size_t workspace_bytes, void *hip_stream);

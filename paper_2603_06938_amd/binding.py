@@ -76,6 +76,10 @@ def _load():
         lib.swimba_stage_prep.argtypes = [dp, vp, vp, vp, sz, vp]
         lib.swimba_prefill_path.restype = ctypes.c_int
         lib.swimba_prefill_path.argtypes = [dp]
+        lib.swimba_stage_mix_chunk.restype = i32
+        lib.swimba_stage_mix_chunk.argtypes = [dp, vp, vp, vp, vp, sz, vp]
+        lib.swimba_stage_tables.restype = i32
+        lib.swimba_stage_tables.argtypes = [dp, vp, vp, vp, sz, vp]
         lib.swimba_stage_pass.restype = i32
         lib.swimba_stage_pass.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         lib.swimba_separated_workspace_bytes.restype = sz
@@ -618,7 +622,7 @@ def swimba_stage_output(dims, x, dt, D, B_experts, C_experts, y, workspace):
                                        _stream()), "swimba_stage_output")
 
 
-PATH_GENERIC, PATH_STAGED, PATH_SINGLE_PASS = 0, 1, 2
+PATH_GENERIC, PATH_STAGED, PATH_SINGLE_PASS, PATH_SINGLE_PASS_CHUNK_MIX = 0, 1, 2, 3
 
 
 def swimba_prefill_path(dims) -> int:
@@ -627,6 +631,19 @@ def swimba_prefill_path(dims) -> int:
     if r < 0:
         _check(-r, "swimba_prefill_path")
     return r
+
+
+def swimba_stage_mix_chunk(dims, B_experts, C_experts, router_logits, workspace):
+    _check(_load().swimba_stage_mix_chunk(ctypes.byref(dims), _ptr(B_experts, "B_experts"), _ptr(C_experts, "C_experts"),
+                                          _ptr(router_logits, "router_logits"),
+                                          _ptr(workspace, "workspace", torch.uint8), workspace.numel(), _stream()),
+           "swimba_stage_mix_chunk")
+
+
+def swimba_stage_tables(dims, dt, A, workspace):
+    _check(_load().swimba_stage_tables(ctypes.byref(dims), _ptr(dt, "dt"), _ptr(A, "A", torch.float32),
+                                       _ptr(workspace, "workspace", torch.uint8), workspace.numel(), _stream()),
+           "swimba_stage_tables")
 
 
 def swimba_stage_prep(dims, dt, A, workspace):

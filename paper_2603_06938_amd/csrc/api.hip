@@ -101,7 +101,8 @@ static void layout_of(const swimba_dims *d, swimba_ws_layout *o)
 // of the chip idles, with more they run in rounds and the staged kernels (which also parallelise
 // over chunks) are faster.  Measured on MI355X: 342 us against 454 us at B2 L16384 H64 (256 chains,
 // 64 chunks), 195 against 190 at B8 L4096 H32 (512 chains), 97 against 75 at B8 L2048 H24 (384).
-static bool use_single_pass(const swimba_dims *d)
+// compute units of the current device (0 if the query fails); asked once
+static int device_cus()
 {
     static std::atomic<int> ncu_cache{0};
     int ncu = ncu_cache.load(std::memory_order_relaxed);
@@ -109,12 +110,30 @@ static bool use_single_pass(const swimba_dims *d)
         int dev = 0;
         if (hipGetDevice(&dev) != hipSuccess ||
             hipDeviceGetAttribute(&ncu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || ncu <= 0)
-            return false;
+            return 0;
         ncu_cache.store(ncu, std::memory_order_relaxed);
     }
+    return ncu;
+}
+
+static bool use_single_pass(const swimba_dims *d)
+{
+    const int ncu = device_cus();
+    if (ncu == 0) return false;
     const int64_t chains = (int64_t)d->batch * d->nheads * ((d->headdim + 31) / 32);
     const int64_t nc = ((int64_t)d->seqlen + d->chunk - 1) / d->chunk;
     return chains <= ncu && 4 * chains >= 3 * (int64_t)ncu && nc >= 16;
+}
+
+// Router, mixing and G^T tiles per whole chunk in one persistent kernel (no operand image of the mixed B
+// rows, no tile pass) in front of the single pass: taken where every compute unit gets at least two
+// (batch, chunk, group) items, so that the gather of the next item overlaps the tiles of the current one.
+static bool use_chunk_mix(const swimba_dims *d, bool selected)
+{
+    if (!use_mfma_path(d) || !use_single_pass(d)) return false;
+    swimba_dims dk = *d;
+    const Shape s = make_shape(&dk);
+    return mix_chunk_covers(s, selected) && (int64_t)s.B * s.nc * s.G >= 2 * (int64_t)device_cus();
 }
 
 struct Ws {
@@ -300,7 +319,41 @@ int swimba_prefill_path(const swimba_dims *dims)
     swimba_status st = check_mixer(dims);
     if (st != SWIMBA_OK) return -(int)st;
     if (!use_mfma_path(dims)) return SWIMBA_PATH_GENERIC;
+    if (use_chunk_mix(dims, false)) return SWIMBA_PATH_SINGLE_PASS_CHUNK_MIX;
     return use_single_pass(dims) ? SWIMBA_PATH_SINGLE_PASS : SWIMBA_PATH_STAGED;
+}
+
+swimba_status swimba_stage_mix_chunk(const swimba_dims *dims, const void *B_experts, const void *C_experts,
+                                     const void *router_logits, void *workspace, size_t workspace_bytes,
+                                     void *hip_stream)
+{
+    Ws ws;
+    swimba_status st = carve(dims, workspace, workspace_bytes, &ws);
+    if (st != SWIMBA_OK) return st;
+    const Shape s = make_shape(dims);
+    if (!use_mfma_path(dims) || !mix_chunk_covers(s, false)) return SWIMBA_ERR_UNSUPPORTED;
+    if ((int64_t)dims->batch * dims->seqlen == 0) return SWIMBA_OK;
+    if (!B_experts || !C_experts || !router_logits) return SWIMBA_ERR_NULL;
+    if (check_align(dims->io_dtype, {B_experts, C_experts}, {router_logits}, {}) != SWIMBA_OK)
+        return SWIMBA_ERR_ALIGNMENT;
+    const int ncu = device_cus();
+    if (ncu == 0) return SWIMBA_ERR_HIP;
+    return launch_mix_chunk_mfma(s, B_experts, C_experts, router_logits, ws.idx, ws.w, ws.cmix, ws.bmix_t8, ws.cb,
+                                 nullptr, ncu, (hipStream_t)hip_stream);
+}
+
+swimba_status swimba_stage_tables(const swimba_dims *dims, const void *dt, const float *A, void *workspace,
+                                  size_t workspace_bytes, void *hip_stream)
+{
+    Ws ws;
+    swimba_status st = carve(dims, workspace, workspace_bytes, &ws);
+    if (st != SWIMBA_OK) return st;
+    if (!use_mfma_path(dims)) return SWIMBA_ERR_UNSUPPORTED;
+    if ((int64_t)dims->batch * dims->seqlen == 0) return SWIMBA_OK;
+    if (!dt || !A) return SWIMBA_ERR_NULL;
+    if (check_align(dims->io_dtype, {}, {dt}, {A}) != SWIMBA_OK) return SWIMBA_ERR_ALIGNMENT;
+    return launch_prep_mfma(make_shape(dims), dt, A, ws.cmix, ws.bmix_frag, ws.cb, ws.cs2, ws.fdec, ws.cdec,
+                            (hipStream_t)hip_stream, false);
 }
 
 swimba_status swimba_stage_prep(const swimba_dims *dims, const void *dt, const float *A, void *workspace,
@@ -359,8 +412,11 @@ swimba_status swimba_mixer_fwd(const swimba_dims *dims, const void *x, const voi
             st = swimba_stage_cumsum(dims, dt, A, workspace, workspace_bytes, hip_stream);
             if (st != SWIMBA_OK) return st;
         }
-        st = swimba_stage_mix(dims, B_experts, C_experts, router_logits, workspace, workspace_bytes,
-                              hip_stream);
+        const bool chunk_mix = use_chunk_mix(dims, false);
+        st = chunk_mix ? swimba_stage_mix_chunk(dims, B_experts, C_experts, router_logits, workspace, workspace_bytes,
+                                                hip_stream)
+                       : swimba_stage_mix(dims, B_experts, C_experts, router_logits, workspace, workspace_bytes,
+                                          hip_stream);
         if (st != SWIMBA_OK) return st;
         if (topk_idx || topk_w) {
             const size_t n = (size_t)T * dims->top_k;
@@ -374,7 +430,7 @@ swimba_status swimba_mixer_fwd(const swimba_dims *dims, const void *x, const voi
         if (mf && use_single_pass(dims)) {
             // single pass: G^T tiles and cumsum tables, then one walk over the chunks per
             // (batch, head, 32 channels) with the state in registers
-            st = launch_prep_mfma(s, dt, A, ws.cmix, ws.bmix_frag, ws.cb, ws.cs2, ws.fdec, ws.cdec, stream);
+            st = launch_prep_mfma(s, dt, A, ws.cmix, ws.bmix_frag, ws.cb, ws.cs2, ws.fdec, ws.cdec, stream, !chunk_mix);
             if (st != SWIMBA_OK) return st;
             return launch_pass_mfma(s, x, dt, D, ws.cmix, ws.bmix_t8, ws.cb, ws.cs2, ws.fdec, ws.cdec, h0, h_final, y,
                                     stream);
@@ -825,11 +881,15 @@ static swimba_status mixer_selected_core(const swimba_dims *dims, const void *x,
     swimba_status st;
     if (T > 0) {
         if (mf) {
-            st = launch_mix_rows_mfma(s, B_sel, C_sel, nullptr, nullptr, nullptr, ws.cmix, ws.bmix_frag,
-                                      ws.bmix_t8, -1, -1, w_sel, stream);
+            const bool chunk_mix = use_chunk_mix(dims, true);
+            st = chunk_mix ? launch_mix_chunk_mfma(s, B_sel, C_sel, nullptr, nullptr, nullptr, ws.cmix, ws.bmix_t8,
+                                                   ws.cb, w_sel, device_cus(), stream)
+                           : launch_mix_rows_mfma(s, B_sel, C_sel, nullptr, nullptr, nullptr, ws.cmix, ws.bmix_frag,
+                                                  ws.bmix_t8, -1, -1, w_sel, stream);
             if (st != SWIMBA_OK) return st;
             if (use_single_pass(dims)) {
-                st = launch_prep_mfma(s, dt, A, ws.cmix, ws.bmix_frag, ws.cb, ws.cs2, ws.fdec, ws.cdec, stream);
+                st = launch_prep_mfma(s, dt, A, ws.cmix, ws.bmix_frag, ws.cb, ws.cs2, ws.fdec, ws.cdec, stream,
+                                      !chunk_mix);
                 if (st != SWIMBA_OK) return st;
                 return launch_pass_mfma(s, x, dt, D, ws.cmix, ws.bmix_t8, ws.cb, ws.cs2, ws.fdec, ws.cdec, h0, h_final, y,
                                         stream);

@@ -117,9 +117,14 @@ swimba_status launch_output_mfma(const Shape &s, const void *x, const void *dt, 
                                  const void *cmix, const void *cb, const float *cs,
                                  const void *states_lp, void *y, const float *skip_w, int skip_stride,
                                  int accumulate, hipStream_t st);
+// router + mixing + G^T tiles of whole chunks in one persistent kernel (mix_chunk.hip)
+bool mix_chunk_covers(const Shape &s, bool selected);
+swimba_status launch_mix_chunk_mfma(const Shape &s, const void *Be, const void *Ce, const void *logits, int32_t *idx,
+                                    float *w, void *cmix, void *bmix_t8, void *cb, const float *w_sel, int ncu,
+                                    hipStream_t st);
 // single-pass forward (fused_pass.hip)
 swimba_status launch_prep_mfma(const Shape &s, const void *dt, const float *A, const void *cmix, const void *bfrag,
-                               void *cb, float *cs2, float *fdec, float *cdec, hipStream_t st);
+                               void *cb, float *cs2, float *fdec, float *cdec, hipStream_t st, bool tiles = true);
 swimba_status launch_pass_mfma(const Shape &s, const void *x, const void *dt, const float *D, const void *cmix,
                                const void *bt8, const void *cb, const float *cs2, const float *fdec,
                                const float *cdec, const float *h0, float *h_final, void *y, hipStream_t st);

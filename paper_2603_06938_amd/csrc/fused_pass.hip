@@ -642,7 +642,7 @@ pass_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ dt, con
 template <int Q>
 static swimba_status launch_prep_q(const Shape &s, const void *dt, const float *A, const void *cmix,
                                    const void *bfrag, void *cb, float *cs2, float *fdec, float *cdec,
-                                   hipStream_t st)
+                                   hipStream_t st, bool tiles)
 {
     constexpr int NT = Q / 32;
     const int64_t nbcg = (int64_t)s.B * s.nc * s.G;
@@ -651,7 +651,8 @@ static swimba_status launch_prep_q(const Shape &s, const void *dt, const float *
     // where there are enough of them to fill the chip (49 against 55 us on the long-sequence
     // workload, 1024 triples), one wave per tile pair otherwise (12 against 17 us with 64 triples)
     const int fine = nbcg < 512;
-    const int64_t ncb = fine ? xcd_padded(nbcg * ((NT * (NT + 1) / 2 + 3) / 4)) : nbcg;
+    // (tiles == false: the tiles exist already, only the tables are made)
+    const int64_t ncb = !tiles ? 0 : fine ? xcd_padded(nbcg * ((NT * (NT + 1) / 2 + 3) / 4)) : nbcg;
     const int64_t ncum = (int64_t)s.B * s.nc * ((s.H + 15) / 16);
     hipLaunchKernelGGL(prep_kernel<Q>, dim3((unsigned)(ncb + ncum)), dim3(MTHREADS), 0, st, (const uint16_t *)dt, A,
                        (const uint16_t *)cmix, (const uint16_t *)bfrag, (uint16_t *)cb, cs2, fdec, cdec, s, nbcg, ncb,
@@ -661,12 +662,12 @@ static swimba_status launch_prep_q(const Shape &s, const void *dt, const float *
 }
 
 swimba_status launch_prep_mfma(const Shape &s, const void *dt, const float *A, const void *cmix, const void *bfrag,
-                               void *cb, float *cs2, float *fdec, float *cdec, hipStream_t st)
+                               void *cb, float *cs2, float *fdec, float *cdec, hipStream_t st, bool tiles)
 {
     switch (s.Q) {
-    case 64: return launch_prep_q<64>(s, dt, A, cmix, bfrag, cb, cs2, fdec, cdec, st);
-    case 128: return launch_prep_q<128>(s, dt, A, cmix, bfrag, cb, cs2, fdec, cdec, st);
-    case 256: return launch_prep_q<256>(s, dt, A, cmix, bfrag, cb, cs2, fdec, cdec, st);
+    case 64: return launch_prep_q<64>(s, dt, A, cmix, bfrag, cb, cs2, fdec, cdec, st, tiles);
+    case 128: return launch_prep_q<128>(s, dt, A, cmix, bfrag, cb, cs2, fdec, cdec, st, tiles);
+    case 256: return launch_prep_q<256>(s, dt, A, cmix, bfrag, cb, cs2, fdec, cdec, st, tiles);
     }
     return SWIMBA_ERR_UNSUPPORTED;
 }

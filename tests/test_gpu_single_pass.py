@@ -112,3 +112,61 @@ def test_stage_calls_refuse_the_fp32_path():
     with pytest.raises(sw.SwimbaError) as e:
         sw.swimba_stage_prep(dims, torch.ones((1, 64, 2), device=dev), -torch.ones(2, device=dev), ws)
     assert e.value.status == 4
+
+
+CHUNK_MIX_CASES = [
+    # B, L, H, P, N, G, E, k, Q
+    (2, 600, 4, 64, 128, 2, 8, 2, 256),
+    (1, 1100, 6, 64, 128, 1, 16, 2, 256),      # 16 experts (two 16-byte loads of logits), ragged tail
+    (2, 300, 4, 64, 128, 2, 5, 2, 128),        # odd expert count: element loads of the logits
+    (2, 257, 2, 64, 128, 1, 8, 1, 64),         # top-1
+    (1, 31, 2, 64, 128, 1, 4, 2, 256),         # one short chunk
+    (1, 400, 4, 40, 96, 2, 16, 1, 128),        # padded state size
+    (3, 2100, 8, 64, 128, 8, 16, 2, 256),      # 216 items: several per workgroup on a small grid, too
+]
+
+
+@pytest.mark.parametrize("case", CHUNK_MIX_CASES, ids=lambda c: "B%dL%dH%dP%dN%dG%dE%dk%dQ%d" % c)
+def test_chunk_level_mix_writes_what_mix_and_prep_write(case):
+    """Router + mixing + tiles per whole chunk in one persistent kernel, and the tables alone, against
+    the per-tile mix and the prep kernel: every byte of the workspace except the operand image of
+    the mixed B rows, which the chunk-level kernel does not need; then the pass on both."""
+    B, L, H, P, N, G, E, k, Q = case
+    w = synth.Workload("cm", B, L, H, P, N, G, E, k, Q, "bf16", 9)
+    p = synth.make_inputs(w, seed=hash(case) % 100000)
+    d = to_device(p, "bf16")
+    dims = sw.dims_of(d["x"], d["B_experts"], k, Q)
+    lo = sw.swimba_mixer_workspace_layout(dims)
+    offs = sorted(getattr(lo, f[0]) for f in lo._fields_)
+    frag_end = min(o for o in offs if o > lo.bmix_frag)
+    out = []
+    for chunked in (False, True):
+        ws = sw.alloc_workspace(dims, "cuda:0")
+        ws.zero_()
+        if chunked:
+            sw.swimba_stage_mix_chunk(dims, d["B_experts"], d["C_experts"], d["router_logits"], ws)
+            sw.swimba_stage_tables(dims, d["dt"], d["A"], ws)
+        else:
+            sw.swimba_stage_mix(dims, d["B_experts"], d["C_experts"], d["router_logits"], ws)
+            sw.swimba_stage_prep(dims, d["dt"], d["A"], ws)
+        y = torch.empty_like(d["x"])
+        hf = torch.empty((B, H, P, N), device="cuda:0")
+        sw.swimba_stage_pass(dims, d["x"], d["dt"], d["D"], None, y, hf, ws)
+        torch.cuda.synchronize()
+        out.append((ws, y, hf))
+    (wa, ya, ha), (wb, yb, hb) = out
+    assert torch.equal(wa[:lo.bmix_frag], wb[:lo.bmix_frag])
+    assert torch.equal(wa[frag_end:], wb[frag_end:])
+    assert (wb[lo.bmix_frag:frag_end] == 0).all()
+    assert torch.equal(ya, yb) and torch.equal(ha, hb)
+
+
+def test_chunk_level_mix_refuses_what_it_does_not_take():
+    dev = "cuda:0"
+    for E, k in ((17, 2), (8, 3)):
+        x = torch.zeros((1, 64, 2, 64), dtype=torch.bfloat16, device=dev)
+        Be = torch.zeros((1, 64, E, 1, 128), dtype=torch.bfloat16, device=dev)
+        dims = sw.dims_of(x, Be, k, 64)
+        ws = sw.alloc_workspace(dims, dev)
+        with pytest.raises(RuntimeError):
+            sw.swimba_stage_mix_chunk(dims, Be, Be, torch.zeros((1, 64, E), dtype=torch.bfloat16, device=dev), ws)
