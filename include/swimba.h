@@ -195,15 +195,22 @@ swimba_status swimba_stage_pass(const swimba_dims *dims, const void *x, const vo
 
 /* Which kernels swimba_mixer_fwd (and the _selected/_proj forms) run for these dims on the
  * current device: SWIMBA_PATH_GENERIC (fp32-capable kernels, any shape), SWIMBA_PATH_STAGED
- * (bf16 MFMA: mix, chunk_state, state_scan, output), SWIMBA_PATH_SINGLE_PASS (bf16 MFMA: mix,
- * prep, pass) or SWIMBA_PATH_SINGLE_PASS_CHUNK_MIX (see below).  The single pass is taken when its (batch, head, 32-channel) chains number between
- * 3/4 of and all of the device's compute units and the sequence has at least 16 chunks; results
- * of the two MFMA paths agree to the rounding of their bf16 operands.  Returns minus the
- * swimba_status for invalid dims.  Host only; launches nothing. */
+ * (bf16 MFMA: mix, chunk_state, state_scan, output), or a single pass over the chunks with the
+ * state in registers: SWIMBA_PATH_SINGLE_PASS_HEAD (mix, prep, pass64: a workgroup per (batch,
+ * head), taken for head dimensions above 32 when batch * heads fills at least 3/4 of the rounds
+ * of workgroups it runs in - one workgroup per compute unit - and the sequence has at least 12
+ * chunks) or SWIMBA_PATH_SINGLE_PASS (mix, prep, pass: a workgroup per (batch, head, 32
+ * channels), taken when those slices number between 3/4 of and all of the compute units and
+ * the sequence has at least 16 chunks), each also with the chunk-level mix kernel in front
+ * (..._CHUNK_MIX, see below).  The results of the MFMA paths agree to the rounding of their
+ * bf16 operands.  Returns minus the swimba_status for invalid dims.  Host only; launches
+ * nothing. */
 #define SWIMBA_PATH_GENERIC 0
 #define SWIMBA_PATH_STAGED 1
 #define SWIMBA_PATH_SINGLE_PASS 2
 #define SWIMBA_PATH_SINGLE_PASS_CHUNK_MIX 3
+#define SWIMBA_PATH_SINGLE_PASS_HEAD 4            /* mix, prep, pass64: one workgroup per (batch, head) */
+#define SWIMBA_PATH_SINGLE_PASS_HEAD_CHUNK_MIX 5  /* mix_chunk, tables, pass64 */
 int swimba_prefill_path(const swimba_dims *dims);
 
 /* Single pass with the router, the mixing and the tiles of Bmix.Cmix^T done per whole chunk in one
@@ -220,6 +227,11 @@ swimba_status swimba_stage_mix_chunk(const swimba_dims *dims, const void *B_expe
 swimba_status swimba_stage_tables(const swimba_dims *dims, const void *dt, const float *A, void *workspace,
                                   size_t workspace_bytes, void *hip_stream);
 
+/* pass with one workgroup per (batch, head) and all channels of the head (up to 64) instead of 32-channel
+ * slices: same inputs and outputs as swimba_stage_pass. */
+swimba_status swimba_stage_pass64(const swimba_dims *dims, const void *x, const void *dt, const float *D,
+                                  const float *h0, void *y, float *h_final, void *workspace,
+                                  size_t workspace_bytes, void *hip_stream);
 swimba_status swimba_stage_router(const swimba_dims *dims, const void *router_logits,
                                   void *workspace, size_t workspace_bytes, void *hip_stream);
 swimba_status swimba_stage_cumsum(const swimba_dims *dims, const void *dt, const float *A,

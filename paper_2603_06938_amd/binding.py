@@ -82,6 +82,8 @@ def _load():
         lib.swimba_stage_tables.argtypes = [dp, vp, vp, vp, sz, vp]
         lib.swimba_stage_pass.restype = i32
         lib.swimba_stage_pass.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        lib.swimba_stage_pass64.restype = i32
+        lib.swimba_stage_pass64.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         lib.swimba_separated_workspace_bytes.restype = sz
         lib.swimba_separated_workspace_bytes.argtypes = [dp]
         lib.swimba_separated_fwd.restype = i32
@@ -622,7 +624,8 @@ def swimba_stage_output(dims, x, dt, D, B_experts, C_experts, y, workspace):
                                        _stream()), "swimba_stage_output")
 
 
-PATH_GENERIC, PATH_STAGED, PATH_SINGLE_PASS, PATH_SINGLE_PASS_CHUNK_MIX = 0, 1, 2, 3
+PATH_GENERIC, PATH_STAGED, PATH_SINGLE_PASS, PATH_SINGLE_PASS_CHUNK_MIX, PATH_SINGLE_PASS_HEAD = 0, 1, 2, 3, 4
+PATH_SINGLE_PASS_HEAD_CHUNK_MIX = 5
 
 
 def swimba_prefill_path(dims) -> int:
@@ -658,6 +661,14 @@ def swimba_stage_pass(dims, x, dt, D, h0, y, h_final, workspace):
                                      _ptr(h_final, "h_final", torch.float32),
                                      _ptr(workspace, "workspace", torch.uint8), workspace.numel(), _stream()),
            "swimba_stage_pass")
+
+
+def swimba_stage_pass64(dims, x, dt, D, h0, y, h_final, workspace):
+    _check(_load().swimba_stage_pass64(ctypes.byref(dims), _ptr(x, "x"), _ptr(dt, "dt"), _ptr(D, "D", torch.float32),
+                                       _ptr(h0, "h0", torch.float32), _ptr(y, "y"),
+                                       _ptr(h_final, "h_final", torch.float32),
+                                       _ptr(workspace, "workspace", torch.uint8), workspace.numel(), _stream()),
+           "swimba_stage_pass64")
 
 
 def workspace_views(dims: swimba_dims, workspace: torch.Tensor):

@@ -95,12 +95,6 @@ static void layout_of(const swimba_dims *d, swimba_ws_layout *o)
     o->total = off > 0 ? off : 256;
 }
 
-// Which evaluation of the SSD part swimba_mixer_fwd takes on the bf16 MFMA path.  The single pass
-// keeps one workgroup per (batch, head, 32 channels) busy for the whole sequence: it needs about
-// one such chain per compute unit and enough chunks per chain to pay off; with fewer chains most
-// of the chip idles, with more they run in rounds and the staged kernels (which also parallelise
-// over chunks) are faster.  Measured on MI355X: 342 us against 454 us at B2 L16384 H64 (256 chains,
-// 64 chunks), 195 against 190 at B8 L4096 H32 (512 chains), 97 against 75 at B8 L2048 H24 (384).
 // compute units of the current device (0 if the query fails); asked once
 static int device_cus()
 {
@@ -116,21 +110,43 @@ static int device_cus()
     return ncu;
 }
 
-static bool use_single_pass(const swimba_dims *d)
+// Which evaluation of the SSD part swimba_mixer_fwd takes on the bf16 MFMA path.  A single pass keeps
+// one workgroup (one per compute unit: its LDS) busy for the whole sequence of its chain, so it
+// needs chains that fill the rounds they run in, and enough chunks per chain to pay for the ramp;
+// the staged kernels also parallelise over chunks and win everywhere else.
+//   head64   a chain per (batch, head), all channels: 7.8 us per chunk.  Takes the shapes whose
+//            B*H chains fill at least 3/4 of their rounds, from 12 chunks on.
+//   slices32 a chain per (batch, head, 32 channels): 5.4 us per chunk, i.e. more per channel (the
+//            operands a group shares are read per slice), but twice the chains: for the shapes
+//            whose heads alone leave the chip half empty.
+// Measured on MI355X, staged / slices32 / head64 in us (device-random inputs, one input set):
+//   B8 L4096 H32 184/204/151   B16 L4096 H32 397/388/296   B8 L4096 H48 288/264/244   B4 L8192 H48 291/305/244
+//   B8 L4096 H24 144/177/131   B8 L3072 H24 111/134/106    B8 L2048 H24  82/103/ 83   B8 L4096 H16 107/105/126
+//   B2 L16384 H64 551/494/561  B4 L8192 H64 539/502/378    B1 L32768 H128 888/792/946
+enum PassKind { PASS_STAGED = 0, PASS_SLICES32 = 1, PASS_HEAD64 = 2 };
+static bool fills_rounds(int64_t chains, int ncu)
+{
+    const int64_t rounds = (chains + ncu - 1) / ncu;
+    return chains > 0 && 4 * chains >= 3 * rounds * ncu;
+}
+static PassKind pass_kind(const swimba_dims *d)
 {
     const int ncu = device_cus();
-    if (ncu == 0) return false;
-    const int64_t chains = (int64_t)d->batch * d->nheads * ((d->headdim + 31) / 32);
+    if (ncu == 0 || !use_mfma_path(d)) return PASS_STAGED;
+    const int64_t heads = (int64_t)d->batch * d->nheads;
     const int64_t nc = ((int64_t)d->seqlen + d->chunk - 1) / d->chunk;
-    return chains <= ncu && 4 * chains >= 3 * (int64_t)ncu && nc >= 16;
+    if (d->headdim > 32 && nc >= 12 && fills_rounds(heads, ncu)) return PASS_HEAD64;
+    const int64_t slices = heads * ((d->headdim + 31) / 32);
+    if (nc >= 16 && slices <= ncu && fills_rounds(slices, ncu)) return PASS_SLICES32;
+    return PASS_STAGED;
 }
 
 // Router, mixing and G^T tiles per whole chunk in one persistent kernel (no operand image of the mixed B
-// rows, no tile pass) in front of the single pass: taken where every compute unit gets at least two
+// rows, no tile pass) in front of a single pass: taken where every compute unit gets at least two
 // (batch, chunk, group) items, so that the gather of the next item overlaps the tiles of the current one.
 static bool use_chunk_mix(const swimba_dims *d, bool selected)
 {
-    if (!use_mfma_path(d) || !use_single_pass(d)) return false;
+    if (pass_kind(d) == PASS_STAGED) return false;
     swimba_dims dk = *d;
     const Shape s = make_shape(&dk);
     return mix_chunk_covers(s, selected) && (int64_t)s.B * s.nc * s.G >= 2 * (int64_t)device_cus();
@@ -319,8 +335,11 @@ int swimba_prefill_path(const swimba_dims *dims)
     swimba_status st = check_mixer(dims);
     if (st != SWIMBA_OK) return -(int)st;
     if (!use_mfma_path(dims)) return SWIMBA_PATH_GENERIC;
-    if (use_chunk_mix(dims, false)) return SWIMBA_PATH_SINGLE_PASS_CHUNK_MIX;
-    return use_single_pass(dims) ? SWIMBA_PATH_SINGLE_PASS : SWIMBA_PATH_STAGED;
+    const PassKind pk = pass_kind(dims);
+    if (pk == PASS_STAGED) return SWIMBA_PATH_STAGED;
+    const bool cm = use_chunk_mix(dims, false);
+    if (pk == PASS_SLICES32) return cm ? SWIMBA_PATH_SINGLE_PASS_CHUNK_MIX : SWIMBA_PATH_SINGLE_PASS;
+    return cm ? SWIMBA_PATH_SINGLE_PASS_HEAD_CHUNK_MIX : SWIMBA_PATH_SINGLE_PASS_HEAD;
 }
 
 swimba_status swimba_stage_mix_chunk(const swimba_dims *dims, const void *B_experts, const void *C_experts,
@@ -385,6 +404,21 @@ swimba_status swimba_stage_pass(const swimba_dims *dims, const void *x, const vo
                             y, (hipStream_t)hip_stream);
 }
 
+swimba_status swimba_stage_pass64(const swimba_dims *dims, const void *x, const void *dt, const float *D,
+                                  const float *h0, void *y, float *h_final, void *workspace,
+                                  size_t workspace_bytes, void *hip_stream)
+{
+    Ws ws;
+    swimba_status st = carve(dims, workspace, workspace_bytes, &ws);
+    if (st != SWIMBA_OK) return st;
+    if (!use_mfma_path(dims)) return SWIMBA_ERR_UNSUPPORTED;
+    if ((int64_t)dims->batch * dims->seqlen == 0) return SWIMBA_OK;
+    if (!x || !dt || !y) return SWIMBA_ERR_NULL;
+    if (check_align(dims->io_dtype, {x, y, h0, h_final}, {dt}, {D}) != SWIMBA_OK) return SWIMBA_ERR_ALIGNMENT;
+    return launch_pass64_mfma(make_shape(dims), x, dt, D, ws.cmix, ws.bmix_t8, ws.cb, ws.cs2, ws.fdec, ws.cdec, h0,
+                              h_final, y, (hipStream_t)hip_stream);
+}
+
 swimba_status swimba_mixer_fwd(const swimba_dims *dims, const void *x, const void *dt,
                                const float *A, const float *D, const void *B_experts,
                                const void *C_experts, const void *router_logits, const float *h0,
@@ -427,13 +461,15 @@ swimba_status swimba_mixer_fwd(const swimba_dims *dims, const void *x, const voi
                 e = hipMemcpyAsync(topk_w, ws.w, n * sizeof(float), hipMemcpyDeviceToDevice, stream);
             if (e != hipSuccess) { set_last_hip_error((int)e); return SWIMBA_ERR_HIP; }
         }
-        if (mf && use_single_pass(dims)) {
+        const PassKind pk = pass_kind(dims);
+        const bool slices = pk == PASS_SLICES32;
+        if (pk != PASS_STAGED) {
             // single pass: G^T tiles and cumsum tables, then one walk over the chunks per
-            // (batch, head, 32 channels) with the state in registers
+            // (batch, head, 32 channels) or per (batch, head) with the state in registers
             st = launch_prep_mfma(s, dt, A, ws.cmix, ws.bmix_frag, ws.cb, ws.cs2, ws.fdec, ws.cdec, stream, !chunk_mix);
             if (st != SWIMBA_OK) return st;
-            return launch_pass_mfma(s, x, dt, D, ws.cmix, ws.bmix_t8, ws.cb, ws.cs2, ws.fdec, ws.cdec, h0, h_final, y,
-                                    stream);
+            return (slices ? launch_pass_mfma : launch_pass64_mfma)(s, x, dt, D, ws.cmix, ws.bmix_t8, ws.cb, ws.cs2,
+                                                                    ws.fdec, ws.cdec, h0, h_final, y, stream);
         }
         st = swimba_stage_chunk_state(dims, x, dt, A, B_experts, workspace, workspace_bytes, hip_stream);
         if (st != SWIMBA_OK) return st;
@@ -887,12 +923,14 @@ static swimba_status mixer_selected_core(const swimba_dims *dims, const void *x,
                            : launch_mix_rows_mfma(s, B_sel, C_sel, nullptr, nullptr, nullptr, ws.cmix, ws.bmix_frag,
                                                   ws.bmix_t8, -1, -1, w_sel, stream);
             if (st != SWIMBA_OK) return st;
-            if (use_single_pass(dims)) {
+            const PassKind pk = pass_kind(dims);
+            const bool slices = pk == PASS_SLICES32;
+            if (pk != PASS_STAGED) {
                 st = launch_prep_mfma(s, dt, A, ws.cmix, ws.bmix_frag, ws.cb, ws.cs2, ws.fdec, ws.cdec, stream,
                                       !chunk_mix);
                 if (st != SWIMBA_OK) return st;
-                return launch_pass_mfma(s, x, dt, D, ws.cmix, ws.bmix_t8, ws.cb, ws.cs2, ws.fdec, ws.cdec, h0, h_final, y,
-                                        stream);
+                return (slices ? launch_pass_mfma : launch_pass64_mfma)(s, x, dt, D, ws.cmix, ws.bmix_t8, ws.cb, ws.cs2,
+                                                                        ws.fdec, ws.cdec, h0, h_final, y, stream);
             }
             st = launch_chunk_state_mfma(s, x, dt, A, ws.bmix_t8, ws.cs, ws.states_lp, stream);
         } else {

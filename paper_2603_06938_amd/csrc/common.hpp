@@ -117,6 +117,10 @@ swimba_status launch_output_mfma(const Shape &s, const void *x, const void *dt, 
                                  const void *cmix, const void *cb, const float *cs,
                                  const void *states_lp, void *y, const float *skip_w, int skip_stride,
                                  int accumulate, hipStream_t st);
+// single pass with all 64 channels of a head per workgroup (fused_pass64.hip); same arguments as launch_pass_mfma
+swimba_status launch_pass64_mfma(const Shape &s, const void *x, const void *dt, const float *D, const void *cmix,
+                                 const void *bt8, const void *cb, const float *cs2, const float *fdec,
+                                 const float *cdec, const float *h0, float *h_final, void *y, hipStream_t st);
 // router + mixing + G^T tiles of whole chunks in one persistent kernel (mix_chunk.hip)
 bool mix_chunk_covers(const Shape &s, bool selected);
 swimba_status launch_mix_chunk_mfma(const Shape &s, const void *Be, const void *Ce, const void *logits, int32_t *idx,

@@ -28,19 +28,22 @@ CASES = [
 ]
 
 
-def single_pass(d, dims, D, h0, k, Q):
+def single_pass(d, dims, D, h0, k, Q, whole_head=False):
+    """mix, prep and the pass: a workgroup per (batch, head, 32 channels), or per (batch, head) with all
+    channels of the head (whole_head)"""
     ws = sw.alloc_workspace(dims, "cuda:0")
     y = torch.full_like(d["x"], float("nan"))
     hf = torch.full((dims.batch, dims.nheads, dims.headdim, dims.dstate), float("nan"), device="cuda:0")
     sw.swimba_stage_mix(dims, d["B_experts"], d["C_experts"], d["router_logits"], ws)
     sw.swimba_stage_prep(dims, d["dt"], d["A"], ws)
-    sw.swimba_stage_pass(dims, d["x"], d["dt"], D, h0, y, hf, ws)
+    (sw.swimba_stage_pass64 if whole_head else sw.swimba_stage_pass)(dims, d["x"], d["dt"], D, h0, y, hf, ws)
     torch.cuda.synchronize()
     return y, hf, ws
 
 
+@pytest.mark.parametrize("whole_head", [False, True], ids=["slices32", "head64"])
 @pytest.mark.parametrize("case", CASES, ids=lambda c: "B%dL%dH%dP%dN%dG%dE%dk%dQ%d_h0%d_D%d" % c)
-def test_single_pass_matches_oracle(case):
+def test_single_pass_matches_oracle(case, whole_head):
     B, L, H, P, N, G, E, k, Q, with_h0, with_D = case
     w = synth.Workload("sp", B, L, H, P, N, G, E, k, Q, "bf16", 7)
     p = synth.make_inputs(w, seed=hash(case) % 100000)
@@ -51,7 +54,7 @@ def test_single_pass_matches_oracle(case):
     d = to_device(p, "bf16")
     dims = sw.dims_of(d["x"], d["B_experts"], k, Q)
     y, hf, ws = single_pass(d, dims, d["D"] if with_D else None,
-                            None if h0 is None else torch.from_numpy(h0).to("cuda:0"), k, Q)
+                            None if h0 is None else torch.from_numpy(h0).to("cuda:0"), k, Q, whole_head)
     ref = orc.mixer_fwd(p["x"], p["dt"], p["A"], D, p["B_experts"], p["C_experts"], p["router_logits"], k, h0=h0)
     idx = sw.workspace_views(dims, ws)["topk_idx"]
     np.testing.assert_array_equal(idx.cpu().numpy(), ref["topk_idx"])
@@ -85,21 +88,22 @@ def test_single_pass_matches_oracle(case):
     assert l2 <= TOL["bf16"] and linf <= TOL["bf16"], ("staged h_final", l2, linf)
 
 
-def test_single_pass_is_deterministic_and_causal():
+@pytest.mark.parametrize("whole_head", [False, True], ids=["slices32", "head64"])
+def test_single_pass_is_deterministic_and_causal(whole_head):
     w = synth.Workload("sp", 2, 600, 4, 64, 128, 2, 8, 2, 256, "bf16", 7)
     p = synth.make_inputs(w, seed=5)
     q = synth.make_inputs(w, seed=6)
     d = to_device(p, "bf16")
     dims = sw.dims_of(d["x"], d["B_experts"], 2, 256)
-    y1, h1, _ = single_pass(d, dims, d["D"], None, 2, 256)
-    y2, h2, _ = single_pass(d, dims, d["D"], None, 2, 256)
+    y1, h1, _ = single_pass(d, dims, d["D"], None, 2, 256, whole_head)
+    y2, h2, _ = single_pass(d, dims, d["D"], None, 2, 256, whole_head)
     assert torch.equal(y1, y2) and torch.equal(h1, h2)
     for s in (37, 256, 300, 599):
         mod = {kk: (np.concatenate([v[:, :s], q[kk][:, s:]], axis=1) if kk in ("x", "dt", "B_experts", "C_experts",
                                                                                  "router_logits") else v)
                for kk, v in p.items()}
         dm = to_device(mod, "bf16")
-        ym, _, _ = single_pass(dm, dims, dm["D"], None, 2, 256)
+        ym, _, _ = single_pass(dm, dims, dm["D"], None, 2, 256, whole_head)
         assert torch.equal(ym[:, :s], y1[:, :s]), s
 
 
