@@ -81,6 +81,15 @@ def work_model(w):
                    "irreducible": T * (2 * H * P * 2 + H * 2), "flops": 2.0 * T * Q * P * H + 2.0 * T * N * P * H},
     }
     kernels["pass64"] = kernels["pass"]
+    # short sequences: the tiles ride in the chunk-state launch, the output kernel reads the chunk states before
+    # its chunk ((nc - 1) / 2 of them on average) instead of one carried state
+    nc = (w.seqlen + Q - 1) // Q
+    kernels["chunk_state_tiles"] = {"moved": kernels["chunk_state"]["moved"] + T * 2 * G * N * 2 + cb_bytes,
+                                    "irreducible": kernels["chunk_state"]["irreducible"],
+                                    "flops": kernels["chunk_state"]["flops"] + 2.0 * T * Q * N * G}
+    kernels["output_carry"] = {"moved": kernels["output"]["moved"] + state_elems * (nc - 3) + w.batch * H * P * N * 4,
+                               "irreducible": kernels["output"]["irreducible"] + w.batch * H * P * N * 4,
+                               "flops": kernels["output"]["flops"]}
     return call, kernels
 
 
@@ -213,6 +222,12 @@ def main() -> int:
                     "tables": lambda d: sw.swimba_stage_tables(dims, d["dt"], d["A"], d["ws"]),
                     "pass64": lambda d: sw.swimba_stage_pass64(dims, d["x"], d["dt"], d["D"], None, d["y"], d["h_final"], d["ws"]),
                 },
+                sw.PATH_STAGED_SHORT: {
+                    "mix": mix,
+                    "chunk_state_tiles": lambda d: sw.swimba_stage_chunk_state_tiles(dims, d["x"], d["dt"], d["A"], d["ws"]),
+                    "output_carry": lambda d: sw.swimba_stage_output_carry(dims, d["x"], d["dt"], d["D"], None, d["y"],
+                                                                           d["h_final"], d["ws"]),
+                },
                 sw.PATH_STAGED: {
                     "mix": mix,
                     "chunk_state": lambda d: sw.swimba_stage_chunk_state(dims, d["x"], d["dt"], d["A"], d["B_experts"], d["ws"]),
@@ -227,9 +242,9 @@ def main() -> int:
             self.path = sw.swimba_prefill_path(dims)
             self.path_name = {sw.PATH_SINGLE_PASS: "single_pass", sw.PATH_STAGED: "staged",
                               sw.PATH_SINGLE_PASS_CHUNK_MIX: "single_pass_chunk_mix",
-                              sw.PATH_SINGLE_PASS_HEAD: "single_pass_head",
+                              sw.PATH_SINGLE_PASS_HEAD: "single_pass_head", sw.PATH_STAGED_SHORT: "staged_short",
                               sw.PATH_SINGLE_PASS_HEAD_CHUNK_MIX: "single_pass_head_chunk_mix"}[self.path]
-            self.other = sw.PATH_SINGLE_PASS if self.path == sw.PATH_STAGED else sw.PATH_STAGED
+            self.other = sw.PATH_SINGLE_PASS if self.path in (sw.PATH_STAGED, sw.PATH_STAGED_SHORT) else sw.PATH_STAGED
             self.paths = {pth: fns for pth, fns in self.paths.items()
                           if pth not in (sw.PATH_SINGLE_PASS_CHUNK_MIX, sw.PATH_SINGLE_PASS_HEAD_CHUNK_MIX)
                           or pth == self.path}   # the chunk-level mix takes few experts only
@@ -669,7 +684,8 @@ def main() -> int:
             "irreducible_bytes": call["irreducible_bytes"], "dense_flops": call["flops"],
             "dominant_kernel": dict(kernels[dom], name=dom)}
     # the targets the kernels are held to, and whether this run met them
-    contr = {n: kernels[n]["mfma_frac"] for n in ("pass", "pass64", "chunk_state", "output") if n in kernels}
+    contr = {n: kernels[n]["mfma_frac"] for n in ("pass", "pass64", "chunk_state", "output", "chunk_state_tiles",
+                                                  "output_carry") if n in kernels}
     targets = {
         "contractions_mfma_frac": {"target": 0.5, "value": contr, "met": all(v >= 0.5 for v in contr.values()),
                                    "note": "the forward is HBM-bound (dense flops / irreducible bytes = %d flop/B, "

@@ -195,7 +195,8 @@ swimba_status swimba_stage_pass(const swimba_dims *dims, const void *x, const vo
 
 /* Which kernels swimba_mixer_fwd (and the _selected/_proj forms) run for these dims on the
  * current device: SWIMBA_PATH_GENERIC (fp32-capable kernels, any shape), SWIMBA_PATH_STAGED
- * (bf16 MFMA: mix, chunk_state, state_scan, output), or a single pass over the chunks with the
+ * (bf16 MFMA: mix, chunk_state, state_scan, output; SWIMBA_PATH_STAGED_SHORT for at most 8 chunks,
+ * see below), or a single pass over the chunks with the
  * state in registers: SWIMBA_PATH_SINGLE_PASS_HEAD (mix, prep, pass64: a workgroup per (batch,
  * head), taken for head dimensions above 32 when batch * heads fills at least 3/4 of the rounds
  * of workgroups it runs in - one workgroup per compute unit - and the sequence has at least 12
@@ -211,6 +212,7 @@ swimba_status swimba_stage_pass(const swimba_dims *dims, const void *x, const vo
 #define SWIMBA_PATH_SINGLE_PASS_CHUNK_MIX 3
 #define SWIMBA_PATH_SINGLE_PASS_HEAD 4            /* mix, prep, pass64: one workgroup per (batch, head) */
 #define SWIMBA_PATH_SINGLE_PASS_HEAD_CHUNK_MIX 5  /* mix_chunk, tables, pass64 */
+#define SWIMBA_PATH_STAGED_SHORT 6                /* mix, chunk_state_tiles, output_carry: at most 8 chunks */
 int swimba_prefill_path(const swimba_dims *dims);
 
 /* Single pass with the router, the mixing and the tiles of Bmix.Cmix^T done per whole chunk in one
@@ -227,6 +229,17 @@ swimba_status swimba_stage_mix_chunk(const swimba_dims *dims, const void *B_expe
 swimba_status swimba_stage_tables(const swimba_dims *dims, const void *dt, const float *A, void *workspace,
                                   size_t workspace_bytes, void *hip_stream);
 
+/* Staged kernels for sequences of at most 8 chunks (SWIMBA_PATH_STAGED_SHORT), without a scan launch:
+ *   chunk_state_tiles : chunk_state, and in the same launch ws.cmix, ws.bmix_frag -> ws.cb
+ *   output_carry      : output on the CHUNK states in ws.states_lp: the workgroups of chunk c carry the
+ *                       state up to c themselves (h0, S_0 .. S_{c-1}, fp32, the scan's order of
+ *                       operations); those of the last chunk write h_final.  SWIMBA_ERR_UNSUPPORTED for
+ *                       more than 8 chunks. */
+swimba_status swimba_stage_chunk_state_tiles(const swimba_dims *dims, const void *x, const void *dt, const float *A,
+                                             void *workspace, size_t workspace_bytes, void *hip_stream);
+swimba_status swimba_stage_output_carry(const swimba_dims *dims, const void *x, const void *dt, const float *D,
+                                        const float *h0, void *y, float *h_final, void *workspace,
+                                        size_t workspace_bytes, void *hip_stream);
 /* pass with one workgroup per (batch, head) and all channels of the head (up to 64) instead of 32-channel
  * slices: same inputs and outputs as swimba_stage_pass. */
 swimba_status swimba_stage_pass64(const swimba_dims *dims, const void *x, const void *dt, const float *D,

@@ -82,6 +82,10 @@ def _load():
         lib.swimba_stage_tables.argtypes = [dp, vp, vp, vp, sz, vp]
         lib.swimba_stage_pass.restype = i32
         lib.swimba_stage_pass.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        lib.swimba_stage_chunk_state_tiles.restype = i32
+        lib.swimba_stage_chunk_state_tiles.argtypes = [dp, vp, vp, vp, vp, sz, vp]
+        lib.swimba_stage_output_carry.restype = i32
+        lib.swimba_stage_output_carry.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         lib.swimba_stage_pass64.restype = i32
         lib.swimba_stage_pass64.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         lib.swimba_separated_workspace_bytes.restype = sz
@@ -625,7 +629,7 @@ def swimba_stage_output(dims, x, dt, D, B_experts, C_experts, y, workspace):
 
 
 PATH_GENERIC, PATH_STAGED, PATH_SINGLE_PASS, PATH_SINGLE_PASS_CHUNK_MIX, PATH_SINGLE_PASS_HEAD = 0, 1, 2, 3, 4
-PATH_SINGLE_PASS_HEAD_CHUNK_MIX = 5
+PATH_SINGLE_PASS_HEAD_CHUNK_MIX, PATH_STAGED_SHORT = 5, 6
 
 
 def swimba_prefill_path(dims) -> int:
@@ -661,6 +665,21 @@ def swimba_stage_pass(dims, x, dt, D, h0, y, h_final, workspace):
                                      _ptr(h_final, "h_final", torch.float32),
                                      _ptr(workspace, "workspace", torch.uint8), workspace.numel(), _stream()),
            "swimba_stage_pass")
+
+
+def swimba_stage_chunk_state_tiles(dims, x, dt, A, workspace):
+    _check(_load().swimba_stage_chunk_state_tiles(ctypes.byref(dims), _ptr(x, "x"), _ptr(dt, "dt"),
+                                                  _ptr(A, "A", torch.float32),
+                                                  _ptr(workspace, "workspace", torch.uint8), workspace.numel(),
+                                                  _stream()), "swimba_stage_chunk_state_tiles")
+
+
+def swimba_stage_output_carry(dims, x, dt, D, h0, y, h_final, workspace):
+    _check(_load().swimba_stage_output_carry(ctypes.byref(dims), _ptr(x, "x"), _ptr(dt, "dt"),
+                                             _ptr(D, "D", torch.float32), _ptr(h0, "h0", torch.float32), _ptr(y, "y"),
+                                             _ptr(h_final, "h_final", torch.float32),
+                                             _ptr(workspace, "workspace", torch.uint8), workspace.numel(), _stream()),
+           "swimba_stage_output_carry")
 
 
 def swimba_stage_pass64(dims, x, dt, D, h0, y, h_final, workspace):

@@ -336,7 +336,10 @@ int swimba_prefill_path(const swimba_dims *dims)
     if (st != SWIMBA_OK) return -(int)st;
     if (!use_mfma_path(dims)) return SWIMBA_PATH_GENERIC;
     const PassKind pk = pass_kind(dims);
-    if (pk == PASS_STAGED) return SWIMBA_PATH_STAGED;
+    if (pk == PASS_STAGED) {
+        const int64_t nc = ((int64_t)dims->seqlen + dims->chunk - 1) / dims->chunk;
+        return nc <= OUTPUT_LOOKBACK_MAX_CHUNKS ? SWIMBA_PATH_STAGED_SHORT : SWIMBA_PATH_STAGED;
+    }
     const bool cm = use_chunk_mix(dims, false);
     if (pk == PASS_SLICES32) return cm ? SWIMBA_PATH_SINGLE_PASS_CHUNK_MIX : SWIMBA_PATH_SINGLE_PASS;
     return cm ? SWIMBA_PATH_SINGLE_PASS_HEAD_CHUNK_MIX : SWIMBA_PATH_SINGLE_PASS_HEAD;
@@ -402,6 +405,36 @@ swimba_status swimba_stage_pass(const swimba_dims *dims, const void *x, const vo
     if (check_align(dims->io_dtype, {x, y, h0, h_final}, {dt}, {D}) != SWIMBA_OK) return SWIMBA_ERR_ALIGNMENT;
     return launch_pass_mfma(make_shape(dims), x, dt, D, ws.cmix, ws.bmix_t8, ws.cb, ws.cs2, ws.fdec, ws.cdec, h0, h_final,
                             y, (hipStream_t)hip_stream);
+}
+
+swimba_status swimba_stage_chunk_state_tiles(const swimba_dims *dims, const void *x, const void *dt, const float *A,
+                                             void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    Ws ws;
+    swimba_status st = carve(dims, workspace, workspace_bytes, &ws);
+    if (st != SWIMBA_OK) return st;
+    if (!use_mfma_path(dims)) return SWIMBA_ERR_UNSUPPORTED;
+    if ((int64_t)dims->batch * dims->seqlen == 0) return SWIMBA_OK;
+    if (!x || !dt || !A) return SWIMBA_ERR_NULL;
+    if (check_align(dims->io_dtype, {x}, {dt}, {A}) != SWIMBA_OK) return SWIMBA_ERR_ALIGNMENT;
+    return launch_chunk_state_mfma(make_shape(dims), x, dt, A, ws.bmix_t8, ws.cs, ws.states_lp, (hipStream_t)hip_stream,
+                                   1, ws.cmix, ws.bmix_frag, ws.cb);
+}
+
+swimba_status swimba_stage_output_carry(const swimba_dims *dims, const void *x, const void *dt, const float *D,
+                                        const float *h0, void *y, float *h_final, void *workspace,
+                                        size_t workspace_bytes, void *hip_stream)
+{
+    Ws ws;
+    swimba_status st = carve(dims, workspace, workspace_bytes, &ws);
+    if (st != SWIMBA_OK) return st;
+    const Shape s = make_shape(dims);
+    if (!use_mfma_path(dims) || s.nc > OUTPUT_LOOKBACK_MAX_CHUNKS) return SWIMBA_ERR_UNSUPPORTED;
+    if ((int64_t)dims->batch * dims->seqlen == 0) return SWIMBA_OK;
+    if (!x || !dt || !y) return SWIMBA_ERR_NULL;
+    if (check_align(dims->io_dtype, {x, y, h0, h_final}, {dt}, {D}) != SWIMBA_OK) return SWIMBA_ERR_ALIGNMENT;
+    return launch_output_lookback_mfma(s, x, dt, D, ws.cmix, ws.cb, ws.cs, ws.states_lp, y, h0, h_final,
+                                       (hipStream_t)hip_stream);
 }
 
 swimba_status swimba_stage_pass64(const swimba_dims *dims, const void *x, const void *dt, const float *D,
@@ -470,6 +503,15 @@ swimba_status swimba_mixer_fwd(const swimba_dims *dims, const void *x, const voi
             if (st != SWIMBA_OK) return st;
             return (slices ? launch_pass_mfma : launch_pass64_mfma)(s, x, dt, D, ws.cmix, ws.bmix_t8, ws.cb, ws.cs2,
                                                                     ws.fdec, ws.cdec, h0, h_final, y, stream);
+        }
+        if (mf && s.nc <= OUTPUT_LOOKBACK_MAX_CHUNKS) {
+            // short sequences: no scan launch; the G^T tiles ride in the chunk-state launch and every
+            // workgroup of the output kernel carries the state up to its own chunk
+            st = launch_chunk_state_mfma(s, x, dt, A, ws.bmix_t8, ws.cs, ws.states_lp, stream, 1, ws.cmix,
+                                         ws.bmix_frag, ws.cb);
+            if (st != SWIMBA_OK) return st;
+            return launch_output_lookback_mfma(s, x, dt, D, ws.cmix, ws.cb, ws.cs, ws.states_lp, y, h0, h_final,
+                                               stream);
         }
         st = swimba_stage_chunk_state(dims, x, dt, A, B_experts, workspace, workspace_bytes, hip_stream);
         if (st != SWIMBA_OK) return st;
@@ -931,6 +973,13 @@ static swimba_status mixer_selected_core(const swimba_dims *dims, const void *x,
                 if (st != SWIMBA_OK) return st;
                 return (slices ? launch_pass_mfma : launch_pass64_mfma)(s, x, dt, D, ws.cmix, ws.bmix_t8, ws.cb, ws.cs2,
                                                                         ws.fdec, ws.cdec, h0, h_final, y, stream);
+            }
+            if (s.nc <= OUTPUT_LOOKBACK_MAX_CHUNKS) {
+                st = launch_chunk_state_mfma(s, x, dt, A, ws.bmix_t8, ws.cs, ws.states_lp, stream, 1, ws.cmix,
+                                             ws.bmix_frag, ws.cb);
+                if (st != SWIMBA_OK) return st;
+                return launch_output_lookback_mfma(s, x, dt, D, ws.cmix, ws.cb, ws.cs, ws.states_lp, y, h0, h_final,
+                                                   stream);
             }
             st = launch_chunk_state_mfma(s, x, dt, A, ws.bmix_t8, ws.cs, ws.states_lp, stream);
         } else {

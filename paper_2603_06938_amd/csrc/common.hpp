@@ -102,10 +102,15 @@ swimba_status launch_sep_accumulate(int io_dtype, int64_t n, const void *y_e, fl
                                     hipStream_t st);
 swimba_status launch_chunk_state_mfma(const Shape &s, const void *x, const void *dt, const float *A,
                                       const void *bmix_t8, float *cs, void *states_lp, hipStream_t st,
-                                      int nslots = 1);
+                                      int nslots = 1, const void *cmix = nullptr, const void *bfrag = nullptr,
+                                      void *cb = nullptr);
 swimba_status launch_scan_cb_mfma(const Shape &s, const float *h0, float *h_final, void *states_lp,
                                   const float *cs, const void *cmix, const void *bfrag, void *cb,
                                   hipStream_t st, int nslots = 1);
+constexpr int OUTPUT_LOOKBACK_MAX_CHUNKS = 8;   // most chunks launch_output_lookback_mfma takes
+swimba_status launch_output_lookback_mfma(const Shape &s, const void *x, const void *dt, const float *D,
+                                          const void *cmix, const void *cb, const float *cs, const void *states_lp,
+                                          void *y, const float *h0, float *h_final, hipStream_t st);
 swimba_status launch_output_slots_mfma(const Shape &s, const void *x, const void *dt, const float *D,
                                        const void *cmix, const void *cb, const float *cs,
                                        const void *states_lp, void *y, const float *w, int nslots,

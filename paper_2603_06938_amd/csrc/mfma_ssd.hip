@@ -413,8 +413,21 @@ __global__ void __launch_bounds__(MTHREADS, 2)   // two waves per SIMD: 256 regi
 chunk_state_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ dt,
                         const float *__restrict__ A, const uint16_t *__restrict__ bmix_t8,
                         float *__restrict__ cs, uint16_t *__restrict__ states_lp, Shape s, int ipw,
-                        int nruns, int total, int nblocks, int xts, int nslots)
+                        int nruns, int total, int nblocks, int xts, int nslots, int ncb,
+                        const uint16_t *__restrict__ cmix, const uint16_t *__restrict__ bmix_frag,
+                        uint16_t *__restrict__ cb)
 {
+    if ((int)blockIdx.x < ncb) {
+        // The first ncb workgroups compute the causal G^T tiles instead (one wave per tile pair, see
+        // cb_pair): on short sequences, where the output kernel carries the states forward itself and
+        // no scan launch exists for them to ride in, they ride here.
+        const int NT = Q / 32, NPAIR = NT * (NT + 1) / 2, PB = (NPAIR + 3) / 4;
+        const int64_t id = xcd_logical_id(blockIdx.x, ncb);
+        const int64_t bcg = id / PB;
+        const int p = (int)(id % PB) * 4 + __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+        if (bcg < (int64_t)s.B * s.nc * s.G && p < NPAIR) cb_pair(cmix, bmix_frag, cb, NT, bcg, p, threadIdx.x & 63);
+        return;
+    }
     constexpr int STR = Q + 8;                    // row stride of the transposed x tile (elements)
     constexpr int KS = Q / 16;
     constexpr int XU = (Q / 8) * 32 / MTHREADS;   // x staging units per lane
@@ -424,7 +437,7 @@ chunk_state_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restri
     float *s_coef = reinterpret_cast<float *>(sXt + 2 * MP * STR);            // [2][Q]
     float *s_part = s_coef + 2 * Q;                                           // [2][4]
 
-    const int lid = xcd_logical_id(blockIdx.x, nblocks);
+    const int lid = xcd_logical_id(blockIdx.x - ncb, nblocks);
     if (lid >= total) return;
     const int run = lid % nruns;
     const int g = (lid / nruns) % s.G;
@@ -573,7 +586,7 @@ chunk_state_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restri
 template <int Q>
 static swimba_status launch_cs_q(const Shape &s, const void *x, const void *dt, const float *A,
                                  const void *bmix_t8, float *cs, void *states_lp, hipStream_t st, int xts,
-                                 int nslots)
+                                 int nslots, const void *cmix, const void *bfrag, void *cb)
 {
     const int hpg = s.H / s.G;
     // heads per workgroup: as many as possible while at least ~2 workgroups per CU remain
@@ -598,23 +611,27 @@ static swimba_status launch_cs_q(const Shape &s, const void *x, const void *dt, 
         if (e != hipSuccess) { set_last_hip_error((int)e); return SWIMBA_ERR_HIP; }
         attr_set.fetch_or(bit, std::memory_order_release);
     }
-    hipLaunchKernelGGL(chunk_state_mfma_kernel<Q>, dim3(nblocks), dim3(MTHREADS), shm, st,
+    // the G^T tiles in front, when the caller wants them from this launch
+    const int ncb = cb ? xcd_padded((int64_t)s.B * s.nc * s.G * (((Q / 32) * (Q / 32 + 1) / 2 + 3) / 4)) : 0;
+    hipLaunchKernelGGL(chunk_state_mfma_kernel<Q>, dim3(ncb + nblocks), dim3(MTHREADS), shm, st,
                        (const uint16_t *)x, (const uint16_t *)dt, A, (const uint16_t *)bmix_t8, cs,
-                       (uint16_t *)states_lp, s, ipw, nruns, (int)total, nblocks, xts, nslots);
+                       (uint16_t *)states_lp, s, ipw, nruns, (int)total, nblocks, xts, nslots, ncb,
+                       (const uint16_t *)cmix, (const uint16_t *)bfrag, (uint16_t *)cb);
     SWIMBA_CHECK_LAUNCH();
     return SWIMBA_OK;
 }
 
-// x is (B, L, nslots, H, P) for nslots > 1 (rows of the selected experts), (B, L, H, P) otherwise
+// x is (B, L, nslots, H, P) for nslots > 1 (rows of the selected experts), (B, L, H, P) otherwise;
+// with cb != nullptr the same launch also computes the G^T tiles from cmix and bfrag
 swimba_status launch_chunk_state_mfma(const Shape &s, const void *x, const void *dt, const float *A,
                                       const void *bmix_t8, float *cs, void *states_lp, hipStream_t st,
-                                      int nslots)
+                                      int nslots, const void *cmix, const void *bfrag, void *cb)
 {
     const int xts = nslots * s.H * s.P;
     switch (s.Q) {
-    case 64: return launch_cs_q<64>(s, x, dt, A, bmix_t8, cs, states_lp, st, xts, nslots);
-    case 128: return launch_cs_q<128>(s, x, dt, A, bmix_t8, cs, states_lp, st, xts, nslots);
-    case 256: return launch_cs_q<256>(s, x, dt, A, bmix_t8, cs, states_lp, st, xts, nslots);
+    case 64: return launch_cs_q<64>(s, x, dt, A, bmix_t8, cs, states_lp, st, xts, nslots, cmix, bfrag, cb);
+    case 128: return launch_cs_q<128>(s, x, dt, A, bmix_t8, cs, states_lp, st, xts, nslots, cmix, bfrag, cb);
+    case 256: return launch_cs_q<256>(s, x, dt, A, bmix_t8, cs, states_lp, st, xts, nslots, cmix, bfrag, cb);
     }
     return SWIMBA_ERR_UNSUPPORTED;
 }
@@ -649,6 +666,12 @@ swimba_status launch_chunk_state_mfma(const Shape &s, const void *x, const void 
 // tile pairs, taken from the slot's G^T image, go into the same accumulators.  The skip term
 // D sum_r pi_r x^(r) is one more contraction per slot, x^T . diag(D pi_{i,r}) with the factor
 // split into two bf16 terms, so the epilogue reads no x; pi_{i,r} = skip_w[token * skip_stride + r].
+// MODE 3 (short sequences, no scan launch): Hlp holds the chunk states S_c as the chunk-state kernel
+// wrote them, and the workgroup of chunk c carries the state forward itself,
+// H_c = S_{c-1} + a_{c-1} (S_{c-2} + ... a_0 h0), a_c = exp(cs_c[Q-1]), in fp32 and in the scan
+// kernel's order of operations; the workgroups of the last chunk also write h_final.  At most
+// OUT_LB_MAX chunks.
+constexpr int OUT_LB_MAX = 8;
 template <int Q, int MODE>
 __global__ void __launch_bounds__(64 * (Q / 32), (Q == 256 ? 4 : 1))   // Q = 256: two workgroups per compute unit
 output_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ dt,
@@ -656,10 +679,11 @@ output_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ 
                    const uint16_t *__restrict__ cb, const float *__restrict__ cs,
                    const uint16_t *__restrict__ Hlp, uint16_t *__restrict__ y, Shape s, int total,
                    int nblocks, const float *__restrict__ skip_w, int skip_stride, int accumulate,
-                   int nslots)
+                   int nslots, const float *__restrict__ h0, float *__restrict__ h_final)
 {
     constexpr bool XE = (MODE == 1);
     constexpr bool SLOTS = (MODE == 2);
+    constexpr bool LOOKBACK = (MODE == 3);
     constexpr int NT = Q / 32;                 // 32-token tiles in the chunk
     constexpr int NP = NT * (NT + 1) / 2;
     constexpr int NTHR = 64 * NT;              // one wave per output tile
@@ -722,13 +746,58 @@ output_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ 
     const uint16_t dt_raw = dt[(tok0 + min(tq, valid - 1)) * s.H + h];
     constexpr int HPASS = 64 * 16 / NTHR;      // 16-byte pieces of the state tile per lane
     uint4 hreg[HPASS];
-    {
+    if constexpr (!LOOKBACK) {
         const uint16_t *Hc = Hlp + (((int64_t)b * s.nc + c) * s.H + h) * MP * MN;
 #pragma unroll
         for (int pass = 0; pass < HPASS; ++pass) {
             const int row = (tid >> 4) + (NTHR / 16) * pass, piece = tid & 15;
             hreg[pass] = load_nt(Hc + row * MN + piece * 8);   // the carried state is read once
         }
+    }
+    // MODE 3: the chunk states before this chunk, four at a time (clamped, unconditional loads)
+    uint4 sprev[LOOKBACK ? 4 : 1][HPASS];
+    float aprev[LOOKBACK ? 4 : 1];
+    auto lb_issue = [&](int c0) __attribute__((always_inline)) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int cp = max(min(c0 + u, c - 1), 0);
+            const uint16_t *Sc = Hlp + (((int64_t)b * s.nc + cp) * s.H + h) * MP * MN;
+#pragma unroll
+            for (int pass = 0; pass < HPASS; ++pass) {
+                const int row = (tid >> 4) + (NTHR / 16) * pass, piece = tid & 15;
+                sprev[u][pass] = *reinterpret_cast<const uint4 *>(Sc + row * MN + piece * 8);
+            }
+            aprev[u] = cs[(((int64_t)b * s.nc + cp) * s.H + h) * Q + Q - 1];
+        }
+    };
+    float hacc[LOOKBACK ? HPASS : 1][8];
+    auto lb_fold = [&](int c0) __attribute__((always_inline)) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            if (c0 + u < c) {
+                const float a = fast_exp2(aprev[u] * LOG2E);
+#pragma unroll
+                for (int pass = 0; pass < HPASS; ++pass) {
+                    float sv[8];
+                    unpack8(sv, sprev[u][pass]);
+#pragma unroll
+                    for (int v = 0; v < 8; ++v) hacc[pass][v] = a * hacc[pass][v] + sv[v];
+                }
+            }
+        }
+    };
+    if constexpr (LOOKBACK) {
+#pragma unroll
+        for (int pass = 0; pass < HPASS; ++pass) {
+            const int row = (tid >> 4) + (NTHR / 16) * pass, piece = tid & 15;
+            const bool real = h0 && row < s.P && piece * 8 < s.N;      // h0 has the caller's P x N
+            const float *hp = h0 + (((int64_t)b * s.H + h) * s.P + (real ? row : 0)) * s.N + (real ? piece * 8 : 0);
+            float4 lo = make_float4(0.f, 0.f, 0.f, 0.f), hi = lo;
+            if (real) { lo = *reinterpret_cast<const float4 *>(hp); hi = *reinterpret_cast<const float4 *>(hp + 4); }
+            hacc[pass][0] = lo.x; hacc[pass][1] = lo.y; hacc[pass][2] = lo.z; hacc[pass][3] = lo.w;
+            hacc[pass][4] = hi.x; hacc[pass][5] = hi.y; hacc[pass][6] = hi.z; hacc[pass][7] = hi.w;
+        }
+        lb_issue(0);
     }
     // x staging: unit = (8 tokens in operand order) x (2 channels)
     constexpr int XU = (Q / 8) * 32 / NTHR;
@@ -756,6 +825,33 @@ output_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ 
         const uint16_t *src = cmix + (((bcg * NT + I) * 8) * 64 + lane) * 8;
 #pragma unroll
         for (int ks = 0; ks < 8; ++ks) cfrag[ks] = *reinterpret_cast<const uint4 *>(src + ks * 64 * 8);
+    }
+    if constexpr (LOOKBACK) {
+        lb_fold(0);
+        if (c > 4) {                               // workgroup-uniform
+            lb_issue(4);
+            lb_fold(4);
+        }
+#pragma unroll
+        for (int pass = 0; pass < HPASS; ++pass) hreg[pass] = pack8(hacc[pass]);
+        if (h_final && c == s.nc - 1) {
+            // the state after the last chunk: one more step of the recurrence, on this chunk's own state
+            const uint16_t *Sc = Hlp + (((int64_t)b * s.nc + c) * s.H + h) * MP * MN;
+            const float a = fast_exp2(csr[Q - 1] * LOG2E);
+#pragma unroll
+            for (int pass = 0; pass < HPASS; ++pass) {
+                const int row = (tid >> 4) + (NTHR / 16) * pass, piece = tid & 15;
+                float sv[8];
+                unpack8(sv, *reinterpret_cast<const uint4 *>(Sc + row * MN + piece * 8));
+                if (row < s.P && piece * 8 < s.N) {
+                    float *hp = h_final + (((int64_t)b * s.H + h) * s.P + row) * s.N + piece * 8;
+                    *reinterpret_cast<float4 *>(hp) = make_float4(a * hacc[pass][0] + sv[0], a * hacc[pass][1] + sv[1],
+                                                                  a * hacc[pass][2] + sv[2], a * hacc[pass][3] + sv[3]);
+                    *reinterpret_cast<float4 *>(hp + 4) = make_float4(a * hacc[pass][4] + sv[4], a * hacc[pass][5] + sv[5],
+                                                                      a * hacc[pass][6] + sv[6], a * hacc[pass][7] + sv[7]);
+                }
+            }
+        }
     }
     // per-token tables: cs (times log2 e), dt, and dt * exp(R_J - cs_j) for the tiles J < I.
     // dt is applied through these tables (i.e. on the M^T operand), so x itself is staged
@@ -1050,7 +1146,8 @@ template <int Q>
 static swimba_status launch_out_q(const Shape &s, const void *x, const void *dt, const float *D,
                                   const void *cmix, const void *cb, const float *cs, const void *Hlp,
                                   void *y, const float *skip_w, int skip_stride, int accumulate, int nslots,
-                                  hipStream_t st)
+                                  hipStream_t st, bool lookback = false, const float *h0 = nullptr,
+                                  float *h_final = nullptr)
 {
     const int64_t total = (int64_t)s.B * s.nc * s.H;
     if (total == 0) return SWIMBA_OK;
@@ -1058,7 +1155,8 @@ static swimba_status launch_out_q(const Shape &s, const void *x, const void *dt,
 #define SWIMBA_OUT_LAUNCH(MODE, SHM, SW, SS, ACC, NSL)                                                             \
     hipLaunchKernelGGL((output_mfma_kernel<Q, MODE>), dim3(nblocks), dim3(64 * (Q / 32)), SHM, st,                \
                        (const uint16_t *)x, (const uint16_t *)dt, D, (const uint16_t *)cmix, (const uint16_t *)cb, \
-                       cs, (const uint16_t *)Hlp, (uint16_t *)y, s, (int)total, nblocks, SW, SS, ACC, NSL)
+                       cs, (const uint16_t *)Hlp, (uint16_t *)y, s, (int)total, nblocks, SW, SS, ACC, NSL, h0,    \
+                       h_final)
     if (nslots > 0) {
         // two x tiles (the second in the place of the carried-state tile) and the three tables
         constexpr int XSTR = Q + 8, HSTR = MN + 8;
@@ -1075,6 +1173,9 @@ static swimba_status launch_out_q(const Shape &s, const void *x, const void *dt,
             attr_set.fetch_or(bit, std::memory_order_release);
         }
         SWIMBA_OUT_LAUNCH(2, shm, skip_w, skip_stride, 0, nslots);
+    } else if (lookback) {
+        if (s.nc > OUT_LB_MAX) return SWIMBA_ERR_UNSUPPORTED;
+        SWIMBA_OUT_LAUNCH(3, 0, nullptr, 0, 0, 1);
     } else if (skip_w || accumulate) {
         SWIMBA_OUT_LAUNCH(1, 0, skip_w, skip_stride, accumulate, 1);
     } else {
@@ -1094,6 +1195,20 @@ swimba_status launch_output_mfma(const Shape &s, const void *x, const void *dt, 
     case 64: return launch_out_q<64>(s, x, dt, D, cmix, cb, cs, states_lp, y, skip_w, skip_stride, accumulate, 0, st);
     case 128: return launch_out_q<128>(s, x, dt, D, cmix, cb, cs, states_lp, y, skip_w, skip_stride, accumulate, 0, st);
     case 256: return launch_out_q<256>(s, x, dt, D, cmix, cb, cs, states_lp, y, skip_w, skip_stride, accumulate, 0, st);
+    }
+    return SWIMBA_ERR_UNSUPPORTED;
+}
+
+// Short sequences (at most OUT_LB_MAX chunks): states_lp holds the chunk states, not the carried ones; every
+// workgroup carries the state up to its chunk itself and the last chunk's workgroups write h_final.
+swimba_status launch_output_lookback_mfma(const Shape &s, const void *x, const void *dt, const float *D,
+                                          const void *cmix, const void *cb, const float *cs, const void *states_lp,
+                                          void *y, const float *h0, float *h_final, hipStream_t st)
+{
+    switch (s.Q) {
+    case 64: return launch_out_q<64>(s, x, dt, D, cmix, cb, cs, states_lp, y, nullptr, 0, 0, 0, st, true, h0, h_final);
+    case 128: return launch_out_q<128>(s, x, dt, D, cmix, cb, cs, states_lp, y, nullptr, 0, 0, 0, st, true, h0, h_final);
+    case 256: return launch_out_q<256>(s, x, dt, D, cmix, cb, cs, states_lp, y, nullptr, 0, 0, 0, st, true, h0, h_final);
     }
     return SWIMBA_ERR_UNSUPPORTED;
 }

@@ -174,3 +174,55 @@ def test_chunk_level_mix_refuses_what_it_does_not_take():
         ws = sw.alloc_workspace(dims, dev)
         with pytest.raises(RuntimeError):
             sw.swimba_stage_mix_chunk(dims, Be, Be, torch.zeros((1, 64, E), dtype=torch.bfloat16, device=dev), ws)
+
+
+@pytest.mark.parametrize("case", [(2, 2048, 4, 64, 128, 2, 8, 2, 256, True), (1, 500, 3, 64, 128, 1, 4, 2, 64, True),
+                                  (2, 300, 4, 40, 96, 2, 8, 3, 128, False), (1, 31, 2, 64, 128, 1, 4, 1, 256, True)],
+                         ids=lambda c: "B%dL%dH%dP%dN%dG%dE%dk%dQ%d_h0%d" % c)
+def test_short_sequence_kernels_equal_the_scan_path(case):
+    """At most 8 chunks: the tiles ride in the chunk-state launch and the output kernel carries the state
+    forward itself (h0, S_0 .. S_{c-1} in fp32, the scan's order of operations), against chunk state,
+    scan and output on the same inputs: the same bits."""
+    B, L, H, P, N, G, E, k, Q, with_h0 = case
+    w = synth.Workload("lb", B, L, H, P, N, G, E, k, Q, "bf16", 5)
+    p = synth.make_inputs(w, seed=hash(case) % 100000)
+    d = to_device(p, "bf16")
+    dims = sw.dims_of(d["x"], d["B_experts"], k, Q)
+    h0 = (0.1 * torch.randn((B, H, P, N), device="cuda:0")) if with_h0 else None
+    res = []
+    for short in (False, True):
+        ws = sw.alloc_workspace(dims, "cuda:0")
+        ws.zero_()
+        y = torch.empty_like(d["x"])
+        hf = torch.empty((B, H, P, N), device="cuda:0")
+        sw.swimba_stage_mix(dims, d["B_experts"], d["C_experts"], d["router_logits"], ws)
+        if short:
+            sw.swimba_stage_chunk_state_tiles(dims, d["x"], d["dt"], d["A"], ws)
+            sw.swimba_stage_output_carry(dims, d["x"], d["dt"], d["D"], h0, y, hf, ws)
+        else:
+            sw.swimba_stage_chunk_state(dims, d["x"], d["dt"], d["A"], d["B_experts"], ws)
+            sw.swimba_stage_state_scan(dims, h0, hf, ws)
+            sw.swimba_stage_output(dims, d["x"], d["dt"], d["D"], d["B_experts"], d["C_experts"], y, ws)
+        torch.cuda.synchronize()
+        res.append((y, hf))
+    assert torch.equal(res[0][0], res[1][0])
+    assert torch.equal(res[0][1], res[1][1])
+    assert sw.swimba_prefill_path(dims) in (sw.PATH_STAGED_SHORT, sw.PATH_SINGLE_PASS_HEAD, sw.PATH_SINGLE_PASS)
+
+
+def test_long_sequence_on_the_scan_path_matches_oracle():
+    """More than 8 chunks and too few chains for a single pass: mix, chunk state, scan, output from the forward."""
+    w = synth.Workload("sc", 2, 700, 4, 64, 128, 2, 8, 2, 64, "bf16", 6)
+    p = synth.make_inputs(w, seed=77)
+    d = to_device(p, "bf16")
+    dims = sw.dims_of(d["x"], d["B_experts"], 2, 64)
+    assert sw.swimba_prefill_path(dims) == sw.PATH_STAGED
+    h0 = (0.1 * np.random.default_rng(3).standard_normal((2, 4, 64, 128))).astype(np.float32)
+    out = sw.swimba_mixer_fwd(d["x"], d["dt"], d["A"], d["D"], d["B_experts"], d["C_experts"], d["router_logits"], 2, 64,
+                              torch.from_numpy(h0).to("cuda:0"))
+    torch.cuda.synchronize()
+    ref = orc.mixer_fwd(p["x"], p["dt"], p["A"], p["D"], p["B_experts"], p["C_experts"], p["router_logits"], 2, h0=h0)
+    l2, linf = rel_errors(host(out.y), ref["y"], (0, 2))
+    assert l2 <= TOL["bf16"] and linf <= TOL["bf16"], (l2, linf)
+    l2, linf = rel_errors(host(out.h_final), ref["h_final"], (0, 1))
+    assert l2 <= TOL["bf16"] and linf <= TOL["bf16"], (l2, linf)
