@@ -248,9 +248,11 @@ def main() -> int:
                               sw.PATH_SINGLE_PASS_HEAD: "single_pass_head", sw.PATH_STAGED_SHORT: "staged_short",
                               sw.PATH_SINGLE_PASS_HEAD_CHUNK_MIX: "single_pass_head_chunk_mix"}[self.path]
             self.other = sw.PATH_SINGLE_PASS if self.path in (sw.PATH_STAGED, sw.PATH_STAGED_SHORT) else sw.PATH_STAGED
+            # the chunk-level mix takes few experts only, the short staged path few chunks
+            nchunks = (w.seqlen + w.chunk - 1) // w.chunk
             self.paths = {pth: fns for pth, fns in self.paths.items()
-                          if pth not in (sw.PATH_SINGLE_PASS_CHUNK_MIX, sw.PATH_SINGLE_PASS_HEAD_CHUNK_MIX)
-                          or pth == self.path}   # the chunk-level mix takes few experts only
+                          if pth == self.path or not (pth in (sw.PATH_SINGLE_PASS_CHUNK_MIX, sw.PATH_SINGLE_PASS_HEAD_CHUNK_MIX)
+                                                      or (pth == sw.PATH_STAGED_SHORT and nchunks > 8))}
 
         def step(self, i):
             d, w = self.sets[i % self.nsets], self.w
