@@ -81,6 +81,13 @@ def work_model(w):
                    "irreducible": T * (2 * H * P * 2 + H * 2), "flops": 2.0 * T * Q * P * H + 2.0 * T * N * P * H},
     }
     kernels["pass64"] = kernels["pass"]
+    # split pass: the chunk states in front of the segment boundaries (at most all chunks but those of the last
+    # segment, two segments assumed here; in fact only those whose decay up to the boundary is not exactly
+    # zero in fp32, which depends on dt and A: an upper bound) and the boundary states.  Nothing of it is
+    # irreducible: x and dt are read a second time.
+    kernels["boundary_states"] = {"moved": 0.5 * (T * (H * P * 2 + H * 2 + G * N * 2) + state_elems * 4)
+                                           + 2 * w.batch * H * P * N * 4,
+                                  "irreducible": 0.0, "flops": 0.5 * 2.0 * T * N * P * H}
     # short sequences: the tiles ride in the chunk-state launch, the output kernel reads the chunk states before
     # its chunk ((nc - 1) / 2 of them on average) instead of one carried state
     nc = (w.seqlen + Q - 1) // Q
@@ -225,6 +232,23 @@ def main() -> int:
                     "tables": lambda d: sw.swimba_stage_tables(dims, d["dt"], d["A"], d["ws"]),
                     "pass64": lambda d: sw.swimba_stage_pass64(dims, d["x"], d["dt"], d["D"], None, d["y"], d["h_final"], d["ws"]),
                 },
+                sw.PATH_SINGLE_PASS_HEAD_SPLIT: {
+                    "mix": mix,
+                    "prep": lambda d: sw.swimba_stage_prep(dims, d["dt"], d["A"], d["ws"]),
+                    "boundary_states": lambda d: sw.swimba_stage_boundary_states(dims, d["x"], d["dt"], d["A"], None,
+                                                                                 self.nseg, d["ws"]),
+                    "pass64": lambda d: sw.swimba_stage_pass64_split(dims, d["x"], d["dt"], d["D"], None, d["y"],
+                                                                     d["h_final"], self.nseg, d["ws"]),
+                },
+                sw.PATH_SINGLE_PASS_HEAD_SPLIT_CHUNK_MIX: {
+                    "mix_chunk": lambda d: sw.swimba_stage_mix_chunk(dims, d["B_experts"], d["C_experts"],
+                                                                     d["router_logits"], d["ws"]),
+                    "tables": lambda d: sw.swimba_stage_tables(dims, d["dt"], d["A"], d["ws"]),
+                    "boundary_states": lambda d: sw.swimba_stage_boundary_states(dims, d["x"], d["dt"], d["A"], None,
+                                                                                 self.nseg, d["ws"]),
+                    "pass64": lambda d: sw.swimba_stage_pass64_split(dims, d["x"], d["dt"], d["D"], None, d["y"],
+                                                                     d["h_final"], self.nseg, d["ws"]),
+                },
                 sw.PATH_STAGED_SHORT: {
                     "mix": mix,
                     "chunk_state_tiles": lambda d: sw.swimba_stage_chunk_state_tiles(dims, d["x"], d["dt"], d["A"], d["ws"]),
@@ -243,15 +267,20 @@ def main() -> int:
             self.extra = {"pass64": lambda d: sw.swimba_stage_pass64(dims, d["x"], d["dt"], d["D"], None, d["y"],
                                                                      d["h_final"], d["ws"])}
             self.path = sw.swimba_prefill_path(dims)
+            self.nseg = sw.swimba_pass_segments(dims)
             self.path_name = {sw.PATH_SINGLE_PASS: "single_pass", sw.PATH_STAGED: "staged",
                               sw.PATH_SINGLE_PASS_CHUNK_MIX: "single_pass_chunk_mix",
                               sw.PATH_SINGLE_PASS_HEAD: "single_pass_head", sw.PATH_STAGED_SHORT: "staged_short",
-                              sw.PATH_SINGLE_PASS_HEAD_CHUNK_MIX: "single_pass_head_chunk_mix"}[self.path]
+                              sw.PATH_SINGLE_PASS_HEAD_CHUNK_MIX: "single_pass_head_chunk_mix",
+                              sw.PATH_SINGLE_PASS_HEAD_SPLIT: "single_pass_head_split",
+                              sw.PATH_SINGLE_PASS_HEAD_SPLIT_CHUNK_MIX: "single_pass_head_split_chunk_mix"}[self.path]
             self.other = sw.PATH_SINGLE_PASS if self.path in (sw.PATH_STAGED, sw.PATH_STAGED_SHORT) else sw.PATH_STAGED
             # the chunk-level mix takes few experts only, the short staged path few chunks
             nchunks = (w.seqlen + w.chunk - 1) // w.chunk
             self.paths = {pth: fns for pth, fns in self.paths.items()
-                          if pth == self.path or not (pth in (sw.PATH_SINGLE_PASS_CHUNK_MIX, sw.PATH_SINGLE_PASS_HEAD_CHUNK_MIX)
+                          if pth == self.path or not (pth in (sw.PATH_SINGLE_PASS_CHUNK_MIX, sw.PATH_SINGLE_PASS_HEAD_CHUNK_MIX,
+                                                              sw.PATH_SINGLE_PASS_HEAD_SPLIT,
+                                                              sw.PATH_SINGLE_PASS_HEAD_SPLIT_CHUNK_MIX)
                                                       or (pth == sw.PATH_STAGED_SHORT and nchunks > 8))}
 
         def step(self, i):

@@ -94,6 +94,8 @@ typedef struct {
     size_t fdec;      /* (B,nc,H,Q) fp32 : dt_j exp(R_J - cs_j), R_J = cs at the end of j's
                          32-token tile; table of the single-pass kernel                  */
     size_t cdec;      /* (B,nc,H,Q) fp32 : dt_j exp(cs_last - cs_j); table of the single-pass kernel */
+    size_t hmid;      /* (B,3,H,P,N) fp32 : states at the segment boundaries of the split single pass
+                         (nseg - 1 of the 3 are used, densely: (B,nseg-1,H,P,N)) */
     size_t total;
 } swimba_ws_layout;
 
@@ -203,7 +205,11 @@ swimba_status swimba_stage_pass(const swimba_dims *dims, const void *x, const vo
  * chunks) or SWIMBA_PATH_SINGLE_PASS (mix, prep, pass: a workgroup per (batch, head, 32
  * channels), taken when those slices number between 3/4 of and all of the compute units and
  * the sequence has at least 16 chunks), each also with the chunk-level mix kernel in front
- * (..._CHUNK_MIX, see below).  The results of the MFMA paths agree to the rounding of their
+ * (..._CHUNK_MIX, see below).  SWIMBA_PATH_SINGLE_PASS_HEAD_SPLIT is the per-head pass on sequences
+ * cut into 2, 3 or 4 equal segments of whole chunks, each a chain of its own (see
+ * swimba_stage_boundary_states): taken ahead of the 32-channel slices where batch * heads alone
+ * leaves the rounds too empty but that many times as many chains fill them, the sequence is a whole
+ * number of chunks and every segment has at least 12.  The results of the MFMA paths agree to the rounding of their
  * bf16 operands.  Returns minus the swimba_status for invalid dims.  Host only; launches
  * nothing. */
 #define SWIMBA_PATH_GENERIC 0
@@ -213,7 +219,12 @@ swimba_status swimba_stage_pass(const swimba_dims *dims, const void *x, const vo
 #define SWIMBA_PATH_SINGLE_PASS_HEAD 4            /* mix, prep, pass64: one workgroup per (batch, head) */
 #define SWIMBA_PATH_SINGLE_PASS_HEAD_CHUNK_MIX 5  /* mix_chunk, tables, pass64 */
 #define SWIMBA_PATH_STAGED_SHORT 6                /* mix, chunk_state_tiles, output_carry: at most 8 chunks */
+#define SWIMBA_PATH_SINGLE_PASS_HEAD_SPLIT 7      /* mix, prep, boundary_states, pass64 on segments */
+#define SWIMBA_PATH_SINGLE_PASS_HEAD_SPLIT_CHUNK_MIX 8   /* mix_chunk, tables, boundary_states, pass64 on segments */
 int swimba_prefill_path(const swimba_dims *dims);
+/* Segments per sequence of the per-head single pass the forward takes for these dims on the current
+ * device (1: whole sequences, also on every other path).  Minus the swimba_status for invalid dims. */
+int swimba_pass_segments(const swimba_dims *dims);
 
 /* Single pass with the router, the mixing and the tiles of Bmix.Cmix^T done per whole chunk in one
  * persistent kernel (SWIMBA_PATH_SINGLE_PASS_CHUNK_MIX: mix_chunk, tables, pass).  Taken by the forward
@@ -245,6 +256,26 @@ swimba_status swimba_stage_output_carry(const swimba_dims *dims, const void *x, 
 swimba_status swimba_stage_pass64(const swimba_dims *dims, const void *x, const void *dt, const float *D,
                                   const float *h0, void *y, float *h_final, void *workspace,
                                   size_t workspace_bytes, void *hip_stream);
+/* Split per-head pass (SWIMBA_PATH_SINGLE_PASS_HEAD_SPLIT): every sequence as nseg (2..4) equal segments
+ * of whole chunks (seqlen = nseg * m * chunk, else SWIMBA_ERR_UNSUPPORTED), each walked by a workgroup
+ * of its own.  The recurrence of S3.2 is linear in the state, so the state at a segment boundary is
+ * sum_c (prod_{c' > c} a_c') S_c over the chunks c in front of it, with S_c the chunk state and a_c =
+ * exp(sum of dt*A over chunk c), plus the decayed h0.
+ *   boundary_states : x, dt, A, h0, ws.bmix_t8, ws.cs2 -> ws.states_lp (chunk states, bf16, of the
+ *                     chunks in front of the last boundary whose factor up to the boundary behind them
+ *                     is not exactly zero in fp32; the others are neither computed nor read), then
+ *                     ws.hmid (B,nseg-1,H,P,N) fp32.  Two launches.  Needs mix (or mix_chunk) and prep
+ *                     (or tables) before it.
+ *   pass64_split    : pass64 with batch * nseg * heads workgroups; segment 0 starts from h0, the
+ *                     others from ws.hmid; the last segment writes h_final.
+ * Both take nseg = 1..4 (boundary_states: 2..4).  Results agree with pass64 to the rounding of the
+ * bf16 chunk states (the same rounding the staged path has). */
+swimba_status swimba_stage_boundary_states(const swimba_dims *dims, const void *x, const void *dt, const float *A,
+                                           const float *h0, int32_t nseg, void *workspace, size_t workspace_bytes,
+                                           void *hip_stream);
+swimba_status swimba_stage_pass64_split(const swimba_dims *dims, const void *x, const void *dt, const float *D,
+                                        const float *h0, void *y, float *h_final, int32_t nseg, void *workspace,
+                                        size_t workspace_bytes, void *hip_stream);
 swimba_status swimba_stage_router(const swimba_dims *dims, const void *router_logits,
                                   void *workspace, size_t workspace_bytes, void *hip_stream);
 swimba_status swimba_stage_cumsum(const swimba_dims *dims, const void *dt, const float *A,

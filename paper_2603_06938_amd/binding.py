@@ -39,7 +39,7 @@ class swimba_dims(ctypes.Structure):
 
 class swimba_ws_layout(ctypes.Structure):
     _fields_ = [(n, ctypes.c_size_t) for n in
-                ("topk_idx", "topk_w", "cs", "states", "states_lp", "cmix", "bmix_t8", "bmix_frag", "cb", "cs2", "fdec", "cdec", "total")]
+                ("topk_idx", "topk_w", "cs", "states", "states_lp", "cmix", "bmix_t8", "bmix_frag", "cb", "cs2", "fdec", "cdec", "hmid", "total")]
 
 
 def _load():
@@ -88,6 +88,12 @@ def _load():
         lib.swimba_stage_output_carry.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
         lib.swimba_stage_pass64.restype = i32
         lib.swimba_stage_pass64.argtypes = [dp, vp, vp, vp, vp, vp, vp, vp, sz, vp]
+        lib.swimba_pass_segments.restype = ctypes.c_int
+        lib.swimba_pass_segments.argtypes = [dp]
+        lib.swimba_stage_boundary_states.restype = i32
+        lib.swimba_stage_boundary_states.argtypes = [dp, vp, vp, vp, vp, i32, vp, sz, vp]
+        lib.swimba_stage_pass64_split.restype = i32
+        lib.swimba_stage_pass64_split.argtypes = [dp, vp, vp, vp, vp, vp, vp, i32, vp, sz, vp]
         lib.swimba_separated_workspace_bytes.restype = sz
         lib.swimba_separated_workspace_bytes.argtypes = [dp]
         lib.swimba_separated_fwd.restype = i32
@@ -630,6 +636,7 @@ def swimba_stage_output(dims, x, dt, D, B_experts, C_experts, y, workspace):
 
 PATH_GENERIC, PATH_STAGED, PATH_SINGLE_PASS, PATH_SINGLE_PASS_CHUNK_MIX, PATH_SINGLE_PASS_HEAD = 0, 1, 2, 3, 4
 PATH_SINGLE_PASS_HEAD_CHUNK_MIX, PATH_STAGED_SHORT = 5, 6
+PATH_SINGLE_PASS_HEAD_SPLIT, PATH_SINGLE_PASS_HEAD_SPLIT_CHUNK_MIX = 7, 8
 
 
 def swimba_prefill_path(dims) -> int:
@@ -688,6 +695,30 @@ def swimba_stage_pass64(dims, x, dt, D, h0, y, h_final, workspace):
                                        _ptr(h_final, "h_final", torch.float32),
                                        _ptr(workspace, "workspace", torch.uint8), workspace.numel(), _stream()),
            "swimba_stage_pass64")
+
+
+def swimba_pass_segments(dims) -> int:
+    """Segments per sequence of the per-head single pass the forward takes for these dims (1: none)."""
+    r = _load().swimba_pass_segments(ctypes.byref(dims))
+    if r < 0:
+        _check(-r, "swimba_pass_segments")
+    return r
+
+
+def swimba_stage_boundary_states(dims, x, dt, A, h0, nseg, workspace):
+    _check(_load().swimba_stage_boundary_states(ctypes.byref(dims), _ptr(x, "x"), _ptr(dt, "dt"),
+                                                _ptr(A, "A", torch.float32), _ptr(h0, "h0", torch.float32), int(nseg),
+                                                _ptr(workspace, "workspace", torch.uint8), workspace.numel(),
+                                                _stream()),
+           "swimba_stage_boundary_states")
+
+
+def swimba_stage_pass64_split(dims, x, dt, D, h0, y, h_final, nseg, workspace):
+    _check(_load().swimba_stage_pass64_split(ctypes.byref(dims), _ptr(x, "x"), _ptr(dt, "dt"),
+                                             _ptr(D, "D", torch.float32), _ptr(h0, "h0", torch.float32), _ptr(y, "y"),
+                                             _ptr(h_final, "h_final", torch.float32), int(nseg),
+                                             _ptr(workspace, "workspace", torch.uint8), workspace.numel(), _stream()),
+           "swimba_stage_pass64_split")
 
 
 def workspace_views(dims: swimba_dims, workspace: torch.Tensor):

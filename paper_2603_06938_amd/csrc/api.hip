@@ -92,6 +92,8 @@ static void layout_of(const swimba_dims *d, swimba_ws_layout *o)
     if (mf) off = align_up(off + (size_t)s.B * s.nc * s.H * s.Q * sizeof(float), 256);
     o->cdec = off;
     if (mf) off = align_up(off + (size_t)s.B * s.nc * s.H * s.Q * sizeof(float), 256);
+    o->hmid = off;
+    if (mf) off = align_up(off + (size_t)s.B * (PASS_SPLIT_MAX_SEGMENTS - 1) * s.H * s.P * s.N * sizeof(float), 256);
     o->total = off > 0 ? off : 256;
 }
 
@@ -123,11 +125,31 @@ static int device_cus()
 //   B8 L4096 H32 184/204/151   B16 L4096 H32 397/388/296   B8 L4096 H48 288/264/244   B4 L8192 H48 291/305/244
 //   B8 L4096 H24 144/177/131   B8 L3072 H24 111/134/106    B8 L2048 H24  82/103/ 83   B8 L4096 H16 107/105/126
 //   B2 L16384 H64 551/494/561  B4 L8192 H64 539/502/378    B1 L32768 H128 888/792/946
+//   head64, split: where B*H leaves the rounds too empty for head64 but 2, 3 or 4 times as many chains
+//            fill them, every sequence is cut into that many equal segments of whole chunks (at least 12
+//            each), each a chain of its own: the state at a segment boundary comes from the chunk states
+//            in front of it, of which only those whose decay up to the boundary is not exactly zero are
+//            computed (launch_boundary_states_mfma).  Ahead of slices32: per channel the head64 kernel is
+//            the cheaper one.
 enum PassKind { PASS_STAGED = 0, PASS_SLICES32 = 1, PASS_HEAD64 = 2 };
 static bool fills_rounds(int64_t chains, int ncu)
 {
     const int64_t rounds = (chains + ncu - 1) / ncu;
     return chains > 0 && 4 * chains >= 3 * rounds * ncu;
+}
+// segments per sequence of the head64 pass (1: whole sequences; 0: head64 does not take the shape)
+static int head64_segments(const swimba_dims *d)
+{
+    const int ncu = device_cus();
+    if (ncu == 0 || !use_mfma_path(d) || d->headdim <= 32) return 0;
+    const int64_t heads = (int64_t)d->batch * d->nheads;
+    const int64_t nc = ((int64_t)d->seqlen + d->chunk - 1) / d->chunk;
+    if (nc >= 12 && fills_rounds(heads, ncu)) return 1;
+    if (nc * d->chunk != d->seqlen) return 0;
+    for (int nseg = 2; nseg <= PASS_SPLIT_MAX_SEGMENTS; ++nseg)
+        if (nc % nseg == 0 && nc / nseg >= 12 && nc / nseg <= PASS_SPLIT_MAX_CHUNKS && fills_rounds(heads * nseg, ncu))
+            return nseg;
+    return 0;
 }
 static PassKind pass_kind(const swimba_dims *d)
 {
@@ -135,7 +157,7 @@ static PassKind pass_kind(const swimba_dims *d)
     if (ncu == 0 || !use_mfma_path(d)) return PASS_STAGED;
     const int64_t heads = (int64_t)d->batch * d->nheads;
     const int64_t nc = ((int64_t)d->seqlen + d->chunk - 1) / d->chunk;
-    if (d->headdim > 32 && nc >= 12 && fills_rounds(heads, ncu)) return PASS_HEAD64;
+    if (head64_segments(d) >= 1) return PASS_HEAD64;
     const int64_t slices = heads * ((d->headdim + 31) / 32);
     if (nc >= 16 && slices <= ncu && fills_rounds(slices, ncu)) return PASS_SLICES32;
     return PASS_STAGED;
@@ -158,7 +180,7 @@ struct Ws {
     float *cs;
     float *states;
     void *states_lp, *cmix, *bmix_t8, *bmix_frag, *cb;
-    float *cs2, *fdec, *cdec;
+    float *cs2, *fdec, *cdec, *hmid;
 };
 
 static swimba_status carve(const swimba_dims *d, void *workspace, size_t bytes, Ws *ws)
@@ -182,6 +204,7 @@ static swimba_status carve(const swimba_dims *d, void *workspace, size_t bytes, 
     ws->cs2 = mf ? (float *)(p + lo.cs2) : nullptr;
     ws->fdec = mf ? (float *)(p + lo.fdec) : nullptr;
     ws->cdec = mf ? (float *)(p + lo.cdec) : nullptr;
+    ws->hmid = mf ? (float *)(p + lo.hmid) : nullptr;
     return SWIMBA_OK;
 }
 
@@ -342,7 +365,16 @@ int swimba_prefill_path(const swimba_dims *dims)
     }
     const bool cm = use_chunk_mix(dims, false);
     if (pk == PASS_SLICES32) return cm ? SWIMBA_PATH_SINGLE_PASS_CHUNK_MIX : SWIMBA_PATH_SINGLE_PASS;
+    if (head64_segments(dims) > 1)
+        return cm ? SWIMBA_PATH_SINGLE_PASS_HEAD_SPLIT_CHUNK_MIX : SWIMBA_PATH_SINGLE_PASS_HEAD_SPLIT;
     return cm ? SWIMBA_PATH_SINGLE_PASS_HEAD_CHUNK_MIX : SWIMBA_PATH_SINGLE_PASS_HEAD;
+}
+
+int swimba_pass_segments(const swimba_dims *dims)
+{
+    swimba_status st = check_mixer(dims);
+    if (st != SWIMBA_OK) return -(int)st;
+    return pass_kind(dims) == PASS_HEAD64 ? head64_segments(dims) : 1;
 }
 
 swimba_status swimba_stage_mix_chunk(const swimba_dims *dims, const void *B_experts, const void *C_experts,
@@ -452,6 +484,36 @@ swimba_status swimba_stage_pass64(const swimba_dims *dims, const void *x, const 
                               h_final, y, (hipStream_t)hip_stream);
 }
 
+swimba_status swimba_stage_boundary_states(const swimba_dims *dims, const void *x, const void *dt, const float *A,
+                                           const float *h0, int32_t nseg, void *workspace, size_t workspace_bytes,
+                                           void *hip_stream)
+{
+    Ws ws;
+    swimba_status st = carve(dims, workspace, workspace_bytes, &ws);
+    if (st != SWIMBA_OK) return st;
+    if (!use_mfma_path(dims)) return SWIMBA_ERR_UNSUPPORTED;
+    if ((int64_t)dims->batch * dims->seqlen == 0) return SWIMBA_OK;
+    if (!x || !dt || !A) return SWIMBA_ERR_NULL;
+    if (check_align(dims->io_dtype, {x, h0}, {dt}, {A}) != SWIMBA_OK) return SWIMBA_ERR_ALIGNMENT;
+    return launch_boundary_states_mfma(make_shape(dims), nseg, x, dt, A, ws.bmix_t8, ws.cs2, ws.states_lp, h0, ws.hmid,
+                                       (hipStream_t)hip_stream);
+}
+
+swimba_status swimba_stage_pass64_split(const swimba_dims *dims, const void *x, const void *dt, const float *D,
+                                        const float *h0, void *y, float *h_final, int32_t nseg, void *workspace,
+                                        size_t workspace_bytes, void *hip_stream)
+{
+    Ws ws;
+    swimba_status st = carve(dims, workspace, workspace_bytes, &ws);
+    if (st != SWIMBA_OK) return st;
+    if (!use_mfma_path(dims)) return SWIMBA_ERR_UNSUPPORTED;
+    if ((int64_t)dims->batch * dims->seqlen == 0) return SWIMBA_OK;
+    if (!x || !dt || !y) return SWIMBA_ERR_NULL;
+    if (check_align(dims->io_dtype, {x, y, h0, h_final}, {dt}, {D}) != SWIMBA_OK) return SWIMBA_ERR_ALIGNMENT;
+    return launch_pass64_mfma(make_shape(dims), x, dt, D, ws.cmix, ws.bmix_t8, ws.cb, ws.cs2, ws.fdec, ws.cdec, h0,
+                              h_final, y, (hipStream_t)hip_stream, nseg, ws.hmid);
+}
+
 swimba_status swimba_mixer_fwd(const swimba_dims *dims, const void *x, const void *dt,
                                const float *A, const float *D, const void *B_experts,
                                const void *C_experts, const void *router_logits, const float *h0,
@@ -501,8 +563,17 @@ swimba_status swimba_mixer_fwd(const swimba_dims *dims, const void *x, const voi
             // (batch, head, 32 channels) or per (batch, head) with the state in registers
             st = launch_prep_mfma(s, dt, A, ws.cmix, ws.bmix_frag, ws.cb, ws.cs2, ws.fdec, ws.cdec, stream, !chunk_mix);
             if (st != SWIMBA_OK) return st;
-            return (slices ? launch_pass_mfma : launch_pass64_mfma)(s, x, dt, D, ws.cmix, ws.bmix_t8, ws.cb, ws.cs2,
-                                                                    ws.fdec, ws.cdec, h0, h_final, y, stream);
+            if (slices)
+                return launch_pass_mfma(s, x, dt, D, ws.cmix, ws.bmix_t8, ws.cb, ws.cs2, ws.fdec, ws.cdec, h0, h_final,
+                                        y, stream);
+            const int nseg = head64_segments(dims);
+            if (nseg > 1) {
+                st = launch_boundary_states_mfma(s, nseg, x, dt, A, ws.bmix_t8, ws.cs2, ws.states_lp, h0, ws.hmid,
+                                                 stream);
+                if (st != SWIMBA_OK) return st;
+            }
+            return launch_pass64_mfma(s, x, dt, D, ws.cmix, ws.bmix_t8, ws.cb, ws.cs2, ws.fdec, ws.cdec, h0, h_final, y,
+                                      stream, nseg, ws.hmid);
         }
         if (mf && s.nc <= OUTPUT_LOOKBACK_MAX_CHUNKS) {
             // short sequences: no scan launch; the G^T tiles ride in the chunk-state launch and every
@@ -971,8 +1042,17 @@ static swimba_status mixer_selected_core(const swimba_dims *dims, const void *x,
                 st = launch_prep_mfma(s, dt, A, ws.cmix, ws.bmix_frag, ws.cb, ws.cs2, ws.fdec, ws.cdec, stream,
                                       !chunk_mix);
                 if (st != SWIMBA_OK) return st;
-                return (slices ? launch_pass_mfma : launch_pass64_mfma)(s, x, dt, D, ws.cmix, ws.bmix_t8, ws.cb, ws.cs2,
-                                                                        ws.fdec, ws.cdec, h0, h_final, y, stream);
+                if (slices)
+                    return launch_pass_mfma(s, x, dt, D, ws.cmix, ws.bmix_t8, ws.cb, ws.cs2, ws.fdec, ws.cdec, h0,
+                                            h_final, y, stream);
+                const int nseg = head64_segments(dims);
+                if (nseg > 1) {
+                    st = launch_boundary_states_mfma(s, nseg, x, dt, A, ws.bmix_t8, ws.cs2, ws.states_lp, h0, ws.hmid,
+                                                     stream);
+                    if (st != SWIMBA_OK) return st;
+                }
+                return launch_pass64_mfma(s, x, dt, D, ws.cmix, ws.bmix_t8, ws.cb, ws.cs2, ws.fdec, ws.cdec, h0,
+                                          h_final, y, stream, nseg, ws.hmid);
             }
             if (s.nc <= OUTPUT_LOOKBACK_MAX_CHUNKS) {
                 st = launch_chunk_state_mfma(s, x, dt, A, ws.bmix_t8, ws.cs, ws.states_lp, stream, 1, ws.cmix,

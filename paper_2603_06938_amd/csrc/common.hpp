@@ -103,7 +103,7 @@ swimba_status launch_sep_accumulate(int io_dtype, int64_t n, const void *y_e, fl
 swimba_status launch_chunk_state_mfma(const Shape &s, const void *x, const void *dt, const float *A,
                                       const void *bmix_t8, float *cs, void *states_lp, hipStream_t st,
                                       int nslots = 1, const void *cmix = nullptr, const void *bfrag = nullptr,
-                                      void *cb = nullptr);
+                                      void *cb = nullptr, int nseg = 1, const float *cs2 = nullptr);
 swimba_status launch_scan_cb_mfma(const Shape &s, const float *h0, float *h_final, void *states_lp,
                                   const float *cs, const void *cmix, const void *bfrag, void *cb,
                                   hipStream_t st, int nslots = 1);
@@ -125,7 +125,18 @@ swimba_status launch_output_mfma(const Shape &s, const void *x, const void *dt, 
 // single pass with all 64 channels of a head per workgroup (fused_pass64.hip); same arguments as launch_pass_mfma
 swimba_status launch_pass64_mfma(const Shape &s, const void *x, const void *dt, const float *D, const void *cmix,
                                  const void *bt8, const void *cb, const float *cs2, const float *fdec,
-                                 const float *cdec, const float *h0, float *h_final, void *y, hipStream_t st);
+                                 const float *cdec, const float *h0, float *h_final, void *y, hipStream_t st,
+                                 int nseg = 1, const float *hmid = nullptr);
+// split pass: the sequences as nseg equal segments of whole chunks, each a chain of its own; the states at
+// the nseg - 1 boundaries (hmid, (B, nseg-1, H, P, N) fp32) come from this launch pair in front of the pass
+constexpr int PASS_SPLIT_MAX_SEGMENTS = 4;
+constexpr int PASS_SPLIT_MAX_CHUNKS = 1024;      // chunks per segment (the boundary kernel keeps their totals in LDS)
+// A chunk state counts at the boundary behind it when the sum of the chunk totals in between (log2 units)
+// is at least this: below it the factor is under 2^-150 and rounds to zero in fp32.
+constexpr float SPLIT_KEEP_LOG2 = -150.f;
+swimba_status launch_boundary_states_mfma(const Shape &s, int nseg, const void *x, const void *dt, const float *A,
+                                          const void *bt8, const float *cs2, void *states_lp, const float *h0,
+                                          float *hmid, hipStream_t st);
 // router + mixing + G^T tiles of whole chunks in one persistent kernel (mix_chunk.hip)
 bool mix_chunk_covers(const Shape &s, bool selected);
 swimba_status launch_mix_chunk_mfma(const Shape &s, const void *Be, const void *Ce, const void *logits, int32_t *idx,

@@ -575,12 +575,20 @@ pass_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ dt, con
                     unpack8(m + 8, cbt[q % CBS][1]);
                     const float *cj = s_cs + J * 32 + 4 * kg;
                     const float *dj = s_dt + J * 32 + 4 * kg;
+                    // All eight table rows are requested before the first is used (one LDS round trip
+                    // instead of four); left alone, the compiler sinks each read under the lane mask
+                    // of the select that consumes it and waits for every one in turn.
+                    float4 c4[4], d4[4];
 #pragma unroll
                     for (int a = 0; a < 4; ++a) {
-                        const float4 c4 = *reinterpret_cast<const float4 *>(cj + 8 * a);
-                        const float4 d4 = *reinterpret_cast<const float4 *>(dj + 8 * a);
-                        const float cc[4] = {c4.x, c4.y, c4.z, c4.w};
-                        const float dd[4] = {d4.x, d4.y, d4.z, d4.w};
+                        c4[a] = *reinterpret_cast<const float4 *>(cj + 8 * a);
+                        d4[a] = *reinterpret_cast<const float4 *>(dj + 8 * a);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                    for (int a = 0; a < 4; ++a) {
+                        const float cc[4] = {c4[a].x, c4[a].y, c4[a].z, c4[a].w};
+                        const float dd[4] = {d4[a].x, d4[a].y, d4[a].z, d4[a].w};
 #pragma unroll
                         for (int bb = 0; bb < 4; ++bb) {
                             const int jl = 8 * a + 4 * kg + bb;

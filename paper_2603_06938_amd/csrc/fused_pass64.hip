@@ -47,7 +47,8 @@ pass64_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ dt, c
               const uint16_t *__restrict__ cmix, const uint16_t *__restrict__ bt8,
               const uint16_t *__restrict__ cb, const float *__restrict__ cs2, const float *__restrict__ fdec,
               const float *__restrict__ cdec, const float *__restrict__ h0, float *__restrict__ h_final,
-              uint16_t *__restrict__ y, Shape s, int total, int nblocks)
+              uint16_t *__restrict__ y, Shape s, int total, int nblocks, int nseg,
+              const float *__restrict__ hmid)
 {
     using Lds = Pass64Lds<Q>;
     constexpr int NT = Q / 32;                   // 32-token tiles per chunk
@@ -73,6 +74,17 @@ pass64_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ dt, c
     const int h = lid % s.H;
     const int b = lid / s.H;
     const int g = (h * s.G) / s.H;
+    // With nseg > 1 the shape is that of the segments: "batch" b is segment b % nseg of sequence
+    // b / nseg (equal segments of whole chunks, so every token and chunk index is the same number in
+    // both views).  A segment behind the first starts from the state at its boundary, which a launch
+    // in front of this one has left in hmid (B, nseg - 1, H, P, N); only the last one ends in h_final.
+    {
+        const int seq = b / nseg, seg = b - seq * nseg;
+        const int64_t hpn = (int64_t)s.P * s.N;
+        if (seg > 0) h0 = hmid + (((int64_t)seq * (nseg - 1) + seg - 1) * s.H + h) * hpn;
+        else if (h0) h0 += ((int64_t)seq * s.H + h) * hpn;
+        h_final = (h_final && seg == nseg - 1) ? h_final + ((int64_t)seq * s.H + h) * hpn : nullptr;
+    }
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int l32 = lane & 31, kg = lane >> 5;
@@ -167,7 +179,7 @@ pass64_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ dt, c
                 const int n0 = 32 * sw + 8 * a + 4 * kg;
                 float4 v = make_float4(0.f, 0.f, 0.f, 0.f);
                 if (h0 && p < s.P && n0 < s.N)
-                    v = *reinterpret_cast<const float4 *>(h0 + (((int64_t)b * s.H + h) * s.P + p) * s.N + n0);
+                    v = *reinterpret_cast<const float4 *>(h0 + (int64_t)p * s.N + n0);
                 st[hf][4 * a + 0] = v.x; st[hf][4 * a + 1] = v.y; st[hf][4 * a + 2] = v.z; st[hf][4 * a + 3] = v.w;
             }
         }
@@ -257,7 +269,7 @@ pass64_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ dt, c
                 for (int a = 0; a < 4; ++a) {
                     const int n0 = 32 * sw + 8 * a + 4 * kg;
                     if (p < s.P && n0 < s.N)
-                        *reinterpret_cast<float4 *>(h_final + (((int64_t)b * s.H + h) * s.P + p) * s.N + n0) =
+                        *reinterpret_cast<float4 *>(h_final + (int64_t)p * s.N + n0) =
                             make_float4(st[hf][4 * a + 0], st[hf][4 * a + 1], st[hf][4 * a + 2], st[hf][4 * a + 3]);
                 }
             }
@@ -307,7 +319,7 @@ pass64_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ dt, c
     // Operand loads run ahead of their use in register slots rotated by name: the mixed C rows of
     // the next tile are requested as soon as those in hand have gone into their contractions, a
     // G^T tile CBS steps ahead of its step, across the chunk boundary.
-    constexpr int CBS = NQ < 5 ? NQ : 5;          // register slots of G^T tiles
+    constexpr int CBS = NQ < 3 ? NQ : 3;          // register slots of G^T tiles (three steps cover the L2 latency)
     constexpr int NQP = (NQ + CBS - 1) / CBS * CBS;   // steps per chunk padded to a multiple of CBS
     uint4 cfrag[8];           // mixed C rows of one output tile at a time
     uint4 cbt[CBS][2];
@@ -349,6 +361,17 @@ pass64_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ dt, c
             f32x16_t yt[TPW][2];
             float csi[TPW];
             const uint16_t *sHr = sH + prowx * HSTR + 64 * kg;
+            // The decay table rows and the pivot of an off-diagonal step are read one step ahead of
+            // it (those of step 0 here, behind the readout's contractions).
+            float4 fpre[4];
+            float rpre;
+#define SWIMBA_P64_LOAD_F(J_)                                                                              \
+    {                                                                                                      \
+        const float *fj_ = s_f + (J_) * 32 + 4 * kg;                                                       \
+        _Pragma("unroll") for (int a = 0; a < 4; ++a) fpre[a] = *reinterpret_cast<const float4 *>(fj_ + 8 * a); \
+        rpre = s_cs[(J_) * 32 + 31];                                                                       \
+    }
+            SWIMBA_P64_LOAD_F(0);
             // ---- Y^T = exp(cs_i) H_c . Cmix^T for the first tile; the second tile's mixed C rows
             // ---- take the buffer's place and its readout follows half-way through the steps ----
             {
@@ -401,11 +424,10 @@ pass64_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ dt, c
                     unpack8(m + 8, cbt[q % CBS][1]);
                     if (J < I) {
                         // dt_j exp(R_J - cs_j) from the table, exp(cs_i - R_J) once per lane
-                        const float *fj = s_f + J * 32 + 4 * kg;
-                        const float ei = fast_exp2(ci - s_cs[J * 32 + 31]);
+                        const float ei = fast_exp2(ci - rpre);
 #pragma unroll
                         for (int a = 0; a < 4; ++a) {
-                            const float4 f4 = *reinterpret_cast<const float4 *>(fj + 8 * a);
+                            const float4 f4 = fpre[a];
                             m[4 * a + 0] *= ei * f4.x;
                             m[4 * a + 1] *= ei * f4.y;
                             m[4 * a + 2] *= ei * f4.z;
@@ -415,12 +437,19 @@ pass64_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ dt, c
                         // diagonal tile: direct masked form
                         const float *cj = s_cs + J * 32 + 4 * kg;
                         const float *dj = s_dt + J * 32 + 4 * kg;
+                        // all eight table rows are requested before the first is used: one LDS round
+                        // trip instead of four, and no read sunk under the lane mask of its select
+                        float4 c4[4], d4[4];
 #pragma unroll
                         for (int a = 0; a < 4; ++a) {
-                            const float4 c4 = *reinterpret_cast<const float4 *>(cj + 8 * a);
-                            const float4 d4 = *reinterpret_cast<const float4 *>(dj + 8 * a);
-                            const float cc[4] = {c4.x, c4.y, c4.z, c4.w};
-                            const float dd[4] = {d4.x, d4.y, d4.z, d4.w};
+                            c4[a] = *reinterpret_cast<const float4 *>(cj + 8 * a);
+                            d4[a] = *reinterpret_cast<const float4 *>(dj + 8 * a);
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                        for (int a = 0; a < 4; ++a) {
+                            const float cc[4] = {c4[a].x, c4[a].y, c4[a].z, c4[a].w};
+                            const float dd[4] = {d4[a].x, d4[a].y, d4[a].z, d4[a].w};
 #pragma unroll
                             for (int bb = 0; bb < 4; ++bb) {
                                 const int jl = 8 * a + 4 * kg + bb;
@@ -429,6 +458,10 @@ pass64_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ dt, c
                                 m[4 * a + bb] *= fast_exp2(arg) * dd[bb];
                             }
                         }
+                    }
+                    if (q + 1 < NQ) {
+                        const int Jn = (TPW == 1 || q + 1 <= wave) ? q + 1 : q - wave;
+                        SWIMBA_P64_LOAD_F(Jn);
                     }
                     const uint4 m0 = pack8(m), m1 = pack8(m + 8);
                     const uint4 x00 = *reinterpret_cast<const uint4 *>(sXr + J * 32);
@@ -516,13 +549,123 @@ pass64_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ dt, c
     }
     lds_barrier();              // pairs with the stage waves' last barrier
 #undef SWIMBA_P64_LOAD_C
+#undef SWIMBA_P64_LOAD_F
 #undef SWIMBA_P64_LOAD_CB
+}
+
+// =========================================================================================
+// States at the segment boundaries of a split pass.  The chunk-state kernel has left S_c (bf16,
+// padded to 64 x 128) for the chunks in front of the last boundary that still count at the
+// boundary behind them; this kernel walks the chunks of one (sequence, head) in order,
+// h <- a_c h + S_c with a_c = exp2(cs2_c[Q-1]) and S_c = 0 for the chunks whose factor up to the
+// boundary is below 2^SPLIT_KEEP_LOG2 (they are not read), and stores h at every boundary.
+// Workgroup = (sequence, head, quarter of the state); a lane owns eight consecutive n of one channel.
+// =========================================================================================
+__global__ void __launch_bounds__(256)
+boundary_states_kernel(const uint16_t *__restrict__ states_lp, const float *__restrict__ cs2,
+                       const float *__restrict__ h0, float *__restrict__ hmid, Shape s, int nseg)
+{
+    // s is the shape of the segments: s.B = sequences * nseg, s.nc = chunks per segment
+    __shared__ float s_tot[PASS_SPLIT_MAX_CHUNKS];
+    __shared__ int s_first;
+    const int part = blockIdx.x & 3;
+    const int h = (blockIdx.x >> 2) % s.H;
+    const int seq = (blockIdx.x >> 2) / s.H;
+    const int e = (part * 256 + threadIdx.x) * 8;        // element of the padded 64 x 128 state
+    const int p = e / MN, n0 = e % MN;
+    const bool inside = p < s.P && n0 < s.N;             // N is a multiple of 8
+    float hv[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    if (h0 && inside) {
+        const float *src = h0 + (((int64_t)seq * s.H + h) * s.P + p) * s.N + n0;
+        const float4 v0 = *reinterpret_cast<const float4 *>(src), v1 = *reinterpret_cast<const float4 *>(src + 4);
+        hv[0] = v0.x; hv[1] = v0.y; hv[2] = v0.z; hv[3] = v0.w; hv[4] = v1.x; hv[5] = v1.y; hv[6] = v1.z; hv[7] = v1.w;
+    }
+    for (int seg = 0; seg + 1 < nseg; ++seg) {
+        const int b = seq * nseg + seg;
+        const float *tot = cs2 + (((int64_t)b * s.nc) * s.H + h) * s.Q + (s.Q - 1);      // + c * H * Q
+        __syncthreads();                                  // the previous segment's totals are no longer read
+        for (int c = threadIdx.x; c < s.nc; c += 256) s_tot[c] = tot[(int64_t)c * s.H * s.Q];
+        __syncthreads();
+        if (threadIdx.x == 0) {
+            // first chunk of the segment that still counts at the boundary
+            int first = s.nc - 1;
+            float suf = 0.f;
+            while (first > 0) {
+                suf += s_tot[first];
+                if (suf < SPLIT_KEEP_LOG2) break;
+                --first;
+            }
+            s_first = first;
+        }
+        __syncthreads();
+        const int first = s_first;
+        {
+            // the chunks in front of it only decay what is carried in
+            float a = 0.f;
+            for (int c = 0; c < first; ++c) a += s_tot[c];
+            a = fast_exp2(a);
+#pragma unroll
+            for (int v = 0; v < 8; ++v) hv[v] *= a;
+        }
+        const uint16_t *src = states_lp + (((int64_t)b * s.nc) * s.H + h) * (MP * MN) + e;   // + c * H * MP * MN
+        for (int c0 = first; c0 < s.nc; c0 += 4) {
+            uint4 sv[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                sv[u] = *reinterpret_cast<const uint4 *>(src + (int64_t)min(c0 + u, s.nc - 1) * s.H * (MP * MN));
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                if (c0 + u < s.nc) {
+                    const float a = fast_exp2(s_tot[c0 + u]);
+                    float f[8];
+                    unpack8(f, sv[u]);
+#pragma unroll
+                    for (int v = 0; v < 8; ++v) hv[v] = a * hv[v] + f[v];
+                }
+            }
+        }
+        if (inside) {
+            float *dst = hmid + ((((int64_t)seq * (nseg - 1) + seg) * s.H + h) * s.P + p) * s.N + n0;
+            *reinterpret_cast<float4 *>(dst) = make_float4(hv[0], hv[1], hv[2], hv[3]);
+            *reinterpret_cast<float4 *>(dst + 4) = make_float4(hv[4], hv[5], hv[6], hv[7]);
+        }
+    }
+}
+
+// the shape of the nseg equal segments of whole chunks a sequence splits into
+static bool segment_shape(const Shape &s, int nseg, Shape *sv)
+{
+    *sv = s;
+    if (nseg == 1) return true;
+    if (nseg < 1 || nseg > PASS_SPLIT_MAX_SEGMENTS || s.nc % nseg != 0 || (int64_t)s.nc * s.Q != s.L ||
+        s.nc / nseg > PASS_SPLIT_MAX_CHUNKS)
+        return false;
+    sv->B = s.B * nseg; sv->L = s.L / nseg; sv->nc = s.nc / nseg;
+    return true;
+}
+
+// chunk states in front of the boundaries (those that still count there), then the boundary states
+swimba_status launch_boundary_states_mfma(const Shape &s, int nseg, const void *x, const void *dt, const float *A,
+                                          const void *bt8, const float *cs2, void *states_lp, const float *h0,
+                                          float *hmid, hipStream_t st)
+{
+    Shape sv;
+    if (nseg < 2 || !segment_shape(s, nseg, &sv)) return SWIMBA_ERR_UNSUPPORTED;
+    if ((int64_t)s.B * s.H == 0 || s.nc == 0) return SWIMBA_OK;
+    swimba_status rc = launch_chunk_state_mfma(sv, x, dt, A, bt8, nullptr, states_lp, st, 1, nullptr, nullptr, nullptr,
+                                               nseg, cs2);
+    if (rc != SWIMBA_OK) return rc;
+    hipLaunchKernelGGL(boundary_states_kernel, dim3((unsigned)((int64_t)s.B * s.H * 4)), dim3(256), 0, st,
+                       (const uint16_t *)states_lp, cs2, h0, hmid, sv, nseg);
+    SWIMBA_CHECK_LAUNCH();
+    return SWIMBA_OK;
 }
 
 template <int Q>
 static swimba_status launch_pass64_q(const Shape &s, const void *x, const void *dt, const float *D, const void *cmix,
                                      const void *bt8, const void *cb, const float *cs2, const float *fdec,
-                                     const float *cdec, const float *h0, float *h_final, void *y, hipStream_t st)
+                                     const float *cdec, const float *h0, float *h_final, void *y, hipStream_t st,
+                                     int nseg, const float *hmid)
 {
     const int64_t total = (int64_t)s.B * s.H;
     if (total == 0 || s.nc == 0) return SWIMBA_OK;
@@ -541,19 +684,23 @@ static swimba_status launch_pass64_q(const Shape &s, const void *x, const void *
     }
     hipLaunchKernelGGL(pass64_kernel<Q>, dim3(nblocks), dim3(PASS64_THREADS), shm, st, (const uint16_t *)x,
                        (const uint16_t *)dt, D, (const uint16_t *)cmix, (const uint16_t *)bt8, (const uint16_t *)cb,
-                       cs2, fdec, cdec, h0, h_final, (uint16_t *)y, s, (int)total, nblocks);
+                       cs2, fdec, cdec, h0, h_final, (uint16_t *)y, s, (int)total, nblocks, nseg, hmid);
     SWIMBA_CHECK_LAUNCH();
     return SWIMBA_OK;
 }
 
 swimba_status launch_pass64_mfma(const Shape &s, const void *x, const void *dt, const float *D, const void *cmix,
                                  const void *bt8, const void *cb, const float *cs2, const float *fdec,
-                                 const float *cdec, const float *h0, float *h_final, void *y, hipStream_t st)
+                                 const float *cdec, const float *h0, float *h_final, void *y, hipStream_t st,
+                                 int nseg, const float *hmid)
 {
+    // nseg > 1: every sequence as nseg chains of its own, each from the boundary state in hmid
+    Shape sv;
+    if (!segment_shape(s, nseg, &sv) || (nseg > 1 && !hmid)) return SWIMBA_ERR_UNSUPPORTED;
     switch (s.Q) {
-    case 64: return launch_pass64_q<64>(s, x, dt, D, cmix, bt8, cb, cs2, fdec, cdec, h0, h_final, y, st);
-    case 128: return launch_pass64_q<128>(s, x, dt, D, cmix, bt8, cb, cs2, fdec, cdec, h0, h_final, y, st);
-    case 256: return launch_pass64_q<256>(s, x, dt, D, cmix, bt8, cb, cs2, fdec, cdec, h0, h_final, y, st);
+    case 64: return launch_pass64_q<64>(sv, x, dt, D, cmix, bt8, cb, cs2, fdec, cdec, h0, h_final, y, st, nseg, hmid);
+    case 128: return launch_pass64_q<128>(sv, x, dt, D, cmix, bt8, cb, cs2, fdec, cdec, h0, h_final, y, st, nseg, hmid);
+    case 256: return launch_pass64_q<256>(sv, x, dt, D, cmix, bt8, cb, cs2, fdec, cdec, h0, h_final, y, st, nseg, hmid);
     }
     return SWIMBA_ERR_UNSUPPORTED;
 }

@@ -415,7 +415,7 @@ chunk_state_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restri
                         float *__restrict__ cs, uint16_t *__restrict__ states_lp, Shape s, int ipw,
                         int nruns, int total, int nblocks, int xts, int nslots, int ncb,
                         const uint16_t *__restrict__ cmix, const uint16_t *__restrict__ bmix_frag,
-                        uint16_t *__restrict__ cb)
+                        uint16_t *__restrict__ cb, int nseg, const float *__restrict__ cs2)
 {
     if ((int)blockIdx.x < ncb) {
         // The first ncb workgroups compute the causal G^T tiles instead (one wave per tile pair, see
@@ -442,8 +442,11 @@ chunk_state_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restri
     const int run = lid % nruns;
     const int g = (lid / nruns) % s.G;
     const int c = (lid / (nruns * s.G)) % s.nc;
-    const int b = (lid / (nruns * s.G * s.nc)) % s.B;
-    const int slot = lid / (nruns * s.G * s.nc * s.B);
+    // split pass (nseg > 1, one slot): the grid covers the segments in front of a boundary only
+    const int bgrid = nseg > 1 ? s.B / nseg * (nseg - 1) : s.B;
+    const int bb = (lid / (nruns * s.G * s.nc)) % bgrid;
+    const int b = nseg > 1 ? bb / (nseg - 1) * nseg + bb % (nseg - 1) : bb;
+    const int slot = lid / (nruns * s.G * s.nc * bgrid);
     x += (int64_t)slot * s.H * s.P;
     bmix_t8 += (int64_t)slot * s.B * s.nc * s.G * Q * MN;
     states_lp += (int64_t)slot * s.B * s.nc * s.H * MP * MN;
@@ -468,6 +471,33 @@ chunk_state_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restri
     // 8a + 4k + b is n = 32*wave + 16k + 4a + b: a lane ends up with 16 consecutive n of one
     // channel p (two 16-byte bf16 stores).  k-step ks covers tokens 16ks + 8kg + 0..7.
     const int prow = 16 * ((l32 >> 2) & 1) + 4 * (l32 >> 3) + (l32 & 3);
+    // Split pass (nseg > 1; the shape is that of the segments, "batch" b is segment b % nseg of its
+    // sequence): only the states at the segment boundaries are wanted, and a chunk state reaches the
+    // boundary behind it times exp2 of the totals of the chunks in between.  Below 2^-150 nothing of
+    // it survives in fp32, and the boundary kernel leaves such a chunk out; this kernel computes the
+    // states down to 2^-151 (the two sum the totals in different orders).  The chunks behind the
+    // last boundary have no workgroups.
+    uint32_t hmask = count >= 32 ? 0xffffffffu : (1u << count) - 1u;
+    if (nseg > 1) {
+        // wave w sums for the heads w, w + 4, ... of the run (a lane per chunk in between), then the
+        // waves put their bits together
+        uint32_t bits = 0;
+        for (int k = wave; k < count; k += 4) {
+            const float *tot = cs2 + (((int64_t)b * s.nc) * s.H + h0 + k) * Q + (Q - 1);
+            float suf = 0.f;
+            for (int cc = c + 1 + lane; cc < s.nc; cc += 64) suf += tot[(int64_t)cc * s.H * Q];
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) suf += __shfl_xor(suf, off);
+            if (suf >= SPLIT_KEEP_LOG2 - 1.f) bits |= 1u << k;
+        }
+        if (lane == 0) reinterpret_cast<uint32_t *>(s_part)[wave] = bits;
+        lds_barrier();
+        hmask = reinterpret_cast<uint32_t *>(s_part)[0] | reinterpret_cast<uint32_t *>(s_part)[1] |
+                reinterpret_cast<uint32_t *>(s_part)[2] | reinterpret_cast<uint32_t *>(s_part)[3];
+        lds_barrier();                                   // s_part is the scan's scratch from here on
+        hmask = __builtin_amdgcn_readfirstlane(hmask);
+        if (hmask == 0) return;
+    }
     uint4 bfrag[KS];
     {
         const uint16_t *src = bmix_t8 + (bcg * (Q / 8) * MN + (wave * 32 + prow)) * 8;
@@ -517,7 +547,7 @@ chunk_state_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restri
 #pragma unroll
         for (int ww = 0; ww <= LASTW; ++ww) cs_last += s_part[buf * 4 + ww];
         if (tid < Q) {
-            cs[(((int64_t)b * s.nc + c) * s.H + h) * Q + tid] = incl;
+            if (cs) cs[(((int64_t)b * s.nc + c) * s.H + h) * Q + tid] = incl;
             s_coef[buf * Q + tid] = dtv * fast_exp2((cs_last - incl) * LOG2E);
         }
         lds_barrier();
@@ -540,8 +570,15 @@ chunk_state_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restri
         }
     };
 
-    issue_loads(h0);
-    stage(0, h0);
+    // the heads of the run that are computed, lowest first
+    auto next_head = [&]() {
+        const int k = __builtin_ctz(hmask);
+        hmask &= hmask - 1;
+        return h0 + k;
+    };
+    int hcur = next_head();
+    issue_loads(hcur);
+    stage(0, hcur);
     {
         // Touch every mixed-B operand register here: the wait for those loads then sits in front
         // of the head loop.  Left inside it, the (static) wait counts of the first MFMAs would also
@@ -553,10 +590,10 @@ chunk_state_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restri
         if (touch == 0x7fc07fc1u && count < 0) s_part[0] = 1.f;   // never true
     }
     lds_barrier();
-    for (int k = 0; k < count; ++k) {
-        const int h = h0 + k;
-        const bool more = (k + 1 < count);
-        if (more) issue_loads(h + 1);
+    for (int k = 0;; ++k) {
+        const int h = hcur;
+        const bool more = hmask != 0;
+        if (more) { hcur = next_head(); issue_loads(hcur); }
         const uint16_t *srcX = sXt + (k & 1) * MP * STR;
         f32x16_t acc0 = {0}, acc1 = {0};
 #pragma unroll
@@ -578,22 +615,26 @@ chunk_state_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restri
             *reinterpret_cast<uint4 *>(out + 32 * MN) = pack8(t1);
             *reinterpret_cast<uint4 *>(out + 32 * MN + 8) = pack8(t1 + 8);
         }
-        if (more) stage((k + 1) & 1, h + 1);
+        if (more) stage((k + 1) & 1, hcur);
         lds_barrier();
+        if (!more) break;
     }
 }
 
 template <int Q>
 static swimba_status launch_cs_q(const Shape &s, const void *x, const void *dt, const float *A,
                                  const void *bmix_t8, float *cs, void *states_lp, hipStream_t st, int xts,
-                                 int nslots, const void *cmix, const void *bfrag, void *cb)
+                                 int nslots, const void *cmix, const void *bfrag, void *cb, int nseg, const float *cs2)
 {
     const int hpg = s.H / s.G;
     // heads per workgroup: as many as possible while at least ~2 workgroups per CU remain
-    int ipw = hpg;
+    int ipw = hpg < 32 ? hpg : 32;               // (the kernel keeps the heads of a run as a 32-bit mask)
     while (ipw > 1 && (int64_t)s.B * s.nc * s.G * ((hpg + ipw - 1) / ipw) < 512) ipw = (ipw + 1) / 2;
+    // split pass: which heads of a run are computed depends on the data, so shorter runs balance better
+    // (measured on the long-sequence workload, whole launch pair: runs of 1, 2, 4, 8 heads 68, 62, 59, 59 us)
+    if (nseg > 1 && ipw > 4) ipw = 4;
     const int nruns = (hpg + ipw - 1) / ipw;
-    const int64_t total = (int64_t)s.B * s.nc * s.G * nruns * nslots;
+    const int64_t total = (int64_t)(nseg > 1 ? s.B / nseg * (nseg - 1) : s.B) * s.nc * s.G * nruns * nslots;
     if (total == 0) return SWIMBA_OK;
     if (total > (int64_t)1 << 30) return SWIMBA_ERR_UNSUPPORTED;
     const int nblocks = xcd_padded(total);
@@ -616,7 +657,7 @@ static swimba_status launch_cs_q(const Shape &s, const void *x, const void *dt, 
     hipLaunchKernelGGL(chunk_state_mfma_kernel<Q>, dim3(ncb + nblocks), dim3(MTHREADS), shm, st,
                        (const uint16_t *)x, (const uint16_t *)dt, A, (const uint16_t *)bmix_t8, cs,
                        (uint16_t *)states_lp, s, ipw, nruns, (int)total, nblocks, xts, nslots, ncb,
-                       (const uint16_t *)cmix, (const uint16_t *)bfrag, (uint16_t *)cb);
+                       (const uint16_t *)cmix, (const uint16_t *)bfrag, (uint16_t *)cb, nseg, cs2);
     SWIMBA_CHECK_LAUNCH();
     return SWIMBA_OK;
 }
@@ -625,13 +666,16 @@ static swimba_status launch_cs_q(const Shape &s, const void *x, const void *dt, 
 // with cb != nullptr the same launch also computes the G^T tiles from cmix and bfrag
 swimba_status launch_chunk_state_mfma(const Shape &s, const void *x, const void *dt, const float *A,
                                       const void *bmix_t8, float *cs, void *states_lp, hipStream_t st,
-                                      int nslots, const void *cmix, const void *bfrag, void *cb)
+                                      int nslots, const void *cmix, const void *bfrag, void *cb, int nseg,
+                                      const float *cs2)
 {
+    if (nseg < 1 || (nseg > 1 && (!cs2 || nslots != 1))) return SWIMBA_ERR_UNSUPPORTED;
+    if (nseg == 1 && !cs) return SWIMBA_ERR_NULL;
     const int xts = nslots * s.H * s.P;
     switch (s.Q) {
-    case 64: return launch_cs_q<64>(s, x, dt, A, bmix_t8, cs, states_lp, st, xts, nslots, cmix, bfrag, cb);
-    case 128: return launch_cs_q<128>(s, x, dt, A, bmix_t8, cs, states_lp, st, xts, nslots, cmix, bfrag, cb);
-    case 256: return launch_cs_q<256>(s, x, dt, A, bmix_t8, cs, states_lp, st, xts, nslots, cmix, bfrag, cb);
+    case 64: return launch_cs_q<64>(s, x, dt, A, bmix_t8, cs, states_lp, st, xts, nslots, cmix, bfrag, cb, nseg, cs2);
+    case 128: return launch_cs_q<128>(s, x, dt, A, bmix_t8, cs, states_lp, st, xts, nslots, cmix, bfrag, cb, nseg, cs2);
+    case 256: return launch_cs_q<256>(s, x, dt, A, bmix_t8, cs, states_lp, st, xts, nslots, cmix, bfrag, cb, nseg, cs2);
     }
     return SWIMBA_ERR_UNSUPPORTED;
 }
@@ -670,8 +714,7 @@ swimba_status launch_chunk_state_mfma(const Shape &s, const void *x, const void 
 // wrote them, and the workgroup of chunk c carries the state forward itself,
 // H_c = S_{c-1} + a_{c-1} (S_{c-2} + ... a_0 h0), a_c = exp(cs_c[Q-1]), in fp32 and in the scan
 // kernel's order of operations; the workgroups of the last chunk also write h_final.  At most
-// OUT_LB_MAX chunks.
-constexpr int OUT_LB_MAX = 8;
+// OUTPUT_LOOKBACK_MAX_CHUNKS chunks.
 template <int Q, int MODE>
 __global__ void __launch_bounds__(64 * (Q / 32), (Q == 256 ? 4 : 1))   // Q = 256: two workgroups per compute unit
 output_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restrict__ dt,
@@ -1174,7 +1217,7 @@ static swimba_status launch_out_q(const Shape &s, const void *x, const void *dt,
         }
         SWIMBA_OUT_LAUNCH(2, shm, skip_w, skip_stride, 0, nslots);
     } else if (lookback) {
-        if (s.nc > OUT_LB_MAX) return SWIMBA_ERR_UNSUPPORTED;
+        if (s.nc > OUTPUT_LOOKBACK_MAX_CHUNKS) return SWIMBA_ERR_UNSUPPORTED;
         SWIMBA_OUT_LAUNCH(3, 0, nullptr, 0, 0, 1);
     } else if (skip_w || accumulate) {
         SWIMBA_OUT_LAUNCH(1, 0, skip_w, skip_stride, accumulate, 1);
@@ -1199,7 +1242,7 @@ swimba_status launch_output_mfma(const Shape &s, const void *x, const void *dt, 
     return SWIMBA_ERR_UNSUPPORTED;
 }
 
-// Short sequences (at most OUT_LB_MAX chunks): states_lp holds the chunk states, not the carried ones; every
+// Short sequences (at most OUTPUT_LOOKBACK_MAX_CHUNKS chunks): states_lp holds the chunk states, not the carried ones; every
 // workgroup carries the state up to its chunk itself and the last chunk's workgroups write h_final.
 swimba_status launch_output_lookback_mfma(const Shape &s, const void *x, const void *dt, const float *D,
                                           const void *cmix, const void *cb, const float *cs, const void *states_lp,

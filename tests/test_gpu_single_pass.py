@@ -226,3 +226,82 @@ def test_long_sequence_on_the_scan_path_matches_oracle():
     assert l2 <= TOL["bf16"] and linf <= TOL["bf16"], (l2, linf)
     l2, linf = rel_errors(host(out.h_final), ref["h_final"], (0, 1))
     assert l2 <= TOL["bf16"] and linf <= TOL["bf16"], (l2, linf)
+
+
+SPLIT_CASES = [
+    # B, L, H, P, N, G, E, k, Q, h0, D, segments, factor on dt
+    (2, 1024, 4, 64, 128, 2, 8, 2, 256, True, True, 2, 1.0),
+    (1, 1536, 3, 64, 128, 1, 8, 2, 128, False, True, 3, 1.0),
+    (1, 1024, 2, 48, 96, 1, 4, 1, 64, True, False, 4, 1.0),
+    (2, 2048, 4, 64, 128, 4, 8, 2, 256, True, True, 2, 0.05),   # hardly any decay: every chunk state counts
+    (1, 3072, 4, 64, 128, 1, 8, 2, 256, True, True, 2, 12.0),   # strong decay: most chunk states are left out
+    (1, 2048, 2, 64, 128, 1, 4, 2, 128, True, True, 4, 12.0),
+]
+
+
+@pytest.mark.parametrize("case", SPLIT_CASES, ids=lambda c: "B%dL%dH%dP%dN%dG%dE%dk%dQ%d_h0%d_D%d_seg%d_dt%g" % c)
+def test_split_pass_matches_oracle_and_the_whole_pass(case):
+    """Every sequence as 2..4 segments, each walked by a workgroup of its own from the state at its boundary
+    (chunk states in front of the boundary, those with a factor of exactly zero left out): against the
+    oracle, and against the same kernel walking whole sequences."""
+    B, L, H, P, N, G, E, k, Q, with_h0, with_D, nseg, dt_scale = case
+    w = synth.Workload("split", B, L, H, P, N, G, E, k, Q, "bf16", 9)
+    p = synth.make_inputs(w, seed=hash(case[:12]) % 100000)
+    # scaled step sizes, rounded to bf16 here so that both sides see the same values
+    p["dt"] = torch.from_numpy(p["dt"] * np.float32(dt_scale)).to(torch.bfloat16).to(torch.float32).numpy()
+    rng = np.random.default_rng(13)
+    p["D"] = rng.standard_normal(H).astype(np.float32)
+    h0 = (0.1 * rng.standard_normal((B, H, P, N))).astype(np.float32) if with_h0 else None
+    D = p["D"] if with_D else None
+    d = to_device(p, "bf16")
+    dims = sw.dims_of(d["x"], d["B_experts"], k, Q)
+    h0d = None if h0 is None else torch.from_numpy(h0).to("cuda:0")
+    Dd = d["D"] if with_D else None
+    ws = sw.alloc_workspace(dims, "cuda:0")
+    ws.fill_(0xff)                              # chunk states that are left out must not be read either
+    y = torch.full_like(d["x"], float("nan"))
+    hf = torch.full((B, H, P, N), float("nan"), device="cuda:0")
+    sw.swimba_stage_mix(dims, d["B_experts"], d["C_experts"], d["router_logits"], ws)
+    sw.swimba_stage_prep(dims, d["dt"], d["A"], ws)
+    sw.swimba_stage_boundary_states(dims, d["x"], d["dt"], d["A"], h0d, nseg, ws)
+    sw.swimba_stage_pass64_split(dims, d["x"], d["dt"], Dd, h0d, y, hf, nseg, ws)
+    torch.cuda.synchronize()
+    assert torch.isfinite(y).all() and torch.isfinite(hf).all()
+    ref = orc.mixer_fwd(p["x"], p["dt"], p["A"], D, p["B_experts"], p["C_experts"], p["router_logits"], k, h0=h0)
+    q = abs_inputs(p)
+    aref = orc.mixer_fwd(q["x"], q["dt"], q["A"], None if D is None else np.abs(D), q["B_experts"], q["C_experts"],
+                         q["router_logits"], k, h0=None if h0 is None else np.abs(h0))
+    ey = componentwise_excess(host(y), ref["y"], aref["y"])
+    eh = componentwise_excess(host(hf), ref["h_final"], aref["h_final"])
+    l2, linf = rel_errors(host(y), ref["y"], (0, 2))
+    hl2, hlinf = rel_errors(host(hf), ref["h_final"], (0, 1))
+    print(case, "y l2 %.2e linf %.2e  h_final l2 %.2e  componentwise %.2e %.2e" % (l2, linf, hl2, ey, eh), flush=True)
+    assert ey <= comp_tol("bf16") and eh <= comp_tol("bf16"), (ey, eh)
+    assert l2 <= TOL["bf16"] and linf <= TOL["bf16"], (l2, linf)
+    assert hl2 <= TOL["bf16"] and hlinf <= TOL["bf16"], (hl2, hlinf)
+    # whole sequences: identical in the first segment, within the operands' rounding behind it
+    y1 = torch.empty_like(y)
+    hf1 = torch.empty_like(hf)
+    sw.swimba_stage_pass64(dims, d["x"], d["dt"], Dd, h0d, y1, hf1, ws)
+    torch.cuda.synchronize()
+    assert torch.equal(y[:, :L // nseg], y1[:, :L // nseg])
+    l2, linf = rel_errors(host(y), host(y1), (0, 2))
+    assert l2 <= TOL["bf16"] and linf <= TOL["bf16"], ("whole", l2, linf)
+    l2, linf = rel_errors(host(hf), host(hf1), (0, 1))
+    assert l2 <= TOL["bf16"] and linf <= TOL["bf16"], ("whole h_final", l2, linf)
+
+
+def test_split_pass_refuses_what_it_does_not_take():
+    dev = "cuda:0"
+    for L, Q, nseg in ((1000, 256, 2), (1536, 256, 4), (1024, 256, 5), (1024, 256, 0)):
+        x = torch.zeros((1, L, 2, 64), dtype=torch.bfloat16, device=dev)
+        Be = torch.zeros((1, L, 4, 1, 128), dtype=torch.bfloat16, device=dev)
+        dt = torch.zeros((1, L, 2), dtype=torch.bfloat16, device=dev)
+        A = -torch.ones(2, device=dev)
+        dims = sw.dims_of(x, Be, 2, Q)
+        ws = sw.alloc_workspace(dims, dev)
+        hf = torch.zeros((1, 2, 64, 128), device=dev)
+        with pytest.raises(RuntimeError):
+            sw.swimba_stage_boundary_states(dims, x, dt, A, None, nseg, ws)
+        with pytest.raises(RuntimeError):
+            sw.swimba_stage_pass64_split(dims, x, dt, None, None, torch.empty_like(x), hf, nseg, ws)
