@@ -200,16 +200,16 @@ swimba_status swimba_stage_pass(const swimba_dims *dims, const void *x, const vo
  * (bf16 MFMA: mix, chunk_state, state_scan, output; SWIMBA_PATH_STAGED_SHORT for at most 8 chunks,
  * see below), or a single pass over the chunks with the
  * state in registers: SWIMBA_PATH_SINGLE_PASS_HEAD (mix, prep, pass64: a workgroup per (batch,
- * head), taken for head dimensions above 32 when batch * heads fills at least 3/4 of the rounds
+ * head), taken for head dimensions above 32 when batch * heads fills at least 5/8 of the rounds
  * of workgroups it runs in - one workgroup per compute unit - and the sequence has at least 12
- * chunks) or SWIMBA_PATH_SINGLE_PASS (mix, prep, pass: a workgroup per (batch, head, 32
- * channels), taken when those slices number between 3/4 of and all of the compute units and
- * the sequence has at least 16 chunks), each also with the chunk-level mix kernel in front
- * (..._CHUNK_MIX, see below).  SWIMBA_PATH_SINGLE_PASS_HEAD_SPLIT is the per-head pass on sequences
- * cut into 2, 3 or 4 equal segments of whole chunks, each a chain of its own (see
- * swimba_stage_boundary_states): taken ahead of the 32-channel slices where batch * heads alone
- * leaves the rounds too empty but that many times as many chains fill them, the sequence is a whole
- * number of chunks and every segment has at least 12.  The results of the MFMA paths agree to the rounding of their
+ * chunks), SWIMBA_PATH_SINGLE_PASS_HEAD_SPLIT (the same pass on sequences cut into 2, 3 or 4 equal
+ * segments of whole chunks, each a chain of its own, see swimba_stage_boundary_states: taken where
+ * batch * heads alone leaves the rounds emptier than that but that many times as many chains fill
+ * 7/8 of them, the sequence is a whole number of chunks and every segment has at least 12) or
+ * SWIMBA_PATH_SINGLE_PASS (mix, prep, pass: a workgroup per (batch, head, 32 channels), taken for
+ * the remaining shapes whose slices number between 7/8 of and all of the compute units when the
+ * sequence has at least 16 chunks), each also with the chunk-level mix kernel in front
+ * (..._CHUNK_MIX, see below).  The results of the MFMA paths agree to the rounding of their
  * bf16 operands.  Returns minus the swimba_status for invalid dims.  Host only; launches
  * nothing. */
 #define SWIMBA_PATH_GENERIC 0

@@ -116,26 +116,29 @@ static int device_cus()
 // one workgroup (one per compute unit: its LDS) busy for the whole sequence of its chain, so it
 // needs chains that fill the rounds they run in, and enough chunks per chain to pay for the ramp;
 // the staged kernels also parallelise over chunks and win everywhere else.
-//   head64   a chain per (batch, head), all channels: 7.8 us per chunk.  Takes the shapes whose
-//            B*H chains fill at least 3/4 of their rounds, from 12 chunks on.
-//   slices32 a chain per (batch, head, 32 channels): 5.4 us per chunk, i.e. more per channel (the
-//            operands a group shares are read per slice), but twice the chains: for the shapes
-//            whose heads alone leave the chip half empty.
-// Measured on MI355X, staged / slices32 / head64 in us (device-random inputs, one input set):
-//   B8 L4096 H32 184/204/151   B16 L4096 H32 397/388/296   B8 L4096 H48 288/264/244   B4 L8192 H48 291/305/244
-//   B8 L4096 H24 144/177/131   B8 L3072 H24 111/134/106    B8 L2048 H24  82/103/ 83   B8 L4096 H16 107/105/126
-//   B2 L16384 H64 551/494/561  B4 L8192 H64 539/502/378    B1 L32768 H128 888/792/946
-//   head64, split: where B*H leaves the rounds too empty for head64 but 2, 3 or 4 times as many chains
-//            fill them, every sequence is cut into that many equal segments of whole chunks (at least 12
-//            each), each a chain of its own: the state at a segment boundary comes from the chunk states
-//            in front of it, of which only those whose decay up to the boundary is not exactly zero are
-//            computed (launch_boundary_states_mfma).  Ahead of slices32: per channel the head64 kernel is
-//            the cheaper one.
+//   head64   a chain per (batch, head), all channels: 7.5 us per chunk with every compute unit busy,
+//            about 6 us with 5/8 of them (the operands come through the same L2s).  Takes the shapes
+//            whose B*H chains fill at least 5/8 of their rounds, from 12 chunks on.
+//   head64, split: where B*H leaves the rounds emptier than that but 2, 3 or 4 times as many chains
+//            fill 7/8 of them, every sequence is cut into that many equal segments of whole chunks (at
+//            least 12 each), each a chain of its own: the state at a segment boundary comes from the
+//            chunk states in front of it, of which only those that still count there are computed
+//            (launch_boundary_states_mfma).  Ahead of slices32: per channel head64 is the cheaper kernel.
+//   slices32 a chain per (batch, head, 32 channels): 5.1 us per chunk, i.e. more per channel (the
+//            operands a group shares are read per slice), but twice the chains: for the remaining
+//            shapes whose slices number between 7/8 of and all of the compute units, from 16 chunks on.
+// Measured on MI355X, staged / slices32 / head64 / head64 split in us (device-random inputs, dt and A
+// drawn as in the workloads, one input set; mix and prep in front of every variant):
+//   B8 L4096 H32 172/184/138/-      B8 L4096 H40 248/243/230/241(2)  B4 L8192 H40 245/293/226/255(4)
+//   B8 L4096 H16 104/101/121/-      B4 L8192 H24 137/163/201/162(2)  B8 L2048 H24  81/ 98/ 79/-
+//   with 8 groups and 16 experts:   B2 L16384 H64 544/491/550/465(2) B1 L32768 H128 887/797/944/707(2)
+//   B1 L16384 H64 297/367/462/267(4)  B2 L8192 H64 290/253/288/241(2)
 enum PassKind { PASS_STAGED = 0, PASS_SLICES32 = 1, PASS_HEAD64 = 2 };
-static bool fills_rounds(int64_t chains, int ncu)
+// chains fill at least num/8 of the rounds of workgroups (one per compute unit) they run in
+static bool fills_rounds(int64_t chains, int ncu, int num)
 {
     const int64_t rounds = (chains + ncu - 1) / ncu;
-    return chains > 0 && 4 * chains >= 3 * rounds * ncu;
+    return chains > 0 && 8 * chains >= num * rounds * ncu;
 }
 // segments per sequence of the head64 pass (1: whole sequences; 0: head64 does not take the shape)
 static int head64_segments(const swimba_dims *d)
@@ -144,10 +147,11 @@ static int head64_segments(const swimba_dims *d)
     if (ncu == 0 || !use_mfma_path(d) || d->headdim <= 32) return 0;
     const int64_t heads = (int64_t)d->batch * d->nheads;
     const int64_t nc = ((int64_t)d->seqlen + d->chunk - 1) / d->chunk;
-    if (nc >= 12 && fills_rounds(heads, ncu)) return 1;
+    if (nc >= 12 && fills_rounds(heads, ncu, 5)) return 1;
     if (nc * d->chunk != d->seqlen) return 0;
     for (int nseg = 2; nseg <= PASS_SPLIT_MAX_SEGMENTS; ++nseg)
-        if (nc % nseg == 0 && nc / nseg >= 12 && nc / nseg <= PASS_SPLIT_MAX_CHUNKS && fills_rounds(heads * nseg, ncu))
+        if (nc % nseg == 0 && nc / nseg >= 12 && nc / nseg <= PASS_SPLIT_MAX_CHUNKS &&
+            fills_rounds(heads * nseg, ncu, 7))
             return nseg;
     return 0;
 }
@@ -159,7 +163,7 @@ static PassKind pass_kind(const swimba_dims *d)
     const int64_t nc = ((int64_t)d->seqlen + d->chunk - 1) / d->chunk;
     if (head64_segments(d) >= 1) return PASS_HEAD64;
     const int64_t slices = heads * ((d->headdim + 31) / 32);
-    if (nc >= 16 && slices <= ncu && fills_rounds(slices, ncu)) return PASS_SLICES32;
+    if (nc >= 16 && slices <= ncu && fills_rounds(slices, ncu, 7)) return PASS_SLICES32;
     return PASS_STAGED;
 }
 
