@@ -31,7 +31,7 @@ PEAK_BF16_TFLOPS = 2500.0
 IO_NAMES = ("x", "dt", "B_experts", "C_experts", "router_logits")
 
 
-def work_model(w):
+def work_model(w, live=1.0, nseg=2):
     """Algorithmic work of one forward and of each of its kernels.
 
     irreducible bytes: tensors that cross the library's boundary (x, y, dt, logits, the k selected
@@ -81,13 +81,13 @@ def work_model(w):
                    "irreducible": T * (2 * H * P * 2 + H * 2), "flops": 2.0 * T * Q * P * H + 2.0 * T * N * P * H},
     }
     kernels["pass64"] = kernels["pass"]
-    # split pass: the chunk states in front of the segment boundaries (at most all chunks but those of the last
-    # segment, two segments assumed here; in fact only those whose decay up to the boundary is not exactly
-    # zero in fp32, which depends on dt and A: an upper bound) and the boundary states.  Nothing of it is
-    # irreducible: x and dt are read a second time.
-    kernels["boundary_states"] = {"moved": 0.5 * (T * (H * P * 2 + H * 2 + G * N * 2) + state_elems * 4)
-                                           + 2 * w.batch * H * P * N * 4,
-                                  "irreducible": 0.0, "flops": 0.5 * 2.0 * T * N * P * H}
+    # split pass: the chunk states in front of the segment boundaries ((nseg - 1) / nseg of the chunks), of which
+    # only the fraction `live` still counts at the boundary behind it (it depends on dt and A; the bench measures
+    # it on its inputs), and the boundary states.  Nothing of it is irreducible: x and dt are read a second time.
+    front = (nseg - 1) / nseg
+    kernels["boundary_states"] = {"moved": front * (live * (T * (H * P * 2 + H * 2) + state_elems * 4) + T * G * N * 2)
+                                           + nseg * w.batch * H * P * N * 4,
+                                  "irreducible": 0.0, "flops": front * live * 2.0 * T * N * P * H}
     # short sequences: the tiles ride in the chunk-state launch, the output kernel reads the chunk states before
     # its chunk ((nc - 1) / 2 of them on average) instead of one carried state
     nc = (w.seqlen + Q - 1) // Q
@@ -98,6 +98,10 @@ def work_model(w):
                                "irreducible": kernels["output"]["irreducible"] + w.batch * H * P * N * 4,
                                "flops": kernels["output"]["flops"]}
     return call, kernels
+
+
+def nchunks_of(w):
+    return (w.seqlen + w.chunk - 1) // w.chunk
 
 
 def main() -> int:
@@ -268,6 +272,16 @@ def main() -> int:
                                                                      d["h_final"], d["ws"])}
             self.path = sw.swimba_prefill_path(dims)
             self.nseg = sw.swimba_pass_segments(dims)
+            self.live = 1.0
+            if self.nseg > 1:
+                # fraction of the (chunk, head) pairs in front of a segment boundary whose chunk state reaches
+                # it with a factor of at least 2^-150 (what the split pass computes and reads)
+                d0 = self.sets[0]
+                nper = nchunks_of(w) // self.nseg
+                tot = (d0["dt"].float() * d0["A"].float()).reshape(w.batch, self.nseg, nper, w.chunk, w.nheads).sum(3)
+                tot = tot[:, :-1] * 1.4426950408889634
+                suf = torch.flip(torch.cumsum(torch.flip(tot, (2,)), 2), (2,)) - tot
+                self.live = float((suf >= -150.0).float().mean().item())
             self.path_name = {sw.PATH_SINGLE_PASS: "single_pass", sw.PATH_STAGED: "staged",
                               sw.PATH_SINGLE_PASS_CHUNK_MIX: "single_pass_chunk_mix",
                               sw.PATH_SINGLE_PASS_HEAD: "single_pass_head", sw.PATH_STAGED_SHORT: "staged_short",
@@ -342,7 +356,7 @@ def main() -> int:
         def kernels(self, other=False):
             """each kernel of the path the forward takes for this shape (or of the other one) alone:
             K launches replayed from one HIP graph between two events"""
-            _, km = work_model(self.w)
+            _, km = work_model(self.w, self.live, max(self.nseg, 2))
             out = {}
             fns = self.paths[self.other if other else self.path]
             for fn in fns.values():   # every workspace holds this path's intermediates
@@ -603,6 +617,7 @@ def main() -> int:
 
     p_head = head.p
     head_desc, head_nsets, head_path = head.describe(), head.nsets, head.path_name
+    head_split = {"segments_per_sequence": head.nseg, "chunk_states_live_at_boundary": round(head.live, 4)} if head.nseg > 1 else {}
     head.close()
     del head
 
@@ -784,7 +799,7 @@ def main() -> int:
         "vs_baseline": None,
         "dtype": "bf16",
         "data": "synthetic",
-        "config": {"workload": head_desc, "input_sets_rotated": head_nsets, "path": head_path},
+        "config": dict({"workload": head_desc, "input_sets_rotated": head_nsets, "path": head_path}, **head_split),
         "roofline": roof,
         "targets": targets,
         "kernels": kernels,
