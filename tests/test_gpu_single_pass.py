@@ -305,3 +305,20 @@ def test_split_pass_refuses_what_it_does_not_take():
             sw.swimba_stage_boundary_states(dims, x, dt, A, None, nseg, ws)
         with pytest.raises(RuntimeError):
             sw.swimba_stage_pass64_split(dims, x, dt, None, None, torch.empty_like(x), hf, nseg, ws)
+
+
+def test_forward_paths_of_the_workloads():
+    """Which evaluation the forward picks for the benchmark shapes (a choice made from the shape and the number
+    of compute units; the figures hold for the 256 units of an MI355X)."""
+    if torch.cuda.get_device_properties(0).multi_processor_count != 256:
+        pytest.skip("the expected choices are those of a device with 256 compute units")
+    want = {1: (sw.PATH_STAGED_SHORT, 1), 2: (sw.PATH_SINGLE_PASS_HEAD, 1), 3: (sw.PATH_SINGLE_PASS_HEAD_SPLIT_CHUNK_MIX, 2)}
+    for idx, (path, nseg) in want.items():
+        w = synth.workload(idx)
+        dims = sw.make_dims(w.batch, w.seqlen, w.nheads, w.headdim, w.dstate, w.ngroups, w.nexperts, w.top_k, w.chunk,
+                            torch.bfloat16)
+        assert sw.swimba_prefill_path(dims) == path, idx
+        assert sw.swimba_pass_segments(dims) == nseg, idx
+    # a ragged sequence is not split, 96 chains do not fill two segments' worth of compute units
+    for shape in ((2, 16384 - 100, 64, 64, 128, 8, 16, 2, 256), (4, 8192, 24, 64, 128, 1, 8, 2, 256)):
+        assert sw.swimba_pass_segments(sw.make_dims(*shape, torch.bfloat16)) == 1, shape
