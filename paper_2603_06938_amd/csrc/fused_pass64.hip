@@ -19,6 +19,11 @@
 //                         (128 x 64 fp32 in accumulators, wave w rows n = 32w .. 32w+31) and
 //                         publish its bf16 image for the next chunk's readout.
 // One LDS-only workgroup barrier per chunk.
+//
+// Split pass: the recurrence between chunks is linear in the state, so a sequence can be walked as
+// nseg segments of whole chunks side by side once the states at the segment boundaries are known;
+// launch_boundary_states_mfma builds them from the chunk states in front of each boundary, and the
+// pass kernel then treats (sequence, segment) as its batch index.
 #include "common.hpp"
 #include "mfma_util.hpp"
 
