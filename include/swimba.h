@@ -202,7 +202,7 @@ swimba_status swimba_stage_pass(const swimba_dims *dims, const void *x, const vo
  * state in registers: SWIMBA_PATH_SINGLE_PASS_HEAD (mix, prep, pass64: a workgroup per (batch,
  * head), taken for head dimensions above 32 when batch * heads fills at least 5/8 of the rounds
  * of workgroups it runs in - one workgroup per compute unit - and the sequence has at least 12
- * chunks), SWIMBA_PATH_SINGLE_PASS_HEAD_SPLIT (the same pass on sequences cut into 2, 3 or 4 equal
+ * chunks, or 7/8 of them from 8 chunks on), SWIMBA_PATH_SINGLE_PASS_HEAD_SPLIT (the same pass on sequences cut into 2, 3 or 4 equal
  * segments of whole chunks, each a chain of its own, see swimba_stage_boundary_states: taken where
  * batch * heads alone leaves the rounds emptier than that but that many times as many chains fill
  * 7/8 of them, the sequence is a whole number of chunks and every segment has at least 12) or

@@ -118,7 +118,8 @@ static int device_cus()
 // the staged kernels also parallelise over chunks and win everywhere else.
 //   head64   a chain per (batch, head), all channels: 7.5 us per chunk with every compute unit busy,
 //            about 6 us with 5/8 of them (the operands come through the same L2s).  Takes the shapes
-//            whose B*H chains fill at least 5/8 of their rounds, from 12 chunks on.
+//            whose B*H chains fill at least 5/8 of their rounds, from 12 chunks on, and those that fill
+//            7/8 from 8 chunks on (B8 L2048 H32: 85 against 99 us staged; H24, workload 1: 86 against 85).
 //   head64, split: where B*H leaves the rounds emptier than that but 2, 3 or 4 times as many chains
 //            fill 7/8 of them, every sequence is cut into that many equal segments of whole chunks (at
 //            least 12 each), each a chain of its own: the state at a segment boundary comes from the
@@ -147,7 +148,7 @@ static int head64_segments(const swimba_dims *d)
     if (ncu == 0 || !use_mfma_path(d) || d->headdim <= 32) return 0;
     const int64_t heads = (int64_t)d->batch * d->nheads;
     const int64_t nc = ((int64_t)d->seqlen + d->chunk - 1) / d->chunk;
-    if (nc >= 12 && fills_rounds(heads, ncu, 5)) return 1;
+    if ((nc >= 12 && fills_rounds(heads, ncu, 5)) || (nc >= 8 && fills_rounds(heads, ncu, 7))) return 1;
     if (nc * d->chunk != d->seqlen) return 0;
     for (int nseg = 2; nseg <= PASS_SPLIT_MAX_SEGMENTS; ++nseg)
         if (nc % nseg == 0 && nc / nseg >= 12 && nc / nseg <= PASS_SPLIT_MAX_CHUNKS &&
