@@ -236,6 +236,8 @@ SPLIT_CASES = [
     (2, 2048, 4, 64, 128, 4, 8, 2, 256, True, True, 2, 0.05),   # hardly any decay: every chunk state counts
     (1, 3072, 4, 64, 128, 1, 8, 2, 256, True, True, 2, 12.0),   # strong decay: most chunk states are left out
     (1, 2048, 2, 64, 128, 1, 4, 2, 128, True, True, 4, 12.0),
+    (1, 10240, 2, 64, 128, 1, 4, 2, 64, True, True, 2, 0.02),   # 80 chunks per segment, nearly all of them count
+    (2, 4096, 8, 64, 128, 8, 4, 2, 128, False, True, 2, 1.0),   # a group per head
 ]
 
 
