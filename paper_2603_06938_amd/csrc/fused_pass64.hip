@@ -613,13 +613,14 @@ boundary_states_kernel(const uint16_t *__restrict__ states_lp, const float *__re
             for (int v = 0; v < 8; ++v) hv[v] *= a;
         }
         const uint16_t *src = states_lp + (((int64_t)b * s.nc) * s.H + h) * (MP * MN) + e;   // + c * H * MP * MN
-        for (int c0 = first; c0 < s.nc; c0 += 4) {
-            uint4 sv[4];
+        constexpr int AHEAD = 16;                         // chunk states requested together
+        for (int c0 = first; c0 < s.nc; c0 += AHEAD) {
+            uint4 sv[AHEAD];
 #pragma unroll
-            for (int u = 0; u < 4; ++u)
+            for (int u = 0; u < AHEAD; ++u)
                 sv[u] = *reinterpret_cast<const uint4 *>(src + (int64_t)min(c0 + u, s.nc - 1) * s.H * (MP * MN));
 #pragma unroll
-            for (int u = 0; u < 4; ++u) {
+            for (int u = 0; u < AHEAD; ++u) {
                 if (c0 + u < s.nc) {
                     const float a = fast_exp2(s_tot[c0 + u]);
                     float f[8];
