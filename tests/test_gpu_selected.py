@@ -115,12 +115,22 @@ def test_mixer_fwd_selected_matches_oracle(cfg):
     assert hl2 <= TOL[io] and hlinf <= TOL[io], (hl2, hlinf)
 
 
-def test_mixer_fwd_selected_equals_mixer_fwd_bitwise():
+@pytest.mark.parametrize("shape", [(2, 600, 4, 64, 128, 2, 8, 2, 256), (2, 1536, 64, 64, 128, 8, 4, 2, 64),
+                                   (4, 1024, 64, 64, 128, 8, 4, 2, 64)],
+                         ids=["staged", "split_pass", "pass_per_head"])
+def test_mixer_fwd_selected_equals_mixer_fwd_bitwise(shape):
     """Same kernels behind both entry points: gathering the selected rows on the host and
-    passing the weights the router kernel produced gives the same bits as the dense call."""
-    w = synth.Workload("selbit", 2, 600, 4, 64, 128, 2, 8, 2, 256, "bf16", 5)
+    passing the weights the router kernel produced gives the same bits as the dense call, on the
+    staged kernels, on the per-head single pass behind the chunk-level mix kernel and on the split pass
+    behind the per-tile one (the paths these shapes take on a device with 256 compute units)."""
+    w = synth.Workload("selbit", *shape, "bf16", 5)
     p = synth.make_inputs(w, seed=41)
     d = to_device(p, "bf16")
+    dims = sw.dims_of(d["x"], d["B_experts"], w.top_k, w.chunk)
+    if torch.cuda.get_device_properties(0).multi_processor_count == 256:
+        want = {256: (sw.PATH_STAGED_SHORT,), 64: (sw.PATH_SINGLE_PASS_HEAD_SPLIT, sw.PATH_SINGLE_PASS_HEAD_CHUNK_MIX)}[w.chunk]
+        assert sw.swimba_prefill_path(dims) in want
+        assert sw.swimba_pass_segments(dims) == (2 if shape[1] == 1536 else 1)
     dense = sw.swimba_mixer_fwd(d["x"], d["dt"], d["A"], d["D"], d["B_experts"], d["C_experts"],
                                 d["router_logits"], w.top_k, w.chunk, want_topk=True)
     idx = dense.topk_idx.to(torch.int64)[..., None, None].expand(-1, -1, -1, w.ngroups, w.dstate)
@@ -130,6 +140,14 @@ def test_mixer_fwd_selected_equals_mixer_fwd_bitwise():
     torch.cuda.synchronize()
     assert torch.equal(sel.y, dense.y)
     assert torch.equal(sel.h_final, dense.h_final)
+    if w.chunk == 64:
+        # the forward on these paths against the oracle as well (the staged case is covered above)
+        ref = orc.mixer_fwd(p["x"], p["dt"], p["A"], p["D"], p["B_experts"], p["C_experts"], p["router_logits"], w.top_k)
+        l2, linf = rel_errors(host(dense.y), ref["y"], (0, 2))
+        hl2, hlinf = rel_errors(host(dense.h_final), ref["h_final"], (0, 1))
+        print(shape, "y rel l2 %.3e linf %.3e  h_final l2 %.3e" % (l2, linf, hl2), flush=True)
+        assert l2 <= TOL["bf16"] and linf <= TOL["bf16"], (l2, linf)
+        assert hl2 <= TOL["bf16"] and hlinf <= TOL["bf16"], (hl2, hlinf)
 
 
 FUSED_SHAPES = [
