@@ -441,7 +441,13 @@ chunk_state_mfma_kernel(const uint16_t *__restrict__ x, const uint16_t *__restri
     if (lid >= total) return;
     const int run = lid % nruns;
     const int g = (lid / nruns) % s.G;
-    const int c = (lid / (nruns * s.G)) % s.nc;
+    // split pass: how much a workgroup has to do depends on its chunk's distance from the boundary (every head
+    // counts next to it, further away only the slowly decaying ones).  The XCD-aware ids give each XCD a
+    // contiguous range of ids, so consecutive ids take chunks nc/8 apart (every XCD gets all distances), and
+    // the chunks next to the boundary come first (the long workgroups are handed out before the short ones).
+    const int cidx = (lid / (nruns * s.G)) % s.nc;
+    const int cperm = (s.nc % 8 == 0) ? (cidx % 8) * (s.nc / 8) + cidx / 8 : cidx;
+    const int c = nseg > 1 ? s.nc - 1 - cperm : cidx;
     // split pass (nseg > 1, one slot): the grid covers the segments in front of a boundary only
     const int bgrid = nseg > 1 ? s.B / nseg * (nseg - 1) : s.B;
     const int bb = (lid / (nruns * s.G * s.nc)) % bgrid;
