@@ -107,15 +107,32 @@ prep_kernel(const uint16_t *__restrict__ dt, const float *__restrict__ A, const 
     const int tid = threadIdx.x;
     const int64_t tok0 = (int64_t)b * s.L + (int64_t)c * Q;
     const int valid = min(Q, s.L - c * Q);
-    for (int i = tid; i < Q * HB; i += MTHREADS) {
-        const int j = i / HB, hh = i % HB, h = hb * HB + hh;
-        float dtv = 0.f, a = 0.f;
-        if (h < s.H && j < valid) {
-            dtv = to_float(bf16{dt[(tok0 + j) * s.H + h]});
-            a = dtv * A[h];
+    if (s.H % 8 == 0) {
+        // eight heads of a token per load (16 bytes; the rows are 2H bytes long, so every piece is aligned)
+        for (int i = tid; i < Q * (HB / 8); i += MTHREADS) {
+            const int j = i / (HB / 8), h8 = (i % (HB / 8)) * 8, h = hb * HB + h8;
+            uint4 raw = make_uint4(0u, 0u, 0u, 0u);
+            const bool in = h < s.H && j < valid;
+            if (in) raw = *reinterpret_cast<const uint4 *>(dt + (tok0 + j) * s.H + h);
+            float dv[8];
+            unpack8(dv, raw);
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                s_a[j][h8 + e] = in ? dv[e] * A[h + e] : 0.f;
+                s_d[j][h8 + e] = dv[e];
+            }
         }
-        s_a[j][hh] = a;
-        s_d[j][hh] = dtv;
+    } else {
+        for (int i = tid; i < Q * HB; i += MTHREADS) {
+            const int j = i / HB, hh = i % HB, h = hb * HB + hh;
+            float dtv = 0.f, a = 0.f;
+            if (h < s.H && j < valid) {
+                dtv = to_float(bf16{dt[(tok0 + j) * s.H + h]});
+                a = dtv * A[h];
+            }
+            s_a[j][hh] = a;
+            s_d[j][hh] = dtv;
+        }
     }
     __syncthreads();
     // the segments of a head are scanned by one lane each, then offset by the totals before them
