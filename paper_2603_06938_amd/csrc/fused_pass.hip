@@ -107,8 +107,9 @@ prep_kernel(const uint16_t *__restrict__ dt, const float *__restrict__ A, const 
     const int tid = threadIdx.x;
     const int64_t tok0 = (int64_t)b * s.L + (int64_t)c * Q;
     const int valid = min(Q, s.L - c * Q);
-    if (s.H % 8 == 0) {
-        // eight heads of a token per load (16 bytes; the rows are 2H bytes long, so every piece is aligned)
+    if (s.H % 8 == 0 && (reinterpret_cast<uintptr_t>(dt) & 15u) == 0) {
+        // eight heads of a token per load (16 bytes; the rows are 2H bytes long, so every piece is aligned
+        // when the tensor is: the interface asks for element alignment only)
         for (int i = tid; i < Q * (HB / 8); i += MTHREADS) {
             const int j = i / (HB / 8), h8 = (i % (HB / 8)) * 8, h = hb * HB + h8;
             uint4 raw = make_uint4(0u, 0u, 0u, 0u);
