@@ -135,7 +135,7 @@ mix_chunk_kernel(const uint16_t *__restrict__ Be, const uint16_t *__restrict__ C
                 // all loads first, conversions after (a value consumed where it is loaded is waited for on
                 // the spot); a row of 16 logits is two 16-byte loads
                 float v[MC_EMAX];
-                if (s.E == MC_EMAX) {
+                if (s.E == MC_EMAX && (reinterpret_cast<uintptr_t>(logits) & 15u) == 0) {   // (the interface asks for element alignment only)
                     const uint4 q0 = *reinterpret_cast<const uint4 *>(gl), q1 = *reinterpret_cast<const uint4 *>(gl + 8);
                     unpack8(v, q0);
                     unpack8(v + 8, q1);
